@@ -1,0 +1,132 @@
+/*
+ * laserkv.h - C-ABI of the MI355X (gfx950) LASER-KV prefill-selection library.
+ *
+ * One call of laserkv_select_block + laserkv_append processes one context block of one
+ * layer for all KV heads: exact attention score of the block keys under the observation
+ * window (Sec. 3.3 "Precision", Alg. 1 step 3), SimHash signatures and collision counts
+ * (Sec. 3.3 "Recall", Alg. 1 step 6), the two-stage TopK of Alg. 1 steps 4-8 under the
+ * protection-divisor partition of Sec. 3.1, and the append of the kept K/V rows onto the
+ * accumulative per-layer cache (Sec. 3, first paragraph).
+ *
+ * Conventions for every function
+ *   - returns LKV_OK (0) or a negative laserkv_status; nothing throws or aborts.
+ *   - pointers marked DEVICE point to GPU memory owned by the caller; the library reads or
+ *     writes them only during the call's kernels and keeps no reference afterwards.
+ *   - all GPU work is enqueued on the caller's hipStream_t (passed as void*) and the call
+ *     returns without synchronising; calls on one context must be issued on one stream at a
+ *     time (the context's workspace is shared by consecutive calls).
+ *   - strides are in ELEMENTS of the storage dtype; the head_dim axis is contiguous.
+ *   - query head h*G + g (G = n_q_heads / n_kv_heads) belongs to KV head h.
+ */
+#ifndef LASERKV_H
+#define LASERKV_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct laserkv_ctx laserkv_ctx; /* opaque; owns only its own device workspace */
+
+typedef enum { LKV_F32 = 0, LKV_BF16 = 1 } laserkv_dtype;
+
+typedef enum {
+  LKV_OK = 0,
+  LKV_EINVAL = -1, /* bad shape, stride, budget or parameter; nothing was launched */
+  LKV_ECAP = -2,   /* append would overflow the cache capacity */
+  LKV_ENOMEM = -3, /* workspace allocation failed */
+  LKV_EHIP = -4    /* a HIP runtime call failed; text in laserkv_last_error */
+} laserkv_status;
+
+typedef struct {
+  int32_t n_q_heads;   /* H_q */
+  int32_t n_kv_heads;  /* H_kv, divides H_q */
+  int32_t head_dim;    /* d: 64 or 128 */
+  int32_t dtype;       /* laserkv_dtype: storage type of Q, K, V, cache and hyperplanes */
+  int32_t lsh_tables;  /* L: number of hash functions h_r (tables), >= 1 */
+  int32_t lsh_bits;    /* K: sign bits per table, 1..16; L*K <= 512 */
+  int32_t max_block;   /* largest S_t (tokens per block) any call will pass, <= 16384 */
+  int32_t max_window;  /* largest W (window queries per head); G*W <= 1024 */
+  int32_t max_ctx_keys;/* largest T (look-back keys) */
+} laserkv_config;
+
+/* Create a context and allocate its device workspace (hipMalloc) on the current device.
+ * *out is set only on success.  Host pointers. */
+int laserkv_create(const laserkv_config* cfg, laserkv_ctx** out);
+
+/* Free the workspace.  The caller must have synchronised the stream(s) it used. NULL is ignored. */
+void laserkv_destroy(laserkv_ctx* ctx);
+
+/* Text of the last error recorded on this context (or a process-wide one when ctx is NULL).
+ * The string is owned by the library and valid until the next failing call. */
+const char* laserkv_last_error(const laserkv_ctx* ctx);
+
+/* Per-block budget B = floor(2 r S_block L_ctx / (S_block + L_ctx)), r = r_num / r_den,
+ * evaluated in exact integer arithmetic (App. B equation).  Returns -1 on bad arguments.
+ * Host only. */
+int64_t laserkv_budget(int64_t s_block, int64_t l_ctx, int64_t r_num, int64_t r_den);
+
+/* Partition of a block's budget (Sec. 3.1; Alg. 1 steps 4 and 7), host only:
+ *   B_t = min(B, s_t); n_anchor = n_local = floor(B_t / n); B_long = B_t - 2 floor(B_t / n);
+ *   k_exact = floor(alpha * B_long); k_lsh = B_long - k_exact.
+ * Requires n >= 2, 0 <= alpha <= 1, B >= 0, s_t >= 1. */
+int laserkv_partition(int32_t B, int32_t n, double alpha, int32_t s_t,
+                      int32_t* n_anchor, int32_t* n_local, int32_t* k_exact, int32_t* k_lsh);
+
+/* Steps a1-a4 for one block: score, hash, count, select.
+ *
+ *   q_win        DEVICE [H_q, w, d]      window queries; query j sits at position q_pos0 + j
+ *   k_blk        DEVICE [H_kv, s_t, d]   block keys; key i sits at position block_pos0 + i
+ *   k_ctx        DEVICE [H_kv, t_ctx, d] look-back keys (tail of the previous block, Sec. 3.2):
+ *                always visible, they enter the softmax normaliser only; NULL iff t_ctx == 0
+ *   hyperplanes  DEVICE [L*K, d] contiguous; row r*K + c decides bit c of table r (bit = proj >= 0)
+ *   causal       non-zero: block key i is visible to query j iff block_pos0 + i <= q_pos0 + j.
+ *                Every query must see at least one key (t_ctx > 0 or q_pos0 >= block_pos0).
+ *   n_anchor, n_local   first / last positions of the block that are always kept
+ *   k_exact      candidates taken by (S_exact descending, index ascending)
+ *   k_lsh        remaining candidates taken by (collision count descending, index ascending)
+ *                n_anchor + n_local + k_exact + k_lsh = B_t <= s_t
+ *   keep_idx     DEVICE out [H_kv, B_t] int32, block-local indices, ascending per head
+ *   dbg_*        optional DEVICE outputs of the intermediate stages (NULL to skip):
+ *                dbg_s_exact [H_kv, s_t] float, dbg_sig_k [H_kv, s_t, L] uint16,
+ *                dbg_sig_q [H_q, w, L] uint16, dbg_count [H_kv, s_t] int32
+ *
+ * S_exact[h, i] = mean over the G*w window rows of KV head h of softmax(q.k / sqrt(d)) at key i.
+ * Errors: LKV_EINVAL for shapes beyond the context's configuration, w < 1, budgets that do
+ * not fit the block, misaligned pointers/strides (16-byte rows required), invisible rows. */
+int laserkv_select_block(laserkv_ctx* ctx,
+                         const void* q_win, int64_t q_stride_head, int64_t q_stride_tok,
+                         const void* k_blk, int64_t k_stride_head, int64_t k_stride_tok,
+                         const void* k_ctx, int64_t c_stride_head, int64_t c_stride_tok,
+                         const void* hyperplanes,
+                         int32_t s_t, int32_t w, int32_t t_ctx,
+                         int64_t block_pos0, int64_t q_pos0, int32_t causal,
+                         int32_t n_anchor, int32_t n_local, int32_t k_exact, int32_t k_lsh,
+                         int32_t* keep_idx,
+                         float* dbg_s_exact, uint16_t* dbg_sig_k, uint16_t* dbg_sig_q, int32_t* dbg_count,
+                         void* hip_stream);
+
+/* Step a5: copy the kept rows to the end of the append-only cache (Sec. 1, first contribution;
+ * Sec. 3 first paragraph).
+ *
+ *   k_blk, v_blk DEVICE [H_kv, s_t, d]
+ *   keep_idx     DEVICE [H_kv, b_t] int32 as written by laserkv_select_block (same stream: no sync needed)
+ *   k_cache, v_cache DEVICE [H_kv, cache_cap, d], rows contiguous, head stride cache_stride_head
+ *   cache_pos    DEVICE [H_kv, cache_cap] int64 absolute token positions, head stride pos_stride_head
+ *   cache_len    rows already present per head (host-known: every block adds exactly b_t rows)
+ * Rows [cache_len, cache_len + b_t) of every head are written; nothing else is touched.
+ * Errors: LKV_ECAP when cache_len + b_t > cache_cap; LKV_EINVAL for bad arguments. */
+int laserkv_append(laserkv_ctx* ctx,
+                   const void* k_blk, int64_t k_stride_head, int64_t k_stride_tok,
+                   const void* v_blk, int64_t v_stride_head, int64_t v_stride_tok,
+                   const int32_t* keep_idx, int32_t b_t, int32_t s_t, int64_t block_pos0,
+                   void* k_cache, void* v_cache, int64_t cache_stride_head,
+                   int64_t* cache_pos, int64_t pos_stride_head,
+                   int64_t cache_len, int64_t cache_cap,
+                   void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LASERKV_H */

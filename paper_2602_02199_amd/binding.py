@@ -1,0 +1,164 @@
+"""Thin ctypes binding of liblaserkv.so: argument marshalling only.
+
+Every step of the path runs in the library's HIP kernels.  There is no CPU
+fallback: loading fails loudly when the library has not been built.
+PyTorch is used by callers for device memory and streams; this module only
+reads `data_ptr()`, strides and the current stream handle.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "liblaserkv.so")
+
+LKV_F32, LKV_BF16 = 0, 1
+LKV_OK, LKV_EINVAL, LKV_ECAP, LKV_ENOMEM, LKV_EHIP = 0, -1, -2, -3, -4
+
+EXPORTS = (
+    "laserkv_create", "laserkv_destroy", "laserkv_last_error", "laserkv_budget",
+    "laserkv_partition", "laserkv_select_block", "laserkv_append",
+)
+
+
+class LaserKVError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"laserkv error {code}: {msg}")
+        self.code = code
+
+
+class Config(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in (
+        "n_q_heads", "n_kv_heads", "head_dim", "dtype", "lsh_tables", "lsh_bits",
+        "max_block", "max_window", "max_ctx_keys")]
+
+
+_lib = None
+
+
+def load():
+    """Load the built library (never builds, never falls back)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(
+            f"{LIB_PATH} is missing: build it first with `python -m paper_2602_02199_amd.build` "
+            "(there is no CPU fallback)")
+    lib = C.CDLL(LIB_PATH)
+    vp, i32, i64 = C.c_void_p, C.c_int32, C.c_int64
+    lib.laserkv_create.argtypes = [C.POINTER(Config), C.POINTER(vp)]
+    lib.laserkv_create.restype = C.c_int
+    lib.laserkv_destroy.argtypes = [vp]
+    lib.laserkv_destroy.restype = None
+    lib.laserkv_last_error.argtypes = [vp]
+    lib.laserkv_last_error.restype = C.c_char_p
+    lib.laserkv_budget.argtypes = [i64, i64, i64, i64]
+    lib.laserkv_budget.restype = i64
+    lib.laserkv_partition.argtypes = [i32, i32, C.c_double, i32] + [C.POINTER(i32)] * 4
+    lib.laserkv_partition.restype = C.c_int
+    lib.laserkv_select_block.argtypes = [
+        vp, vp, i64, i64, vp, i64, i64, vp, i64, i64, vp,
+        i32, i32, i32, i64, i64, i32, i32, i32, i32, i32,
+        vp, vp, vp, vp, vp, vp]
+    lib.laserkv_select_block.restype = C.c_int
+    lib.laserkv_append.argtypes = [
+        vp, vp, i64, i64, vp, i64, i64, vp, i32, i32, i64,
+        vp, vp, i64, vp, i64, i64, i64, vp]
+    lib.laserkv_append.restype = C.c_int
+    _lib = lib
+    return lib
+
+
+def laserkv_budget(s_block: int, l_ctx: int, r_num: int = 1, r_den: int = 4) -> int:
+    b = load().laserkv_budget(s_block, l_ctx, r_num, r_den)
+    if b < 0:
+        raise LaserKVError(LKV_EINVAL, "budget: bad arguments")
+    return int(b)
+
+
+def laserkv_partition(B: int, n: int, alpha: float, s_t: int):
+    lib = load()
+    out = [C.c_int32() for _ in range(4)]
+    rc = lib.laserkv_partition(B, n, alpha, s_t, *[C.byref(o) for o in out])
+    if rc != LKV_OK:
+        raise LaserKVError(rc, lib.laserkv_last_error(None).decode())
+    return tuple(int(o.value) for o in out)
+
+
+def _ptr(t):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _strides3(t, d):
+    assert t.dim() == 3 and t.stride(2) == 1 and t.shape[2] == d, "expected [heads, rows, d] with d contiguous"
+    return t.stride(0), t.stride(1)
+
+
+class LaserKV:
+    """One library context (owns the device workspace).  Methods mirror the C entry points."""
+
+    def __init__(self, n_q_heads, n_kv_heads, head_dim, dtype, lsh_tables, lsh_bits,
+                 max_block, max_window, max_ctx_keys):
+        import torch
+        self._lib = load()
+        self._torch = torch
+        if not torch.cuda.is_available():
+            raise RuntimeError("laserkv needs a GPU: there is no CPU path")
+        self.cfg = Config(n_q_heads, n_kv_heads, head_dim,
+                          {"f32": LKV_F32, "bf16": LKV_BF16}[dtype] if isinstance(dtype, str) else dtype,
+                          lsh_tables, lsh_bits, max_block, max_window, max_ctx_keys)
+        self._ctx = C.c_void_p()
+        rc = self._lib.laserkv_create(C.byref(self.cfg), C.byref(self._ctx))
+        if rc != LKV_OK:
+            raise LaserKVError(rc, self._lib.laserkv_last_error(None).decode())
+
+    def close(self):
+        if getattr(self, "_ctx", None) is not None and self._ctx:
+            self._lib.laserkv_destroy(self._ctx)
+            self._ctx = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def _check(self, rc):
+        if rc != LKV_OK:
+            raise LaserKVError(rc, self._lib.laserkv_last_error(self._ctx).decode())
+
+    def _stream(self, stream):
+        if stream is None:
+            stream = self._torch.cuda.current_stream().cuda_stream
+        return C.c_void_p(stream)
+
+    def laserkv_select_block(self, q_win, k_blk, k_ctx, hyperplanes, *, block_pos0, q_pos0=None, causal=True,
+                             n_anchor, n_local, k_exact, k_lsh, keep_idx,
+                             dbg_s_exact=None, dbg_sig_k=None, dbg_sig_q=None, dbg_count=None, stream=None):
+        d = self.cfg.head_dim
+        s_t, w = k_blk.shape[1], q_win.shape[1]
+        t_ctx = 0 if k_ctx is None else k_ctx.shape[1]
+        if q_pos0 is None:
+            q_pos0 = block_pos0 + s_t - w
+        qs, ks = _strides3(q_win, d), _strides3(k_blk, d)
+        cs = _strides3(k_ctx, d) if k_ctx is not None else (0, 0)
+        assert hyperplanes.is_contiguous()
+        rc = self._lib.laserkv_select_block(
+            self._ctx, _ptr(q_win), qs[0], qs[1], _ptr(k_blk), ks[0], ks[1], _ptr(k_ctx), cs[0], cs[1],
+            _ptr(hyperplanes), s_t, w, t_ctx, block_pos0, q_pos0, 1 if causal else 0,
+            n_anchor, n_local, k_exact, k_lsh, _ptr(keep_idx),
+            _ptr(dbg_s_exact), _ptr(dbg_sig_k), _ptr(dbg_sig_q), _ptr(dbg_count), self._stream(stream))
+        self._check(rc)
+
+    def laserkv_append(self, k_blk, v_blk, keep_idx, *, b_t, block_pos0, k_cache, v_cache, cache_pos,
+                       cache_len, stream=None):
+        d = self.cfg.head_dim
+        ks, vs = _strides3(k_blk, d), _strides3(v_blk, d)
+        assert k_cache.stride(2) == 1 and k_cache.stride(1) == d and v_cache.stride() == k_cache.stride()
+        rc = self._lib.laserkv_append(
+            self._ctx, _ptr(k_blk), ks[0], ks[1], _ptr(v_blk), vs[0], vs[1], _ptr(keep_idx), b_t, k_blk.shape[1],
+            block_pos0, _ptr(k_cache), _ptr(v_cache), k_cache.stride(0), _ptr(cache_pos), cache_pos.stride(0),
+            cache_len, k_cache.shape[1], self._stream(stream))
+        self._check(rc)

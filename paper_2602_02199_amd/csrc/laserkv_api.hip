@@ -1,0 +1,350 @@
+// C-ABI of the LASER-KV block-selection library: argument checks, workspace, launch sequence.
+#include "../../include/laserkv.h"
+#include "laserkv_kernels.h"
+
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+
+namespace {
+
+constexpr int kMaxRanges = 64;   // key ranges per (head, query-row group) in the score sweeps
+constexpr int kMaxBlock = 16384;
+constexpr int kMaxRows = 1024;   // G * W
+constexpr int kMaxPlanes = 512;  // L * K
+
+char g_error[512] = "";
+
+}  // namespace
+
+struct laserkv_ctx {
+  laserkv_config cfg;
+  int device;
+  int n_cu;
+  int group;
+  int elem_size;
+  // device workspace
+  float2* part;      // [H_kv, kMaxRanges, m_pad]
+  float* s_part;     // [n_qgroups_max, H_kv, max_block]
+  float* s_exact;    // [H_kv, max_block]
+  int32_t* cnt;      // [H_kv, max_block]
+  uint16_t* sig_k;   // [H_kv, max_block, L]
+  uint16_t* sig_q;   // [H_q, max_window, L]
+  int m_pad;
+  char error[512];
+};
+
+namespace {
+
+int fail(laserkv_ctx* ctx, int code, const char* fmt, ...) {
+  char* dst = ctx ? ctx->error : g_error;
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(dst, 512, fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+int fail_hip(laserkv_ctx* ctx, hipError_t e, const char* what) {
+  return fail(ctx, LKV_EHIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+int env_int(const char* name, int dflt) {
+  const char* v = getenv(name);
+  if (!v || !*v) return dflt;
+  return atoi(v);
+}
+
+int bits_for(int64_t v) {
+  int b = 1;
+  while ((int64_t(1) << b) <= v) ++b;
+  return b;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* laserkv_last_error(const laserkv_ctx* ctx) { return ctx ? ctx->error : g_error; }
+
+int64_t laserkv_budget(int64_t s_block, int64_t l_ctx, int64_t r_num, int64_t r_den) {
+  if (s_block <= 0 || l_ctx <= 0 || r_num < 0 || r_den <= 0) return -1;
+  const __int128 num = (__int128)2 * r_num * s_block * l_ctx;
+  const __int128 den = (__int128)r_den * (s_block + l_ctx);
+  return (int64_t)(num / den);
+}
+
+int laserkv_partition(int32_t B, int32_t n, double alpha, int32_t s_t,
+                      int32_t* n_anchor, int32_t* n_local, int32_t* k_exact, int32_t* k_lsh) {
+  if (!n_anchor || !n_local || !k_exact || !k_lsh) return fail(nullptr, LKV_EINVAL, "partition: null output");
+  if (n < 2) return fail(nullptr, LKV_EINVAL, "partition: protection divisor n must be >= 2 (got %d)", n);
+  if (!(alpha >= 0.0 && alpha <= 1.0)) return fail(nullptr, LKV_EINVAL, "partition: alpha must lie in [0, 1]");
+  if (B < 0 || s_t < 1) return fail(nullptr, LKV_EINVAL, "partition: need B >= 0 and s_t >= 1");
+  const int32_t b_t = B < s_t ? B : s_t;
+  const int32_t a = b_t / n;
+  const int32_t b_long = b_t - 2 * a;
+  const int32_t ke = (int32_t)std::floor(alpha * (double)b_long);
+  *n_anchor = a;
+  *n_local = a;
+  *k_exact = ke;
+  *k_lsh = b_long - ke;
+  return LKV_OK;
+}
+
+int laserkv_create(const laserkv_config* cfg, laserkv_ctx** out) {
+  if (!cfg || !out) return fail(nullptr, LKV_EINVAL, "create: null argument");
+  const laserkv_config& c = *cfg;
+  if (c.n_kv_heads < 1 || c.n_q_heads < c.n_kv_heads || c.n_q_heads % c.n_kv_heads)
+    return fail(nullptr, LKV_EINVAL, "create: n_kv_heads must divide n_q_heads");
+  if (c.head_dim != 64 && c.head_dim != 128) return fail(nullptr, LKV_EINVAL, "create: head_dim must be 64 or 128");
+  if (c.dtype != LKV_F32 && c.dtype != LKV_BF16) return fail(nullptr, LKV_EINVAL, "create: unknown dtype");
+  if (c.lsh_tables < 1 || c.lsh_bits < 1 || c.lsh_bits > 16 || c.lsh_tables * c.lsh_bits > kMaxPlanes)
+    return fail(nullptr, LKV_EINVAL, "create: need 1 <= K <= 16 and L*K <= %d", kMaxPlanes);
+  if (c.max_block < 1 || c.max_block > kMaxBlock) return fail(nullptr, LKV_EINVAL, "create: max_block must be 1..%d", kMaxBlock);
+  const int group = c.n_q_heads / c.n_kv_heads;
+  if (c.max_window < 1 || (int64_t)group * c.max_window > kMaxRows)
+    return fail(nullptr, LKV_EINVAL, "create: G * max_window must be 1..%d", kMaxRows);
+  if (c.max_ctx_keys < 0) return fail(nullptr, LKV_EINVAL, "create: max_ctx_keys < 0");
+
+  laserkv_ctx* ctx = new (std::nothrow) laserkv_ctx();
+  if (!ctx) return fail(nullptr, LKV_ENOMEM, "create: host allocation failed");
+  memset(ctx, 0, sizeof(*ctx));
+  ctx->cfg = c;
+  ctx->group = group;
+  ctx->elem_size = c.dtype == LKV_BF16 ? 2 : 4;
+  hipError_t e = hipGetDevice(&ctx->device);
+  hipDeviceProp_t prop;
+  if (e == hipSuccess) e = hipGetDeviceProperties(&prop, ctx->device);
+  if (e != hipSuccess) {
+    delete ctx;
+    return fail_hip(nullptr, e, "create: device query");
+  }
+  ctx->n_cu = prop.multiProcessorCount;
+  e = lkv::init_kernel_attributes();
+  if (e != hipSuccess) {
+    delete ctx;
+    return fail_hip(nullptr, e, "create: kernel attribute");
+  }
+  const int m_rows = group * c.max_window;
+  ctx->m_pad = (m_rows + 255) / 256 * 256;
+  const int n_qg_max = (m_rows + 127) / 128;
+  const size_t hk = c.n_kv_heads, sb = c.max_block;
+  struct { void** p; size_t bytes; } allocs[] = {
+      {(void**)&ctx->part, hk * kMaxRanges * ctx->m_pad * sizeof(float2)},
+      {(void**)&ctx->s_part, (size_t)n_qg_max * hk * sb * sizeof(float)},
+      {(void**)&ctx->s_exact, hk * sb * sizeof(float)},
+      {(void**)&ctx->cnt, hk * sb * sizeof(int32_t)},
+      {(void**)&ctx->sig_k, hk * sb * c.lsh_tables * sizeof(uint16_t)},
+      {(void**)&ctx->sig_q, (size_t)c.n_q_heads * c.max_window * c.lsh_tables * sizeof(uint16_t)},
+  };
+  for (auto& al : allocs) {
+    e = hipMalloc(al.p, al.bytes);
+    if (e != hipSuccess) {
+      laserkv_destroy(ctx);
+      return fail(nullptr, LKV_ENOMEM, "create: hipMalloc of %zu bytes failed: %s", al.bytes, hipGetErrorString(e));
+    }
+  }
+  *out = ctx;
+  return LKV_OK;
+}
+
+void laserkv_destroy(laserkv_ctx* ctx) {
+  if (!ctx) return;
+  void* ptrs[] = {ctx->part, ctx->s_part, ctx->s_exact, ctx->cnt, ctx->sig_k, ctx->sig_q};
+  for (void* p : ptrs)
+    if (p) (void)hipFree(p);
+  delete ctx;
+}
+
+int laserkv_select_block(laserkv_ctx* ctx,
+                         const void* q_win, int64_t q_stride_head, int64_t q_stride_tok,
+                         const void* k_blk, int64_t k_stride_head, int64_t k_stride_tok,
+                         const void* k_ctx, int64_t c_stride_head, int64_t c_stride_tok,
+                         const void* hyperplanes,
+                         int32_t s_t, int32_t w, int32_t t_ctx,
+                         int64_t block_pos0, int64_t q_pos0, int32_t causal,
+                         int32_t n_anchor, int32_t n_local, int32_t k_exact, int32_t k_lsh,
+                         int32_t* keep_idx,
+                         float* dbg_s_exact, uint16_t* dbg_sig_k, uint16_t* dbg_sig_q, int32_t* dbg_count,
+                         void* hip_stream) {
+  if (!ctx) return fail(nullptr, LKV_EINVAL, "select_block: null context");
+  const laserkv_config& c = ctx->cfg;
+  const int es = ctx->elem_size, d = c.head_dim, G = ctx->group;
+  if (!q_win || !k_blk || !hyperplanes || !keep_idx) return fail(ctx, LKV_EINVAL, "select_block: null tensor");
+  if (s_t < 1 || s_t > c.max_block) return fail(ctx, LKV_EINVAL, "select_block: s_t=%d outside 1..max_block=%d", s_t, c.max_block);
+  if (w < 1 || w > c.max_window) return fail(ctx, LKV_EINVAL, "select_block: w=%d outside 1..max_window=%d", w, c.max_window);
+  if (t_ctx < 0 || t_ctx > c.max_ctx_keys) return fail(ctx, LKV_EINVAL, "select_block: t_ctx=%d outside 0..max_ctx_keys=%d", t_ctx, c.max_ctx_keys);
+  if ((t_ctx > 0) != (k_ctx != nullptr)) return fail(ctx, LKV_EINVAL, "select_block: k_ctx must be given iff t_ctx > 0");
+  if (n_anchor < 0 || n_local < 0 || k_exact < 0 || k_lsh < 0) return fail(ctx, LKV_EINVAL, "select_block: negative budget");
+  if ((int64_t)n_anchor + n_local > s_t) return fail(ctx, LKV_EINVAL, "select_block: protected sets exceed the block");
+  if ((int64_t)k_exact + k_lsh > (int64_t)s_t - n_anchor - n_local)
+    return fail(ctx, LKV_EINVAL, "select_block: recall budget exceeds the candidate set");
+  if (causal && q_pos0 < block_pos0) return fail(ctx, LKV_EINVAL, "select_block: causal window must not start before the block");
+  const int64_t row_elems = d;
+  auto bad_stride = [&](int64_t sh, int64_t st) { return st < row_elems || sh < 0 || ((st * es) & 15) || ((sh * es) & 15); };
+  if (bad_stride(q_stride_head, q_stride_tok) || bad_stride(k_stride_head, k_stride_tok) ||
+      (t_ctx > 0 && bad_stride(c_stride_head, c_stride_tok)))
+    return fail(ctx, LKV_EINVAL, "select_block: strides must cover a row and keep rows 16-byte aligned");
+  if (!aligned16(q_win) || !aligned16(k_blk) || !aligned16(hyperplanes) || (k_ctx && !aligned16(k_ctx)))
+    return fail(ctx, LKV_EINVAL, "select_block: tensors must be 16-byte aligned");
+
+  hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
+  const int m_rows = G * w;
+  const int n_keys = t_ctx + s_t;
+
+  lkv::ScoreParams sp;
+  sp.q = {(const char*)q_win, q_stride_head * es, q_stride_tok * es};
+  sp.kb = {(const char*)k_blk, k_stride_head * es, k_stride_tok * es};
+  sp.kc = {(const char*)k_ctx, c_stride_head * es, c_stride_tok * es};
+  sp.group = G;
+  sp.w = w;
+  sp.m_rows = m_rows;
+  sp.s_t = s_t;
+  sp.t_ctx = t_ctx;
+  sp.n_keys = n_keys;
+  sp.rows_per_group = m_rows > 128 ? 256 : 128;
+  const int n_qg = (m_rows + sp.rows_per_group - 1) / sp.rows_per_group;
+  // key ranges: aim at a few workgroups per compute unit
+  const int wg_target = ctx->n_cu * env_int("LASERKV_SCORE_WG_PER_CU", 2);
+  int nr = wg_target / (c.n_kv_heads * n_qg);
+  if (nr < 1) nr = 1;
+  if (nr > kMaxRanges) nr = kMaxRanges;
+  int nk = ((n_keys + nr - 1) / nr + 31) / 32 * 32;
+  sp.keys_per_range = nk;
+  sp.n_ranges = (n_keys + nk - 1) / nk;
+  sp.causal = causal ? 1 : 0;
+  int64_t lim0 = (int64_t)t_ctx + (q_pos0 - block_pos0);
+  if (lim0 > (1 << 30)) lim0 = 1 << 30;
+  sp.lim0 = (int)lim0;
+  sp.scale2 = (float)(1.4426950408889634 / std::sqrt((double)d));
+  sp.part = ctx->part;
+  sp.m_pad = ctx->m_pad;
+  sp.s_part = ctx->s_part;
+
+  lkv::SigParams gp;
+  gp.kb = sp.kb;
+  gp.q = sp.q;
+  gp.planes = (const char*)hyperplanes;
+  gp.n_kv_heads = c.n_kv_heads;
+  gp.n_q_heads = c.n_q_heads;
+  gp.s_t = s_t;
+  gp.w = w;
+  gp.n_tables = c.lsh_tables;
+  gp.n_bits = c.lsh_bits;
+  gp.n_planes = c.lsh_tables * c.lsh_bits;
+  {
+    const int64_t rows = (int64_t)c.n_kv_heads * s_t + (int64_t)c.n_q_heads * w;
+    int rpw = (int)((rows + wg_target - 1) / wg_target);
+    rpw = (rpw + 31) / 32 * 32;
+    if (rpw < 32) rpw = 32;
+    gp.rows_per_wg = rpw;
+  }
+  gp.sig_k = ctx->sig_k;
+  gp.sig_q = ctx->sig_q;
+  gp.cnt = ctx->cnt;
+
+  lkv::CountParams cp;
+  cp.sig_k = ctx->sig_k;
+  cp.sig_q = ctx->sig_q;
+  cp.cnt = ctx->cnt;
+  cp.group = G;
+  cp.w = w;
+  cp.s_t = s_t;
+  cp.n_tables = c.lsh_tables;
+  cp.n_bits = c.lsh_bits;
+  {
+    // tables per group: keep the histogram within 64 KiB of LDS (one table at K = 16 takes 128 KiB)
+    int tg = (64 * 1024) / ((1 << c.lsh_bits) * 2);
+    if (tg < 1) tg = 1;
+    if (tg > c.lsh_tables) tg = c.lsh_tables;
+    cp.tables_per_group = tg;
+    const int n_tg = (c.lsh_tables + tg - 1) / tg;
+    int n_kr = wg_target / (c.n_kv_heads * n_tg);
+    if (n_kr < 1) n_kr = 1;
+    int kpr = ((s_t + n_kr - 1) / n_kr + 255) / 256 * 256;
+    cp.keys_per_range = kpr;
+  }
+
+  lkv::SelectParams lp;
+  lp.s_part = ctx->s_part;
+  lp.n_qgroups = n_qg;
+  lp.n_kv_heads = c.n_kv_heads;
+  lp.inv_m = 1.0f / (float)m_rows;
+  lp.cnt = ctx->cnt;
+  lp.s_t = s_t;
+  lp.n_anchor = n_anchor;
+  lp.n_local = n_local;
+  lp.k_exact = k_exact;
+  lp.k_lsh = k_lsh;
+  lp.cnt_bits = bits_for((int64_t)m_rows * c.lsh_tables);
+  lp.s_exact = ctx->s_exact;
+  lp.keep = keep_idx;
+
+  hipError_t e;
+  if ((e = lkv::launch_sig(c.dtype, d, gp, st)) != hipSuccess) return fail_hip(ctx, e, "select_block: signature kernel");
+  if ((e = lkv::launch_stats(c.dtype, d, sp, n_qg, c.n_kv_heads, st)) != hipSuccess) return fail_hip(ctx, e, "select_block: score sweep 1");
+  if ((e = lkv::launch_score(c.dtype, d, sp, n_qg, c.n_kv_heads, st)) != hipSuccess) return fail_hip(ctx, e, "select_block: score sweep 2");
+  if ((e = lkv::launch_count(cp, c.n_kv_heads, st)) != hipSuccess) return fail_hip(ctx, e, "select_block: count kernel");
+  if ((e = lkv::launch_select(lp, st)) != hipSuccess) return fail_hip(ctx, e, "select_block: select kernel");
+
+  const size_t hk = c.n_kv_heads;
+  if (dbg_s_exact && (e = hipMemcpyAsync(dbg_s_exact, ctx->s_exact, hk * s_t * sizeof(float), hipMemcpyDeviceToDevice, st)) != hipSuccess)
+    return fail_hip(ctx, e, "select_block: copy of S_exact");
+  if (dbg_sig_k && (e = hipMemcpyAsync(dbg_sig_k, ctx->sig_k, hk * s_t * c.lsh_tables * sizeof(uint16_t), hipMemcpyDeviceToDevice, st)) != hipSuccess)
+    return fail_hip(ctx, e, "select_block: copy of key signatures");
+  if (dbg_sig_q && (e = hipMemcpyAsync(dbg_sig_q, ctx->sig_q, (size_t)c.n_q_heads * w * c.lsh_tables * sizeof(uint16_t), hipMemcpyDeviceToDevice, st)) != hipSuccess)
+    return fail_hip(ctx, e, "select_block: copy of query signatures");
+  if (dbg_count && (e = hipMemcpyAsync(dbg_count, ctx->cnt, hk * s_t * sizeof(int32_t), hipMemcpyDeviceToDevice, st)) != hipSuccess)
+    return fail_hip(ctx, e, "select_block: copy of counts");
+  return LKV_OK;
+}
+
+int laserkv_append(laserkv_ctx* ctx,
+                   const void* k_blk, int64_t k_stride_head, int64_t k_stride_tok,
+                   const void* v_blk, int64_t v_stride_head, int64_t v_stride_tok,
+                   const int32_t* keep_idx, int32_t b_t, int32_t s_t, int64_t block_pos0,
+                   void* k_cache, void* v_cache, int64_t cache_stride_head,
+                   int64_t* cache_pos, int64_t pos_stride_head,
+                   int64_t cache_len, int64_t cache_cap,
+                   void* hip_stream) {
+  if (!ctx) return fail(nullptr, LKV_EINVAL, "append: null context");
+  const laserkv_config& c = ctx->cfg;
+  const int es = ctx->elem_size, d = c.head_dim;
+  if (!k_blk || !v_blk || !keep_idx || !k_cache || !v_cache || !cache_pos) return fail(ctx, LKV_EINVAL, "append: null tensor");
+  if (s_t < 1 || b_t < 0 || b_t > s_t) return fail(ctx, LKV_EINVAL, "append: need 0 <= b_t <= s_t");
+  if (cache_len < 0 || cache_cap < 0) return fail(ctx, LKV_EINVAL, "append: negative cache length or capacity");
+  if (cache_len + b_t > cache_cap) return fail(ctx, LKV_ECAP, "append: %lld + %d rows exceed the capacity %lld", (long long)cache_len, b_t, (long long)cache_cap);
+  auto bad_stride = [&](int64_t sh, int64_t st) { return st < d || sh < 0 || ((st * es) & 15) || ((sh * es) & 15); };
+  if (bad_stride(k_stride_head, k_stride_tok) || bad_stride(v_stride_head, v_stride_tok))
+    return fail(ctx, LKV_EINVAL, "append: strides must cover a row and keep rows 16-byte aligned");
+  if (cache_stride_head < cache_cap * d || ((cache_stride_head * es) & 15)) return fail(ctx, LKV_EINVAL, "append: cache head stride too small or misaligned");
+  if (pos_stride_head < cache_cap) return fail(ctx, LKV_EINVAL, "append: position head stride below the capacity");
+  if (!aligned16(k_blk) || !aligned16(v_blk) || !aligned16(k_cache) || !aligned16(v_cache))
+    return fail(ctx, LKV_EINVAL, "append: tensors must be 16-byte aligned");
+  lkv::AppendParams ap;
+  ap.kb = {(const char*)k_blk, k_stride_head * es, k_stride_tok * es};
+  ap.vb = {(const char*)v_blk, v_stride_head * es, v_stride_tok * es};
+  ap.keep = keep_idx;
+  ap.b_t = b_t;
+  ap.s_t = s_t;
+  ap.row_bytes = d * es;
+  ap.k_cache = (char*)k_cache;
+  ap.v_cache = (char*)v_cache;
+  ap.cache_stride_head = cache_stride_head * es;
+  ap.cache_pos = cache_pos;
+  ap.pos_stride_head = pos_stride_head;
+  ap.cache_len = cache_len;
+  ap.block_pos0 = block_pos0;
+  hipError_t e = lkv::launch_append(ap, c.n_kv_heads, reinterpret_cast<hipStream_t>(hip_stream));
+  if (e != hipSuccess) return fail_hip(ctx, e, "append: gather kernel");
+  return LKV_OK;
+}
+
+}  // extern "C"

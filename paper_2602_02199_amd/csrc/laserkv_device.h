@@ -1,0 +1,69 @@
+// Device-side helpers shared by the LASER-KV kernels (gfx950 / CDNA4, wave64).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace lkv {
+
+constexpr int DT_F32 = 0;
+constexpr int DT_BF16 = 1;
+
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+
+constexpr float NEG_BIG = -1.0e30f;  // finite stand-in for -inf (keeps max/sub free of NaN)
+
+// One 32x32 MFMA tile step over a 16-byte operand chunk per lane.
+//
+// Operand convention used by every kernel here: lane l = (rl, kg) with rl = l & 31 the
+// row (of A) / column (of B) inside the 32-wide tile and kg = l >> 5 the half of the
+// contraction slice the lane feeds.  For chunk-pair index i a lane loads the 16-byte
+// chunk 2*i + kg of its row.  A and B use the same assignment, so whichever k indices a
+// lane's chunk holds, every k is multiplied with its partner exactly once.
+//
+// Accumulator layout of the 32x32 MFMAs: register r of lane l holds
+//   C[row = 8*(r/4) + 4*(l>>5) + (r&3)][col = l & 31].
+template <int DT>
+struct Mma;
+
+template <>
+struct Mma<DT_BF16> {
+  static __device__ __forceinline__ void run(f32x16& c, const uint4& a, const uint4& b) {
+    c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a),
+                                                __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+  }
+};
+
+template <>
+struct Mma<DT_F32> {
+  static __device__ __forceinline__ void run(f32x16& c, const uint4& a, const uint4& b) {
+    c = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.x), __uint_as_float(b.x), c, 0, 0, 0);
+    c = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.y), __uint_as_float(b.y), c, 0, 0, 0);
+    c = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.z), __uint_as_float(b.z), c, 0, 0, 0);
+    c = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.w), __uint_as_float(b.w), c, 0, 0, 0);
+  }
+};
+
+__device__ __forceinline__ int acc_row(int r, int kg) { return 8 * (r >> 2) + 4 * kg + (r & 3); }
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+__device__ __forceinline__ float fast_log2(float x) { return __builtin_amdgcn_logf(x); }
+
+__device__ __forceinline__ uint4 ld16(const void* p) { return *reinterpret_cast<const uint4*>(p); }
+
+// (m, s) pairs describe sum_i 2^(x_i) as s * 2^m.
+__device__ __forceinline__ void lse_merge(float& m, float& s, float m2, float s2) {
+  float mn = fmaxf(m, m2);
+  s = s * fast_exp2(m - mn) + s2 * fast_exp2(m2 - mn);
+  m = mn;
+}
+
+__device__ __forceinline__ void lse_push(float& m, float& s, float x) {
+  float dlt = x - m;
+  float e = fast_exp2(-fabsf(dlt));
+  s = dlt > 0.0f ? fmaf(s, e, 1.0f) : s + e;
+  m = fmaxf(m, x);
+}
+
+}  // namespace lkv

@@ -1,0 +1,96 @@
+// Kernel parameter blocks and launch entry points (host side sees only this header).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace lkv {
+
+// Rows of a [heads, rows, d] tensor with element strides; d contiguous.
+struct RowSrc {
+  const char* base;
+  int64_t stride_head;  // bytes
+  int64_t stride_row;   // bytes
+};
+
+struct ScoreParams {
+  RowSrc q;        // [H_q, W, d]
+  RowSrc kb;       // [H_kv, S, d]
+  RowSrc kc;       // [H_kv, T, d] (base may be null when T == 0)
+  int group;       // G
+  int w;           // W
+  int m_rows;      // M = G * W
+  int s_t;         // S
+  int t_ctx;       // T
+  int n_keys;      // T + S
+  int keys_per_range;   // NK (multiple of 32)
+  int n_ranges;         // NR
+  int rows_per_group;   // MQ = 128 * MT
+  int causal;
+  int lim0;        // key index kidx is visible to window row j iff kidx <= lim0 + j (when causal)
+  float scale2;    // log2(e) / sqrt(d)
+  float2* part;    // [H_kv, NR, m_pad] partial (max, sum) in the exp2 domain
+  int m_pad;       // row pitch of part
+  float* s_part;   // [n_qgroups, H_kv, S] partial pooled probabilities
+};
+
+struct SigParams {
+  RowSrc kb;       // keys  [H_kv, S, d]
+  RowSrc q;        // queries [H_q, W, d]
+  const char* planes;  // [L*K, d] contiguous
+  int n_kv_heads, n_q_heads;
+  int s_t, w;
+  int n_tables, n_bits, n_planes;  // L, K, L*K
+  int rows_per_wg;     // multiple of 32
+  uint16_t* sig_k;     // [H_kv, S, L]
+  uint16_t* sig_q;     // [H_q, W, L]
+  int32_t* cnt;        // [H_kv, S]: zeroed here for the count kernel's atomics
+};
+
+struct CountParams {
+  const uint16_t* sig_k;  // [H_kv, S, L]
+  const uint16_t* sig_q;  // [H_q, W, L]
+  int32_t* cnt;           // [H_kv, S]
+  int group, w, s_t;
+  int n_tables, n_bits;
+  int tables_per_group;   // TG
+  int keys_per_range;
+};
+
+struct SelectParams {
+  const float* s_part;  // [n_qgroups, H_kv, S]
+  int n_qgroups;
+  int n_kv_heads;
+  float inv_m;          // 1 / (G * W)
+  const int32_t* cnt;   // [H_kv, S]
+  int s_t;
+  int n_anchor, n_local, k_exact, k_lsh;
+  int cnt_bits;         // bits needed to hold G * W * L
+  float* s_exact;       // [H_kv, S] final scores (always written)
+  int32_t* keep;        // [H_kv, B_t]
+};
+
+struct AppendParams {
+  RowSrc kb, vb;        // [H_kv, S, d]
+  const int32_t* keep;  // [H_kv, B_t]
+  int b_t;
+  int s_t;              // rows in the block: indices are clamped into it
+  int row_bytes;        // d * elem size
+  char* k_cache;
+  char* v_cache;
+  int64_t cache_stride_head;  // bytes
+  int64_t* cache_pos;
+  int64_t pos_stride_head;    // elements
+  int64_t cache_len;
+  int64_t block_pos0;
+};
+
+hipError_t launch_stats(int dtype, int head_dim, const ScoreParams& p, int n_qgroups, int n_kv_heads, hipStream_t st);
+hipError_t launch_score(int dtype, int head_dim, const ScoreParams& p, int n_qgroups, int n_kv_heads, hipStream_t st);
+hipError_t launch_sig(int dtype, int head_dim, const SigParams& p, hipStream_t st);
+hipError_t launch_count(const CountParams& p, int n_kv_heads, hipStream_t st);
+hipError_t launch_select(const SelectParams& p, hipStream_t st);
+hipError_t launch_append(const AppendParams& p, int n_kv_heads, hipStream_t st);
+hipError_t init_kernel_attributes();
+
+}  // namespace lkv

@@ -1,0 +1,523 @@
+// HIP kernels of the LASER-KV block-selection path for gfx950 (wave64, MFMA, LDS).
+//
+//   score_kernel<PASS2=false>  Alg. 1 step 3, first sweep: per window row, partial (max, sum) of
+//                              2^(logit) over each key range                      [MFMA]
+//   score_kernel<PASS2=true>   second sweep: pooled softmax probability per key    [MFMA]
+//   sig_kernel                 SimHash codes of keys and window queries            [MFMA + ballot-free bit packing]
+//   count_kernel               Alg. 1 step 6: collision counts via per-table LDS histograms of the query codes
+//   select_kernel              Alg. 1 steps 4-8 + Sec. 3.1 partition: two rank selections and compaction
+//   append_kernel              gather of the kept K/V rows onto the cache tail
+#include "laserkv_device.h"
+#include "laserkv_kernels.h"
+
+#include <limits.h>
+
+namespace lkv {
+
+// ---------------------------------------------------------------------------------------------
+// Exact score, both sweeps.  Workgroup = (key range, query-row group, KV head); 4 waves, wave w
+// keeps the A fragments of MT 32-row query tiles in registers and streams the range's keys
+// through LDS in stages of 64.
+// ---------------------------------------------------------------------------------------------
+template <int DT, int D, int MT, bool PASS2>
+__global__ __launch_bounds__(256) void score_kernel(ScoreParams p) {
+  constexpr int ES = DT == DT_BF16 ? 2 : 4;
+  constexpr int CH = D * ES / 16;  // 16-byte chunks per row
+  constexpr int NCH = CH / 2;      // chunk pairs = MFMA steps (bf16) per tile
+  constexpr int KT = 64;           // keys per LDS stage
+  constexpr int MQ = 128 * MT;     // query rows per workgroup
+  constexpr int LDT = KT * CH / 256;
+
+  __shared__ uint4 sK[KT * CH];
+  __shared__ float sLse[MQ];
+  __shared__ int sLim[MQ];
+  __shared__ float sCol[4][KT];
+
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, rl = lane & 31, kg = lane >> 5;
+  const int kr = blockIdx.x, qg = blockIdx.y, h = blockIdx.z;
+  const int k0 = kr * p.keys_per_range;
+  const int k1 = min(k0 + p.keys_per_range, p.n_keys);
+
+  for (int t = tid; t < MQ; t += 256) {
+    const int m = qg * MQ + t;
+    const int j = (m < p.m_rows) ? m % p.w : 0;
+    sLim[t] = p.causal ? p.lim0 + j : INT_MAX;
+    if (PASS2) {
+      float lse = 1.0e30f;  // rows past M are padding: probability 0
+      if (m < p.m_rows) {
+        const float2* pp = p.part + (size_t)h * p.n_ranges * p.m_pad + m;
+        float mm = NEG_BIG, ss = 0.0f;
+        for (int r = 0; r < p.n_ranges; ++r) {
+          const float2 v = pp[(size_t)r * p.m_pad];
+          lse_merge(mm, ss, v.x, v.y);
+        }
+        lse = mm + fast_log2(ss);
+      }
+      sLse[t] = lse;
+    }
+  }
+
+  uint4 a[MT][NCH];
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt) {
+    const int m = qg * MQ + (wave * MT + mt) * 32 + rl;
+    const int mc = min(m, p.m_rows - 1);
+    const int g = mc / p.w, j = mc - g * p.w;
+    const char* ptr = p.q.base + (int64_t)(h * p.group + g) * p.q.stride_head + (int64_t)j * p.q.stride_row;
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) a[mt][i] = ld16(ptr + (2 * i + kg) * 16);
+  }
+
+  float rm[MT][16], rs[MT][16];  // sweep 1: running (max, sum); sweep 2: rm holds the row lse
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      rm[mt][r] = NEG_BIG;
+      rs[mt][r] = 0.0f;
+    }
+
+  const int n_stage = (k1 - k0 + KT - 1) / KT;
+  uint4 pre[LDT];
+  auto gload = [&](int s) {
+#pragma unroll
+    for (int u = 0; u < LDT; ++u) {
+      const int q = tid + 256 * u;
+      const int row = q / CH, c = q % CH;
+      const int kidx = min(k0 + s * KT + row, p.n_keys - 1);
+      const char* ptr = kidx < p.t_ctx
+                            ? p.kc.base + (int64_t)h * p.kc.stride_head + (int64_t)kidx * p.kc.stride_row
+                            : p.kb.base + (int64_t)h * p.kb.stride_head + (int64_t)(kidx - p.t_ctx) * p.kb.stride_row;
+      pre[u] = ld16(ptr + c * 16);
+    }
+  };
+  gload(0);
+  __syncthreads();  // sLse / sLim visible
+  if (PASS2) {
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) rm[mt][r] = sLse[(wave * MT + mt) * 32 + acc_row(r, kg)];
+  }
+
+  for (int s = 0; s < n_stage; ++s) {
+#pragma unroll
+    for (int u = 0; u < LDT; ++u) {
+      const int q = tid + 256 * u;
+      const int row = q / CH, c = q % CH;
+      sK[row * CH + (c ^ (row & 7))] = pre[u];
+    }
+    __syncthreads();
+    if (s + 1 < n_stage) gload(s + 1);
+
+#pragma unroll
+    for (int nt = 0; nt < KT / 32; ++nt) {
+      const int kbase = k0 + s * KT + nt * 32;
+      if (kbase >= k1) break;
+      f32x16 acc[MT];
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[mt][r] = 0.0f;
+#pragma unroll
+      for (int i = 0; i < NCH; ++i) {
+        const uint4 b = sK[(nt * 32 + rl) * CH + ((2 * i + kg) ^ (rl & 7))];
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) Mma<DT>::run(acc[mt], a[mt][i], b);
+      }
+      const int kidx = kbase + rl;
+      const bool in_range = kidx < k1;
+      const bool need_mask = p.causal && (kbase + 31 > p.lim0);  // wave-uniform
+      float col = 0.0f;
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          bool vis = in_range;
+          if (need_mask) vis = vis && (kidx <= sLim[(wave * MT + mt) * 32 + acc_row(r, kg)]);
+          if (PASS2) {
+            const float e = fast_exp2(acc[mt][r] * p.scale2 - rm[mt][r]);
+            col += vis ? e : 0.0f;
+          } else {
+            const float x = vis ? acc[mt][r] * p.scale2 : NEG_BIG;
+            lse_push(rm[mt][r], rs[mt][r], x);
+          }
+        }
+      }
+      if (PASS2) {
+        col += __shfl_xor(col, 32);
+        if (kg == 0) sCol[wave][nt * 32 + rl] = col;
+      }
+    }
+    __syncthreads();
+    if (PASS2 && tid < KT) {
+      const int kidx = k0 + s * KT + tid;
+      if (kidx < k1 && kidx >= p.t_ctx) {
+        const float v = (sCol[0][tid] + sCol[1][tid]) + (sCol[2][tid] + sCol[3][tid]);
+        p.s_part[((size_t)qg * gridDim.z + h) * p.s_t + (kidx - p.t_ctx)] = v;
+      }
+    }
+  }
+
+  if (!PASS2) {
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        float m = rm[mt][r], s = rs[mt][r];
+#pragma unroll
+        for (int off = 1; off < 32; off <<= 1) {
+          const float m2 = __shfl_xor(m, off);
+          const float s2 = __shfl_xor(s, off);
+          lse_merge(m, s, m2, s2);
+        }
+        const int row = qg * MQ + (wave * MT + mt) * 32 + acc_row(r, kg);
+        if (rl == 0 && row < p.m_rows) p.part[((size_t)h * p.n_ranges + kr) * p.m_pad + row] = make_float2(m, s);
+      }
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// SimHash codes.  Workgroup = (row range, head); heads 0..H_kv-1 are key heads, the rest query
+// heads.  The hyperplanes are the A operand (MTS 32-row tiles per wave in registers), the vectors
+// stream through LDS 32 at a time; sign bits are packed per 32-plane word, then cut into K-bit codes.
+// ---------------------------------------------------------------------------------------------
+template <int DT, int D, int MTS>
+__global__ __launch_bounds__(256) void sig_kernel(SigParams p) {
+  constexpr int ES = DT == DT_BF16 ? 2 : 4;
+  constexpr int CH = D * ES / 16;
+  constexpr int NCH = CH / 2;
+  constexpr int RT = 32;
+  constexpr int LDT = RT * CH / 256;
+
+  __shared__ uint4 sX[RT * CH];
+  __shared__ uint32_t sBits[RT][17];
+
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, rl = lane & 31, kg = lane >> 5;
+  const bool is_key = (int)blockIdx.y < p.n_kv_heads;
+  const int head = is_key ? blockIdx.y : blockIdx.y - p.n_kv_heads;
+  const int n_rows = is_key ? p.s_t : p.w;
+  const RowSrc src = is_key ? p.kb : p.q;
+  const int r0 = blockIdx.x * p.rows_per_wg;
+  if (r0 >= n_rows) return;
+  const int r1 = min(r0 + p.rows_per_wg, n_rows);
+  uint16_t* out = (is_key ? p.sig_k : p.sig_q) + (size_t)head * n_rows * p.n_tables;
+
+  uint4 a[MTS][NCH];
+#pragma unroll
+  for (int mt = 0; mt < MTS; ++mt) {
+    const int pm = min((wave * MTS + mt) * 32 + rl, p.n_planes - 1);
+    const char* ptr = p.planes + (size_t)pm * D * ES;
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) a[mt][i] = ld16(ptr + (2 * i + kg) * 16);
+  }
+  for (int t = tid; t < RT * 17; t += 256) sBits[t / 17][t % 17] = 0u;
+
+  const uint32_t code_mask = (1u << p.n_bits) - 1u;
+  const char* hbase = src.base + (int64_t)head * src.stride_head;
+  for (int rs0 = r0; rs0 < r1; rs0 += RT) {
+#pragma unroll
+    for (int u = 0; u < LDT; ++u) {
+      const int q = tid + 256 * u;
+      const int row = q / CH, c = q % CH;
+      const int gr = min(rs0 + row, n_rows - 1);
+      sX[row * CH + (c ^ (row & 7))] = ld16(hbase + (int64_t)gr * src.stride_row + c * 16);
+    }
+    __syncthreads();
+    f32x16 acc[MTS];
+#pragma unroll
+    for (int mt = 0; mt < MTS; ++mt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[mt][r] = 0.0f;
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) {
+      const uint4 b = sX[rl * CH + ((2 * i + kg) ^ (rl & 7))];
+#pragma unroll
+      for (int mt = 0; mt < MTS; ++mt) Mma<DT>::run(acc[mt], a[mt][i], b);
+    }
+#pragma unroll
+    for (int mt = 0; mt < MTS; ++mt) {
+      uint32_t mask = 0u;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) mask |= (acc[mt][r] >= 0.0f ? 1u : 0u) << acc_row(r, kg);
+      mask |= (uint32_t)__shfl_xor((int)mask, 32);
+      const int word = wave * MTS + mt;
+      if (kg == 0 && word < 16) sBits[rl][word] = mask;
+    }
+    __syncthreads();
+    for (int e = tid; e < RT * p.n_tables; e += 256) {
+      const int row = e / p.n_tables, t = e - row * p.n_tables;
+      const int gr = rs0 + row;
+      if (gr < r1) {
+        const int bitpos = t * p.n_bits;
+        const int w0 = bitpos >> 5, sh = bitpos & 31;
+        const uint64_t two = (uint64_t)sBits[row][w0] | ((uint64_t)sBits[row][w0 + 1] << 32);
+        out[(size_t)gr * p.n_tables + t] = (uint16_t)((uint32_t)(two >> sh) & code_mask);
+      }
+    }
+    if (is_key && tid < RT && rs0 + tid < r1) p.cnt[(size_t)head * p.s_t + rs0 + tid] = 0;
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Collision counts.  Workgroup = (key range, table group, KV head).  The G*W query codes of each
+// table in the group are histogrammed into LDS (two 16-bit bins per word); each key then looks
+// its own code up per table.  Partial sums over table groups meet in integer atomics.
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void count_kernel(CountParams p) {
+  extern __shared__ uint32_t bins[];
+  const int tid = threadIdx.x;
+  const int kr = blockIdx.x, tg = blockIdx.y, h = blockIdx.z;
+  const int t0 = tg * p.tables_per_group;
+  const int tga = min(p.tables_per_group, p.n_tables - t0);
+  const int n_words = (tga << p.n_bits) >> 1;
+  for (int i = tid; i < n_words; i += 256) bins[i] = 0u;
+  __syncthreads();
+  const int nq = p.group * p.w;
+  const uint16_t* sq = p.sig_q + (size_t)h * nq * p.n_tables + t0;
+  for (int e = tid; e < nq * tga; e += 256) {
+    const int qrow = e / tga, tl = e - qrow * tga;
+    const uint32_t idx = ((uint32_t)tl << p.n_bits) | sq[(size_t)qrow * p.n_tables + tl];
+    atomicAdd(&bins[idx >> 1], 1u << ((idx & 1u) * 16));
+  }
+  __syncthreads();
+  const int i0 = kr * p.keys_per_range;
+  const int i1 = min(i0 + p.keys_per_range, p.s_t);
+  for (int i = i0 + tid; i < i1; i += 256) {
+    const uint16_t* sk = p.sig_k + ((size_t)h * p.s_t + i) * p.n_tables + t0;
+    int sum = 0;
+    for (int tl = 0; tl < tga; ++tl) {
+      const uint32_t idx = ((uint32_t)tl << p.n_bits) | sk[tl];
+      sum += (bins[idx >> 1] >> ((idx & 1u) * 16)) & 0xffffu;
+    }
+    atomicAdd(&p.cnt[(size_t)h * p.s_t + i], sum);
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Selection.  One 1024-thread workgroup per KV head; thread t owns the EPT consecutive positions
+// starting at t*EPT.  The k-th largest key is found bit by bit from the top (one block-wide count
+// per bit), ties at the threshold are taken in index order via a prefix count.
+// ---------------------------------------------------------------------------------------------
+template <int EPT>
+__global__ __launch_bounds__(1024) void select_kernel(SelectParams p) {
+  __shared__ int sCnt[2][16];
+  __shared__ int sScan[16];
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int h = blockIdx.x;
+  int round = 0;
+
+  uint32_t key[EPT];
+  int c2[EPT];
+  bool inr[EPT], cand[EPT], sel[EPT];
+#pragma unroll
+  for (int e = 0; e < EPT; ++e) {
+    const int i = tid * EPT + e;
+    inr[e] = i < p.s_t;
+    cand[e] = inr[e] && i >= p.n_anchor && i < p.s_t - p.n_local;
+    sel[e] = false;
+    key[e] = 0u;
+    c2[e] = 0;
+    if (inr[e]) {
+      float s = 0.0f;
+      for (int qg = 0; qg < p.n_qgroups; ++qg) s += p.s_part[((size_t)qg * p.n_kv_heads + h) * p.s_t + i];
+      s *= p.inv_m;
+      p.s_exact[(size_t)h * p.s_t + i] = s;
+      key[e] = __float_as_uint(s);
+      c2[e] = p.cnt[(size_t)h * p.s_t + i];
+    }
+  }
+
+  auto block_count = [&](const bool* pred) -> int {
+    int c = 0;
+#pragma unroll
+    for (int e = 0; e < EPT; ++e) c += __popcll(__ballot(pred[e]));
+    const int buf = round & 1;
+    ++round;
+    if (lane == 0) sCnt[buf][wave] = c;
+    __syncthreads();
+    int tot = 0;
+#pragma unroll
+    for (int w = 0; w < 16; ++w) tot += sCnt[buf][w];
+    return tot;
+  };
+  // exclusive prefix of per-thread counts over the block, in thread (= index) order
+  auto block_excl_scan = [&](int v) -> int {
+    int inc = v;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+      const int o = __shfl_up(inc, off);
+      if (lane >= off) inc += o;
+    }
+    __syncthreads();
+    if (lane == 63) sScan[wave] = inc;
+    __syncthreads();
+    int base = 0;
+    for (int w = 0; w < wave; ++w) base += sScan[w];
+    return base + inc - v;
+  };
+  // marks in sel[] the k active elements ranked first by (val descending, index ascending)
+  auto take_top = [&](const uint32_t* val, const bool* active, int k, int top_bit) {
+    if (k <= 0) return;
+    bool pred[EPT];
+    uint32_t thr = 0u;
+    for (int bit = top_bit; bit >= 0; --bit) {
+      const uint32_t trial = thr | (1u << bit);
+#pragma unroll
+      for (int e = 0; e < EPT; ++e) pred[e] = active[e] && val[e] >= trial;
+      if (block_count(pred) >= k) thr = trial;
+    }
+#pragma unroll
+    for (int e = 0; e < EPT; ++e) pred[e] = active[e] && val[e] > thr;
+    const int need = k - block_count(pred);
+    int n_eq = 0;
+#pragma unroll
+    for (int e = 0; e < EPT; ++e) n_eq += (active[e] && val[e] == thr) ? 1 : 0;
+    int rank = block_excl_scan(n_eq);
+#pragma unroll
+    for (int e = 0; e < EPT; ++e) {
+      if (active[e]) {
+        if (val[e] > thr) {
+          sel[e] = true;
+        } else if (val[e] == thr) {
+          if (rank < need) sel[e] = true;
+          ++rank;
+        }
+      }
+    }
+  };
+
+  take_top(key, cand, p.k_exact, 30);
+  bool act2[EPT];
+  uint32_t v2[EPT];
+#pragma unroll
+  for (int e = 0; e < EPT; ++e) {
+    act2[e] = cand[e] && !sel[e];
+    v2[e] = (uint32_t)c2[e];
+  }
+  take_top(v2, act2, p.k_lsh, p.cnt_bits - 1);
+
+  int n_keep = 0;
+#pragma unroll
+  for (int e = 0; e < EPT; ++e) {
+    sel[e] = inr[e] && (!cand[e] || sel[e]);
+    n_keep += sel[e] ? 1 : 0;
+  }
+  int pos = block_excl_scan(n_keep);
+  const int b_t = p.n_anchor + p.n_local + p.k_exact + p.k_lsh;
+#pragma unroll
+  for (int e = 0; e < EPT; ++e) {
+    if (sel[e]) {
+      if (pos < b_t) p.keep[(size_t)h * b_t + pos] = tid * EPT + e;
+      ++pos;
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Append: every thread moves one 16-byte chunk of one kept K row and the matching V chunk.
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void append_kernel(AppendParams p) {
+  const int h = blockIdx.y;
+  const int cpr = p.row_bytes / 16;
+  const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  const int row = (int)(t / cpr), c = (int)(t % cpr);
+  if (row >= p.b_t) return;
+  const int src = min(max(p.keep[(size_t)h * p.b_t + row], 0), p.s_t - 1);
+  const int64_t dst_off = (int64_t)h * p.cache_stride_head + (p.cache_len + row) * (int64_t)p.row_bytes + c * 16;
+  const uint4 kv = ld16(p.kb.base + (int64_t)h * p.kb.stride_head + (int64_t)src * p.kb.stride_row + c * 16);
+  const uint4 vv = ld16(p.vb.base + (int64_t)h * p.vb.stride_head + (int64_t)src * p.vb.stride_row + c * 16);
+  *reinterpret_cast<uint4*>(p.k_cache + dst_off) = kv;
+  *reinterpret_cast<uint4*>(p.v_cache + dst_off) = vv;
+  if (c == 0) p.cache_pos[(int64_t)h * p.pos_stride_head + p.cache_len + row] = p.block_pos0 + src;
+}
+
+// ---------------------------------------------------------------------------------------------
+// launchers
+// ---------------------------------------------------------------------------------------------
+template <int DT, int D, bool PASS2>
+static hipError_t launch_score_t(const ScoreParams& p, int n_qgroups, int n_kv_heads, hipStream_t st) {
+  dim3 grid(p.n_ranges, n_qgroups, n_kv_heads);
+  if (p.rows_per_group == 256)
+    hipLaunchKernelGGL((score_kernel<DT, D, 2, PASS2>), grid, dim3(256), 0, st, p);
+  else
+    hipLaunchKernelGGL((score_kernel<DT, D, 1, PASS2>), grid, dim3(256), 0, st, p);
+  return hipGetLastError();
+}
+
+template <bool PASS2>
+static hipError_t launch_score_any(int dtype, int head_dim, const ScoreParams& p, int nq, int nh, hipStream_t st) {
+  if (dtype == DT_BF16 && head_dim == 128) return launch_score_t<DT_BF16, 128, PASS2>(p, nq, nh, st);
+  if (dtype == DT_BF16 && head_dim == 64) return launch_score_t<DT_BF16, 64, PASS2>(p, nq, nh, st);
+  if (dtype == DT_F32 && head_dim == 128) return launch_score_t<DT_F32, 128, PASS2>(p, nq, nh, st);
+  if (dtype == DT_F32 && head_dim == 64) return launch_score_t<DT_F32, 64, PASS2>(p, nq, nh, st);
+  return hipErrorInvalidValue;
+}
+
+hipError_t launch_stats(int dtype, int head_dim, const ScoreParams& p, int nq, int nh, hipStream_t st) {
+  return launch_score_any<false>(dtype, head_dim, p, nq, nh, st);
+}
+hipError_t launch_score(int dtype, int head_dim, const ScoreParams& p, int nq, int nh, hipStream_t st) {
+  return launch_score_any<true>(dtype, head_dim, p, nq, nh, st);
+}
+
+template <int DT, int D>
+static hipError_t launch_sig_t(const SigParams& p, hipStream_t st) {
+  const int n_mt = (p.n_planes + 31) / 32;
+  const int mts = (n_mt + 3) / 4;
+  const int max_rows = p.s_t > p.w ? p.s_t : p.w;
+  dim3 grid((max_rows + p.rows_per_wg - 1) / p.rows_per_wg, p.n_kv_heads + p.n_q_heads);
+  switch (mts) {
+    case 1: hipLaunchKernelGGL((sig_kernel<DT, D, 1>), grid, dim3(256), 0, st, p); break;
+    case 2: hipLaunchKernelGGL((sig_kernel<DT, D, 2>), grid, dim3(256), 0, st, p); break;
+    case 3: hipLaunchKernelGGL((sig_kernel<DT, D, 3>), grid, dim3(256), 0, st, p); break;
+    case 4: hipLaunchKernelGGL((sig_kernel<DT, D, 4>), grid, dim3(256), 0, st, p); break;
+    default: return hipErrorInvalidValue;
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_sig(int dtype, int head_dim, const SigParams& p, hipStream_t st) {
+  if (dtype == DT_BF16 && head_dim == 128) return launch_sig_t<DT_BF16, 128>(p, st);
+  if (dtype == DT_BF16 && head_dim == 64) return launch_sig_t<DT_BF16, 64>(p, st);
+  if (dtype == DT_F32 && head_dim == 128) return launch_sig_t<DT_F32, 128>(p, st);
+  if (dtype == DT_F32 && head_dim == 64) return launch_sig_t<DT_F32, 64>(p, st);
+  return hipErrorInvalidValue;
+}
+
+hipError_t init_kernel_attributes() {
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(&count_kernel),
+                             hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024);
+}
+
+hipError_t launch_count(const CountParams& p, int n_kv_heads, hipStream_t st) {
+  const int n_tg = (p.n_tables + p.tables_per_group - 1) / p.tables_per_group;
+  const int n_kr = (p.s_t + p.keys_per_range - 1) / p.keys_per_range;
+  const size_t lds = ((size_t)p.tables_per_group << p.n_bits) * 2;
+  dim3 grid(n_kr, n_tg, n_kv_heads);
+  hipLaunchKernelGGL(count_kernel, grid, dim3(256), lds, st, p);
+  return hipGetLastError();
+}
+
+hipError_t launch_select(const SelectParams& p, hipStream_t st) {
+  const int ept = (p.s_t + 1023) / 1024;
+  dim3 grid(p.n_kv_heads);
+  if (ept <= 1) hipLaunchKernelGGL((select_kernel<1>), grid, dim3(1024), 0, st, p);
+  else if (ept <= 2) hipLaunchKernelGGL((select_kernel<2>), grid, dim3(1024), 0, st, p);
+  else if (ept <= 4) hipLaunchKernelGGL((select_kernel<4>), grid, dim3(1024), 0, st, p);
+  else if (ept <= 8) hipLaunchKernelGGL((select_kernel<8>), grid, dim3(1024), 0, st, p);
+  else if (ept <= 16) hipLaunchKernelGGL((select_kernel<16>), grid, dim3(1024), 0, st, p);
+  else return hipErrorInvalidValue;
+  return hipGetLastError();
+}
+
+hipError_t launch_append(const AppendParams& p, int n_kv_heads, hipStream_t st) {
+  const int64_t n_chunks = (int64_t)p.b_t * (p.row_bytes / 16);
+  if (n_chunks == 0) return hipSuccess;
+  dim3 grid((unsigned)((n_chunks + 255) / 256), n_kv_heads);
+  hipLaunchKernelGGL(append_kernel, grid, dim3(256), 0, st, p);
+  return hipGetLastError();
+}
+
+}  // namespace lkv

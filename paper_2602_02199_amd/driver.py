@@ -1,0 +1,82 @@
+"""Block loop of one layer on the GPU: the sequence of library calls a prefill engine makes.
+
+For every context block (Sec. 3.2) it calls laserkv_select_block and laserkv_append on the
+current stream without any host synchronisation: each block adds exactly B_t rows per head, so
+cache lengths are known on the host.  Look-back keys of block t are the previous block's local
+window, i.e. the last n_local rows already in the cache (passed as a strided view, no copy).
+"""
+from __future__ import annotations
+
+import torch
+
+from . import binding
+
+
+class LayerCompressor:
+    def __init__(self, wl, device="cuda:0", max_blocks=None):
+        self.wl = wl
+        self.device = torch.device(device)
+        self.B = binding.laserkv_budget(wl.s_block, wl.l_ctx, wl.r_num, wl.r_den)
+        self.parts = binding.laserkv_partition(self.B, wl.n_div, wl.alpha, wl.s_block)
+        nb = wl.n_blocks if max_blocks is None else max_blocks
+        self.cap = nb * min(self.B, wl.s_block)
+        self.lib = binding.LaserKV(wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.dtype, wl.lsh_tables, wl.lsh_bits,
+                                   max_block=wl.s_block, max_window=wl.window, max_ctx_keys=self.parts[1])
+        dt = wl.torch_dtype
+        self.k_cache = torch.zeros(wl.n_kv_heads, self.cap, wl.head_dim, dtype=dt, device=self.device)
+        self.v_cache = torch.zeros_like(self.k_cache)
+        self.cache_pos = torch.full((wl.n_kv_heads, self.cap), -1, dtype=torch.int64, device=self.device)
+        self.keep = torch.empty(wl.n_kv_heads, min(self.B, wl.s_block), dtype=torch.int32, device=self.device)
+        self.cache_len = 0
+
+    def reset(self):
+        self.cache_len = 0
+
+    def block_budget(self, s_t):
+        """(n_anchor, n_local, k_exact, k_lsh) of a block with s_t tokens."""
+        if s_t == self.wl.s_block:
+            return self.parts
+        return binding.laserkv_partition(self.B, self.wl.n_div, self.wl.alpha, s_t)
+
+    def step(self, q_win, k_blk, v_blk, planes, block_pos0, prev_local, dbg=None, keep_out=None):
+        """One block: select + append.  Returns (this block's n_local, the keep tensor used).
+
+        keep_out: optional [H_kv, B_t] int32 device tensor to receive the kept indices (the internal
+        buffer is reused from block to block otherwise).  dbg: optional dict of device tensors for the
+        stage outputs (s_exact, sig_k, sig_q, cnt).
+        """
+        s_t = k_blk.shape[1]
+        na, nl, ke, kl = self.block_budget(s_t)
+        b_t = na + nl + ke + kl
+        k_ctx = None
+        if self.cache_len and prev_local:
+            k_ctx = self.k_cache[:, self.cache_len - prev_local:self.cache_len]
+        if keep_out is not None:
+            keep = keep_out
+        elif b_t == self.keep.shape[1]:
+            keep = self.keep
+        else:
+            keep = torch.empty(self.wl.n_kv_heads, b_t, dtype=torch.int32, device=self.device)
+        assert keep.shape == (self.wl.n_kv_heads, b_t) and keep.is_contiguous()
+        dbg = dbg or {}
+        self.lib.laserkv_select_block(q_win, k_blk, k_ctx, planes, block_pos0=block_pos0, causal=True,
+                                      n_anchor=na, n_local=nl, k_exact=ke, k_lsh=kl, keep_idx=keep,
+                                      dbg_s_exact=dbg.get("s_exact"), dbg_sig_k=dbg.get("sig_k"),
+                                      dbg_sig_q=dbg.get("sig_q"), dbg_count=dbg.get("cnt"))
+        self.lib.laserkv_append(k_blk, v_blk, keep, b_t=b_t, block_pos0=block_pos0, k_cache=self.k_cache,
+                                v_cache=self.v_cache, cache_pos=self.cache_pos, cache_len=self.cache_len)
+        self.cache_len += b_t
+        return nl, keep
+
+    def run_layer(self, data, n_blocks=None):
+        """All blocks of one layer, back to back, no host sync.  data: device tensors from synth.make_layer."""
+        wl = self.wl
+        self.reset()
+        nb = data["q_win"].shape[0] if n_blocks is None else n_blocks
+        prev_local = 0
+        l_tot = data["k"].shape[1]
+        for t in range(nb):
+            lo, hi = t * wl.s_block, min((t + 1) * wl.s_block, l_tot)
+            prev_local, _ = self.step(data["q_win"][t], data["k"][:, lo:hi], data["v"][:, lo:hi], data["planes"],
+                                      lo, prev_local)
+        return self.cache_len

@@ -1,0 +1,203 @@
+"""GPU parity: the HIP path through the C-ABI against the CPU oracle on the same seeded inputs."""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import laserkv_oracle as O
+from paper_2602_02199_amd import binding, synth
+from paper_2602_02199_amd.driver import LayerCompressor
+from tests.parity_util import check_block
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+def to_dev(data):
+    return {k: (v.to(DEV) if k != "needles" else v) for k, v in data.items()}
+
+
+def f64(t):
+    return t.detach().cpu().to(torch.float64).numpy()
+
+
+def dbg_buffers(wl, s_t):
+    return dict(
+        s_exact=torch.empty(wl.n_kv_heads, s_t, dtype=torch.float32, device=DEV),
+        sig_k=torch.empty(wl.n_kv_heads, s_t, wl.lsh_tables, dtype=torch.int16, device=DEV),
+        sig_q=torch.empty(wl.n_q_heads, wl.window, wl.lsh_tables, dtype=torch.int16, device=DEV),
+        cnt=torch.empty(wl.n_kv_heads, s_t, dtype=torch.int32, device=DEV),
+    )
+
+
+def gpu_stage(dbg, keep):
+    return dict(
+        s_exact=dbg["s_exact"].cpu().numpy(),
+        sig_k=dbg["sig_k"].cpu().numpy().view(np.uint16),
+        sig_q=dbg["sig_q"].cpu().numpy().view(np.uint16),
+        cnt=dbg["cnt"].cpu().numpy(),
+        keep=keep.cpu().numpy(),
+    )
+
+
+def run_and_check(wl, layer=0, n_blocks=None, check_blocks=None, label=""):
+    """Run the layer's blocks on the GPU in the benchmark's launch configuration; check the listed
+    blocks stage by stage against the oracle, and whole-run invariants on the cache."""
+    B = O.budget(wl.s_block, wl.l_ctx, wl.r_num, wl.r_den)
+    parts_full = O.partition(B, wl.n_div, wl.alpha, wl.s_block)
+    data = synth.make_layer(wl, layer, parts_full[0], n_blocks=n_blocks)
+    nb = data["q_win"].shape[0]
+    check_blocks = list(range(nb)) if check_blocks is None else check_blocks
+    dev = to_dev(data)
+    comp = LayerCompressor(wl, DEV)
+    assert comp.B == B and comp.parts == parts_full
+    l_tot = data["k"].shape[1]
+    prev_local, saved = 0, {}
+    for t in range(nb):
+        lo, hi = t * wl.s_block, min((t + 1) * wl.s_block, l_tot)
+        dbg = dbg_buffers(wl, hi - lo) if t in check_blocks else None
+        keep_out = None
+        if t in check_blocks:
+            b_t = sum(O.partition(B, wl.n_div, wl.alpha, hi - lo))
+            keep_out = torch.empty(wl.n_kv_heads, b_t, dtype=torch.int32, device=DEV)
+        n_ctx = prev_local
+        prev_local, keep = comp.step(dev["q_win"][t], dev["k"][:, lo:hi], dev["v"][:, lo:hi], dev["planes"], lo,
+                                     prev_local, dbg=dbg, keep_out=keep_out)
+        if t in check_blocks:
+            saved[t] = (dbg, keep, n_ctx)
+    torch.cuda.synchronize()
+    k64, planes64 = f64(data["k"]), f64(data["planes"])
+    reports = []
+    for t in check_blocks:
+        dbg, keep, n_ctx = saved[t]
+        lo, hi = t * wl.s_block, min((t + 1) * wl.s_block, l_tot)
+        parts = O.partition(B, wl.n_div, wl.alpha, hi - lo)
+        k_ctx = k64[:, lo - n_ctx:lo] if n_ctx else None      # previous block's local window
+        st = O.select_block(f64(data["q_win"][t]), k64[:, lo:hi], k_ctx, planes64, wl.lsh_tables, wl.lsh_bits,
+                            *parts, block_pos0=lo)
+        rep = check_block(st, gpu_stage(dbg, keep), parts, wl.dtype)
+        reports.append(rep)
+        say(f"[{label or wl.name} L{layer} blk {t}] unsure codes k/q {rep['unsure_k']}/{rep['unsure_q']}, "
+            f"max score err/(s+s_k) {rep['max_rel']:.2e}, tolerated index diffs per head {rep['tolerated']}")
+    # whole-run invariants on the device cache
+    n = comp.cache_len
+    pos = comp.cache_pos[:, :n]
+    assert n == sum(sum(O.partition(B, wl.n_div, wl.alpha, min(wl.s_block, l_tot - t * wl.s_block))) for t in range(nb))
+    assert bool((pos[:, 1:] > pos[:, :-1]).all()), "cache positions not strictly increasing"
+    assert bool((comp.cache_pos[:, n:] == -1).all()), "rows past the cache length were written"
+    gk = torch.gather(dev["k"], 1, pos[:, :, None].expand(-1, -1, wl.head_dim))
+    gv = torch.gather(dev["v"], 1, pos[:, :, None].expand(-1, -1, wl.head_dim))
+    assert torch.equal(gk, comp.k_cache[:, :n]) and torch.equal(gv, comp.v_cache[:, :n]), "cache rows are not verbatim copies"
+    off = 0
+    for t in range(nb):
+        lo = t * wl.s_block
+        b_t = sum(O.partition(B, wl.n_div, wl.alpha, min(wl.s_block, l_tot - lo)))
+        if t in saved:
+            assert torch.equal(pos[:, off:off + b_t], saved[t][1].to(torch.int64) + lo)
+        off += b_t
+    return data, comp, reports
+
+
+def test_tiny_fp32_all_blocks():
+    wl = synth.WORKLOADS["tiny"]
+    data, comp, reps = run_and_check(wl)
+    kept = {(int(p) // wl.s_block, h, int(p) % wl.s_block) for h in range(wl.n_kv_heads)
+            for p in comp.cache_pos[h, :comp.cache_len].cpu().tolist()}
+    for blk, h, p in data["needles"].tolist():
+        assert (blk, h, p) in kept
+
+
+def test_llama16k_bf16_all_blocks():
+    run_and_check(synth.WORKLOADS["llama8b-16k"])
+
+
+@pytest.mark.parametrize("case", [
+    dict(name="ragged-bf16-d64", n_q_heads=6, n_kv_heads=2, head_dim=64, dtype="bf16", l_ctx=2500, s_block=1000,
+         window=24, n_div=5, lsh_tables=5, lsh_bits=7),
+    dict(name="ragged-f32-d128", n_q_heads=3, n_kv_heads=3, head_dim=128, dtype="f32", l_ctx=700, s_block=333,
+         window=17, n_div=3, lsh_tables=3, lsh_bits=11),
+    dict(name="wide-rows-bf16", n_q_heads=16, n_kv_heads=1, head_dim=128, dtype="bf16", l_ctx=1536, s_block=768,
+         window=40, n_div=4, lsh_tables=31, lsh_bits=16),
+    dict(name="one-table-one-bit", n_q_heads=2, n_kv_heads=2, head_dim=64, dtype="f32", l_ctx=130, s_block=65,
+         window=3, n_div=2, lsh_tables=1, lsh_bits=1),
+])
+def test_ragged_shapes(case):
+    base = synth.WORKLOADS["tiny"]
+    wl = synth.shrink(base, index=7, needles_per_block=2, outlier_channels=2, **case)
+    run_and_check(wl, label=case["name"])
+
+
+@pytest.mark.parametrize("alpha", [0.0, 1.0, 0.5])
+def test_alpha_end_points(alpha):
+    wl = synth.shrink(synth.WORKLOADS["tiny"], alpha=alpha, l_ctx=1024)
+    run_and_check(wl, label=f"tiny-alpha{alpha}")
+
+
+def test_llama128k_full_size_sampled_blocks():
+    wl = synth.WORKLOADS["llama8b-128k"]
+    run_and_check(wl, check_blocks=[0, 13, 31])
+
+
+def test_gqa8_128k_full_size_sampled_blocks():
+    wl = synth.WORKLOADS["gqa8-128k"]
+    run_and_check(wl, check_blocks=[0, 15])
+
+
+def test_llama64k_two_layers_sampled_blocks():
+    wl = synth.WORKLOADS["llama8b-64k"]
+    for layer in (0, 31):
+        run_and_check(wl, layer=layer, check_blocks=[0, 31])
+
+
+def test_repeat_runs_are_bit_identical():
+    wl = synth.WORKLOADS["llama8b-16k"]
+    B = O.budget(wl.s_block, wl.l_ctx, wl.r_num, wl.r_den)
+    na = O.partition(B, wl.n_div, wl.alpha, wl.s_block)[0]
+    dev = to_dev(synth.make_layer(wl, 3, na, n_blocks=2))
+    comp = LayerCompressor(wl, DEV, max_blocks=2)
+    ref = None
+    for _ in range(5):
+        comp.run_layer(dev)
+        torch.cuda.synchronize()
+        cur = (comp.cache_pos.clone(), comp.k_cache.clone())
+        if ref is None:
+            ref = cur
+        assert torch.equal(ref[0], cur[0]) and torch.equal(ref[1], cur[1])
+
+
+def test_error_paths_return_codes_and_launch_nothing():
+    wl = synth.WORKLOADS["tiny"]
+    lib = binding.LaserKV(wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.dtype, wl.lsh_tables, wl.lsh_bits,
+                          max_block=512, max_window=32, max_ctx_keys=56)
+    q = torch.zeros(4, 32, 64, device=DEV)
+    k = torch.zeros(2, 512, 64, device=DEV)
+    planes = torch.zeros(64, 64, device=DEV)
+    keep = torch.full((2, 227), -7, dtype=torch.int32, device=DEV)
+    ok = dict(block_pos0=0, n_anchor=56, n_local=56, k_exact=86, k_lsh=29, keep_idx=keep)
+    bad_calls = [
+        dict(ok, k_exact=500),                                   # recall budget > candidates
+        dict(ok, n_anchor=400, n_local=400),                     # protected sets exceed the block
+        dict(ok, q_pos0=-5),                                     # causal window before the block
+    ]
+    for kw in bad_calls:
+        with pytest.raises(binding.LaserKVError) as ei:
+            lib.laserkv_select_block(q, k, None, planes, **kw)
+        assert ei.value.code == binding.LKV_EINVAL
+    with pytest.raises(binding.LaserKVError):                    # block longer than the configured maximum
+        lib.laserkv_select_block(q, torch.zeros(2, 600, 64, device=DEV), None, planes, **ok)
+    with pytest.raises(binding.LaserKVError):                    # look-back keys beyond the configured maximum
+        lib.laserkv_select_block(q, k, torch.zeros(2, 100, 64, device=DEV), planes, **ok)
+    torch.cuda.synchronize()
+    assert bool((keep == -7).all())
+    kc = torch.zeros(2, 300, 64, device=DEV)
+    pos = torch.zeros(2, 300, dtype=torch.int64, device=DEV)
+    with pytest.raises(binding.LaserKVError) as ei:
+        lib.laserkv_append(k, k, keep, b_t=227, block_pos0=0, k_cache=kc, v_cache=kc.clone(), cache_pos=pos, cache_len=100)
+    assert ei.value.code == binding.LKV_ECAP
+    lib.close()
