@@ -1,0 +1,186 @@
+#!/usr/bin/env python3
+"""Benchmark of the LASER-KV prefill-compression hot path on one MI355X.
+
+A step is one pass of the whole path (score + LSH + top-k + gather-append) over one layer of one
+synthetic context: every block of the workload, issued back to back on one stream with no host
+synchronisation, inputs resident in HBM.  Prints ONE JSON line: context tokens per second per layer,
+the roofline position of the dominant kernel (timed live with HIP events around every kernel launch)
+and the CPU oracle's rate on the same box as a reported baseline.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_MFMA_BF16_TFLOPS = 2500.0   # dense bf16 MFMA, MI355X
+PEAK_MFMA_F32_TFLOPS = 157.3
+PEAK_HBM_GBS = 8000.0
+
+
+def algorithmic_work(wl, B):
+    """Per-launch algorithmic work of every kernel: (bound, amount, unit). One launch = one block, all KV heads.
+    flops: 2*d*rows*S per contraction (look-back keys and the query projections are extras, not counted);
+    bytes: what the step must move at least once."""
+    d, s, hk = wl.head_dim, wl.s_block, wl.n_kv_heads
+    es = 2 if wl.dtype == "bf16" else 4
+    m = wl.group * wl.window
+    lk = wl.lsh_tables * wl.lsh_bits
+    score = 2.0 * d * m * hk * s
+    return {
+        "stats": ("mfma", score),                      # the score contraction is priced once per sweep kernel
+        "score": ("mfma", score),
+        "sig": ("mfma", 2.0 * d * lk * hk * s),
+        "count": ("hbm", hk * s * (wl.lsh_tables * 2 + 4) + wl.n_q_heads * wl.window * wl.lsh_tables * 2),
+        "select": ("hbm", hk * s * 8 + hk * B * 4),
+        "append": ("hbm", hk * B * (4 * d * es + 4 + 8)),
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="llama8b-128k")
+    ap.add_argument("--layer", type=int, default=0)
+    ap.add_argument("--mode", choices=["graph", "eager"], default="graph")
+    ap.add_argument("--profile-steps", type=int, default=3)
+    ap.add_argument("--cpu-seconds", type=float, default=12.0, help="lower bound of oracle work for cpu_baseline; 0 skips")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (no collectives, no sharding); --gpus must be 1", file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_2602_02199_amd import synth
+    from paper_2602_02199_amd.driver import LayerCompressor
+
+    wl = synth.WORKLOADS[args.workload]
+    dev = "cuda:0"
+    comp = LayerCompressor(wl, dev)
+    t_gen = time.time()
+    data = synth.make_layer(wl, args.layer, comp.parts[0])
+    ddev = {k: v.to(dev) for k, v in data.items() if k != "needles"}
+    torch.cuda.synchronize()
+    print(f"[bench] workload {wl.name}: inputs generated and resident in {time.time() - t_gen:.1f}s "
+          f"(B={comp.B}, parts={comp.parts})", file=sys.stderr, flush=True)
+
+    plan = comp.plan_layer(ddev)
+    stream = torch.cuda.Stream()
+    graph = None
+    with torch.cuda.stream(stream):
+        for _ in range(args.warmup):
+            comp.run_plan(plan)
+        stream.synchronize()
+        if args.mode == "graph":
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph, stream=stream):
+                comp.run_plan(plan)
+            graph.replay()
+            stream.synchronize()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            if graph is not None:
+                graph.replay()
+            else:
+                comp.run_plan(plan)
+        stream.synchronize()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        ms_per_step = (t1 - t0) * 1e3 / args.steps
+        # per-kernel durations: the same calls with an event pair around every launch
+        comp.lib.laserkv_profile_begin()
+        for _ in range(args.profile_steps):
+            comp.run_plan(plan)
+        prof = comp.lib.laserkv_profile_end()
+    tokens = ddev["k"].shape[1]
+    value = tokens / (ms_per_step * 1e-3)
+
+    work = algorithmic_work(wl, comp.B)
+    kern = {k: dict(avg_us=1e3 * ms / max(n, 1), launches=n) for k, (ms, n) in prof.items()}
+    dom = max(kern, key=lambda k: kern[k]["avg_us"])
+    bound, amount = work[dom]
+    dur_s = kern[dom]["avg_us"] * 1e-6
+    if bound == "mfma":
+        peak = PEAK_MFMA_BF16_TFLOPS if wl.dtype == "bf16" else PEAK_MFMA_F32_TFLOPS
+        achieved, unit = amount / dur_s / 1e12, "TFLOP/s"
+    else:
+        peak, achieved, unit = PEAK_HBM_GBS, amount / dur_s / 1e9, "GB/s"
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", f"traffic_{wl.name}.json")
+    if os.path.exists(tpath):
+        traffic = json.load(open(tpath)).get(dom)
+    roofline = dict(bound=bound, kernel=dom, achieved=round(achieved, 3), peak=peak, unit=unit,
+                    frac=round(achieved / peak, 4), traffic=traffic,
+                    avg_us=round(kern[dom]["avg_us"], 2),
+                    per_kernel_us={k: round(v["avg_us"], 2) for k, v in kern.items()})
+    # whole-path roofline: serial sum of the contraction time at MFMA peak and the byte time at HBM peak
+    es = 2 if wl.dtype == "bf16" else 4
+    flops_blk = work["score"][1] + work["sig"][1]
+    bytes_blk = wl.n_kv_heads * wl.s_block * wl.head_dim * es + wl.n_q_heads * wl.window * wl.head_dim * es \
+        + work["append"][1]
+    peak_f = (PEAK_MFMA_BF16_TFLOPS if wl.dtype == "bf16" else PEAK_MFMA_F32_TFLOPS) * 1e12
+    t_roof = (flops_blk / peak_f + bytes_blk / (PEAK_HBM_GBS * 1e9)) * wl.n_blocks
+    roofline["path_frac_of_roofline"] = round(t_roof / (ms_per_step * 1e-3), 4)
+
+    cpu = None
+    if args.cpu_seconds > 0:
+        cpu = cpu_baseline(wl, data, comp.B, args.cpu_seconds)
+
+    out = dict(metric="prefill-compression tokens/s/layer (score+LSH+top-k+gather) @128k; % roofline",
+               value=round(value, 1), unit="tokens/s/layer", n_gpus=1, steps=args.steps, warmup=args.warmup,
+               ms_per_step=round(ms_per_step, 4), higher_is_better=True, scaling="weak", vs_baseline=None,
+               dtype=wl.dtype, data="synthetic",
+               config=dict(workload=wl.name, l_ctx=wl.l_ctx, s_block=wl.s_block, window=wl.window, n=wl.n_div,
+                           lsh_tables=wl.lsh_tables, lsh_bits=wl.lsh_bits, n_q_heads=wl.n_q_heads,
+                           n_kv_heads=wl.n_kv_heads, head_dim=wl.head_dim, budget_per_block=comp.B,
+                           blocks=wl.n_blocks, layers_timed=1, launch=args.mode),
+               roofline=roofline, cpu_baseline=cpu)
+    print(json.dumps(out), flush=True)
+    return 0
+
+
+def cpu_baseline(wl, data, B, min_seconds):
+    """The CPU oracle, as it stands, on the first blocks of the same inputs (bounded sample)."""
+    import numpy as np
+    import torch
+    from oracle import laserkv_oracle as O
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        threads = len(os.sched_getaffinity(0))
+    s = wl.s_block
+    planes = data["planes"].double().numpy()
+    cap = wl.n_blocks * B
+    ck = cv = cp = None
+    clen, prev_local, nblk = 0, 0, 0
+    t0 = time.perf_counter()
+    while nblk < wl.n_blocks and (time.perf_counter() - t0 < min_seconds or nblk < 1):
+        lo = nblk * s
+        k = data["k"][:, lo:lo + s].double().numpy()
+        v = data["v"][:, lo:lo + s].double().numpy()
+        q = data["q_win"][nblk].double().numpy()
+        if ck is None:
+            ck = np.zeros((wl.n_kv_heads, cap, wl.head_dim)); cv = np.zeros_like(ck)
+            cp = np.full((wl.n_kv_heads, cap), -1, dtype=np.int64)
+        parts = O.partition(B, wl.n_div, wl.alpha, k.shape[1])
+        k_ctx = ck[:, clen - prev_local:clen] if clen and prev_local else None
+        st = O.select_block(q, k, k_ctx, planes, wl.lsh_tables, wl.lsh_bits, *parts, block_pos0=lo)
+        clen = O.append(ck, cv, cp, clen, k, v, st["keep"], lo)
+        prev_local = parts[1]
+        nblk += 1
+    dt = time.perf_counter() - t0
+    return dict(value=round(nblk * s / dt, 1), unit="tokens/s/layer", cores=int(threads), kind="oracle",
+                sample=f"first {nblk} of {wl.n_blocks} blocks of the same layer ({nblk * s} tokens) in {dt:.1f}s, "
+                       f"NumPy float64, affinity {len(os.sched_getaffinity(0))} cores")
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -126,6 +126,27 @@ int laserkv_append(laserkv_ctx* ctx,
                    int64_t cache_len, int64_t cache_cap,
                    void* hip_stream);
 
+/* Per-kernel timing for benchmarks.  Between laserkv_profile_begin and laserkv_profile_end every
+ * kernel the context launches is bracketed by a pair of HIP events on the call's stream (which adds
+ * a little time between kernels, so whole-path timings belong outside such a bracket).
+ * laserkv_profile_end synchronises on those events and returns, per kernel kind (laserkv_kernel_id),
+ * the summed elapsed milliseconds and the number of launches; both arrays are HOST pointers with
+ * LKV_N_KERNELS entries.  At most LKV_PROFILE_MAX_LAUNCHES launches are recorded per bracket;
+ * later ones run untimed.  Errors: LKV_EINVAL (null / not begun), LKV_EHIP. */
+typedef enum {
+  LKV_KERN_SIG = 0,    /* SimHash codes of keys and window queries */
+  LKV_KERN_STATS = 1,  /* exact score, sweep 1: row maxima and sums */
+  LKV_KERN_SCORE = 2,  /* exact score, sweep 2: pooled probabilities */
+  LKV_KERN_COUNT = 3,  /* collision counts */
+  LKV_KERN_SELECT = 4, /* two-stage TopK and compaction */
+  LKV_KERN_APPEND = 5, /* gather-append */
+  LKV_N_KERNELS = 6
+} laserkv_kernel_id;
+#define LKV_PROFILE_MAX_LAUNCHES 8192
+
+int laserkv_profile_begin(laserkv_ctx* ctx);
+int laserkv_profile_end(laserkv_ctx* ctx, double* ms_per_kernel, int64_t* launches);
+
 #ifdef __cplusplus
 }
 #endif

@@ -19,7 +19,9 @@ LKV_OK, LKV_EINVAL, LKV_ECAP, LKV_ENOMEM, LKV_EHIP = 0, -1, -2, -3, -4
 EXPORTS = (
     "laserkv_create", "laserkv_destroy", "laserkv_last_error", "laserkv_budget",
     "laserkv_partition", "laserkv_select_block", "laserkv_append",
+    "laserkv_profile_begin", "laserkv_profile_end",
 )
+KERNEL_NAMES = ("sig", "stats", "score", "count", "select", "append")
 
 
 class LaserKVError(RuntimeError):
@@ -67,6 +69,10 @@ def load():
         vp, vp, i64, i64, vp, i64, i64, vp, i32, i32, i64,
         vp, vp, i64, vp, i64, i64, i64, vp]
     lib.laserkv_append.restype = C.c_int
+    lib.laserkv_profile_begin.argtypes = [vp]
+    lib.laserkv_profile_begin.restype = C.c_int
+    lib.laserkv_profile_end.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(i64)]
+    lib.laserkv_profile_end.restype = C.c_int
     _lib = lib
     return lib
 
@@ -162,3 +168,14 @@ class LaserKV:
             block_pos0, _ptr(k_cache), _ptr(v_cache), k_cache.stride(0), _ptr(cache_pos), cache_pos.stride(0),
             cache_len, k_cache.shape[1], self._stream(stream))
         self._check(rc)
+
+    def laserkv_profile_begin(self):
+        self._check(self._lib.laserkv_profile_begin(self._ctx))
+
+    def laserkv_profile_end(self):
+        """Returns {kernel name: (total ms, launches)}."""
+        n = len(KERNEL_NAMES)
+        ms = (C.c_double * n)()
+        cnt = (C.c_int64 * n)()
+        self._check(self._lib.laserkv_profile_end(self._ctx, ms, cnt))
+        return {KERNEL_NAMES[i]: (float(ms[i]), int(cnt[i])) for i in range(n)}

@@ -10,6 +10,7 @@
 #include <cstdlib>
 #include <cstring>
 #include <new>
+#include <vector>
 
 namespace {
 
@@ -37,6 +38,10 @@ struct laserkv_ctx {
   uint16_t* sig_q;   // [H_q, max_window, L]
   int m_pad;
   char error[512];
+  // per-kernel event timing (benchmarks only)
+  bool profiling;
+  std::vector<hipEvent_t>* ev_pool;   // pairs: [2*i] start, [2*i+1] stop
+  std::vector<int>* ev_kind;          // kernel id of recorded pair i
 };
 
 namespace {
@@ -66,6 +71,27 @@ int bits_for(int64_t v) {
   int b = 1;
   while ((int64_t(1) << b) <= v) ++b;
   return b;
+}
+
+// Runs `launch` bracketed by an event pair when the context is profiling.
+template <typename F>
+hipError_t timed(laserkv_ctx* ctx, int kind, hipStream_t st, F launch) {
+  if (!ctx->profiling || ctx->ev_kind->size() >= LKV_PROFILE_MAX_LAUNCHES) return launch();
+  const size_t i = ctx->ev_kind->size();
+  while (ctx->ev_pool->size() < 2 * (i + 1)) {
+    hipEvent_t ev;
+    hipError_t e = hipEventCreate(&ev);
+    if (e != hipSuccess) return e;
+    ctx->ev_pool->push_back(ev);
+  }
+  hipError_t e = hipEventRecord((*ctx->ev_pool)[2 * i], st);
+  if (e != hipSuccess) return e;
+  e = launch();
+  if (e != hipSuccess) return e;
+  e = hipEventRecord((*ctx->ev_pool)[2 * i + 1], st);
+  if (e != hipSuccess) return e;
+  ctx->ev_kind->push_back(kind);
+  return hipSuccess;
 }
 
 }  // namespace
@@ -117,18 +143,30 @@ int laserkv_create(const laserkv_config* cfg, laserkv_ctx** out) {
   if (!ctx) return fail(nullptr, LKV_ENOMEM, "create: host allocation failed");
   memset(ctx, 0, sizeof(*ctx));
   ctx->cfg = c;
+  ctx->ev_pool = new (std::nothrow) std::vector<hipEvent_t>();
+  ctx->ev_kind = new (std::nothrow) std::vector<int>();
+  if (!ctx->ev_pool || !ctx->ev_kind) {
+    delete ctx->ev_pool;
+    delete ctx->ev_kind;
+    delete ctx;
+    return fail(nullptr, LKV_ENOMEM, "create: host allocation failed");
+  }
   ctx->group = group;
   ctx->elem_size = c.dtype == LKV_BF16 ? 2 : 4;
   hipError_t e = hipGetDevice(&ctx->device);
   hipDeviceProp_t prop;
   if (e == hipSuccess) e = hipGetDeviceProperties(&prop, ctx->device);
   if (e != hipSuccess) {
+    delete ctx->ev_pool;
+    delete ctx->ev_kind;
     delete ctx;
     return fail_hip(nullptr, e, "create: device query");
   }
   ctx->n_cu = prop.multiProcessorCount;
   e = lkv::init_kernel_attributes();
   if (e != hipSuccess) {
+    delete ctx->ev_pool;
+    delete ctx->ev_kind;
     delete ctx;
     return fail_hip(nullptr, e, "create: kernel attribute");
   }
@@ -160,6 +198,10 @@ void laserkv_destroy(laserkv_ctx* ctx) {
   void* ptrs[] = {ctx->part, ctx->s_part, ctx->s_exact, ctx->cnt, ctx->sig_k, ctx->sig_q};
   for (void* p : ptrs)
     if (p) (void)hipFree(p);
+  if (ctx->ev_pool)
+    for (hipEvent_t ev : *ctx->ev_pool) (void)hipEventDestroy(ev);
+  delete ctx->ev_pool;
+  delete ctx->ev_kind;
   delete ctx;
 }
 
@@ -288,11 +330,17 @@ int laserkv_select_block(laserkv_ctx* ctx,
   lp.keep = keep_idx;
 
   hipError_t e;
-  if ((e = lkv::launch_sig(c.dtype, d, gp, st)) != hipSuccess) return fail_hip(ctx, e, "select_block: signature kernel");
-  if ((e = lkv::launch_stats(c.dtype, d, sp, n_qg, c.n_kv_heads, st)) != hipSuccess) return fail_hip(ctx, e, "select_block: score sweep 1");
-  if ((e = lkv::launch_score(c.dtype, d, sp, n_qg, c.n_kv_heads, st)) != hipSuccess) return fail_hip(ctx, e, "select_block: score sweep 2");
-  if ((e = lkv::launch_count(cp, c.n_kv_heads, st)) != hipSuccess) return fail_hip(ctx, e, "select_block: count kernel");
-  if ((e = lkv::launch_select(lp, st)) != hipSuccess) return fail_hip(ctx, e, "select_block: select kernel");
+  const int nh = c.n_kv_heads, dt = c.dtype;
+  if ((e = timed(ctx, LKV_KERN_SIG, st, [&] { return lkv::launch_sig(dt, d, gp, st); })) != hipSuccess)
+    return fail_hip(ctx, e, "select_block: signature kernel");
+  if ((e = timed(ctx, LKV_KERN_STATS, st, [&] { return lkv::launch_stats(dt, d, sp, n_qg, nh, st); })) != hipSuccess)
+    return fail_hip(ctx, e, "select_block: score sweep 1");
+  if ((e = timed(ctx, LKV_KERN_SCORE, st, [&] { return lkv::launch_score(dt, d, sp, n_qg, nh, st); })) != hipSuccess)
+    return fail_hip(ctx, e, "select_block: score sweep 2");
+  if ((e = timed(ctx, LKV_KERN_COUNT, st, [&] { return lkv::launch_count(cp, nh, st); })) != hipSuccess)
+    return fail_hip(ctx, e, "select_block: count kernel");
+  if ((e = timed(ctx, LKV_KERN_SELECT, st, [&] { return lkv::launch_select(lp, st); })) != hipSuccess)
+    return fail_hip(ctx, e, "select_block: select kernel");
 
   const size_t hk = c.n_kv_heads;
   if (dbg_s_exact && (e = hipMemcpyAsync(dbg_s_exact, ctx->s_exact, hk * s_t * sizeof(float), hipMemcpyDeviceToDevice, st)) != hipSuccess)
@@ -342,8 +390,40 @@ int laserkv_append(laserkv_ctx* ctx,
   ap.pos_stride_head = pos_stride_head;
   ap.cache_len = cache_len;
   ap.block_pos0 = block_pos0;
-  hipError_t e = lkv::launch_append(ap, c.n_kv_heads, reinterpret_cast<hipStream_t>(hip_stream));
+  hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
+  const int nh = c.n_kv_heads;
+  hipError_t e = timed(ctx, LKV_KERN_APPEND, st, [&] { return lkv::launch_append(ap, nh, st); });
   if (e != hipSuccess) return fail_hip(ctx, e, "append: gather kernel");
+  return LKV_OK;
+}
+
+int laserkv_profile_begin(laserkv_ctx* ctx) {
+  if (!ctx) return fail(nullptr, LKV_EINVAL, "profile_begin: null context");
+  ctx->ev_kind->clear();
+  ctx->profiling = true;
+  return LKV_OK;
+}
+
+int laserkv_profile_end(laserkv_ctx* ctx, double* ms_per_kernel, int64_t* launches) {
+  if (!ctx || !ms_per_kernel || !launches) return fail(ctx, LKV_EINVAL, "profile_end: null argument");
+  if (!ctx->profiling) return fail(ctx, LKV_EINVAL, "profile_end: profile_begin was not called");
+  ctx->profiling = false;
+  for (int k = 0; k < LKV_N_KERNELS; ++k) {
+    ms_per_kernel[k] = 0.0;
+    launches[k] = 0;
+  }
+  for (size_t i = 0; i < ctx->ev_kind->size(); ++i) {
+    hipError_t e = hipEventSynchronize((*ctx->ev_pool)[2 * i + 1]);
+    float ms = 0.0f;
+    if (e == hipSuccess) e = hipEventElapsedTime(&ms, (*ctx->ev_pool)[2 * i], (*ctx->ev_pool)[2 * i + 1]);
+    if (e != hipSuccess) {
+      ctx->ev_kind->clear();
+      return fail_hip(ctx, e, "profile_end: event timing");
+    }
+    ms_per_kernel[(*ctx->ev_kind)[i]] += ms;
+    launches[(*ctx->ev_kind)[i]] += 1;
+  }
+  ctx->ev_kind->clear();
   return LKV_OK;
 }
 

@@ -80,3 +80,56 @@ class LayerCompressor:
             prev_local, _ = self.step(data["q_win"][t], data["k"][:, lo:hi], data["v"][:, lo:hi], data["planes"],
                                       lo, prev_local)
         return self.cache_len
+
+    # ---- pre-marshalled call lists: one ctypes call per library entry point, nothing else ----
+    def plan_layer(self, data, n_blocks=None):
+        """Builds the layer's call list once: [(c_function, argument tuple without the stream)].
+
+        The tensors in `data`, the cache and the keep buffer must stay alive and in place while the
+        plan is used.  run_plan() then issues the calls back to back with no per-call Python work
+        beyond the foreign call itself (and can be captured into a HIP graph).
+        """
+        import ctypes as C
+        wl, lib = self.wl, self.lib._lib
+        ctx = self.lib._ctx
+        vp = C.c_void_p
+        nb = data["q_win"].shape[0] if n_blocks is None else n_blocks
+        l_tot = data["k"].shape[1]
+        d = wl.head_dim
+        calls, cache_len, prev_local = [], 0, 0
+        kc_sh, kc_st = self.k_cache.stride(0), self.k_cache.stride(1)
+        es = self.k_cache.element_size()
+        for t in range(nb):
+            lo, hi = t * wl.s_block, min((t + 1) * wl.s_block, l_tot)
+            s_t = hi - lo
+            na, nl, ke, kl = self.block_budget(s_t)
+            b_t = na + nl + ke + kl
+            assert b_t == self.keep.shape[1], "plans cover equal-sized blocks only"
+            q, k, v = data["q_win"][t], data["k"][:, lo:hi], data["v"][:, lo:hi]
+            t_ctx = prev_local if cache_len else 0
+            ctx_ptr = vp(self.k_cache.data_ptr() + (cache_len - t_ctx) * kc_st * es) if t_ctx else None
+            calls.append((lib.laserkv_select_block, (
+                ctx, vp(q.data_ptr()), q.stride(0), q.stride(1), vp(k.data_ptr()), k.stride(0), k.stride(1),
+                ctx_ptr, kc_sh if t_ctx else 0, kc_st if t_ctx else 0, vp(data["planes"].data_ptr()),
+                s_t, wl.window, t_ctx, lo, lo + s_t - wl.window, 1, na, nl, ke, kl,
+                vp(self.keep.data_ptr()), None, None, None, None)))
+            calls.append((lib.laserkv_append, (
+                ctx, vp(k.data_ptr()), k.stride(0), k.stride(1), vp(v.data_ptr()), v.stride(0), v.stride(1),
+                vp(self.keep.data_ptr()), b_t, s_t, lo, vp(self.k_cache.data_ptr()), vp(self.v_cache.data_ptr()),
+                kc_sh, vp(self.cache_pos.data_ptr()), self.cache_pos.stride(0), cache_len, self.cap)))
+            cache_len += b_t
+            prev_local = nl
+        self._plan_len = cache_len
+        return calls
+
+    def run_plan(self, calls, stream=None):
+        import ctypes as C
+        if stream is None:
+            stream = torch.cuda.current_stream().cuda_stream
+        sp = C.c_void_p(stream)
+        for fn, args in calls:
+            rc = fn(*args, sp)
+            if rc != 0:
+                self.lib._check(rc)
+        self.cache_len = self._plan_len
+        return self.cache_len

@@ -201,3 +201,33 @@ def test_error_paths_return_codes_and_launch_nothing():
         lib.laserkv_append(k, k, keep, b_t=227, block_pos0=0, k_cache=kc, v_cache=kc.clone(), cache_pos=pos, cache_len=100)
     assert ei.value.code == binding.LKV_ECAP
     lib.close()
+
+
+def test_graph_replay_matches_eager_every_time():
+    """A captured layer (what bench.py times) must reproduce the eager result on every replay, with eager
+    work and synchronisations between replays."""
+    wl = synth.WORKLOADS["llama8b-16k"]
+    B = O.budget(wl.s_block, wl.l_ctx, wl.r_num, wl.r_den)
+    na = O.partition(B, wl.n_div, wl.alpha, wl.s_block)[0]
+    dev = to_dev(synth.make_layer(wl, 5, na, n_blocks=3))
+    comp = LayerCompressor(wl, DEV, max_blocks=3)
+    plan = comp.plan_layer(dev)
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        comp.run_plan(plan)
+        stream.synchronize()
+        ref = (comp.cache_pos.clone(), comp.k_cache.clone(), comp.v_cache.clone())
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=stream):
+            comp.run_plan(plan)
+        for it in range(4):
+            comp.cache_pos.fill_(-1)
+            comp.k_cache.zero_()
+            comp.v_cache.zero_()
+            stream.synchronize()
+            graph.replay()
+            stream.synchronize()
+            assert torch.equal(comp.cache_pos, ref[0]) and torch.equal(comp.k_cache, ref[1]) and torch.equal(comp.v_cache, ref[2]), it
+            comp.run_plan(plan)          # eager work between replays
+            stream.synchronize()
+            assert torch.equal(comp.cache_pos, ref[0])
