@@ -14,7 +14,6 @@
 
 namespace {
 
-constexpr int kMaxRanges = 64;   // key ranges per (head, query-row group) in the score sweeps
 constexpr int kMaxBlock = 16384;
 constexpr int kMaxRows = 1024;   // G * W
 constexpr int kMaxPlanes = 512;  // L * K
@@ -30,7 +29,8 @@ struct laserkv_ctx {
   int group;
   int elem_size;
   // device workspace
-  float2* part;      // [H_kv, kMaxRanges, m_pad]
+  int max_ranges;    // key ranges per (head, query-row group) the workspace is sized for
+  float2* part;      // [H_kv, max_ranges, m_pad]
   float* s_part;     // [n_qgroups_max, H_kv, max_block]
   float* s_exact;    // [H_kv, max_block]
   int32_t* cnt;      // [H_kv, max_block]
@@ -173,9 +173,12 @@ int laserkv_create(const laserkv_config* cfg, laserkv_ctx** out) {
   const int m_rows = group * c.max_window;
   ctx->m_pad = (m_rows + 255) / 256 * 256;
   const int n_qg_max = (m_rows + 127) / 128;
+  // ranges of at most score_max_range() keys, plus one for the look-back keys, and room for finer splits
+  ctx->max_ranges = (c.max_block + c.max_ctx_keys) / lkv::score_max_range() + 2;
+  if (ctx->max_ranges < 64) ctx->max_ranges = 64;
   const size_t hk = c.n_kv_heads, sb = c.max_block;
   struct { void** p; size_t bytes; } allocs[] = {
-      {(void**)&ctx->part, hk * kMaxRanges * ctx->m_pad * sizeof(float2)},
+      {(void**)&ctx->part, hk * ctx->max_ranges * ctx->m_pad * sizeof(float2)},
       {(void**)&ctx->s_part, (size_t)n_qg_max * hk * sb * sizeof(float)},
       {(void**)&ctx->s_exact, hk * sb * sizeof(float)},
       {(void**)&ctx->cnt, hk * sb * sizeof(int32_t)},
@@ -234,6 +237,8 @@ int laserkv_select_block(laserkv_ctx* ctx,
   if (bad_stride(q_stride_head, q_stride_tok) || bad_stride(k_stride_head, k_stride_tok) ||
       (t_ctx > 0 && bad_stride(c_stride_head, c_stride_tok)))
     return fail(ctx, LKV_EINVAL, "select_block: strides must cover a row and keep rows 16-byte aligned");
+  if ((int64_t)s_t * k_stride_tok * es >= (int64_t(1) << 31) || (int64_t)t_ctx * c_stride_tok * es >= (int64_t(1) << 31))
+    return fail(ctx, LKV_EINVAL, "select_block: a head's keys must span less than 2 GiB");
   if (!aligned16(q_win) || !aligned16(k_blk) || !aligned16(hyperplanes) || (k_ctx && !aligned16(k_ctx)))
     return fail(ctx, LKV_EINVAL, "select_block: tensors must be 16-byte aligned");
 
@@ -252,15 +257,21 @@ int laserkv_select_block(laserkv_ctx* ctx,
   sp.t_ctx = t_ctx;
   sp.n_keys = n_keys;
   sp.rows_per_group = m_rows > 128 ? 256 : 128;
+  if (env_int("LASERKV_SCORE_MQ", 0) == 128) sp.rows_per_group = 128;
   const int n_qg = (m_rows + sp.rows_per_group - 1) / sp.rows_per_group;
+  sp.n_qgroups = n_qg;
+  sp.n_kv_heads = c.n_kv_heads;
   // key ranges: aim at a few workgroups per compute unit
   const int wg_target = ctx->n_cu * env_int("LASERKV_SCORE_WG_PER_CU", 2);
   int nr = wg_target / (c.n_kv_heads * n_qg);
   if (nr < 1) nr = 1;
-  if (nr > kMaxRanges) nr = kMaxRanges;
+  if (nr > ctx->max_ranges - 1) nr = ctx->max_ranges - 1;
   int nk = ((n_keys + nr - 1) / nr + 31) / 32 * 32;
+  if (nk > lkv::score_max_range()) nk = lkv::score_max_range();
   sp.keys_per_range = nk;
-  sp.n_ranges = (n_keys + nk - 1) / nk;
+  sp.n_ctx_ranges = (t_ctx + nk - 1) / nk;
+  sp.n_ranges = sp.n_ctx_ranges + (s_t + nk - 1) / nk;
+  if (sp.n_ranges > ctx->max_ranges) return fail(ctx, LKV_EINVAL, "select_block: internal range split too fine");
   sp.causal = causal ? 1 : 0;
   int64_t lim0 = (int64_t)t_ctx + (q_pos0 - block_pos0);
   if (lim0 > (1 << 30)) lim0 = 1 << 30;

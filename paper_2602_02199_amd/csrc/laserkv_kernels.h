@@ -24,8 +24,11 @@ struct ScoreParams {
   int t_ctx;       // T
   int n_keys;      // T + S
   int keys_per_range;   // NK (multiple of 32)
-  int n_ranges;         // NR
-  int rows_per_group;   // MQ = 128 * MT
+  int n_ranges;         // NR = n_ctx_ranges + ranges over the block keys
+  int n_ctx_ranges;     // ranges that cover the look-back keys (each range lies in one source)
+  int rows_per_group;   // MQ = 32 * waves per workgroup (128 or 256)
+  int n_qgroups;        // ceil(M / MQ)
+  int n_kv_heads;
   int causal;
   int lim0;        // key index kidx is visible to window row j iff kidx <= lim0 + j (when causal)
   float scale2;    // log2(e) / sqrt(d)
@@ -92,5 +95,6 @@ hipError_t launch_count(const CountParams& p, int n_kv_heads, hipStream_t st);
 hipError_t launch_select(const SelectParams& p, hipStream_t st);
 hipError_t launch_append(const AppendParams& p, int n_kv_heads, hipStream_t st);
 hipError_t init_kernel_attributes();
+int score_max_range();  // most keys one score workgroup takes (its LDS holds the whole range)
 
 }  // namespace lkv

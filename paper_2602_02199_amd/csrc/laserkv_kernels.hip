@@ -12,170 +12,262 @@
 
 #include <limits.h>
 
+// Timestamp hook for bench harnesses that include this file with their own definition; nothing in the library build.
+#ifndef LKV_TS
+#define LKV_TS(n)
+#endif
+
 namespace lkv {
 
 // ---------------------------------------------------------------------------------------------
-// Exact score, both sweeps.  Workgroup = (key range, query-row group, KV head); 4 waves, wave w
-// keeps the A fragments of MT 32-row query tiles in registers and streams the range's keys
-// through LDS in stages of 64.
+// Exact score, both sweeps.  Workgroup = (key range, query-row group, KV head) with NW waves.
+//
+// The whole key range of the workgroup (<= 256 keys) is fetched into LDS up front: a range is only
+// microseconds of work, so what matters is having all of its loads in flight at once rather than a
+// staged pipeline whose every stage would wait a full HBM round trip.  After one barrier each wave
+// walks the range's 32-key tiles on its own: A fragments of ONE 32-row query tile stay in registers,
+// B fragments come from LDS (row pitch padded by one 16-byte chunk: conflict-free reads at
+// base + immediate addresses).  Everything is sized for <= 128 registers per lane so that four
+// waves share a SIMD: one wave alone issues a vector instruction only every ~10 clocks, so the
+// softmax arithmetic needs that many waves to keep the ALU and the matrix pipe busy.
+//
+// Sweep 1 keeps, per window row, sum_i 2^(x_i - ref) against a reference ref shared by the 32 lanes
+// that hold the row; ref starts as the row maximum of the first tile and is raised (with the sum
+// rescaled) only when a logit exceeds it by more than 2^64, so the common case costs one fma, one
+// max, one exp and one add per logit.  Sweep 2 needs one fma, one exp and one add per logit.
 // ---------------------------------------------------------------------------------------------
-template <int DT, int D, int MT, bool PASS2>
-__global__ __launch_bounds__(256) void score_kernel(ScoreParams p) {
+constexpr int SCORE_MAX_RANGE = 256;  // keys per workgroup at most
+
+template <int DT, int D>
+__host__ __device__ constexpr int score_row_pitch_chunks() { return D * (DT == DT_BF16 ? 2 : 4) / 16 + 1; }
+
+// dynamic LDS of a score workgroup: key rows, per-wave column sums (sweep 2), row limits and lse
+template <int DT, int D, int NW>
+__host__ __device__ constexpr size_t score_lds_bytes(int range_keys) {
+  return (size_t)range_keys * score_row_pitch_chunks<DT, D>() * 16 + (size_t)NW * range_keys * 4 + (size_t)NW * 32 * 8;
+}
+
+template <int DT, int D, int NW, bool PASS2>
+__global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu((DT == DT_BF16 ? 2 : 4) * D <= 256 ? 4 : 2, 8)))
+void score_kernel(ScoreParams p) {
   constexpr int ES = DT == DT_BF16 ? 2 : 4;
   constexpr int CH = D * ES / 16;  // 16-byte chunks per row
-  constexpr int NCH = CH / 2;      // chunk pairs = MFMA steps (bf16) per tile
-  constexpr int KT = 64;           // keys per LDS stage
-  constexpr int MQ = 128 * MT;     // query rows per workgroup
-  constexpr int LDT = KT * CH / 256;
+  constexpr int NCH = CH / 2;      // chunk pairs per tile
+  constexpr int CHP = CH + 1;      // LDS row pitch in chunks
+  constexpr int NTHR = NW * 64;
+  constexpr int MQ = 32 * NW;      // query rows per workgroup
+  constexpr int LDB = 8;           // 16-byte loads a thread keeps in flight per round
+  constexpr float RESCALE_AT = 64.0f;
 
-  __shared__ uint4 sK[KT * CH];
-  __shared__ float sLse[MQ];
-  __shared__ int sLim[MQ];
-  __shared__ float sCol[4][KT];
+  extern __shared__ uint4 smem[];
+  const int nkr = p.keys_per_range;
+  uint4* sK = smem;                                             // [nkr][CHP]
+  float* sCol = reinterpret_cast<float*>(smem + (size_t)nkr * CHP);  // [NW][nkr]
+  int* sLim = reinterpret_cast<int*>(sCol + (size_t)NW * nkr);      // [MQ]
+  float* sLse = reinterpret_cast<float*>(sLim + MQ);               // [MQ]
 
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, rl = lane & 31, kg = lane >> 5;
-  const int kr = blockIdx.x, qg = blockIdx.y, h = blockIdx.z;
-  const int k0 = kr * p.keys_per_range;
-  const int k1 = min(k0 + p.keys_per_range, p.n_keys);
+  LKV_TS(0);
+  // work item: consecutive linear ids land on different XCDs (id % 8), so the query-row groups of
+  // one (head, key range) are given ids that differ by a multiple of 8 and share an L2.
+  const int n_qg = p.n_qgroups;
+  int kr, qg, h;
+  {
+    const int id = blockIdx.x;
+    const int n_pairs = p.n_ranges * p.n_kv_heads;
+    const int xcd = id & 7, slot = id >> 3;
+    const int pair_hi = slot / n_qg;
+    int pair = pair_hi * 8 + xcd;
+    qg = slot - pair_hi * n_qg;
+    if ((n_pairs & 7) != 0) {  // plain order when the pairs do not tile the XCDs
+      pair = id / n_qg;
+      qg = id - pair * n_qg;
+    }
+    h = pair / p.n_ranges;
+    kr = pair - h * p.n_ranges;
+  }
+  // a range lies entirely in the look-back keys or entirely in the block keys, so the source
+  // base, stride and row offset are uniform over the workgroup
+  const bool in_ctx = kr < p.n_ctx_ranges;
+  const int seg_row0 = in_ctx ? kr * nkr : (kr - p.n_ctx_ranges) * nkr;
+  const int seg_rows = in_ctx ? p.t_ctx : p.s_t;
+  const int n_keys_wg = min(nkr, seg_rows - seg_row0);             // keys of this range
+  const int k0 = in_ctx ? seg_row0 : p.t_ctx + seg_row0;            // global key index of the range start
+  const int k1 = k0 + n_keys_wg;
+  const RowSrc ksrc = in_ctx ? p.kc : p.kb;
+  const char* kbase_ptr = ksrc.base + (int64_t)h * ksrc.stride_head;
+  const int kstride = (int)ksrc.stride_row;
+  const int n_tiles = (n_keys_wg + 31) >> 5;
+  const int n_chunks = n_tiles * 32 * CH;  // rows past the range are clamped copies (masked later)
 
-  for (int t = tid; t < MQ; t += 256) {
-    const int m = qg * MQ + t;
-    const int j = (m < p.m_rows) ? m % p.w : 0;
-    sLim[t] = p.causal ? p.lim0 + j : INT_MAX;
-    if (PASS2) {
-      float lse = 1.0e30f;  // rows past M are padding: probability 0
-      if (m < p.m_rows) {
-        const float2* pp = p.part + (size_t)h * p.n_ranges * p.m_pad + m;
-        float mm = NEG_BIG, ss = 0.0f;
-        for (int r = 0; r < p.n_ranges; ++r) {
-          const float2 v = pp[(size_t)r * p.m_pad];
-          lse_merge(mm, ss, v.x, v.y);
+  // 1. all key loads of the range in flight (rounds of LDB per thread), then into LDS
+  for (int c0 = 0; c0 < n_chunks; c0 += NTHR * LDB) {
+    uint4 pre[LDB];
+#pragma unroll
+    for (int u = 0; u < LDB; ++u) {
+      const int q = c0 + tid + NTHR * u;
+      const int row = q / CH, c = q % CH;
+      const int lrow = min(seg_row0 + row, seg_rows - 1);
+      if (q < n_chunks) pre[u] = ld16(kbase_ptr + (uint32_t)(lrow * kstride + c * 16));
+    }
+    if (c0 == 0) {
+      // row set-up overlaps the first round's latency
+      for (int t = tid; t < MQ; t += NTHR) {
+        const int m = qg * MQ + t;
+        const int j = (m < p.m_rows) ? m % p.w : 0;
+        sLim[t] = p.causal ? p.lim0 + j : INT_MAX;
+        if (PASS2) {
+          float lse = 1.0e30f;  // rows past M are padding: probability 0
+          if (m < p.m_rows) {
+            const float2* pp = p.part + (size_t)h * p.n_ranges * p.m_pad + m;
+            float mm = NEG_BIG, ss = 0.0f;
+            int r = 0;
+            for (; r + 8 <= p.n_ranges; r += 8) {
+              float2 v[8];
+#pragma unroll
+              for (int u = 0; u < 8; ++u) v[u] = pp[(size_t)(r + u) * p.m_pad];
+#pragma unroll
+              for (int u = 0; u < 8; ++u) lse_merge(mm, ss, v[u].x, v[u].y);
+            }
+            for (; r < p.n_ranges; ++r) {
+              const float2 v = pp[(size_t)r * p.m_pad];
+              lse_merge(mm, ss, v.x, v.y);
+            }
+            lse = mm + fast_log2(ss);
+          }
+          sLse[t] = lse;
         }
-        lse = mm + fast_log2(ss);
       }
-      sLse[t] = lse;
+    }
+#pragma unroll
+    for (int u = 0; u < LDB; ++u) {
+      const int q = c0 + tid + NTHR * u;
+      const int row = q / CH, c = q % CH;
+      if (q < n_chunks) sK[row * CHP + c] = pre[u];
     }
   }
+  LKV_TS(1);
 
-  uint4 a[MT][NCH];
-#pragma unroll
-  for (int mt = 0; mt < MT; ++mt) {
-    const int m = qg * MQ + (wave * MT + mt) * 32 + rl;
+  // 2. this wave's query tile
+  uint4 a[NCH];
+  {
+    const int m = qg * MQ + wave * 32 + rl;
     const int mc = min(m, p.m_rows - 1);
     const int g = mc / p.w, j = mc - g * p.w;
     const char* ptr = p.q.base + (int64_t)(h * p.group + g) * p.q.stride_head + (int64_t)j * p.q.stride_row;
 #pragma unroll
-    for (int i = 0; i < NCH; ++i) a[mt][i] = ld16(ptr + (2 * i + kg) * 16);
+    for (int i = 0; i < NCH; ++i) a[i] = ld16(ptr + (2 * i + kg) * 16);
   }
+  __syncthreads();
+  LKV_TS(2);
 
-  float rm[MT][16], rs[MT][16];  // sweep 1: running (max, sum); sweep 2: rm holds the row lse
+  float ref[16], sum[16];  // sweep 1: (reference, sum); sweep 2: ref holds the row lse
 #pragma unroll
-  for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      rm[mt][r] = NEG_BIG;
-      rs[mt][r] = 0.0f;
-    }
-
-  const int n_stage = (k1 - k0 + KT - 1) / KT;
-  uint4 pre[LDT];
-  auto gload = [&](int s) {
-#pragma unroll
-    for (int u = 0; u < LDT; ++u) {
-      const int q = tid + 256 * u;
-      const int row = q / CH, c = q % CH;
-      const int kidx = min(k0 + s * KT + row, p.n_keys - 1);
-      const char* ptr = kidx < p.t_ctx
-                            ? p.kc.base + (int64_t)h * p.kc.stride_head + (int64_t)kidx * p.kc.stride_row
-                            : p.kb.base + (int64_t)h * p.kb.stride_head + (int64_t)(kidx - p.t_ctx) * p.kb.stride_row;
-      pre[u] = ld16(ptr + c * 16);
-    }
-  };
-  gload(0);
-  __syncthreads();  // sLse / sLim visible
-  if (PASS2) {
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) rm[mt][r] = sLse[(wave * MT + mt) * 32 + acc_row(r, kg)];
+  for (int r = 0; r < 16; ++r) {
+    ref[r] = PASS2 ? sLse[wave * 32 + acc_row(r, kg)] : NEG_BIG;
+    sum[r] = 0.0f;
   }
+  LKV_TS(3);
 
-  for (int s = 0; s < n_stage; ++s) {
+  // 3. the range's tiles; rolled on purpose (microsecond kernels start from a cold instruction cache)
+#pragma unroll 1
+  for (int nt = 0; nt < n_tiles; ++nt) {
+    const int kbase = k0 + nt * 32;
+    f32x16 acc;
 #pragma unroll
-    for (int u = 0; u < LDT; ++u) {
-      const int q = tid + 256 * u;
-      const int row = q / CH, c = q % CH;
-      sK[row * CH + (c ^ (row & 7))] = pre[u];
-    }
-    __syncthreads();
-    if (s + 1 < n_stage) gload(s + 1);
-
+    for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
+    const uint4* brow = sK + (size_t)(nt * 32 + rl) * CHP + kg;
 #pragma unroll
-    for (int nt = 0; nt < KT / 32; ++nt) {
-      const int kbase = k0 + s * KT + nt * 32;
-      if (kbase >= k1) break;
-      f32x16 acc[MT];
-#pragma unroll
-      for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) acc[mt][r] = 0.0f;
-#pragma unroll
-      for (int i = 0; i < NCH; ++i) {
-        const uint4 b = sK[(nt * 32 + rl) * CH + ((2 * i + kg) ^ (rl & 7))];
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt) Mma<DT>::run(acc[mt], a[mt][i], b);
-      }
-      const int kidx = kbase + rl;
-      const bool in_range = kidx < k1;
-      const bool need_mask = p.causal && (kbase + 31 > p.lim0);  // wave-uniform
+    for (int i = 0; i < NCH; ++i) Mma<DT>::run(acc, a[i], brow[2 * i]);
+    const int kidx = kbase + rl;
+    const bool partial = (kbase + 32 > k1) || (p.causal && (kbase + 31 > p.lim0));  // wave-uniform
+    if (PASS2) {
       float col = 0.0f;
+      if (!partial) {
 #pragma unroll
-      for (int mt = 0; mt < MT; ++mt) {
+        for (int r = 0; r < 16; ++r) col += fast_exp2(fmaf(acc[r], p.scale2, -ref[r]));
+      } else {
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-          bool vis = in_range;
-          if (need_mask) vis = vis && (kidx <= sLim[(wave * MT + mt) * 32 + acc_row(r, kg)]);
-          if (PASS2) {
-            const float e = fast_exp2(acc[mt][r] * p.scale2 - rm[mt][r]);
-            col += vis ? e : 0.0f;
-          } else {
-            const float x = vis ? acc[mt][r] * p.scale2 : NEG_BIG;
-            lse_push(rm[mt][r], rs[mt][r], x);
+          const bool vis = kidx < k1 && kidx <= sLim[wave * 32 + acc_row(r, kg)];
+          const float e = fast_exp2(fmaf(acc[r], p.scale2, -ref[r]));
+          col += vis ? e : 0.0f;
+        }
+      }
+      col += __shfl_xor(col, 32);
+      if (kg == 0) sCol[wave * nkr + nt * 32 + rl] = col;
+    } else {
+      // acc is turned in place into t = x - ref (x = scaled logit, masked -> NEG_BIG)
+      if (nt == 0) {
+        // first tile of the range: the references start at this tile's row maxima
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          float x = acc[r] * p.scale2;
+          if (partial) {
+            const bool vis = kidx < k1 && kidx <= sLim[wave * 32 + acc_row(r, kg)];
+            x = vis ? x : NEG_BIG;
+          }
+          ref[r] = half_allmax(x);
+          acc[r] = x - ref[r];
+          __builtin_amdgcn_sched_barrier(0);  // one row at a time: keeps register pressure low
+        }
+      } else {
+        float tmax = NEG_BIG;
+        if (!partial) {
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            acc[r] = fmaf(acc[r], p.scale2, -ref[r]);
+            tmax = fmaxf(tmax, acc[r]);
+          }
+        } else {
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const bool vis = kidx < k1 && kidx <= sLim[wave * 32 + acc_row(r, kg)];
+            acc[r] = (vis ? acc[r] * p.scale2 : NEG_BIG) - ref[r];
+            tmax = fmaxf(tmax, acc[r]);
+          }
+        }
+        if (__any(tmax > RESCALE_AT)) {
+          // rare: raise the references of this wave's rows to the row maxima of this tile.
+          // (masks only ever hide the tail of a range, so a row whose reference is still unset
+          // has t = 0 here and never enters this branch with a visible key)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const float x = acc[r] + ref[r];
+            const float nref = fmaxf(ref[r], half_allmax(x));
+            sum[r] *= fast_exp2(ref[r] - nref);
+            ref[r] = nref;
+            acc[r] = x - nref;
+            __builtin_amdgcn_sched_barrier(0);
           }
         }
       }
-      if (PASS2) {
-        col += __shfl_xor(col, 32);
-        if (kg == 0) sCol[wave][nt * 32 + rl] = col;
-      }
-    }
-    __syncthreads();
-    if (PASS2 && tid < KT) {
-      const int kidx = k0 + s * KT + tid;
-      if (kidx < k1 && kidx >= p.t_ctx) {
-        const float v = (sCol[0][tid] + sCol[1][tid]) + (sCol[2][tid] + sCol[3][tid]);
-        p.s_part[((size_t)qg * gridDim.z + h) * p.s_t + (kidx - p.t_ctx)] = v;
-      }
+#pragma unroll
+      for (int r = 0; r < 16; ++r) sum[r] += fast_exp2(acc[r]);
     }
   }
+  LKV_TS(4);
 
-  if (!PASS2) {
+  if (PASS2) {
+    __syncthreads();
+    for (int t = tid; t < n_keys_wg; t += NTHR) {
+      const int kidx = k0 + t;
+      if (kidx >= p.t_ctx) {
+        float v = 0.0f;
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt) {
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        float m = rm[mt][r], s = rs[mt][r];
-#pragma unroll
-        for (int off = 1; off < 32; off <<= 1) {
-          const float m2 = __shfl_xor(m, off);
-          const float s2 = __shfl_xor(s, off);
-          lse_merge(m, s, m2, s2);
-        }
-        const int row = qg * MQ + (wave * MT + mt) * 32 + acc_row(r, kg);
-        if (rl == 0 && row < p.m_rows) p.part[((size_t)h * p.n_ranges + kr) * p.m_pad + row] = make_float2(m, s);
+        for (int w = 0; w < NW; ++w) v += sCol[w * nkr + t];
+        p.s_part[((size_t)qg * p.n_kv_heads + h) * p.s_t + (kidx - p.t_ctx)] = v;
       }
     }
+  } else {
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const float s = half_allsum(sum[r]);
+      const int row = qg * MQ + wave * 32 + acc_row(r, kg);
+      if (rl == 0 && row < p.m_rows) p.part[((size_t)h * p.n_ranges + kr) * p.m_pad + row] = make_float2(ref[r], s);
+    }
   }
+  LKV_TS(5);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -438,12 +530,26 @@ __global__ __launch_bounds__(256) void append_kernel(AppendParams p) {
 // ---------------------------------------------------------------------------------------------
 template <int DT, int D, bool PASS2>
 static hipError_t launch_score_t(const ScoreParams& p, int n_qgroups, int n_kv_heads, hipStream_t st) {
-  dim3 grid(p.n_ranges, n_qgroups, n_kv_heads);
+  dim3 grid(p.n_ranges * n_qgroups * n_kv_heads);
+  const size_t lds8 = score_lds_bytes<DT, D, 8>(p.keys_per_range);
+  const size_t lds4 = score_lds_bytes<DT, D, 4>(p.keys_per_range);
   if (p.rows_per_group == 256)
-    hipLaunchKernelGGL((score_kernel<DT, D, 2, PASS2>), grid, dim3(256), 0, st, p);
+    hipLaunchKernelGGL((score_kernel<DT, D, 8, PASS2>), grid, dim3(512), lds8, st, p);
   else
-    hipLaunchKernelGGL((score_kernel<DT, D, 1, PASS2>), grid, dim3(256), 0, st, p);
+    hipLaunchKernelGGL((score_kernel<DT, D, 4, PASS2>), grid, dim3(256), lds4, st, p);
   return hipGetLastError();
+}
+
+template <int DT, int D>
+static hipError_t score_attrs() {
+  const void* fns[] = {
+      reinterpret_cast<const void*>(&score_kernel<DT, D, 8, false>), reinterpret_cast<const void*>(&score_kernel<DT, D, 8, true>),
+      reinterpret_cast<const void*>(&score_kernel<DT, D, 4, false>), reinterpret_cast<const void*>(&score_kernel<DT, D, 4, true>)};
+  for (const void* f : fns) {
+    hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    if (e != hipSuccess) return e;
+  }
+  return hipSuccess;
 }
 
 template <bool PASS2>
@@ -487,9 +593,16 @@ hipError_t launch_sig(int dtype, int head_dim, const SigParams& p, hipStream_t s
 }
 
 hipError_t init_kernel_attributes() {
-  return hipFuncSetAttribute(reinterpret_cast<const void*>(&count_kernel),
-                             hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024);
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&count_kernel),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024);
+  if (e == hipSuccess) e = score_attrs<DT_BF16, 128>();
+  if (e == hipSuccess) e = score_attrs<DT_BF16, 64>();
+  if (e == hipSuccess) e = score_attrs<DT_F32, 128>();
+  if (e == hipSuccess) e = score_attrs<DT_F32, 64>();
+  return e;
 }
+
+int score_max_range() { return SCORE_MAX_RANGE; }
 
 hipError_t launch_count(const CountParams& p, int n_kv_heads, hipStream_t st) {
   const int n_tg = (p.n_tables + p.tables_per_group - 1) / p.tables_per_group;
