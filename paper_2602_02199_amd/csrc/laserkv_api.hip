@@ -293,11 +293,10 @@ int laserkv_select_block(laserkv_ctx* ctx,
   gp.n_bits = c.lsh_bits;
   gp.n_planes = c.lsh_tables * c.lsh_bits;
   {
-    const int64_t rows = (int64_t)c.n_kv_heads * s_t + (int64_t)c.n_q_heads * w;
-    int rpw = (int)((rows + wg_target - 1) / wg_target);
-    rpw = (rpw + 31) / 32 * 32;
-    if (rpw < 32) rpw = 32;
-    gp.rows_per_wg = rpw;
+    // table groups: as few as fit the LDS plane budget, evenly sized
+    const int max_tab = lkv::sig_max_planes() / c.lsh_bits;
+    const int n_tg = (c.lsh_tables + max_tab - 1) / max_tab;
+    gp.tables_per_group = (c.lsh_tables + n_tg - 1) / n_tg;
   }
   gp.sig_k = ctx->sig_k;
   gp.sig_q = ctx->sig_q;

@@ -77,6 +77,17 @@ __device__ __forceinline__ float half_allsum(float v) {
   return v + swizzle_xor16(v);
 }
 
+// inclusive prefix sum over the 64 lanes of a wave (DPP row shifts, then row broadcasts)
+__device__ __forceinline__ int wave_incl_scan(int v) {
+  v += __builtin_amdgcn_update_dpp(0, v, 0x111, 0xf, 0xf, true);  // row_shr:1
+  v += __builtin_amdgcn_update_dpp(0, v, 0x112, 0xf, 0xf, true);  // row_shr:2
+  v += __builtin_amdgcn_update_dpp(0, v, 0x114, 0xf, 0xf, true);  // row_shr:4
+  v += __builtin_amdgcn_update_dpp(0, v, 0x118, 0xf, 0xf, true);  // row_shr:8
+  v += __builtin_amdgcn_update_dpp(0, v, 0x142, 0xa, 0xf, false); // row_bcast:15 into rows 1 and 3
+  v += __builtin_amdgcn_update_dpp(0, v, 0x143, 0xc, 0xf, false); // row_bcast:31 into rows 2 and 3
+  return v;
+}
+
 // (m, s) pairs describe sum_i 2^(x_i) as s * 2^m.
 __device__ __forceinline__ void lse_merge(float& m, float& s, float m2, float s2) {
   float mn = fmaxf(m, m2);

@@ -44,7 +44,7 @@ struct SigParams {
   int n_kv_heads, n_q_heads;
   int s_t, w;
   int n_tables, n_bits, n_planes;  // L, K, L*K
-  int rows_per_wg;     // multiple of 32
+  int tables_per_group;  // tables one workgroup hashes: tables_per_group * K <= sig_max_planes()
   uint16_t* sig_k;     // [H_kv, S, L]
   uint16_t* sig_q;     // [H_q, W, L]
   int32_t* cnt;        // [H_kv, S]: zeroed here for the count kernel's atomics
@@ -95,6 +95,7 @@ hipError_t launch_count(const CountParams& p, int n_kv_heads, hipStream_t st);
 hipError_t launch_select(const SelectParams& p, hipStream_t st);
 hipError_t launch_append(const AppendParams& p, int n_kv_heads, hipStream_t st);
 hipError_t init_kernel_attributes();
+int sig_max_planes();   // most hyperplanes one signature workgroup holds in LDS
 int score_max_range();  // most keys one score workgroup takes (its LDS holds the whole range)
 
 }  // namespace lkv

@@ -271,84 +271,128 @@ void score_kernel(ScoreParams p) {
 }
 
 // ---------------------------------------------------------------------------------------------
-// SimHash codes.  Workgroup = (row range, head); heads 0..H_kv-1 are key heads, the rest query
-// heads.  The hyperplanes are the A operand (MTS 32-row tiles per wave in registers), the vectors
-// stream through LDS 32 at a time; sign bits are packed per 32-plane word, then cut into K-bit codes.
+// SimHash codes.  Workgroup = (vector range, table group, head); heads 0..H_kv-1 are key heads, the
+// rest query heads.  Each of the NW waves keeps 32 vectors (keys or queries) as the A operand in
+// registers; the table group's hyperplanes sit in LDS as the B operand.  In this orientation an
+// accumulator register holds, across the lanes, one vector's projections on 32 consecutive planes,
+// so one compare-to-ballot per register yields that vector's 32 sign bits at once.  The words are
+// parked in LDS and cut into K-bit codes, eight tables (one 16-byte store) per lane.
 // ---------------------------------------------------------------------------------------------
-template <int DT, int D, int MTS>
-__global__ __launch_bounds__(256) void sig_kernel(SigParams p) {
+constexpr int SIG_MAX_PLANES = 192;  // planes per table group (LDS-resident)
+
+template <int DT, int D>
+__host__ __device__ constexpr size_t sig_lds_bytes(int n_waves) {
+  return (size_t)SIG_MAX_PLANES * score_row_pitch_chunks<DT, D>() * 16 + (size_t)n_waves * 32 * (SIG_MAX_PLANES / 32 + 2) * 4;
+}
+
+template <int DT, int D, int NW>
+__global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu((DT == DT_BF16 ? 2 : 4) * D <= 256 ? 4 : 2, 8)))
+void sig_kernel(SigParams p) {
   constexpr int ES = DT == DT_BF16 ? 2 : 4;
   constexpr int CH = D * ES / 16;
   constexpr int NCH = CH / 2;
-  constexpr int RT = 32;
-  constexpr int LDT = RT * CH / 256;
+  constexpr int CHP = CH + 1;
+  constexpr int NTHR = NW * 64;
+  constexpr int WPR = SIG_MAX_PLANES / 32 + 2;  // words per vector row in LDS (one spare for straddling reads)
+  constexpr int LDB = 8;
 
-  __shared__ uint4 sX[RT * CH];
-  __shared__ uint32_t sBits[RT][17];
+  extern __shared__ uint4 smem[];
+  uint4* sP = smem;                                                               // [planes][CHP]
+  uint32_t* sBits = reinterpret_cast<uint32_t*>(smem + (size_t)SIG_MAX_PLANES * CHP);  // [NW][32][WPR]
 
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, rl = lane & 31, kg = lane >> 5;
-  const bool is_key = (int)blockIdx.y < p.n_kv_heads;
-  const int head = is_key ? blockIdx.y : blockIdx.y - p.n_kv_heads;
+  const bool is_key = (int)blockIdx.z < p.n_kv_heads;
+  const int head = is_key ? blockIdx.z : blockIdx.z - p.n_kv_heads;
   const int n_rows = is_key ? p.s_t : p.w;
   const RowSrc src = is_key ? p.kb : p.q;
-  const int r0 = blockIdx.x * p.rows_per_wg;
+  const int r0 = blockIdx.x * (NW * 32);
   if (r0 >= n_rows) return;
-  const int r1 = min(r0 + p.rows_per_wg, n_rows);
+  const int tg = blockIdx.y;
+  const int t0 = tg * p.tables_per_group;
+  const int n_tab = min(p.tables_per_group, p.n_tables - t0);
+  const int plane0 = t0 * p.n_bits;
+  const int n_pl = n_tab * p.n_bits;       // planes of this group (<= SIG_MAX_PLANES)
+  const int n_tiles = (n_pl + 31) >> 5;
   uint16_t* out = (is_key ? p.sig_k : p.sig_q) + (size_t)head * n_rows * p.n_tables;
 
-  uint4 a[MTS][NCH];
+  // this wave's 32 vectors
+  uint4 a[NCH];
+  {
+    const int row = min(r0 + wave * 32 + rl, n_rows - 1);
+    const char* ptr = src.base + (int64_t)head * src.stride_head + (int64_t)row * src.stride_row;
 #pragma unroll
-  for (int mt = 0; mt < MTS; ++mt) {
-    const int pm = min((wave * MTS + mt) * 32 + rl, p.n_planes - 1);
-    const char* ptr = p.planes + (size_t)pm * D * ES;
-#pragma unroll
-    for (int i = 0; i < NCH; ++i) a[mt][i] = ld16(ptr + (2 * i + kg) * 16);
+    for (int i = 0; i < NCH; ++i) a[i] = ld16(ptr + (2 * i + kg) * 16);
   }
-  for (int t = tid; t < RT * 17; t += 256) sBits[t / 17][t % 17] = 0u;
+  // the group's planes into LDS (rows past the group are clamped copies whose bits are never read)
+  const int n_chunks = n_tiles * 32 * CH;
+  const char* pbase = p.planes + (size_t)plane0 * D * ES;
+  for (int c0 = 0; c0 < n_chunks; c0 += NTHR * LDB) {
+    uint4 pre[LDB];
+#pragma unroll
+    for (int u = 0; u < LDB; ++u) {
+      const int q = c0 + tid + NTHR * u;
+      const int row = min(q / CH, n_pl - 1), c = q % CH;
+      if (q < n_chunks) pre[u] = ld16(pbase + (size_t)row * (D * ES) + c * 16);
+    }
+#pragma unroll
+    for (int u = 0; u < LDB; ++u) {
+      const int q = c0 + tid + NTHR * u;
+      if (q < n_chunks) sP[(q / CH) * CHP + q % CH] = pre[u];
+    }
+  }
+  if (is_key && tg == 0) {
+    for (int t = tid; t < NW * 32; t += NTHR)
+      if (r0 + t < n_rows) p.cnt[(size_t)head * p.s_t + r0 + t] = 0;
+  }
+  uint32_t* myBits = sBits + (size_t)wave * 32 * WPR;
+  // vector row l (l < 32) is row acc_row(r, half) of the tile with r = 4*(l>>3) + (l&3), half = (l>>2)&1
+  const int my_r = 4 * (rl >> 3) + (rl & 3);
+  const bool my_hi = ((rl >> 2) & 1) != 0;
+  if (lane < 32) myBits[lane * WPR + n_tiles] = 0u;  // the spare word a straddling read may touch
+  __syncthreads();
 
+#pragma unroll 1
+  for (int nt = 0; nt < n_tiles; ++nt) {
+    f32x16 acc;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
+    const uint4* brow = sP + (size_t)(nt * 32 + rl) * CHP + kg;
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) Mma<DT>::run(acc, a[i], brow[2 * i]);
+    // lane l < 32 collects the word of vector row l: register r covers rows acc_row(r, 0) (low
+    // half of the ballot) and acc_row(r, 1) (high half)
+    uint64_t pick = 0u;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const uint64_t m = __ballot(acc[r] >= 0.0f);
+      pick = (my_r == r) ? m : pick;
+    }
+    if (lane < 32) myBits[lane * WPR + nt] = my_hi ? (uint32_t)(pick >> 32) : (uint32_t)pick;
+  }
+  __syncthreads();
+  // codes: lane = (vector row, group of 8 tables)
   const uint32_t code_mask = (1u << p.n_bits) - 1u;
-  const char* hbase = src.base + (int64_t)head * src.stride_head;
-  for (int rs0 = r0; rs0 < r1; rs0 += RT) {
+  const int vrow = r0 + wave * 32 + rl;
+  for (int tb = kg * 8; tb < n_tab; tb += 16) {
+    uint32_t codes[8];
 #pragma unroll
-    for (int u = 0; u < LDT; ++u) {
-      const int q = tid + 256 * u;
-      const int row = q / CH, c = q % CH;
-      const int gr = min(rs0 + row, n_rows - 1);
-      sX[row * CH + (c ^ (row & 7))] = ld16(hbase + (int64_t)gr * src.stride_row + c * 16);
+    for (int u = 0; u < 8; ++u) {
+      const int bitpos = min(tb + u, n_tab - 1) * p.n_bits;
+      const int w0 = bitpos >> 5, sh = bitpos & 31;
+      const uint64_t two = (uint64_t)myBits[rl * WPR + w0] | ((uint64_t)myBits[rl * WPR + w0 + 1] << 32);
+      codes[u] = (uint32_t)(two >> sh) & code_mask;
     }
-    __syncthreads();
-    f32x16 acc[MTS];
+    if (vrow < n_rows) {
+      uint16_t* dst = out + (size_t)vrow * p.n_tables + t0 + tb;
+      if (tb + 8 <= n_tab && ((reinterpret_cast<uintptr_t>(dst) & 15) == 0)) {
+        *reinterpret_cast<uint4*>(dst) = make_uint4(codes[0] | (codes[1] << 16), codes[2] | (codes[3] << 16),
+                                                    codes[4] | (codes[5] << 16), codes[6] | (codes[7] << 16));
+      } else {
 #pragma unroll
-    for (int mt = 0; mt < MTS; ++mt)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[mt][r] = 0.0f;
-#pragma unroll
-    for (int i = 0; i < NCH; ++i) {
-      const uint4 b = sX[rl * CH + ((2 * i + kg) ^ (rl & 7))];
-#pragma unroll
-      for (int mt = 0; mt < MTS; ++mt) Mma<DT>::run(acc[mt], a[mt][i], b);
-    }
-#pragma unroll
-    for (int mt = 0; mt < MTS; ++mt) {
-      uint32_t mask = 0u;
-#pragma unroll
-      for (int r = 0; r < 16; ++r) mask |= (acc[mt][r] >= 0.0f ? 1u : 0u) << acc_row(r, kg);
-      mask |= (uint32_t)__shfl_xor((int)mask, 32);
-      const int word = wave * MTS + mt;
-      if (kg == 0 && word < 16) sBits[rl][word] = mask;
-    }
-    __syncthreads();
-    for (int e = tid; e < RT * p.n_tables; e += 256) {
-      const int row = e / p.n_tables, t = e - row * p.n_tables;
-      const int gr = rs0 + row;
-      if (gr < r1) {
-        const int bitpos = t * p.n_bits;
-        const int w0 = bitpos >> 5, sh = bitpos & 31;
-        const uint64_t two = (uint64_t)sBits[row][w0] | ((uint64_t)sBits[row][w0 + 1] << 32);
-        out[(size_t)gr * p.n_tables + t] = (uint16_t)((uint32_t)(two >> sh) & code_mask);
+        for (int u = 0; u < 8; ++u)
+          if (tb + u < n_tab) dst[u] = (uint16_t)codes[u];
       }
     }
-    if (is_key && tid < RT && rs0 + tid < r1) p.cnt[(size_t)head * p.s_t + rs0 + tid] = 0;
   }
 }
 
@@ -389,19 +433,20 @@ __global__ __launch_bounds__(256) void count_kernel(CountParams p) {
 
 // ---------------------------------------------------------------------------------------------
 // Selection.  One 1024-thread workgroup per KV head; thread t owns the EPT consecutive positions
-// starting at t*EPT.  The k-th largest key is found bit by bit from the top (one block-wide count
-// per bit), ties at the threshold are taken in index order via a prefix count.
+// starting at t*EPT, so thread order is index order.  The k-th largest key is found by a radix
+// descent over 8-bit digits from the top (LDS histogram, four interleaved copies against same-
+// address atomics), which also yields how many keys equal to the threshold are still needed; those
+// are taken in index order via a prefix count.
 // ---------------------------------------------------------------------------------------------
 template <int EPT>
 __global__ __launch_bounds__(1024) void select_kernel(SelectParams p) {
-  __shared__ int sCnt[2][16];
-  __shared__ int sScan[16];
+  __shared__ uint32_t sHist[4][256];
+  __shared__ int sWave[16];
+  __shared__ int sPick[2];  // digit chosen in this round, keys still needed below it
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int h = blockIdx.x;
-  int round = 0;
 
-  uint32_t key[EPT];
-  int c2[EPT];
+  uint32_t key[EPT], c2[EPT];
   bool inr[EPT], cand[EPT], sel[EPT];
 #pragma unroll
   for (int e = 0; e < EPT; ++e) {
@@ -410,69 +455,81 @@ __global__ __launch_bounds__(1024) void select_kernel(SelectParams p) {
     cand[e] = inr[e] && i >= p.n_anchor && i < p.s_t - p.n_local;
     sel[e] = false;
     key[e] = 0u;
-    c2[e] = 0;
+    c2[e] = 0u;
     if (inr[e]) {
       float s = 0.0f;
       for (int qg = 0; qg < p.n_qgroups; ++qg) s += p.s_part[((size_t)qg * p.n_kv_heads + h) * p.s_t + i];
       s *= p.inv_m;
       p.s_exact[(size_t)h * p.s_t + i] = s;
-      key[e] = __float_as_uint(s);
-      c2[e] = p.cnt[(size_t)h * p.s_t + i];
+      key[e] = __float_as_uint(s);  // scores are >= 0: their bit patterns order like the values
+      c2[e] = (uint32_t)p.cnt[(size_t)h * p.s_t + i];
     }
   }
 
-  auto block_count = [&](const bool* pred) -> int {
-    int c = 0;
-#pragma unroll
-    for (int e = 0; e < EPT; ++e) c += __popcll(__ballot(pred[e]));
-    const int buf = round & 1;
-    ++round;
-    if (lane == 0) sCnt[buf][wave] = c;
-    __syncthreads();
-    int tot = 0;
-#pragma unroll
-    for (int w = 0; w < 16; ++w) tot += sCnt[buf][w];
-    return tot;
-  };
   // exclusive prefix of per-thread counts over the block, in thread (= index) order
   auto block_excl_scan = [&](int v) -> int {
-    int inc = v;
-#pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-      const int o = __shfl_up(inc, off);
-      if (lane >= off) inc += o;
-    }
-    __syncthreads();
-    if (lane == 63) sScan[wave] = inc;
+    const int inc = wave_incl_scan(v);
+    __syncthreads();  // sWave free again
+    if (lane == 63) sWave[wave] = inc;
     __syncthreads();
     int base = 0;
-    for (int w = 0; w < wave; ++w) base += sScan[w];
+#pragma unroll
+    for (int w = 0; w < 16; ++w) base += (w < wave) ? sWave[w] : 0;
     return base + inc - v;
   };
-  // marks in sel[] the k active elements ranked first by (val descending, index ascending)
-  auto take_top = [&](const uint32_t* val, const bool* active, int k, int top_bit) {
-    if (k <= 0) return;
-    bool pred[EPT];
-    uint32_t thr = 0u;
-    for (int bit = top_bit; bit >= 0; --bit) {
-      const uint32_t trial = thr | (1u << bit);
+  // marks in sel[] the k active elements ranked first by (val descending, index ascending);
+  // val < 2^(8*n_digits)
+  auto take_top = [&](const uint32_t* val, const bool* active, int k, int n_digits) {
+    if (k <= 0) return;  // block-uniform
+    uint32_t prefix = 0u, pmask = 0u;
+    int need = k;
+    for (int dg = n_digits - 1; dg >= 0; --dg) {
+      const int shift = 8 * dg;
+      // the histogram is zero here: cleared before the first use and by wave 0 after every read
 #pragma unroll
-      for (int e = 0; e < EPT; ++e) pred[e] = active[e] && val[e] >= trial;
-      if (block_count(pred) >= k) thr = trial;
+      for (int e = 0; e < EPT; ++e)
+        if (active[e] && (val[e] & pmask) == prefix) atomicAdd(&sHist[lane & 3][(val[e] >> shift) & 255u], 1u);
+      __syncthreads();
+      if (wave == 0) {
+        // lane l owns digits 4l..4l+3; walk from the top digit down
+        uint4 q[4];
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+          q[b] = *reinterpret_cast<const uint4*>(&sHist[b][4 * lane]);
+          *reinterpret_cast<uint4*>(&sHist[b][4 * lane]) = make_uint4(0u, 0u, 0u, 0u);
+        }
+        const uint32_t c[4] = {q[0].x + q[1].x + q[2].x + q[3].x, q[0].y + q[1].y + q[2].y + q[3].y,
+                               q[0].z + q[1].z + q[2].z + q[3].z, q[0].w + q[1].w + q[2].w + q[3].w};
+        const int mine = (int)(c[0] + c[1] + c[2] + c[3]);
+        const int incl = wave_incl_scan(mine);
+        const int total = __builtin_amdgcn_readlane(incl, 63);
+        int above = total - incl;  // keys in digits owned by higher lanes
+        // the digit holding the need-th largest key: above < need <= above + count
+#pragma unroll
+        for (int b = 3; b >= 0; --b) {
+          if (above < need && need <= above + (int)c[b]) {
+            sPick[0] = 4 * lane + b;
+            sPick[1] = need - above;
+          }
+          above += (int)c[b];
+        }
+      }
+      __syncthreads();
+      prefix |= (uint32_t)sPick[0] << shift;
+      pmask |= 255u << shift;
+      need = sPick[1];
     }
-#pragma unroll
-    for (int e = 0; e < EPT; ++e) pred[e] = active[e] && val[e] > thr;
-    const int need = k - block_count(pred);
+    // prefix is the k-th largest value; `need` of the keys equal to it are taken, lowest index first
     int n_eq = 0;
 #pragma unroll
-    for (int e = 0; e < EPT; ++e) n_eq += (active[e] && val[e] == thr) ? 1 : 0;
+    for (int e = 0; e < EPT; ++e) n_eq += (active[e] && val[e] == prefix) ? 1 : 0;
     int rank = block_excl_scan(n_eq);
 #pragma unroll
     for (int e = 0; e < EPT; ++e) {
       if (active[e]) {
-        if (val[e] > thr) {
+        if (val[e] > prefix) {
           sel[e] = true;
-        } else if (val[e] == thr) {
+        } else if (val[e] == prefix) {
           if (rank < need) sel[e] = true;
           ++rank;
         }
@@ -480,15 +537,13 @@ __global__ __launch_bounds__(1024) void select_kernel(SelectParams p) {
     }
   };
 
-  take_top(key, cand, p.k_exact, 30);
+  sHist[tid >> 8][tid & 255] = 0u;
+  __syncthreads();
+  take_top(key, cand, p.k_exact, 4);
   bool act2[EPT];
-  uint32_t v2[EPT];
 #pragma unroll
-  for (int e = 0; e < EPT; ++e) {
-    act2[e] = cand[e] && !sel[e];
-    v2[e] = (uint32_t)c2[e];
-  }
-  take_top(v2, act2, p.k_lsh, p.cnt_bits - 1);
+  for (int e = 0; e < EPT; ++e) act2[e] = cand[e] && !sel[e];
+  take_top(c2, act2, p.k_lsh, (p.cnt_bits + 7) >> 3);
 
   int n_keep = 0;
 #pragma unroll
@@ -570,18 +625,19 @@ hipError_t launch_score(int dtype, int head_dim, const ScoreParams& p, int nq, i
 
 template <int DT, int D>
 static hipError_t launch_sig_t(const SigParams& p, hipStream_t st) {
-  const int n_mt = (p.n_planes + 31) / 32;
-  const int mts = (n_mt + 3) / 4;
+  constexpr int NW = 8;
   const int max_rows = p.s_t > p.w ? p.s_t : p.w;
-  dim3 grid((max_rows + p.rows_per_wg - 1) / p.rows_per_wg, p.n_kv_heads + p.n_q_heads);
-  switch (mts) {
-    case 1: hipLaunchKernelGGL((sig_kernel<DT, D, 1>), grid, dim3(256), 0, st, p); break;
-    case 2: hipLaunchKernelGGL((sig_kernel<DT, D, 2>), grid, dim3(256), 0, st, p); break;
-    case 3: hipLaunchKernelGGL((sig_kernel<DT, D, 3>), grid, dim3(256), 0, st, p); break;
-    case 4: hipLaunchKernelGGL((sig_kernel<DT, D, 4>), grid, dim3(256), 0, st, p); break;
-    default: return hipErrorInvalidValue;
-  }
+  const int n_tg = (p.n_tables + p.tables_per_group - 1) / p.tables_per_group;
+  dim3 grid((max_rows + NW * 32 - 1) / (NW * 32), n_tg, p.n_kv_heads + p.n_q_heads);
+  const size_t lds = sig_lds_bytes<DT, D>(NW);
+  hipLaunchKernelGGL((sig_kernel<DT, D, NW>), grid, dim3(NW * 64), lds, st, p);
   return hipGetLastError();
+}
+
+template <int DT, int D>
+static hipError_t sig_attrs() {
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(&sig_kernel<DT, D, 8>),
+                             hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
 }
 
 hipError_t launch_sig(int dtype, int head_dim, const SigParams& p, hipStream_t st) {
@@ -599,10 +655,15 @@ hipError_t init_kernel_attributes() {
   if (e == hipSuccess) e = score_attrs<DT_BF16, 64>();
   if (e == hipSuccess) e = score_attrs<DT_F32, 128>();
   if (e == hipSuccess) e = score_attrs<DT_F32, 64>();
+  if (e == hipSuccess) e = sig_attrs<DT_BF16, 128>();
+  if (e == hipSuccess) e = sig_attrs<DT_BF16, 64>();
+  if (e == hipSuccess) e = sig_attrs<DT_F32, 128>();
+  if (e == hipSuccess) e = sig_attrs<DT_F32, 64>();
   return e;
 }
 
 int score_max_range() { return SCORE_MAX_RANGE; }
+int sig_max_planes() { return SIG_MAX_PLANES; }
 
 hipError_t launch_count(const CountParams& p, int n_kv_heads, hipStream_t st) {
   const int n_tg = (p.n_tables + p.tables_per_group - 1) / p.tables_per_group;
