@@ -134,13 +134,12 @@ int laserkv_append(laserkv_ctx* ctx,
  * LKV_N_KERNELS entries.  At most LKV_PROFILE_MAX_LAUNCHES launches are recorded per bracket;
  * later ones run untimed.  Errors: LKV_EINVAL (null / not begun), LKV_EHIP. */
 typedef enum {
-  LKV_KERN_SIG = 0,    /* SimHash codes of keys and window queries */
-  LKV_KERN_STATS = 1,  /* exact score, sweep 1: row maxima and sums */
-  LKV_KERN_SCORE = 2,  /* exact score, sweep 2: pooled probabilities */
-  LKV_KERN_COUNT = 3,  /* collision counts */
-  LKV_KERN_SELECT = 4, /* two-stage TopK and compaction */
-  LKV_KERN_APPEND = 5, /* gather-append */
-  LKV_N_KERNELS = 6
+  LKV_KERN_SWEEP1 = 0, /* exact score sweep 1 (row maxima and sums) + SimHash codes of keys and queries */
+  LKV_KERN_SWEEP2 = 1, /* exact score sweep 2: pooled probabilities */
+  LKV_KERN_COUNT = 2,  /* collision counts */
+  LKV_KERN_SELECT = 3, /* two-stage TopK and compaction */
+  LKV_KERN_APPEND = 4, /* gather-append */
+  LKV_N_KERNELS = 5
 } laserkv_kernel_id;
 #define LKV_PROFILE_MAX_LAUNCHES 8192
 

@@ -21,7 +21,7 @@ EXPORTS = (
     "laserkv_partition", "laserkv_select_block", "laserkv_append",
     "laserkv_profile_begin", "laserkv_profile_end",
 )
-KERNEL_NAMES = ("sig", "stats", "score", "count", "select", "append")
+KERNEL_NAMES = ("sweep1", "sweep2", "count", "select", "append")
 
 
 class LaserKVError(RuntimeError):

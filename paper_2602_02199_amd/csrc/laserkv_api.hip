@@ -246,31 +246,39 @@ int laserkv_select_block(laserkv_ctx* ctx,
   const int m_rows = G * w;
   const int n_keys = t_ctx + s_t;
 
-  lkv::ScoreParams sp;
+  lkv::PassParams sp;
   sp.q = {(const char*)q_win, q_stride_head * es, q_stride_tok * es};
   sp.kb = {(const char*)k_blk, k_stride_head * es, k_stride_tok * es};
   sp.kc = {(const char*)k_ctx, c_stride_head * es, c_stride_tok * es};
+  sp.planes = (const char*)hyperplanes;
   sp.group = G;
   sp.w = w;
   sp.m_rows = m_rows;
   sp.s_t = s_t;
   sp.t_ctx = t_ctx;
-  sp.n_keys = n_keys;
-  sp.rows_per_group = m_rows > 128 ? 256 : 128;
-  if (env_int("LASERKV_SCORE_MQ", 0) == 128) sp.rows_per_group = 128;
+  sp.rows_per_group = m_rows > 256 ? 512 : (m_rows > 128 ? 256 : 128);
+  {
+    const int forced = env_int("LASERKV_SWEEP_ROWS", 0);
+    if (forced == 128 || forced == 256 || forced == 512) sp.rows_per_group = forced;
+  }
   const int n_qg = (m_rows + sp.rows_per_group - 1) / sp.rows_per_group;
   sp.n_qgroups = n_qg;
   sp.n_kv_heads = c.n_kv_heads;
-  // key ranges: aim at a few workgroups per compute unit
-  const int wg_target = ctx->n_cu * env_int("LASERKV_SCORE_WG_PER_CU", 2);
+  // key ranges: about one workgroup per compute unit per query-row group, each range in one source
+  const int wg_target = ctx->n_cu * env_int("LASERKV_SWEEP_WG_PER_CU", 1);
   int nr = wg_target / (c.n_kv_heads * n_qg);
   if (nr < 1) nr = 1;
   if (nr > ctx->max_ranges - 1) nr = ctx->max_ranges - 1;
   int nk = ((n_keys + nr - 1) / nr + 31) / 32 * 32;
   if (nk > lkv::score_max_range()) nk = lkv::score_max_range();
-  sp.keys_per_range = nk;
-  sp.n_ctx_ranges = (t_ctx + nk - 1) / nk;
-  sp.n_ranges = sp.n_ctx_ranges + (s_t + nk - 1) / nk;
+  for (;;) {
+    sp.keys_per_range = nk;
+    sp.n_ctx_ranges = (t_ctx + nk - 1) / nk;
+    sp.n_ranges = sp.n_ctx_ranges + (s_t + nk - 1) / nk;
+    sp.q_rows_per_wg = (m_rows + sp.n_ranges - 1) / sp.n_ranges;
+    if (nk <= 32 || lkv::sweep_lds_bytes(c.dtype, d, sp.rows_per_group, nk, sp.q_rows_per_wg) <= 150 * 1024) break;
+    nk -= 32;
+  }
   if (sp.n_ranges > ctx->max_ranges) return fail(ctx, LKV_EINVAL, "select_block: internal range split too fine");
   sp.causal = causal ? 1 : 0;
   int64_t lim0 = (int64_t)t_ctx + (q_pos0 - block_pos0);
@@ -280,27 +288,12 @@ int laserkv_select_block(laserkv_ctx* ctx,
   sp.part = ctx->part;
   sp.m_pad = ctx->m_pad;
   sp.s_part = ctx->s_part;
-
-  lkv::SigParams gp;
-  gp.kb = sp.kb;
-  gp.q = sp.q;
-  gp.planes = (const char*)hyperplanes;
-  gp.n_kv_heads = c.n_kv_heads;
-  gp.n_q_heads = c.n_q_heads;
-  gp.s_t = s_t;
-  gp.w = w;
-  gp.n_tables = c.lsh_tables;
-  gp.n_bits = c.lsh_bits;
-  gp.n_planes = c.lsh_tables * c.lsh_bits;
-  {
-    // table groups: as few as fit the LDS plane budget, evenly sized
-    const int max_tab = lkv::sig_max_planes() / c.lsh_bits;
-    const int n_tg = (c.lsh_tables + max_tab - 1) / max_tab;
-    gp.tables_per_group = (c.lsh_tables + n_tg - 1) / n_tg;
-  }
-  gp.sig_k = ctx->sig_k;
-  gp.sig_q = ctx->sig_q;
-  gp.cnt = ctx->cnt;
+  sp.n_tables = c.lsh_tables;
+  sp.n_bits = c.lsh_bits;
+  sp.n_planes = c.lsh_tables * c.lsh_bits;
+  sp.sig_k = ctx->sig_k;
+  sp.sig_q = ctx->sig_q;
+  sp.cnt = ctx->cnt;
 
   lkv::CountParams cp;
   cp.sig_k = ctx->sig_k;
@@ -341,12 +334,10 @@ int laserkv_select_block(laserkv_ctx* ctx,
 
   hipError_t e;
   const int nh = c.n_kv_heads, dt = c.dtype;
-  if ((e = timed(ctx, LKV_KERN_SIG, st, [&] { return lkv::launch_sig(dt, d, gp, st); })) != hipSuccess)
-    return fail_hip(ctx, e, "select_block: signature kernel");
-  if ((e = timed(ctx, LKV_KERN_STATS, st, [&] { return lkv::launch_stats(dt, d, sp, n_qg, nh, st); })) != hipSuccess)
-    return fail_hip(ctx, e, "select_block: score sweep 1");
-  if ((e = timed(ctx, LKV_KERN_SCORE, st, [&] { return lkv::launch_score(dt, d, sp, n_qg, nh, st); })) != hipSuccess)
-    return fail_hip(ctx, e, "select_block: score sweep 2");
+  if ((e = timed(ctx, LKV_KERN_SWEEP1, st, [&] { return lkv::launch_sweep1(dt, d, sp, st); })) != hipSuccess)
+    return fail_hip(ctx, e, "select_block: sweep 1 (row statistics + SimHash codes)");
+  if ((e = timed(ctx, LKV_KERN_SWEEP2, st, [&] { return lkv::launch_sweep2(dt, d, sp, st); })) != hipSuccess)
+    return fail_hip(ctx, e, "select_block: sweep 2 (pooled probabilities)");
   if ((e = timed(ctx, LKV_KERN_COUNT, st, [&] { return lkv::launch_count(cp, nh, st); })) != hipSuccess)
     return fail_hip(ctx, e, "select_block: count kernel");
   if ((e = timed(ctx, LKV_KERN_SELECT, st, [&] { return lkv::launch_select(lp, st); })) != hipSuccess)

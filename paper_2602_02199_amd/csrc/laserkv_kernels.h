@@ -13,41 +13,34 @@ struct RowSrc {
   int64_t stride_row;   // bytes
 };
 
-struct ScoreParams {
+struct PassParams {
   RowSrc q;        // [H_q, W, d]
   RowSrc kb;       // [H_kv, S, d]
   RowSrc kc;       // [H_kv, T, d] (base may be null when T == 0)
+  const char* planes;   // [L*K, d] contiguous
   int group;       // G
   int w;           // W
   int m_rows;      // M = G * W
   int s_t;         // S
   int t_ctx;       // T
-  int n_keys;      // T + S
-  int keys_per_range;   // NK (multiple of 32)
+  int keys_per_range;   // NK (multiple of 32, <= score_max_range())
   int n_ranges;         // NR = n_ctx_ranges + ranges over the block keys
   int n_ctx_ranges;     // ranges that cover the look-back keys (each range lies in one source)
-  int rows_per_group;   // MQ = 32 * waves per workgroup (128 or 256)
+  int rows_per_group;   // MQ = 32 * waves per workgroup (128, 256 or 512)
   int n_qgroups;        // ceil(M / MQ)
   int n_kv_heads;
   int causal;
   int lim0;        // key index kidx is visible to window row j iff kidx <= lim0 + j (when causal)
   float scale2;    // log2(e) / sqrt(d)
-  float2* part;    // [H_kv, NR, m_pad] partial (max, sum) in the exp2 domain
+  float2* part;    // [H_kv, NR, m_pad] sweep-1 partials (reference, sum) in the exp2 domain
   int m_pad;       // row pitch of part
-  float* s_part;   // [n_qgroups, H_kv, S] partial pooled probabilities
-};
-
-struct SigParams {
-  RowSrc kb;       // keys  [H_kv, S, d]
-  RowSrc q;        // queries [H_q, W, d]
-  const char* planes;  // [L*K, d] contiguous
-  int n_kv_heads, n_q_heads;
-  int s_t, w;
-  int n_tables, n_bits, n_planes;  // L, K, L*K
-  int tables_per_group;  // tables one workgroup hashes: tables_per_group * K <= sig_max_planes()
-  uint16_t* sig_k;     // [H_kv, S, L]
-  uint16_t* sig_q;     // [H_q, W, L]
-  int32_t* cnt;        // [H_kv, S]: zeroed here for the count kernel's atomics
+  float* s_part;   // [n_qgroups, H_kv, S] sweep-2 pooled probabilities (sum over the group's rows)
+  // hashing (sweep 1)
+  int n_tables, n_bits, n_planes;  // L, K, L*K (<= 512)
+  int q_rows_per_wg;    // window rows of the head hashed by each key range's workgroup
+  uint16_t* sig_k;      // [H_kv, S, L]
+  uint16_t* sig_q;      // [H_q, W, L] = [H_kv, M, L]
+  int32_t* cnt;         // [H_kv, S]: zeroed in sweep 1 for the count kernel's atomics
 };
 
 struct CountParams {
@@ -88,14 +81,13 @@ struct AppendParams {
   int64_t block_pos0;
 };
 
-hipError_t launch_stats(int dtype, int head_dim, const ScoreParams& p, int n_qgroups, int n_kv_heads, hipStream_t st);
-hipError_t launch_score(int dtype, int head_dim, const ScoreParams& p, int n_qgroups, int n_kv_heads, hipStream_t st);
-hipError_t launch_sig(int dtype, int head_dim, const SigParams& p, hipStream_t st);
+hipError_t launch_sweep1(int dtype, int head_dim, const PassParams& p, hipStream_t st);
+hipError_t launch_sweep2(int dtype, int head_dim, const PassParams& p, hipStream_t st);
 hipError_t launch_count(const CountParams& p, int n_kv_heads, hipStream_t st);
 hipError_t launch_select(const SelectParams& p, hipStream_t st);
 hipError_t launch_append(const AppendParams& p, int n_kv_heads, hipStream_t st);
 hipError_t init_kernel_attributes();
-int sig_max_planes();   // most hyperplanes one signature workgroup holds in LDS
+size_t sweep_lds_bytes(int dtype, int head_dim, int rows_per_group, int range_keys, int q_rows_per_wg);
 int score_max_range();  // most keys one score workgroup takes (its LDS holds the whole range)
 
 }  // namespace lkv

@@ -20,51 +20,54 @@
 namespace lkv {
 
 // ---------------------------------------------------------------------------------------------
-// Exact score, both sweeps.  Workgroup = (key range, query-row group, KV head) with NW waves.
+// The two sweeps over a block's keys.  Workgroup = (key range, query-row group, KV head), NW waves.
 //
-// The whole key range of the workgroup (<= 256 keys) is fetched into LDS up front: a range is only
-// microseconds of work, so what matters is having all of its loads in flight at once rather than a
-// staged pipeline whose every stage would wait a full HBM round trip.  After one barrier each wave
-// walks the range's 32-key tiles on its own: A fragments of ONE 32-row query tile stay in registers,
-// B fragments come from LDS (row pitch padded by one 16-byte chunk: conflict-free reads at
-// base + immediate addresses).  Everything is sized for <= 128 registers per lane so that four
-// waves share a SIMD: one wave alone issues a vector instruction only every ~10 clocks, so the
-// softmax arithmetic needs that many waves to keep the ALU and the matrix pipe busy.
+//   sweep 1 (PASS2 = false): per window row, partial softmax statistics over the range (Alg. 1
+//            step 3, normaliser), then the SimHash codes of the range's keys and of this
+//            workgroup's share of the window queries (Sec. 3.3 "Recall") from the SAME LDS tile:
+//            the block's keys are read from HBM once for both contractions.
+//   sweep 2 (PASS2 = true):  pooled softmax probability of every key of the range (Alg. 1 step 3).
+//
+// The whole range (<= SCORE_MAX_RANGE keys) is fetched into LDS up front: a range is microseconds
+// of work, so what matters is having all of its loads in flight at once.  After one barrier each
+// wave walks the range's 32-key tiles on its own: A fragments of ONE 32-row query tile stay in
+// registers, B fragments come from LDS (row pitch padded by one 16-byte chunk: conflict-free reads
+// at base + immediate addresses).  Everything is sized for <= 128 registers per lane so that four
+// waves share a SIMD: one wave alone issues a vector instruction only every ~10 clocks.
 //
 // Sweep 1 keeps, per window row, sum_i 2^(x_i - ref) against a reference ref shared by the 32 lanes
 // that hold the row; ref starts as the row maximum of the first tile and is raised (with the sum
 // rescaled) only when a logit exceeds it by more than 2^64, so the common case costs one fma, one
 // max, one exp and one add per logit.  Sweep 2 needs one fma, one exp and one add per logit.
+//
+// Hashing: wave w takes the 32-plane tiles w, w+NW, ... as the A operand (registers) against the
+// same LDS rows; lane = vector, so 16 compares per tile give 16 of its sign bits and one exchange
+// with the partner lane completes the 32-bit word of that vector and plane tile.
 // ---------------------------------------------------------------------------------------------
 constexpr int SCORE_MAX_RANGE = 256;  // keys per workgroup at most
+constexpr int BITS_PITCH = 17;        // words per vector row in the sign-bit scratch (<= 16 plane tiles)
 
 template <int DT, int D>
-__host__ __device__ constexpr int score_row_pitch_chunks() { return D * (DT == DT_BF16 ? 2 : 4) / 16 + 1; }
+__host__ __device__ constexpr int row_pitch_chunks() { return D * (DT == DT_BF16 ? 2 : 4) / 16 + 1; }
 
-// dynamic LDS of a score workgroup: key rows, per-wave column sums (sweep 2), row limits and lse
-template <int DT, int D, int NW>
-__host__ __device__ constexpr size_t score_lds_bytes(int range_keys) {
-  return (size_t)range_keys * score_row_pitch_chunks<DT, D>() * 16 + (size_t)NW * range_keys * 4 + (size_t)NW * 32 * 8;
+// dynamic LDS of a sweep workgroup
+template <int DT, int D, int NW, bool PASS2>
+__host__ __device__ constexpr size_t pass_lds_bytes(int range_keys, int q_tile_rows) {
+  const size_t rows = (size_t)range_keys + (PASS2 ? 0 : q_tile_rows);
+  return rows * row_pitch_chunks<DT, D>() * 16 + (PASS2 ? (size_t)NW * range_keys * 4 : rows * BITS_PITCH * 4) + (size_t)NW * 32 * 8;
 }
 
 template <int DT, int D, int NW, bool PASS2>
 __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu((DT == DT_BF16 ? 2 : 4) * D <= 256 ? 4 : 2, 8)))
-void score_kernel(ScoreParams p) {
+void pass_kernel(PassParams p) {
   constexpr int ES = DT == DT_BF16 ? 2 : 4;
   constexpr int CH = D * ES / 16;  // 16-byte chunks per row
   constexpr int NCH = CH / 2;      // chunk pairs per tile
   constexpr int CHP = CH + 1;      // LDS row pitch in chunks
   constexpr int NTHR = NW * 64;
   constexpr int MQ = 32 * NW;      // query rows per workgroup
-  constexpr int LDB = 8;           // 16-byte loads a thread keeps in flight per round
+  constexpr int LDB = 4;           // 16-byte loads a thread keeps in flight per round
   constexpr float RESCALE_AT = 64.0f;
-
-  extern __shared__ uint4 smem[];
-  const int nkr = p.keys_per_range;
-  uint4* sK = smem;                                             // [nkr][CHP]
-  float* sCol = reinterpret_cast<float*>(smem + (size_t)nkr * CHP);  // [NW][nkr]
-  int* sLim = reinterpret_cast<int*>(sCol + (size_t)NW * nkr);      // [MQ]
-  float* sLse = reinterpret_cast<float*>(sLim + MQ);               // [MQ]
 
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, rl = lane & 31, kg = lane >> 5;
   LKV_TS(0);
@@ -86,6 +89,7 @@ void score_kernel(ScoreParams p) {
     h = pair / p.n_ranges;
     kr = pair - h * p.n_ranges;
   }
+  const int nkr = p.keys_per_range;
   // a range lies entirely in the look-back keys or entirely in the block keys, so the source
   // base, stride and row offset are uniform over the workgroup
   const bool in_ctx = kr < p.n_ctx_ranges;
@@ -98,68 +102,110 @@ void score_kernel(ScoreParams p) {
   const char* kbase_ptr = ksrc.base + (int64_t)h * ksrc.stride_head;
   const int kstride = (int)ksrc.stride_row;
   const int n_tiles = (n_keys_wg + 31) >> 5;
-  const int n_chunks = n_tiles * 32 * CH;  // rows past the range are clamped copies (masked later)
+  // window queries this workgroup hashes (sweep 1, first query-row group only)
+  const bool do_hash = !PASS2 && qg == 0;
+  const int hq0 = kr * p.q_rows_per_wg;
+  const int n_hq = do_hash ? max(0, min(p.q_rows_per_wg, p.m_rows - hq0)) : 0;
+  const int n_hq_tiles = (n_hq + 31) >> 5;
+  const int q_tile_rows = PASS2 ? 0 : ((p.q_rows_per_wg + 31) & ~31);
 
-  // 1. all key loads of the range in flight (rounds of LDB per thread), then into LDS
-  for (int c0 = 0; c0 < n_chunks; c0 += NTHR * LDB) {
-    uint4 pre[LDB];
-#pragma unroll
-    for (int u = 0; u < LDB; ++u) {
-      const int q = c0 + tid + NTHR * u;
-      const int row = q / CH, c = q % CH;
-      const int lrow = min(seg_row0 + row, seg_rows - 1);
-      if (q < n_chunks) pre[u] = ld16(kbase_ptr + (uint32_t)(lrow * kstride + c * 16));
-    }
-    if (c0 == 0) {
-      // row set-up overlaps the first round's latency
-      for (int t = tid; t < MQ; t += NTHR) {
-        const int m = qg * MQ + t;
-        const int j = (m < p.m_rows) ? m % p.w : 0;
-        sLim[t] = p.causal ? p.lim0 + j : INT_MAX;
-        if (PASS2) {
-          float lse = 1.0e30f;  // rows past M are padding: probability 0
-          if (m < p.m_rows) {
-            const float2* pp = p.part + (size_t)h * p.n_ranges * p.m_pad + m;
-            float mm = NEG_BIG, ss = 0.0f;
-            int r = 0;
-            for (; r + 8 <= p.n_ranges; r += 8) {
-              float2 v[8];
-#pragma unroll
-              for (int u = 0; u < 8; ++u) v[u] = pp[(size_t)(r + u) * p.m_pad];
-#pragma unroll
-              for (int u = 0; u < 8; ++u) lse_merge(mm, ss, v[u].x, v[u].y);
-            }
-            for (; r < p.n_ranges; ++r) {
-              const float2 v = pp[(size_t)r * p.m_pad];
-              lse_merge(mm, ss, v.x, v.y);
-            }
-            lse = mm + fast_log2(ss);
-          }
-          sLse[t] = lse;
-        }
-      }
-    }
-#pragma unroll
-    for (int u = 0; u < LDB; ++u) {
-      const int q = c0 + tid + NTHR * u;
-      const int row = q / CH, c = q % CH;
-      if (q < n_chunks) sK[row * CHP + c] = pre[u];
-    }
-  }
-  LKV_TS(1);
+  extern __shared__ uint4 smem[];
+  uint4* sK = smem;                                                    // [nkr + q_tile_rows][CHP]
+  char* after_rows = reinterpret_cast<char*>(smem + (size_t)(nkr + q_tile_rows) * CHP);
+  float* sCol = reinterpret_cast<float*>(after_rows);                  // sweep 2: [NW][nkr]
+  uint32_t* sBits = reinterpret_cast<uint32_t*>(after_rows);           // sweep 1: [nkr + q_tile_rows][BITS_PITCH]
+  int* sLim = reinterpret_cast<int*>(after_rows + (PASS2 ? (size_t)NW * nkr * 4 : (size_t)(nkr + q_tile_rows) * BITS_PITCH * 4));  // [MQ]
+  float* sLse = reinterpret_cast<float*>(sLim + MQ);                   // [MQ]
 
-  // 2. this wave's query tile
-  uint4 a[NCH];
+  // 1. everything this workgroup reads from memory, issued back to back
+  uint4 a[NCH];  // this wave's query tile
   {
     const int m = qg * MQ + wave * 32 + rl;
     const int mc = min(m, p.m_rows - 1);
     const int g = mc / p.w, j = mc - g * p.w;
     const char* ptr = p.q.base + (int64_t)(h * p.group + g) * p.q.stride_head + (int64_t)j * p.q.stride_row;
+#ifdef LKV_EXP_SKIP_A
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) a[i] = make_uint4(tid, i, 0x3f803f80u, 0x3f803f80u);
+#else
 #pragma unroll
     for (int i = 0; i < NCH; ++i) a[i] = ld16(ptr + (2 * i + kg) * 16);
+#endif
+  }
+  LKV_TS(5);
+  {
+    // key rows (rows past the range are clamped copies, masked later) and hashed query rows
+    const int n_kchunks = n_tiles * 32 * CH;
+    const int n_chunks = n_kchunks + n_hq_tiles * 32 * CH;
+    for (int c0 = 0; c0 < n_chunks; c0 += NTHR * LDB) {
+      uint4 pre[LDB];
+#pragma unroll
+      for (int u = 0; u < LDB; ++u) {
+        const int q = c0 + tid + NTHR * u;
+        if (q < n_kchunks) {
+          const int row = q / CH, c = q % CH;
+          const int lrow = min(seg_row0 + row, seg_rows - 1);
+#ifdef LKV_EXP_SKIP_K
+          pre[u] = make_uint4(lrow, c, 0x3f803f80u, 0x3f803f80u);
+#else
+          pre[u] = ld16(kbase_ptr + (uint32_t)(lrow * kstride + c * 16));
+#endif
+        } else if (q < n_chunks) {
+          const int qq = q - n_kchunks;
+          const int row = qq / CH, c = qq % CH;
+          const int m = min(hq0 + row, p.m_rows - 1);
+          const int g = m / p.w, j = m - g * p.w;
+          pre[u] = ld16(p.q.base + (int64_t)(h * p.group + g) * p.q.stride_head + (int64_t)j * p.q.stride_row + c * 16);
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < LDB; ++u) {
+        const int q = c0 + tid + NTHR * u;
+        if (q < n_kchunks) {
+          sK[(q / CH) * CHP + q % CH] = pre[u];
+        } else if (q < n_chunks) {
+          const int qq = q - n_kchunks;
+          sK[(nkr + qq / CH) * CHP + qq % CH] = pre[u];
+        }
+      }
+    }
+  }
+  LKV_TS(6);
+  for (int t = tid; t < MQ; t += NTHR) {
+    const int m = qg * MQ + t;
+    const int j = (m < p.m_rows) ? m % p.w : 0;
+    sLim[t] = p.causal ? p.lim0 + j : INT_MAX;
+  }
+  if (PASS2) {
+    // row log-sum-exp from the sweep-1 partials: two threads per row, half of the ranges each
+    for (int t2 = tid; t2 < 2 * MQ; t2 += NTHR) {
+      const int t = t2 >> 1, half = t2 & 1;
+      const int m = qg * MQ + t;
+      float mm = NEG_BIG, ss = 0.0f;
+      if (m < p.m_rows) {
+        const float2* pp = p.part + (size_t)h * p.n_ranges * p.m_pad + m;
+        const int r_mid = (p.n_ranges + 1) >> 1;
+        const int r_beg = half ? r_mid : 0, r_end = half ? p.n_ranges : r_mid;
+        int r = r_beg;
+        for (; r + 8 <= r_end; r += 8) {
+          float2 v[8];
+#pragma unroll
+          for (int u = 0; u < 8; ++u) v[u] = pp[(size_t)(r + u) * p.m_pad];
+#pragma unroll
+          for (int u = 0; u < 8; ++u) lse_merge(mm, ss, v[u].x, v[u].y);
+        }
+        for (; r < r_end; ++r) {
+          const float2 v = pp[(size_t)r * p.m_pad];
+          lse_merge(mm, ss, v.x, v.y);
+        }
+      }
+      const float m2 = __shfl_xor(mm, 1), s2 = __shfl_xor(ss, 1);
+      lse_merge(mm, ss, m2, s2);
+      if (half == 0) sLse[t] = (m < p.m_rows) ? mm + fast_log2(ss) : 1.0e30f;  // padding rows: probability 0
+    }
   }
   __syncthreads();
-  LKV_TS(2);
+  LKV_TS(1);
 
   float ref[16], sum[16];  // sweep 1: (reference, sum); sweep 2: ref holds the row lse
 #pragma unroll
@@ -167,9 +213,8 @@ void score_kernel(ScoreParams p) {
     ref[r] = PASS2 ? sLse[wave * 32 + acc_row(r, kg)] : NEG_BIG;
     sum[r] = 0.0f;
   }
-  LKV_TS(3);
 
-  // 3. the range's tiles; rolled on purpose (microsecond kernels start from a cold instruction cache)
+  // 2. the range's tiles; rolled on purpose (microsecond kernels start from a cold instruction cache)
 #pragma unroll 1
   for (int nt = 0; nt < n_tiles; ++nt) {
     const int kbase = k0 + nt * 32;
@@ -246,7 +291,7 @@ void score_kernel(ScoreParams p) {
       for (int r = 0; r < 16; ++r) sum[r] += fast_exp2(acc[r]);
     }
   }
-  LKV_TS(4);
+  LKV_TS(2);
 
   if (PASS2) {
     __syncthreads();
@@ -266,134 +311,72 @@ void score_kernel(ScoreParams p) {
       const int row = qg * MQ + wave * 32 + acc_row(r, kg);
       if (rl == 0 && row < p.m_rows) p.part[((size_t)h * p.n_ranges + kr) * p.m_pad + row] = make_float2(ref[r], s);
     }
-  }
-  LKV_TS(5);
-}
+    LKV_TS(3);
 
-// ---------------------------------------------------------------------------------------------
-// SimHash codes.  Workgroup = (vector range, table group, head); heads 0..H_kv-1 are key heads, the
-// rest query heads.  Each of the NW waves keeps 32 vectors (keys or queries) as the A operand in
-// registers; the table group's hyperplanes sit in LDS as the B operand.  In this orientation an
-// accumulator register holds, across the lanes, one vector's projections on 32 consecutive planes,
-// so one compare-to-ballot per register yields that vector's 32 sign bits at once.  The words are
-// parked in LDS and cut into K-bit codes, eight tables (one 16-byte store) per lane.
-// ---------------------------------------------------------------------------------------------
-constexpr int SIG_MAX_PLANES = 192;  // planes per table group (LDS-resident)
-
-template <int DT, int D>
-__host__ __device__ constexpr size_t sig_lds_bytes(int n_waves) {
-  return (size_t)SIG_MAX_PLANES * score_row_pitch_chunks<DT, D>() * 16 + (size_t)n_waves * 32 * (SIG_MAX_PLANES / 32 + 2) * 4;
-}
-
-template <int DT, int D, int NW>
-__global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu((DT == DT_BF16 ? 2 : 4) * D <= 256 ? 4 : 2, 8)))
-void sig_kernel(SigParams p) {
-  constexpr int ES = DT == DT_BF16 ? 2 : 4;
-  constexpr int CH = D * ES / 16;
-  constexpr int NCH = CH / 2;
-  constexpr int CHP = CH + 1;
-  constexpr int NTHR = NW * 64;
-  constexpr int WPR = SIG_MAX_PLANES / 32 + 2;  // words per vector row in LDS (one spare for straddling reads)
-  constexpr int LDB = 8;
-
-  extern __shared__ uint4 smem[];
-  uint4* sP = smem;                                                               // [planes][CHP]
-  uint32_t* sBits = reinterpret_cast<uint32_t*>(smem + (size_t)SIG_MAX_PLANES * CHP);  // [NW][32][WPR]
-
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, rl = lane & 31, kg = lane >> 5;
-  const bool is_key = (int)blockIdx.z < p.n_kv_heads;
-  const int head = is_key ? blockIdx.z : blockIdx.z - p.n_kv_heads;
-  const int n_rows = is_key ? p.s_t : p.w;
-  const RowSrc src = is_key ? p.kb : p.q;
-  const int r0 = blockIdx.x * (NW * 32);
-  if (r0 >= n_rows) return;
-  const int tg = blockIdx.y;
-  const int t0 = tg * p.tables_per_group;
-  const int n_tab = min(p.tables_per_group, p.n_tables - t0);
-  const int plane0 = t0 * p.n_bits;
-  const int n_pl = n_tab * p.n_bits;       // planes of this group (<= SIG_MAX_PLANES)
-  const int n_tiles = (n_pl + 31) >> 5;
-  uint16_t* out = (is_key ? p.sig_k : p.sig_q) + (size_t)head * n_rows * p.n_tables;
-
-  // this wave's 32 vectors
-  uint4 a[NCH];
-  {
-    const int row = min(r0 + wave * 32 + rl, n_rows - 1);
-    const char* ptr = src.base + (int64_t)head * src.stride_head + (int64_t)row * src.stride_row;
-#pragma unroll
-    for (int i = 0; i < NCH; ++i) a[i] = ld16(ptr + (2 * i + kg) * 16);
-  }
-  // the group's planes into LDS (rows past the group are clamped copies whose bits are never read)
-  const int n_chunks = n_tiles * 32 * CH;
-  const char* pbase = p.planes + (size_t)plane0 * D * ES;
-  for (int c0 = 0; c0 < n_chunks; c0 += NTHR * LDB) {
-    uint4 pre[LDB];
-#pragma unroll
-    for (int u = 0; u < LDB; ++u) {
-      const int q = c0 + tid + NTHR * u;
-      const int row = min(q / CH, n_pl - 1), c = q % CH;
-      if (q < n_chunks) pre[u] = ld16(pbase + (size_t)row * (D * ES) + c * 16);
-    }
-#pragma unroll
-    for (int u = 0; u < LDB; ++u) {
-      const int q = c0 + tid + NTHR * u;
-      if (q < n_chunks) sP[(q / CH) * CHP + q % CH] = pre[u];
-    }
-  }
-  if (is_key && tg == 0) {
-    for (int t = tid; t < NW * 32; t += NTHR)
-      if (r0 + t < n_rows) p.cnt[(size_t)head * p.s_t + r0 + t] = 0;
-  }
-  uint32_t* myBits = sBits + (size_t)wave * 32 * WPR;
-  // vector row l (l < 32) is row acc_row(r, half) of the tile with r = 4*(l>>3) + (l&3), half = (l>>2)&1
-  const int my_r = 4 * (rl >> 3) + (rl & 3);
-  const bool my_hi = ((rl >> 2) & 1) != 0;
-  if (lane < 32) myBits[lane * WPR + n_tiles] = 0u;  // the spare word a straddling read may touch
-  __syncthreads();
-
+    // 3. SimHash codes of the range's block keys and of this workgroup's window queries
+    if (do_hash) {
+      const int n_ktiles_h = in_ctx ? 0 : n_tiles;  // look-back keys are never candidates: not hashed
+      const int n_vt = n_ktiles_h + n_hq_tiles;
+      const int n_mt = (p.n_planes + 31) >> 5;
 #pragma unroll 1
-  for (int nt = 0; nt < n_tiles; ++nt) {
-    f32x16 acc;
+      for (int mt = wave; mt < n_mt; mt += NW) {
+        {
+          const int pm = min(mt * 32 + rl, p.n_planes - 1);
+          const char* ptr = p.planes + (size_t)pm * (D * ES);
 #pragma unroll
-    for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
-    const uint4* brow = sP + (size_t)(nt * 32 + rl) * CHP + kg;
+          for (int i = 0; i < NCH; ++i) a[i] = ld16(ptr + (2 * i + kg) * 16);
+        }
+#pragma unroll 1
+        for (int vt = 0; vt < n_vt; ++vt) {
+          const int base = vt < n_ktiles_h ? vt * 32 : nkr + (vt - n_ktiles_h) * 32;
+          f32x16 acc;
 #pragma unroll
-    for (int i = 0; i < NCH; ++i) Mma<DT>::run(acc, a[i], brow[2 * i]);
-    // lane l < 32 collects the word of vector row l: register r covers rows acc_row(r, 0) (low
-    // half of the ballot) and acc_row(r, 1) (high half)
-    uint64_t pick = 0u;
+          for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
+          const uint4* brow = sK + (size_t)(base + rl) * CHP + kg;
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      const uint64_t m = __ballot(acc[r] >= 0.0f);
-      pick = (my_r == r) ? m : pick;
-    }
-    if (lane < 32) myBits[lane * WPR + nt] = my_hi ? (uint32_t)(pick >> 32) : (uint32_t)pick;
-  }
-  __syncthreads();
-  // codes: lane = (vector row, group of 8 tables)
-  const uint32_t code_mask = (1u << p.n_bits) - 1u;
-  const int vrow = r0 + wave * 32 + rl;
-  for (int tb = kg * 8; tb < n_tab; tb += 16) {
-    uint32_t codes[8];
+          for (int i = 0; i < NCH; ++i) Mma<DT>::run(acc, a[i], brow[2 * i]);
+          uint32_t mask = 0u;
 #pragma unroll
-    for (int u = 0; u < 8; ++u) {
-      const int bitpos = min(tb + u, n_tab - 1) * p.n_bits;
-      const int w0 = bitpos >> 5, sh = bitpos & 31;
-      const uint64_t two = (uint64_t)myBits[rl * WPR + w0] | ((uint64_t)myBits[rl * WPR + w0 + 1] << 32);
-      codes[u] = (uint32_t)(two >> sh) & code_mask;
-    }
-    if (vrow < n_rows) {
-      uint16_t* dst = out + (size_t)vrow * p.n_tables + t0 + tb;
-      if (tb + 8 <= n_tab && ((reinterpret_cast<uintptr_t>(dst) & 15) == 0)) {
-        *reinterpret_cast<uint4*>(dst) = make_uint4(codes[0] | (codes[1] << 16), codes[2] | (codes[3] << 16),
-                                                    codes[4] | (codes[5] << 16), codes[6] | (codes[7] << 16));
-      } else {
-#pragma unroll
-        for (int u = 0; u < 8; ++u)
-          if (tb + u < n_tab) dst[u] = (uint16_t)codes[u];
+          for (int r = 0; r < 16; ++r) mask |= (acc[r] >= 0.0f ? 1u : 0u) << acc_row(r, kg);
+          mask |= (uint32_t)__shfl_xor((int)mask, 32);
+          if (kg == 0) sBits[(size_t)(base + rl) * BITS_PITCH + mt] = mask;
+        }
       }
+      __syncthreads();
+      // codes: one item = (vector row, group of 8 tables) -> one 16-byte store where aligned
+      const uint32_t code_mask = (1u << p.n_bits) - 1u;
+      const int n_tg8 = (p.n_tables + 7) >> 3;
+      const int n_krows_h = in_ctx ? 0 : n_keys_wg;
+      const int n_items = (n_krows_h + n_hq) * n_tg8;
+      for (int it = tid; it < n_items; it += NTHR) {
+        const int vr = it / n_tg8, tb = (it - vr * n_tg8) * 8;
+        const bool is_key = vr < n_krows_h;
+        const int lrow = is_key ? vr : nkr + (vr - n_krows_h);
+        const uint32_t* bits = sBits + (size_t)lrow * BITS_PITCH;
+        uint32_t codes[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+          const int bitpos = min(tb + u, p.n_tables - 1) * p.n_bits;
+          const int w0 = bitpos >> 5, sh = bitpos & 31;
+          const uint64_t two = (uint64_t)bits[w0] | ((uint64_t)bits[w0 + 1] << 32);
+          codes[u] = (uint32_t)(two >> sh) & code_mask;
+        }
+        uint16_t* dst = is_key ? p.sig_k + ((size_t)h * p.s_t + seg_row0 + vr) * p.n_tables + tb
+                               : p.sig_q + ((size_t)h * p.m_rows + hq0 + (vr - n_krows_h)) * p.n_tables + tb;
+        if (tb + 8 <= p.n_tables && ((reinterpret_cast<uintptr_t>(dst) & 15) == 0)) {
+          *reinterpret_cast<uint4*>(dst) = make_uint4(codes[0] | (codes[1] << 16), codes[2] | (codes[3] << 16),
+                                                      codes[4] | (codes[5] << 16), codes[6] | (codes[7] << 16));
+        } else {
+#pragma unroll
+          for (int u = 0; u < 8; ++u)
+            if (tb + u < p.n_tables) dst[u] = (uint16_t)codes[u];
+        }
+      }
+      if (!in_ctx)
+        for (int t = tid; t < n_keys_wg; t += NTHR) p.cnt[(size_t)h * p.s_t + seg_row0 + t] = 0;
     }
   }
+  LKV_TS(4);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -583,23 +566,47 @@ __global__ __launch_bounds__(256) void append_kernel(AppendParams p) {
 // ---------------------------------------------------------------------------------------------
 // launchers
 // ---------------------------------------------------------------------------------------------
-template <int DT, int D, bool PASS2>
-static hipError_t launch_score_t(const ScoreParams& p, int n_qgroups, int n_kv_heads, hipStream_t st) {
-  dim3 grid(p.n_ranges * n_qgroups * n_kv_heads);
-  const size_t lds8 = score_lds_bytes<DT, D, 8>(p.keys_per_range);
-  const size_t lds4 = score_lds_bytes<DT, D, 4>(p.keys_per_range);
-  if (p.rows_per_group == 256)
-    hipLaunchKernelGGL((score_kernel<DT, D, 8, PASS2>), grid, dim3(512), lds8, st, p);
-  else
-    hipLaunchKernelGGL((score_kernel<DT, D, 4, PASS2>), grid, dim3(256), lds4, st, p);
+template <int DT, int D, int NW, bool PASS2>
+static hipError_t launch_pass_nw(const PassParams& p, hipStream_t st) {
+  dim3 grid(p.n_ranges * p.n_qgroups * p.n_kv_heads);
+  const int q_tile_rows = (p.q_rows_per_wg + 31) & ~31;
+  const size_t lds = pass_lds_bytes<DT, D, NW, PASS2>(p.keys_per_range, q_tile_rows);
+  hipLaunchKernelGGL((pass_kernel<DT, D, NW, PASS2>), grid, dim3(NW * 64), lds, st, p);
   return hipGetLastError();
 }
 
+template <int DT, int D, bool PASS2>
+static hipError_t launch_pass_t(const PassParams& p, hipStream_t st) {
+  switch (p.rows_per_group) {
+    case 512: return launch_pass_nw<DT, D, 16, PASS2>(p, st);
+    case 256: return launch_pass_nw<DT, D, 8, PASS2>(p, st);
+    case 128: return launch_pass_nw<DT, D, 4, PASS2>(p, st);
+    default: return hipErrorInvalidValue;
+  }
+}
+
+template <bool PASS2>
+static hipError_t launch_pass_any(int dtype, int head_dim, const PassParams& p, hipStream_t st) {
+  if (dtype == DT_BF16 && head_dim == 128) return launch_pass_t<DT_BF16, 128, PASS2>(p, st);
+  if (dtype == DT_BF16 && head_dim == 64) return launch_pass_t<DT_BF16, 64, PASS2>(p, st);
+  if (dtype == DT_F32 && head_dim == 128) return launch_pass_t<DT_F32, 128, PASS2>(p, st);
+  if (dtype == DT_F32 && head_dim == 64) return launch_pass_t<DT_F32, 64, PASS2>(p, st);
+  return hipErrorInvalidValue;
+}
+
+hipError_t launch_sweep1(int dtype, int head_dim, const PassParams& p, hipStream_t st) {
+  return launch_pass_any<false>(dtype, head_dim, p, st);
+}
+hipError_t launch_sweep2(int dtype, int head_dim, const PassParams& p, hipStream_t st) {
+  return launch_pass_any<true>(dtype, head_dim, p, st);
+}
+
 template <int DT, int D>
-static hipError_t score_attrs() {
+static hipError_t pass_attrs() {
   const void* fns[] = {
-      reinterpret_cast<const void*>(&score_kernel<DT, D, 8, false>), reinterpret_cast<const void*>(&score_kernel<DT, D, 8, true>),
-      reinterpret_cast<const void*>(&score_kernel<DT, D, 4, false>), reinterpret_cast<const void*>(&score_kernel<DT, D, 4, true>)};
+      reinterpret_cast<const void*>(&pass_kernel<DT, D, 16, false>), reinterpret_cast<const void*>(&pass_kernel<DT, D, 16, true>),
+      reinterpret_cast<const void*>(&pass_kernel<DT, D, 8, false>), reinterpret_cast<const void*>(&pass_kernel<DT, D, 8, true>),
+      reinterpret_cast<const void*>(&pass_kernel<DT, D, 4, false>), reinterpret_cast<const void*>(&pass_kernel<DT, D, 4, true>)};
   for (const void* f : fns) {
     hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
     if (e != hipSuccess) return e;
@@ -607,63 +614,28 @@ static hipError_t score_attrs() {
   return hipSuccess;
 }
 
-template <bool PASS2>
-static hipError_t launch_score_any(int dtype, int head_dim, const ScoreParams& p, int nq, int nh, hipStream_t st) {
-  if (dtype == DT_BF16 && head_dim == 128) return launch_score_t<DT_BF16, 128, PASS2>(p, nq, nh, st);
-  if (dtype == DT_BF16 && head_dim == 64) return launch_score_t<DT_BF16, 64, PASS2>(p, nq, nh, st);
-  if (dtype == DT_F32 && head_dim == 128) return launch_score_t<DT_F32, 128, PASS2>(p, nq, nh, st);
-  if (dtype == DT_F32 && head_dim == 64) return launch_score_t<DT_F32, 64, PASS2>(p, nq, nh, st);
-  return hipErrorInvalidValue;
-}
-
-hipError_t launch_stats(int dtype, int head_dim, const ScoreParams& p, int nq, int nh, hipStream_t st) {
-  return launch_score_any<false>(dtype, head_dim, p, nq, nh, st);
-}
-hipError_t launch_score(int dtype, int head_dim, const ScoreParams& p, int nq, int nh, hipStream_t st) {
-  return launch_score_any<true>(dtype, head_dim, p, nq, nh, st);
-}
-
-template <int DT, int D>
-static hipError_t launch_sig_t(const SigParams& p, hipStream_t st) {
-  constexpr int NW = 8;
-  const int max_rows = p.s_t > p.w ? p.s_t : p.w;
-  const int n_tg = (p.n_tables + p.tables_per_group - 1) / p.tables_per_group;
-  dim3 grid((max_rows + NW * 32 - 1) / (NW * 32), n_tg, p.n_kv_heads + p.n_q_heads);
-  const size_t lds = sig_lds_bytes<DT, D>(NW);
-  hipLaunchKernelGGL((sig_kernel<DT, D, NW>), grid, dim3(NW * 64), lds, st, p);
-  return hipGetLastError();
-}
-
-template <int DT, int D>
-static hipError_t sig_attrs() {
-  return hipFuncSetAttribute(reinterpret_cast<const void*>(&sig_kernel<DT, D, 8>),
-                             hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-}
-
-hipError_t launch_sig(int dtype, int head_dim, const SigParams& p, hipStream_t st) {
-  if (dtype == DT_BF16 && head_dim == 128) return launch_sig_t<DT_BF16, 128>(p, st);
-  if (dtype == DT_BF16 && head_dim == 64) return launch_sig_t<DT_BF16, 64>(p, st);
-  if (dtype == DT_F32 && head_dim == 128) return launch_sig_t<DT_F32, 128>(p, st);
-  if (dtype == DT_F32 && head_dim == 64) return launch_sig_t<DT_F32, 64>(p, st);
-  return hipErrorInvalidValue;
-}
-
 hipError_t init_kernel_attributes() {
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&count_kernel),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024);
-  if (e == hipSuccess) e = score_attrs<DT_BF16, 128>();
-  if (e == hipSuccess) e = score_attrs<DT_BF16, 64>();
-  if (e == hipSuccess) e = score_attrs<DT_F32, 128>();
-  if (e == hipSuccess) e = score_attrs<DT_F32, 64>();
-  if (e == hipSuccess) e = sig_attrs<DT_BF16, 128>();
-  if (e == hipSuccess) e = sig_attrs<DT_BF16, 64>();
-  if (e == hipSuccess) e = sig_attrs<DT_F32, 128>();
-  if (e == hipSuccess) e = sig_attrs<DT_F32, 64>();
+  if (e == hipSuccess) e = pass_attrs<DT_BF16, 128>();
+  if (e == hipSuccess) e = pass_attrs<DT_BF16, 64>();
+  if (e == hipSuccess) e = pass_attrs<DT_F32, 128>();
+  if (e == hipSuccess) e = pass_attrs<DT_F32, 64>();
   return e;
 }
 
 int score_max_range() { return SCORE_MAX_RANGE; }
-int sig_max_planes() { return SIG_MAX_PLANES; }
+
+size_t sweep_lds_bytes(int dtype, int head_dim, int rows_per_group, int range_keys, int q_rows_per_wg) {
+  // the larger of the two sweeps, for the host's range sizing
+  const int es = dtype == DT_BF16 ? 2 : 4;
+  const size_t pitch = (size_t)(head_dim * es / 16 + 1) * 16;
+  const int nw = rows_per_group / 32;
+  const size_t qt = (size_t)((q_rows_per_wg + 31) & ~31);
+  const size_t s1 = (range_keys + qt) * pitch + (range_keys + qt) * BITS_PITCH * 4 + (size_t)nw * 32 * 8;
+  const size_t s2 = (size_t)range_keys * pitch + (size_t)nw * range_keys * 4 + (size_t)nw * 32 * 8;
+  return s1 > s2 ? s1 : s2;
+}
 
 hipError_t launch_count(const CountParams& p, int n_kv_heads, hipStream_t st) {
   const int n_tg = (p.n_tables + p.tables_per_group - 1) / p.tables_per_group;
