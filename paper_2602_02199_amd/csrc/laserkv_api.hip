@@ -256,12 +256,8 @@ int laserkv_select_block(laserkv_ctx* ctx,
   sp.m_rows = m_rows;
   sp.s_t = s_t;
   sp.t_ctx = t_ctx;
-  sp.rows_per_group = m_rows > 256 ? 512 : (m_rows > 128 ? 256 : 128);
-  {
-    const int forced = env_int("LASERKV_SWEEP_ROWS", 0);
-    if (forced == 128 || forced == 256 || forced == 512) sp.rows_per_group = forced;
-  }
-  const int n_qg = (m_rows + sp.rows_per_group - 1) / sp.rows_per_group;
+  sp.w_magic = (uint32_t)(((uint64_t(1) << 32) + (uint64_t)w - 1) / (uint64_t)w);
+  const int n_qg = (m_rows + lkv::sweep_rows_per_group() - 1) / lkv::sweep_rows_per_group();
   sp.n_qgroups = n_qg;
   sp.n_kv_heads = c.n_kv_heads;
   // key ranges: about one workgroup per compute unit per query-row group, each range in one source
@@ -276,7 +272,7 @@ int laserkv_select_block(laserkv_ctx* ctx,
     sp.n_ctx_ranges = (t_ctx + nk - 1) / nk;
     sp.n_ranges = sp.n_ctx_ranges + (s_t + nk - 1) / nk;
     sp.q_rows_per_wg = (m_rows + sp.n_ranges - 1) / sp.n_ranges;
-    if (nk <= 32 || lkv::sweep_lds_bytes(c.dtype, d, sp.rows_per_group, nk, sp.q_rows_per_wg) <= 150 * 1024) break;
+    if (nk <= 32 || lkv::sweep_lds_bytes(c.dtype, d, false, nk, sp.q_rows_per_wg) <= 150 * 1024) break;
     nk -= 32;
   }
   if (sp.n_ranges > ctx->max_ranges) return fail(ctx, LKV_EINVAL, "select_block: internal range split too fine");
@@ -291,6 +287,7 @@ int laserkv_select_block(laserkv_ctx* ctx,
   sp.n_tables = c.lsh_tables;
   sp.n_bits = c.lsh_bits;
   sp.n_planes = c.lsh_tables * c.lsh_bits;
+  sp.tables_per_split = (c.lsh_tables + n_qg - 1) / n_qg;
   sp.sig_k = ctx->sig_k;
   sp.sig_q = ctx->sig_q;
   sp.cnt = ctx->cnt;

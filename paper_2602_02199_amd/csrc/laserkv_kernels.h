@@ -20,24 +20,26 @@ struct PassParams {
   const char* planes;   // [L*K, d] contiguous
   int group;       // G
   int w;           // W
+  uint32_t w_magic;  // ceil(2^32 / W): row / W == umulhi(row, w_magic) for row <= 1024
   int m_rows;      // M = G * W
   int s_t;         // S
   int t_ctx;       // T
   int keys_per_range;   // NK (multiple of 32, <= score_max_range())
   int n_ranges;         // NR = n_ctx_ranges + ranges over the block keys
   int n_ctx_ranges;     // ranges that cover the look-back keys (each range lies in one source)
-  int rows_per_group;   // MQ = 32 * waves per workgroup (128, 256 or 512)
-  int n_qgroups;        // ceil(M / MQ)
+  int n_qgroups;        // ceil(M / sweep_rows_per_group())
   int n_kv_heads;
   int causal;
   int lim0;        // key index kidx is visible to window row j iff kidx <= lim0 + j (when causal)
   float scale2;    // log2(e) / sqrt(d)
   float2* part;    // [H_kv, NR, m_pad] sweep-1 partials (reference, sum) in the exp2 domain
   int m_pad;       // row pitch of part
+  int lds_tail_offset;  // byte offset of the per-row LDS arrays (set by the launcher)
   float* s_part;   // [n_qgroups, H_kv, S] sweep-2 pooled probabilities (sum over the group's rows)
   // hashing (sweep 1)
   int n_tables, n_bits, n_planes;  // L, K, L*K (<= 512)
   int q_rows_per_wg;    // window rows of the head hashed by each key range's workgroup
+  int tables_per_split; // tables hashed by one query-row group's workgroups: ceil(L / n_qgroups)
   uint16_t* sig_k;      // [H_kv, S, L]
   uint16_t* sig_q;      // [H_q, W, L] = [H_kv, M, L]
   int32_t* cnt;         // [H_kv, S]: zeroed in sweep 1 for the count kernel's atomics
@@ -87,7 +89,8 @@ hipError_t launch_count(const CountParams& p, int n_kv_heads, hipStream_t st);
 hipError_t launch_select(const SelectParams& p, hipStream_t st);
 hipError_t launch_append(const AppendParams& p, int n_kv_heads, hipStream_t st);
 hipError_t init_kernel_attributes();
-size_t sweep_lds_bytes(int dtype, int head_dim, int rows_per_group, int range_keys, int q_rows_per_wg);
+size_t sweep_lds_bytes(int dtype, int head_dim, bool pass2, int range_keys, int q_rows_per_wg);
+int sweep_rows_per_group();  // window rows one sweep workgroup covers
 int score_max_range();  // most keys one score workgroup takes (its LDS holds the whole range)
 
 }  // namespace lkv

@@ -20,53 +20,51 @@
 namespace lkv {
 
 // ---------------------------------------------------------------------------------------------
-// The two sweeps over a block's keys.  Workgroup = (key range, query-row group, KV head), NW waves.
+// The two sweeps over a block's keys.  Workgroup = (key range, query-row group of 256 rows, KV
+// head); 16 waves, one workgroup per compute unit.
 //
-//   sweep 1 (PASS2 = false): per window row, partial softmax statistics over the range (Alg. 1
-//            step 3, normaliser), then the SimHash codes of the range's keys and of this
-//            workgroup's share of the window queries (Sec. 3.3 "Recall") from the SAME LDS tile:
-//            the block's keys are read from HBM once for both contractions.
-//   sweep 2 (PASS2 = true):  pooled softmax probability of every key of the range (Alg. 1 step 3).
+//   sweep 1 (PASS2 = false): waves 0-7 compute, per window row, partial softmax statistics over the
+//            range (Alg. 1 step 3, normaliser); waves 8-15 compute the SimHash sign bits of the
+//            range's keys and of this workgroup's share of the window queries (Sec. 3.3 "Recall")
+//            from the SAME LDS rows, so the block's keys are read from HBM once for both
+//            contractions and the two roles overlap on every SIMD.
+//   sweep 2 (PASS2 = true):  pooled softmax probability of every key of the range (Alg. 1 step 3);
+//            wave = (row tile, half of the range).
 //
 // The whole range (<= SCORE_MAX_RANGE keys) is fetched into LDS up front: a range is microseconds
 // of work, so what matters is having all of its loads in flight at once.  After one barrier each
-// wave walks the range's 32-key tiles on its own: A fragments of ONE 32-row query tile stay in
-// registers, B fragments come from LDS (row pitch padded by one 16-byte chunk: conflict-free reads
-// at base + immediate addresses).  Everything is sized for <= 128 registers per lane so that four
-// waves share a SIMD: one wave alone issues a vector instruction only every ~10 clocks.
+// wave walks its 32-key tiles on its own: A fragments of ONE 32-row tile (queries, or hyperplanes
+// for the hashing waves) stay in registers, B fragments come from LDS (row pitch padded by one
+// 16-byte chunk: conflict-free reads at base + immediate addresses).  Four waves share a SIMD
+// (<= 128 registers per lane): one wave alone issues a vector instruction only every ~10 clocks.
 //
 // Sweep 1 keeps, per window row, sum_i 2^(x_i - ref) against a reference ref shared by the 32 lanes
 // that hold the row; ref starts as the row maximum of the first tile and is raised (with the sum
 // rescaled) only when a logit exceeds it by more than 2^64, so the common case costs one fma, one
 // max, one exp and one add per logit.  Sweep 2 needs one fma, one exp and one add per logit.
 //
-// Hashing: wave w takes the 32-plane tiles w, w+NW, ... as the A operand (registers) against the
-// same LDS rows; lane = vector, so 16 compares per tile give 16 of its sign bits and one exchange
-// with the partner lane completes the 32-bit word of that vector and plane tile.
+// Hashing: lane = vector, accumulator register = plane, so 16 compares per tile give 16 sign bits of
+// the lane's vector and one exchange with the partner lane completes its 32-bit word for that
+// 32-plane tile.  With several query-row groups the tables are split between their workgroups.
 // ---------------------------------------------------------------------------------------------
-constexpr int SCORE_MAX_RANGE = 256;  // keys per workgroup at most
+constexpr int PASS_WAVES = 16;
+constexpr int PASS_ROWS = 256;        // window rows per workgroup: 8 row tiles
+constexpr int SCORE_MAX_RANGE = 288;  // keys per workgroup at most
 constexpr int BITS_PITCH = 17;        // words per vector row in the sign-bit scratch (<= 16 plane tiles)
 
 template <int DT, int D>
 __host__ __device__ constexpr int row_pitch_chunks() { return D * (DT == DT_BF16 ? 2 : 4) / 16 + 1; }
 
-// dynamic LDS of a sweep workgroup
-template <int DT, int D, int NW, bool PASS2>
-__host__ __device__ constexpr size_t pass_lds_bytes(int range_keys, int q_tile_rows) {
-  const size_t rows = (size_t)range_keys + (PASS2 ? 0 : q_tile_rows);
-  return rows * row_pitch_chunks<DT, D>() * 16 + (PASS2 ? (size_t)NW * range_keys * 4 : rows * BITS_PITCH * 4) + (size_t)NW * 32 * 8;
-}
+__device__ __forceinline__ int div_w(int m, uint32_t magic) { return (int)__umulhi((uint32_t)m, magic); }
 
-template <int DT, int D, int NW, bool PASS2>
-__global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu((DT == DT_BF16 ? 2 : 4) * D <= 256 ? 4 : 2, 8)))
-void pass_kernel(PassParams p) {
+template <int DT, int D, bool PASS2>
+__global__ __launch_bounds__(PASS_WAVES * 64) void pass_kernel(PassParams p) {
   constexpr int ES = DT == DT_BF16 ? 2 : 4;
   constexpr int CH = D * ES / 16;  // 16-byte chunks per row
   constexpr int NCH = CH / 2;      // chunk pairs per tile
   constexpr int CHP = CH + 1;      // LDS row pitch in chunks
-  constexpr int NTHR = NW * 64;
-  constexpr int MQ = 32 * NW;      // query rows per workgroup
-  constexpr int LDB = 4;           // 16-byte loads a thread keeps in flight per round
+  constexpr int NTHR = PASS_WAVES * 64;
+  constexpr int MQ = PASS_ROWS;
   constexpr float RESCALE_AT = 64.0f;
 
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, rl = lane & 31, kg = lane >> 5;
@@ -102,193 +100,300 @@ void pass_kernel(PassParams p) {
   const char* kbase_ptr = ksrc.base + (int64_t)h * ksrc.stride_head;
   const int kstride = (int)ksrc.stride_row;
   const int n_tiles = (n_keys_wg + 31) >> 5;
-  // window queries this workgroup hashes (sweep 1, first query-row group only)
-  const bool do_hash = !PASS2 && qg == 0;
+  // window queries this workgroup hashes (sweep 1) and its share of the tables
   const int hq0 = kr * p.q_rows_per_wg;
-  const int n_hq = do_hash ? max(0, min(p.q_rows_per_wg, p.m_rows - hq0)) : 0;
+  const int n_hq = PASS2 ? 0 : max(0, min(p.q_rows_per_wg, p.m_rows - hq0));
   const int n_hq_tiles = (n_hq + 31) >> 5;
   const int q_tile_rows = PASS2 ? 0 : ((p.q_rows_per_wg + 31) & ~31);
+  const int tab0 = qg * p.tables_per_split;
+  const int n_tab = PASS2 ? 0 : max(0, min(p.tables_per_split, p.n_tables - tab0));
+  const int plane0 = tab0 * p.n_bits;
+  const int n_pl = n_tab * p.n_bits;
+  const int n_mt = (n_pl + 31) >> 5;
+  // roles
+  const bool hash_wave = !PASS2 && wave >= 8;
+  const int rt = wave & 7;  // row tile of a score wave; index of a hashing wave
 
   extern __shared__ uint4 smem[];
   uint4* sK = smem;                                                    // [nkr + q_tile_rows][CHP]
   char* after_rows = reinterpret_cast<char*>(smem + (size_t)(nkr + q_tile_rows) * CHP);
-  float* sCol = reinterpret_cast<float*>(after_rows);                  // sweep 2: [NW][nkr]
+  float* sCol = reinterpret_cast<float*>(after_rows);                  // sweep 2: [8][nkr]
   uint32_t* sBits = reinterpret_cast<uint32_t*>(after_rows);           // sweep 1: [nkr + q_tile_rows][BITS_PITCH]
-  int* sLim = reinterpret_cast<int*>(after_rows + (PASS2 ? (size_t)NW * nkr * 4 : (size_t)(nkr + q_tile_rows) * BITS_PITCH * 4));  // [MQ]
+  // row limits and lse sit past both the steady-state arrays and the A-operand staging area
+  int* sLim = reinterpret_cast<int*>(reinterpret_cast<char*>(smem) + p.lds_tail_offset);  // [MQ]
   float* sLse = reinterpret_cast<float*>(sLim + MQ);                   // [MQ]
 
-  // 1. everything this workgroup reads from memory, issued back to back
-  uint4 a[NCH];  // this wave's query tile
-  {
-    const int m = qg * MQ + wave * 32 + rl;
-    const int mc = min(m, p.m_rows - 1);
-    const int g = mc / p.w, j = mc - g * p.w;
-    const char* ptr = p.q.base + (int64_t)(h * p.group + g) * p.q.stride_head + (int64_t)j * p.q.stride_row;
-#ifdef LKV_EXP_SKIP_A
+  // 1. everything this workgroup reads from memory, issued back to back.  The A operands (256 window
+  // rows; in sweep 1 also up to 256 hyperplanes) are fetched as whole rows by all threads and passed
+  // through LDS into the fragment layout: a wave fetching its own 32 rows 16 bytes per lane would
+  // touch 32 cache lines per instruction and dominate the kernel.  The key rows wait in registers
+  // meanwhile and then take over the same LDS space.
+  constexpr bool STAGE_A = CH <= 16;                 // wider rows: fragments straight from memory
+  constexpr int QL = STAGE_A ? MQ * CH / NTHR : 1;   // 16-byte chunks per thread: query panel
+  constexpr int KL = STAGE_A ? ((SCORE_MAX_RANGE + 32) * CH + NTHR - 1) / NTHR : 1;  // keys + hashed queries
+  const int n_kchunks = n_tiles * 32 * CH;           // rows past the range are clamped copies, masked later
+  const int n_chunks = n_kchunks + n_hq_tiles * 32 * CH;
+  auto key_chunk = [&](int q) -> uint4 {
+    if (q < n_kchunks) {
+      const int row = q / CH, c = q % CH;
+      const int lrow = min(seg_row0 + row, seg_rows - 1);
+      return ld16(kbase_ptr + (uint32_t)(lrow * kstride + c * 16));
+    }
+    const int qq = q - n_kchunks;
+    const int row = qq / CH, c = qq % CH;
+    const int m = min(hq0 + row, p.m_rows - 1);
+    const int g = div_w(m, p.w_magic), j = m - g * p.w;
+    return ld16(p.q.base + (int64_t)(h * p.group + g) * p.q.stride_head + (int64_t)j * p.q.stride_row + c * 16);
+  };
+  auto key_slot = [&](int q) -> int {
+    if (q < n_kchunks) return (q / CH) * CHP + q % CH;
+    const int qq = q - n_kchunks;
+    return (nkr + qq / CH) * CHP + qq % CH;
+  };
+
+  float2 pv[PASS2 ? 8 : 1];  // sweep 2: this thread's share of the row's sweep-1 partials
+  int pr_beg = 0, pr_end = 0;
+  if (PASS2) {
+    // four threads per row, a quarter of the ranges each; the first eight are prefetched here
+    const int t = tid >> 2, part = tid & 3;
+    const int m = qg * MQ + t;
+    const int per = (p.n_ranges + 3) >> 2;
+    pr_beg = min(part * per, p.n_ranges);
+    pr_end = (m < p.m_rows) ? min(pr_beg + per, p.n_ranges) : pr_beg;
+    const float2* pp = p.part + (size_t)h * p.n_ranges * p.m_pad + min(m, p.m_rows - 1);
 #pragma unroll
-    for (int i = 0; i < NCH; ++i) a[i] = make_uint4(tid, i, 0x3f803f80u, 0x3f803f80u);
-#else
-#pragma unroll
-    for (int i = 0; i < NCH; ++i) a[i] = ld16(ptr + (2 * i + kg) * 16);
-#endif
+    for (int u = 0; u < 8; ++u) {
+      const int r = min(pr_beg + u, p.n_ranges - 1);
+      pv[u] = pp[(size_t)r * p.m_pad];
+    }
   }
-  LKV_TS(5);
-  {
-    // key rows (rows past the range are clamped copies, masked later) and hashed query rows
-    const int n_kchunks = n_tiles * 32 * CH;
-    const int n_chunks = n_kchunks + n_hq_tiles * 32 * CH;
+  uint4 a[NCH];  // A operand: this wave's 32 window rows, or (hashing waves) its first 32 planes
+  if (STAGE_A) {
+    uint4 qpre[QL], ppre[QL], kpre[KL];
+#pragma unroll
+    for (int u = 0; u < QL; ++u) {
+      const int q = tid + NTHR * u;
+      const int row = q / CH, c = q % CH;
+      const int m = min(qg * MQ + row, p.m_rows - 1);
+      const int g = div_w(m, p.w_magic), j = m - g * p.w;
+      qpre[u] = ld16(p.q.base + (int64_t)(h * p.group + g) * p.q.stride_head + (int64_t)j * p.q.stride_row + c * 16);
+    }
+    if (!PASS2) {
+#pragma unroll
+      for (int u = 0; u < QL; ++u) {
+        const int q = tid + NTHR * u;
+        const int row = q / CH, c = q % CH;
+        const int pm = min(plane0 + min(row, max(n_pl - 1, 0)), p.n_planes - 1);
+        ppre[u] = ld16(p.planes + (size_t)pm * (D * ES) + c * 16);
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < KL; ++u) {
+      const int q = tid + NTHR * u;
+      if (q < n_chunks) kpre[u] = key_chunk(q);
+    }
+    LKV_TS(5);
+    // staging area: rows [0, 256) queries, rows [256, 512) planes, pitch CHP
+#pragma unroll
+    for (int u = 0; u < QL; ++u) {
+      const int q = tid + NTHR * u;
+      smem[(q / CH) * CHP + q % CH] = qpre[u];
+      if (!PASS2) smem[(MQ + q / CH) * CHP + q % CH] = ppre[u];
+    }
+    __syncthreads();
+    {
+      const uint4* arow = smem + (size_t)((hash_wave ? MQ : 0) + rt * 32 + rl) * CHP + kg;
+#pragma unroll
+      for (int i = 0; i < NCH; ++i) a[i] = arow[2 * i];
+    }
+    __syncthreads();  // fragments are in registers: the key rows may take the space
+#pragma unroll
+    for (int u = 0; u < KL; ++u) {
+      const int q = tid + NTHR * u;
+      if (q < n_chunks) sK[key_slot(q)] = kpre[u];
+    }
+  } else {
+    if (hash_wave) {
+      const int pm = min(plane0 + min(rt * 32 + rl, max(n_pl - 1, 0)), p.n_planes - 1);
+      const char* ptr = p.planes + (size_t)pm * (D * ES);
+#pragma unroll
+      for (int i = 0; i < NCH; ++i) a[i] = ld16(ptr + (2 * i + kg) * 16);
+    } else {
+      const int mc = min(qg * MQ + rt * 32 + rl, p.m_rows - 1);
+      const int g = div_w(mc, p.w_magic), j = mc - g * p.w;
+      const char* ptr = p.q.base + (int64_t)(h * p.group + g) * p.q.stride_head + (int64_t)j * p.q.stride_row;
+#pragma unroll
+      for (int i = 0; i < NCH; ++i) a[i] = ld16(ptr + (2 * i + kg) * 16);
+    }
+    LKV_TS(5);
+    constexpr int LDB = 4;
     for (int c0 = 0; c0 < n_chunks; c0 += NTHR * LDB) {
       uint4 pre[LDB];
 #pragma unroll
       for (int u = 0; u < LDB; ++u) {
         const int q = c0 + tid + NTHR * u;
-        if (q < n_kchunks) {
-          const int row = q / CH, c = q % CH;
-          const int lrow = min(seg_row0 + row, seg_rows - 1);
-#ifdef LKV_EXP_SKIP_K
-          pre[u] = make_uint4(lrow, c, 0x3f803f80u, 0x3f803f80u);
-#else
-          pre[u] = ld16(kbase_ptr + (uint32_t)(lrow * kstride + c * 16));
-#endif
-        } else if (q < n_chunks) {
-          const int qq = q - n_kchunks;
-          const int row = qq / CH, c = qq % CH;
-          const int m = min(hq0 + row, p.m_rows - 1);
-          const int g = m / p.w, j = m - g * p.w;
-          pre[u] = ld16(p.q.base + (int64_t)(h * p.group + g) * p.q.stride_head + (int64_t)j * p.q.stride_row + c * 16);
-        }
+        if (q < n_chunks) pre[u] = key_chunk(q);
       }
 #pragma unroll
       for (int u = 0; u < LDB; ++u) {
         const int q = c0 + tid + NTHR * u;
-        if (q < n_kchunks) {
-          sK[(q / CH) * CHP + q % CH] = pre[u];
-        } else if (q < n_chunks) {
-          const int qq = q - n_kchunks;
-          sK[(nkr + qq / CH) * CHP + qq % CH] = pre[u];
-        }
+        if (q < n_chunks) sK[key_slot(q)] = pre[u];
       }
     }
   }
   LKV_TS(6);
   for (int t = tid; t < MQ; t += NTHR) {
-    const int m = qg * MQ + t;
-    const int j = (m < p.m_rows) ? m % p.w : 0;
+    const int m = min(qg * MQ + t, p.m_rows - 1);
+    const int j = m - div_w(m, p.w_magic) * p.w;
     sLim[t] = p.causal ? p.lim0 + j : INT_MAX;
   }
   if (PASS2) {
-    // row log-sum-exp from the sweep-1 partials: two threads per row, half of the ranges each
-    for (int t2 = tid; t2 < 2 * MQ; t2 += NTHR) {
-      const int t = t2 >> 1, half = t2 & 1;
-      const int m = qg * MQ + t;
-      float mm = NEG_BIG, ss = 0.0f;
-      if (m < p.m_rows) {
-        const float2* pp = p.part + (size_t)h * p.n_ranges * p.m_pad + m;
-        const int r_mid = (p.n_ranges + 1) >> 1;
-        const int r_beg = half ? r_mid : 0, r_end = half ? p.n_ranges : r_mid;
-        int r = r_beg;
-        for (; r + 8 <= r_end; r += 8) {
-          float2 v[8];
+    // row log-sum-exp from the sweep-1 partials
+    float mm = NEG_BIG, ss = 0.0f;
 #pragma unroll
-          for (int u = 0; u < 8; ++u) v[u] = pp[(size_t)(r + u) * p.m_pad];
-#pragma unroll
-          for (int u = 0; u < 8; ++u) lse_merge(mm, ss, v[u].x, v[u].y);
-        }
-        for (; r < r_end; ++r) {
-          const float2 v = pp[(size_t)r * p.m_pad];
-          lse_merge(mm, ss, v.x, v.y);
-        }
+    for (int u = 0; u < 8; ++u)
+      if (pr_beg + u < pr_end) lse_merge(mm, ss, pv[u].x, pv[u].y);
+    if (pr_end - pr_beg > 8) {  // more than 32 ranges per head: the rest, not prefetched
+      const float2* pp = p.part + (size_t)h * p.n_ranges * p.m_pad + qg * MQ + (tid >> 2);
+      for (int r = pr_beg + 8; r < pr_end; ++r) {
+        const float2 v = pp[(size_t)r * p.m_pad];
+        lse_merge(mm, ss, v.x, v.y);
       }
-      const float m2 = __shfl_xor(mm, 1), s2 = __shfl_xor(ss, 1);
-      lse_merge(mm, ss, m2, s2);
-      if (half == 0) sLse[t] = (m < p.m_rows) ? mm + fast_log2(ss) : 1.0e30f;  // padding rows: probability 0
     }
+#pragma unroll
+    for (int off = 1; off < 4; off <<= 1) {
+      const float m2 = __shfl_xor(mm, off), s2 = __shfl_xor(ss, off);
+      lse_merge(mm, ss, m2, s2);
+    }
+    const int t = tid >> 2;
+    if ((tid & 3) == 0) sLse[t] = (qg * MQ + t < p.m_rows) ? mm + fast_log2(ss) : 1.0e30f;  // padding rows: probability 0
   }
   __syncthreads();
   LKV_TS(1);
 
-  float ref[16], sum[16];  // sweep 1: (reference, sum); sweep 2: ref holds the row lse
+  if (!hash_wave) {
+    float ref[16], sum[16];  // sweep 1: (reference, sum); sweep 2: ref holds the row lse
 #pragma unroll
-  for (int r = 0; r < 16; ++r) {
-    ref[r] = PASS2 ? sLse[wave * 32 + acc_row(r, kg)] : NEG_BIG;
-    sum[r] = 0.0f;
-  }
-
-  // 2. the range's tiles; rolled on purpose (microsecond kernels start from a cold instruction cache)
+    for (int r = 0; r < 16; ++r) {
+      ref[r] = PASS2 ? sLse[rt * 32 + acc_row(r, kg)] : NEG_BIG;
+      sum[r] = 0.0f;
+    }
+    // sweep 1: all tiles of the range; sweep 2: this wave's half of them
+    const int t_half = (n_tiles + 1) >> 1;
+    const int nt_beg = PASS2 ? (wave >> 3) * t_half : 0;
+    const int nt_end = PASS2 ? min(n_tiles, nt_beg + t_half) : n_tiles;
+    // rolled on purpose (microsecond kernels start from a cold instruction cache)
 #pragma unroll 1
-  for (int nt = 0; nt < n_tiles; ++nt) {
-    const int kbase = k0 + nt * 32;
-    f32x16 acc;
+    for (int nt = nt_beg; nt < nt_end; ++nt) {
+      const int kbase = k0 + nt * 32;
+      f32x16 acc;
 #pragma unroll
-    for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
-    const uint4* brow = sK + (size_t)(nt * 32 + rl) * CHP + kg;
+      for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
+      const uint4* brow = sK + (size_t)(nt * 32 + rl) * CHP + kg;
 #pragma unroll
-    for (int i = 0; i < NCH; ++i) Mma<DT>::run(acc, a[i], brow[2 * i]);
-    const int kidx = kbase + rl;
-    const bool partial = (kbase + 32 > k1) || (p.causal && (kbase + 31 > p.lim0));  // wave-uniform
-    if (PASS2) {
-      float col = 0.0f;
-      if (!partial) {
-#pragma unroll
-        for (int r = 0; r < 16; ++r) col += fast_exp2(fmaf(acc[r], p.scale2, -ref[r]));
-      } else {
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const bool vis = kidx < k1 && kidx <= sLim[wave * 32 + acc_row(r, kg)];
-          const float e = fast_exp2(fmaf(acc[r], p.scale2, -ref[r]));
-          col += vis ? e : 0.0f;
-        }
-      }
-      col += __shfl_xor(col, 32);
-      if (kg == 0) sCol[wave * nkr + nt * 32 + rl] = col;
-    } else {
-      // acc is turned in place into t = x - ref (x = scaled logit, masked -> NEG_BIG)
-      if (nt == 0) {
-        // first tile of the range: the references start at this tile's row maxima
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          float x = acc[r] * p.scale2;
-          if (partial) {
-            const bool vis = kidx < k1 && kidx <= sLim[wave * 32 + acc_row(r, kg)];
-            x = vis ? x : NEG_BIG;
-          }
-          ref[r] = half_allmax(x);
-          acc[r] = x - ref[r];
-          __builtin_amdgcn_sched_barrier(0);  // one row at a time: keeps register pressure low
-        }
-      } else {
-        float tmax = NEG_BIG;
+      for (int i = 0; i < NCH; ++i) Mma<DT>::run(acc, a[i], brow[2 * i]);
+      const int kidx = kbase + rl;
+      const bool partial = (kbase + 32 > k1) || (p.causal && (kbase + 31 > p.lim0));  // wave-uniform
+      if (PASS2) {
+        float col = 0.0f;
         if (!partial) {
 #pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            acc[r] = fmaf(acc[r], p.scale2, -ref[r]);
-            tmax = fmaxf(tmax, acc[r]);
-          }
+          for (int r = 0; r < 16; ++r) col += fast_exp2(fmaf(acc[r], p.scale2, -ref[r]));
         } else {
 #pragma unroll
           for (int r = 0; r < 16; ++r) {
-            const bool vis = kidx < k1 && kidx <= sLim[wave * 32 + acc_row(r, kg)];
-            acc[r] = (vis ? acc[r] * p.scale2 : NEG_BIG) - ref[r];
-            tmax = fmaxf(tmax, acc[r]);
+            const bool vis = kidx < k1 && kidx <= sLim[rt * 32 + acc_row(r, kg)];
+            const float e = fast_exp2(fmaf(acc[r], p.scale2, -ref[r]));
+            col += vis ? e : 0.0f;
           }
         }
-        if (__any(tmax > RESCALE_AT)) {
-          // rare: raise the references of this wave's rows to the row maxima of this tile.
-          // (masks only ever hide the tail of a range, so a row whose reference is still unset
-          // has t = 0 here and never enters this branch with a visible key)
+        col += __shfl_xor(col, 32);
+        if (kg == 0) sCol[rt * nkr + nt * 32 + rl] = col;
+      } else {
+        // acc is turned in place into t = x - ref (x = scaled logit, masked -> NEG_BIG)
+        if (nt == 0) {
+          // first tile of the range: the references start at this tile's row maxima
 #pragma unroll
           for (int r = 0; r < 16; ++r) {
-            const float x = acc[r] + ref[r];
-            const float nref = fmaxf(ref[r], half_allmax(x));
-            sum[r] *= fast_exp2(ref[r] - nref);
-            ref[r] = nref;
-            acc[r] = x - nref;
-            __builtin_amdgcn_sched_barrier(0);
+            float x = acc[r] * p.scale2;
+            if (partial) {
+              const bool vis = kidx < k1 && kidx <= sLim[rt * 32 + acc_row(r, kg)];
+              x = vis ? x : NEG_BIG;
+            }
+            ref[r] = half_allmax(x);
+            acc[r] = x - ref[r];
+            __builtin_amdgcn_sched_barrier(0);  // one row at a time: keeps register pressure low
+          }
+        } else {
+          float tmax = NEG_BIG;
+          if (!partial) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+              acc[r] = fmaf(acc[r], p.scale2, -ref[r]);
+              tmax = fmaxf(tmax, acc[r]);
+            }
+          } else {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+              const bool vis = kidx < k1 && kidx <= sLim[rt * 32 + acc_row(r, kg)];
+              acc[r] = (vis ? acc[r] * p.scale2 : NEG_BIG) - ref[r];
+              tmax = fmaxf(tmax, acc[r]);
+            }
+          }
+          if (__any(tmax > RESCALE_AT)) {
+            // rare: raise the references of this wave's rows to the row maxima of this tile.
+            // (masks only ever hide the tail of a range, so a row whose reference is still unset
+            // has t = 0 here and never enters this branch with a visible key)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+              const float x = acc[r] + ref[r];
+              const float nref = fmaxf(ref[r], half_allmax(x));
+              sum[r] *= fast_exp2(ref[r] - nref);
+              ref[r] = nref;
+              acc[r] = x - nref;
+              __builtin_amdgcn_sched_barrier(0);
+            }
           }
         }
-      }
 #pragma unroll
-      for (int r = 0; r < 16; ++r) sum[r] += fast_exp2(acc[r]);
+        for (int r = 0; r < 16; ++r) sum[r] += fast_exp2(acc[r]);
+      }
+    }
+    if (!PASS2) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const float s = half_allsum(sum[r]);
+        const int row = qg * MQ + rt * 32 + acc_row(r, kg);
+        if (rl == 0 && row < p.m_rows) p.part[((size_t)h * p.n_ranges + kr) * p.m_pad + row] = make_float2(ref[r], s);
+      }
+    }
+  } else {
+    // hashing waves: SimHash sign bits of the range's block keys and of this workgroup's queries
+    const int n_ktiles_h = in_ctx ? 0 : n_tiles;  // look-back keys are never candidates: not hashed
+    const int n_vt = n_ktiles_h + n_hq_tiles;
+#pragma unroll 1
+    for (int mt = rt; mt < n_mt; mt += 8) {
+      if (mt != rt) {
+        const int pm = plane0 + min(mt * 32 + rl, n_pl - 1);
+        const char* ptr = p.planes + (size_t)pm * (D * ES);
+#pragma unroll
+        for (int i = 0; i < NCH; ++i) a[i] = ld16(ptr + (2 * i + kg) * 16);
+      }
+#pragma unroll 1
+      for (int vt = 0; vt < n_vt; ++vt) {
+        const int base = vt < n_ktiles_h ? vt * 32 : nkr + (vt - n_ktiles_h) * 32;
+        f32x16 acc;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
+        const uint4* brow = sK + (size_t)(base + rl) * CHP + kg;
+#pragma unroll
+        for (int i = 0; i < NCH; ++i) Mma<DT>::run(acc, a[i], brow[2 * i]);
+        uint32_t mask = 0u;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) mask |= (acc[r] >= 0.0f ? 1u : 0u) << acc_row(r, kg);
+        mask |= (uint32_t)__shfl_xor((int)mask, 32);
+        if (kg == 0) sBits[(size_t)(base + rl) * BITS_PITCH + mt] = mask;
+      }
     }
   }
   LKV_TS(2);
@@ -300,81 +405,44 @@ void pass_kernel(PassParams p) {
       if (kidx >= p.t_ctx) {
         float v = 0.0f;
 #pragma unroll
-        for (int w = 0; w < NW; ++w) v += sCol[w * nkr + t];
+        for (int w = 0; w < 8; ++w) v += sCol[w * nkr + t];
         p.s_part[((size_t)qg * p.n_kv_heads + h) * p.s_t + (kidx - p.t_ctx)] = v;
       }
     }
   } else {
-#pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      const float s = half_allsum(sum[r]);
-      const int row = qg * MQ + wave * 32 + acc_row(r, kg);
-      if (rl == 0 && row < p.m_rows) p.part[((size_t)h * p.n_ranges + kr) * p.m_pad + row] = make_float2(ref[r], s);
-    }
+    __syncthreads();
     LKV_TS(3);
-
-    // 3. SimHash codes of the range's block keys and of this workgroup's window queries
-    if (do_hash) {
-      const int n_ktiles_h = in_ctx ? 0 : n_tiles;  // look-back keys are never candidates: not hashed
-      const int n_vt = n_ktiles_h + n_hq_tiles;
-      const int n_mt = (p.n_planes + 31) >> 5;
-#pragma unroll 1
-      for (int mt = wave; mt < n_mt; mt += NW) {
-        {
-          const int pm = min(mt * 32 + rl, p.n_planes - 1);
-          const char* ptr = p.planes + (size_t)pm * (D * ES);
+    // codes: one item = (vector row, group of 8 tables) -> one 16-byte store where aligned
+    const uint32_t code_mask = (1u << p.n_bits) - 1u;
+    const int n_tg8 = (n_tab + 7) >> 3;
+    const int n_krows_h = in_ctx ? 0 : n_keys_wg;
+    const int n_items = (n_krows_h + n_hq) * n_tg8;
+    for (int it = tid; it < n_items; it += NTHR) {
+      const int vr = it / n_tg8, tb = (it - vr * n_tg8) * 8;
+      const bool is_key = vr < n_krows_h;
+      const int lrow = is_key ? vr : nkr + (vr - n_krows_h);
+      const uint32_t* bits = sBits + (size_t)lrow * BITS_PITCH;
+      uint32_t codes[8];
 #pragma unroll
-          for (int i = 0; i < NCH; ++i) a[i] = ld16(ptr + (2 * i + kg) * 16);
-        }
-#pragma unroll 1
-        for (int vt = 0; vt < n_vt; ++vt) {
-          const int base = vt < n_ktiles_h ? vt * 32 : nkr + (vt - n_ktiles_h) * 32;
-          f32x16 acc;
-#pragma unroll
-          for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
-          const uint4* brow = sK + (size_t)(base + rl) * CHP + kg;
-#pragma unroll
-          for (int i = 0; i < NCH; ++i) Mma<DT>::run(acc, a[i], brow[2 * i]);
-          uint32_t mask = 0u;
-#pragma unroll
-          for (int r = 0; r < 16; ++r) mask |= (acc[r] >= 0.0f ? 1u : 0u) << acc_row(r, kg);
-          mask |= (uint32_t)__shfl_xor((int)mask, 32);
-          if (kg == 0) sBits[(size_t)(base + rl) * BITS_PITCH + mt] = mask;
-        }
+      for (int u = 0; u < 8; ++u) {
+        const int bitpos = min(tb + u, n_tab - 1) * p.n_bits;
+        const int w0 = bitpos >> 5, sh = bitpos & 31;
+        const uint64_t two = (uint64_t)bits[w0] | ((uint64_t)bits[w0 + 1] << 32);
+        codes[u] = (uint32_t)(two >> sh) & code_mask;
       }
-      __syncthreads();
-      // codes: one item = (vector row, group of 8 tables) -> one 16-byte store where aligned
-      const uint32_t code_mask = (1u << p.n_bits) - 1u;
-      const int n_tg8 = (p.n_tables + 7) >> 3;
-      const int n_krows_h = in_ctx ? 0 : n_keys_wg;
-      const int n_items = (n_krows_h + n_hq) * n_tg8;
-      for (int it = tid; it < n_items; it += NTHR) {
-        const int vr = it / n_tg8, tb = (it - vr * n_tg8) * 8;
-        const bool is_key = vr < n_krows_h;
-        const int lrow = is_key ? vr : nkr + (vr - n_krows_h);
-        const uint32_t* bits = sBits + (size_t)lrow * BITS_PITCH;
-        uint32_t codes[8];
+      uint16_t* dst = is_key ? p.sig_k + ((size_t)h * p.s_t + seg_row0 + vr) * p.n_tables + tab0 + tb
+                             : p.sig_q + ((size_t)h * p.m_rows + hq0 + (vr - n_krows_h)) * p.n_tables + tab0 + tb;
+      if (tb + 8 <= n_tab && ((reinterpret_cast<uintptr_t>(dst) & 15) == 0)) {
+        *reinterpret_cast<uint4*>(dst) = make_uint4(codes[0] | (codes[1] << 16), codes[2] | (codes[3] << 16),
+                                                    codes[4] | (codes[5] << 16), codes[6] | (codes[7] << 16));
+      } else {
 #pragma unroll
-        for (int u = 0; u < 8; ++u) {
-          const int bitpos = min(tb + u, p.n_tables - 1) * p.n_bits;
-          const int w0 = bitpos >> 5, sh = bitpos & 31;
-          const uint64_t two = (uint64_t)bits[w0] | ((uint64_t)bits[w0 + 1] << 32);
-          codes[u] = (uint32_t)(two >> sh) & code_mask;
-        }
-        uint16_t* dst = is_key ? p.sig_k + ((size_t)h * p.s_t + seg_row0 + vr) * p.n_tables + tb
-                               : p.sig_q + ((size_t)h * p.m_rows + hq0 + (vr - n_krows_h)) * p.n_tables + tb;
-        if (tb + 8 <= p.n_tables && ((reinterpret_cast<uintptr_t>(dst) & 15) == 0)) {
-          *reinterpret_cast<uint4*>(dst) = make_uint4(codes[0] | (codes[1] << 16), codes[2] | (codes[3] << 16),
-                                                      codes[4] | (codes[5] << 16), codes[6] | (codes[7] << 16));
-        } else {
-#pragma unroll
-          for (int u = 0; u < 8; ++u)
-            if (tb + u < p.n_tables) dst[u] = (uint16_t)codes[u];
-        }
+        for (int u = 0; u < 8; ++u)
+          if (tb + u < n_tab) dst[u] = (uint16_t)codes[u];
       }
-      if (!in_ctx)
-        for (int t = tid; t < n_keys_wg; t += NTHR) p.cnt[(size_t)h * p.s_t + seg_row0 + t] = 0;
     }
+    if (!in_ctx && qg == 0)
+      for (int t = tid; t < n_keys_wg; t += NTHR) p.cnt[(size_t)h * p.s_t + seg_row0 + t] = 0;
   }
   LKV_TS(4);
 }
@@ -566,23 +634,30 @@ __global__ __launch_bounds__(256) void append_kernel(AppendParams p) {
 // ---------------------------------------------------------------------------------------------
 // launchers
 // ---------------------------------------------------------------------------------------------
-template <int DT, int D, int NW, bool PASS2>
-static hipError_t launch_pass_nw(const PassParams& p, hipStream_t st) {
-  dim3 grid(p.n_ranges * p.n_qgroups * p.n_kv_heads);
-  const int q_tile_rows = (p.q_rows_per_wg + 31) & ~31;
-  const size_t lds = pass_lds_bytes<DT, D, NW, PASS2>(p.keys_per_range, q_tile_rows);
-  hipLaunchKernelGGL((pass_kernel<DT, D, NW, PASS2>), grid, dim3(NW * 64), lds, st, p);
-  return hipGetLastError();
+// offset of the small per-row arrays = size of the larger of the two big LDS layouts of a sweep
+size_t sweep_lds_tail_offset(int dtype, int head_dim, bool pass2, int range_keys, int q_rows_per_wg) {
+  const int es = dtype == DT_BF16 ? 2 : 4;
+  const int ch = head_dim * es / 16;
+  const size_t pitch = (size_t)(ch + 1) * 16;
+  const size_t qt = pass2 ? 0 : (size_t)((q_rows_per_wg + 31) & ~31);
+  const size_t rows = range_keys + qt;
+  const size_t steady = rows * pitch + (pass2 ? (size_t)8 * range_keys * 4 : rows * BITS_PITCH * 4);
+  const size_t staging = ch <= 16 ? (size_t)(pass2 ? 1 : 2) * PASS_ROWS * pitch : 0;
+  return ((steady > staging ? steady : staging) + 15) & ~(size_t)15;
+}
+
+size_t sweep_lds_bytes(int dtype, int head_dim, bool pass2, int range_keys, int q_rows_per_wg) {
+  return sweep_lds_tail_offset(dtype, head_dim, pass2, range_keys, q_rows_per_wg) + (size_t)PASS_ROWS * 8;
 }
 
 template <int DT, int D, bool PASS2>
 static hipError_t launch_pass_t(const PassParams& p, hipStream_t st) {
-  switch (p.rows_per_group) {
-    case 512: return launch_pass_nw<DT, D, 16, PASS2>(p, st);
-    case 256: return launch_pass_nw<DT, D, 8, PASS2>(p, st);
-    case 128: return launch_pass_nw<DT, D, 4, PASS2>(p, st);
-    default: return hipErrorInvalidValue;
-  }
+  dim3 grid(p.n_ranges * p.n_qgroups * p.n_kv_heads);
+  PassParams q = p;
+  q.lds_tail_offset = (int)sweep_lds_tail_offset(DT, D, PASS2, p.keys_per_range, p.q_rows_per_wg);
+  const size_t lds = sweep_lds_bytes(DT, D, PASS2, p.keys_per_range, p.q_rows_per_wg);
+  hipLaunchKernelGGL((pass_kernel<DT, D, PASS2>), grid, dim3(PASS_WAVES * 64), lds, st, q);
+  return hipGetLastError();
 }
 
 template <bool PASS2>
@@ -603,10 +678,7 @@ hipError_t launch_sweep2(int dtype, int head_dim, const PassParams& p, hipStream
 
 template <int DT, int D>
 static hipError_t pass_attrs() {
-  const void* fns[] = {
-      reinterpret_cast<const void*>(&pass_kernel<DT, D, 16, false>), reinterpret_cast<const void*>(&pass_kernel<DT, D, 16, true>),
-      reinterpret_cast<const void*>(&pass_kernel<DT, D, 8, false>), reinterpret_cast<const void*>(&pass_kernel<DT, D, 8, true>),
-      reinterpret_cast<const void*>(&pass_kernel<DT, D, 4, false>), reinterpret_cast<const void*>(&pass_kernel<DT, D, 4, true>)};
+  const void* fns[] = {reinterpret_cast<const void*>(&pass_kernel<DT, D, false>), reinterpret_cast<const void*>(&pass_kernel<DT, D, true>)};
   for (const void* f : fns) {
     hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
     if (e != hipSuccess) return e;
@@ -625,17 +697,7 @@ hipError_t init_kernel_attributes() {
 }
 
 int score_max_range() { return SCORE_MAX_RANGE; }
-
-size_t sweep_lds_bytes(int dtype, int head_dim, int rows_per_group, int range_keys, int q_rows_per_wg) {
-  // the larger of the two sweeps, for the host's range sizing
-  const int es = dtype == DT_BF16 ? 2 : 4;
-  const size_t pitch = (size_t)(head_dim * es / 16 + 1) * 16;
-  const int nw = rows_per_group / 32;
-  const size_t qt = (size_t)((q_rows_per_wg + 31) & ~31);
-  const size_t s1 = (range_keys + qt) * pitch + (range_keys + qt) * BITS_PITCH * 4 + (size_t)nw * 32 * 8;
-  const size_t s2 = (size_t)range_keys * pitch + (size_t)nw * range_keys * 4 + (size_t)nw * 32 * 8;
-  return s1 > s2 ? s1 : s2;
-}
+int sweep_rows_per_group() { return PASS_ROWS; }
 
 hipError_t launch_count(const CountParams& p, int n_kv_heads, hipStream_t st) {
   const int n_tg = (p.n_tables + p.tables_per_group - 1) / p.tables_per_group;
