@@ -50,6 +50,7 @@ def main():
     ap.add_argument("--layer", type=int, default=0)
     ap.add_argument("--mode", choices=["graph", "eager"], default="graph")
     ap.add_argument("--profile-steps", type=int, default=3)
+    ap.add_argument("--unfused", action="store_true", help="laserkv_select_block + laserkv_append instead of laserkv_compress_block")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="lower bound of oracle work for cpu_baseline; 0 skips")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -70,7 +71,7 @@ def main():
     print(f"[bench] workload {wl.name}: inputs generated and resident in {time.time() - t_gen:.1f}s "
           f"(B={comp.B}, parts={comp.parts})", file=sys.stderr, flush=True)
 
-    plan = comp.plan_layer(ddev)
+    plan = comp.plan_layer(ddev, fused=not args.unfused)
     stream = torch.cuda.Stream()
     graph = None
     with torch.cuda.stream(stream):
@@ -104,6 +105,8 @@ def main():
     value = tokens / (ms_per_step * 1e-3)
 
     work = algorithmic_work(wl, comp.B)
+    if not args.unfused:  # the last kernel selects and appends
+        work["select"] = ("hbm", work["select"][1] + work["append"][1])
     kern = {k: dict(avg_us=1e3 * ms / max(n, 1), launches=n) for k, (ms, n) in prof.items()}
     if not any(v["launches"] for v in kern.values()):
         print(json.dumps(dict(value=round(value, 1), unit="tokens/s/layer", ms_per_step=round(ms_per_step, 4),
@@ -145,7 +148,8 @@ def main():
                config=dict(workload=wl.name, l_ctx=wl.l_ctx, s_block=wl.s_block, window=wl.window, n=wl.n_div,
                            lsh_tables=wl.lsh_tables, lsh_bits=wl.lsh_bits, n_q_heads=wl.n_q_heads,
                            n_kv_heads=wl.n_kv_heads, head_dim=wl.head_dim, budget_per_block=comp.B,
-                           blocks=wl.n_blocks, layers_timed=1, launch=args.mode),
+                           blocks=wl.n_blocks, layers_timed=1, launch=args.mode,
+                           entry="laserkv_select_block+laserkv_append" if args.unfused else "laserkv_compress_block"),
                roofline=roofline, cpu_baseline=cpu)
     print(json.dumps(out), flush=True)
     return 0

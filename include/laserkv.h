@@ -126,6 +126,26 @@ int laserkv_append(laserkv_ctx* ctx,
                    int64_t cache_len, int64_t cache_cap,
                    void* hip_stream);
 
+/* Steps a1-a5 in one call: laserkv_select_block followed by laserkv_append with the same arguments
+ * (Alg. 1 and the Sec. 3.1 partition, then the append-only retention of Sec. 3, first paragraph),
+ * but with the selection and the gather sharing one kernel, which saves a kernel boundary per block.
+ * Results are identical to the two separate calls.  keep_idx still receives the kept indices.
+ * Errors: those of both calls; nothing is launched when any check fails. */
+int laserkv_compress_block(laserkv_ctx* ctx,
+                           const void* q_win, int64_t q_stride_head, int64_t q_stride_tok,
+                           const void* k_blk, int64_t k_stride_head, int64_t k_stride_tok,
+                           const void* v_blk, int64_t v_stride_head, int64_t v_stride_tok,
+                           const void* k_ctx, int64_t c_stride_head, int64_t c_stride_tok,
+                           const void* hyperplanes,
+                           int32_t s_t, int32_t w, int32_t t_ctx,
+                           int64_t block_pos0, int64_t q_pos0, int32_t causal,
+                           int32_t n_anchor, int32_t n_local, int32_t k_exact, int32_t k_lsh,
+                           int32_t* keep_idx,
+                           void* k_cache, void* v_cache, int64_t cache_stride_head,
+                           int64_t* cache_pos, int64_t pos_stride_head,
+                           int64_t cache_len, int64_t cache_cap,
+                           void* hip_stream);
+
 /* Per-kernel timing for benchmarks.  Between laserkv_profile_begin and laserkv_profile_end every
  * kernel the context launches is bracketed by a pair of HIP events on the call's stream (which adds
  * a little time between kernels, so whole-path timings belong outside such a bracket).

@@ -18,7 +18,7 @@ LKV_OK, LKV_EINVAL, LKV_ECAP, LKV_ENOMEM, LKV_EHIP = 0, -1, -2, -3, -4
 
 EXPORTS = (
     "laserkv_create", "laserkv_destroy", "laserkv_last_error", "laserkv_budget",
-    "laserkv_partition", "laserkv_select_block", "laserkv_append",
+    "laserkv_partition", "laserkv_select_block", "laserkv_append", "laserkv_compress_block",
     "laserkv_profile_begin", "laserkv_profile_end",
 )
 KERNEL_NAMES = ("sweep1", "sweep2", "count", "select", "append")
@@ -69,6 +69,11 @@ def load():
         vp, vp, i64, i64, vp, i64, i64, vp, i32, i32, i64,
         vp, vp, i64, vp, i64, i64, i64, vp]
     lib.laserkv_append.restype = C.c_int
+    lib.laserkv_compress_block.argtypes = [
+        vp, vp, i64, i64, vp, i64, i64, vp, i64, i64, vp, i64, i64, vp,
+        i32, i32, i32, i64, i64, i32, i32, i32, i32, i32,
+        vp, vp, vp, i64, vp, i64, i64, i64, vp]
+    lib.laserkv_compress_block.restype = C.c_int
     lib.laserkv_profile_begin.argtypes = [vp]
     lib.laserkv_profile_begin.restype = C.c_int
     lib.laserkv_profile_end.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(i64)]
@@ -167,6 +172,25 @@ class LaserKV:
             self._ctx, _ptr(k_blk), ks[0], ks[1], _ptr(v_blk), vs[0], vs[1], _ptr(keep_idx), b_t, k_blk.shape[1],
             block_pos0, _ptr(k_cache), _ptr(v_cache), k_cache.stride(0), _ptr(cache_pos), cache_pos.stride(0),
             cache_len, k_cache.shape[1], self._stream(stream))
+        self._check(rc)
+
+    def laserkv_compress_block(self, q_win, k_blk, v_blk, k_ctx, hyperplanes, *, block_pos0, q_pos0=None, causal=True,
+                               n_anchor, n_local, k_exact, k_lsh, keep_idx, k_cache, v_cache, cache_pos, cache_len,
+                               stream=None):
+        d = self.cfg.head_dim
+        s_t, w = k_blk.shape[1], q_win.shape[1]
+        t_ctx = 0 if k_ctx is None else k_ctx.shape[1]
+        if q_pos0 is None:
+            q_pos0 = block_pos0 + s_t - w
+        qs, ks, vs = _strides3(q_win, d), _strides3(k_blk, d), _strides3(v_blk, d)
+        cs = _strides3(k_ctx, d) if k_ctx is not None else (0, 0)
+        assert hyperplanes.is_contiguous()
+        assert k_cache.stride(2) == 1 and k_cache.stride(1) == d and v_cache.stride() == k_cache.stride()
+        rc = self._lib.laserkv_compress_block(
+            self._ctx, _ptr(q_win), qs[0], qs[1], _ptr(k_blk), ks[0], ks[1], _ptr(v_blk), vs[0], vs[1],
+            _ptr(k_ctx), cs[0], cs[1], _ptr(hyperplanes), s_t, w, t_ctx, block_pos0, q_pos0, 1 if causal else 0,
+            n_anchor, n_local, k_exact, k_lsh, _ptr(keep_idx), _ptr(k_cache), _ptr(v_cache), k_cache.stride(0),
+            _ptr(cache_pos), cache_pos.stride(0), cache_len, k_cache.shape[1], self._stream(stream))
         self._check(rc)
 
     def laserkv_profile_begin(self):

@@ -33,7 +33,10 @@ struct laserkv_ctx {
   float2* part;      // [H_kv, max_ranges, m_pad]
   float* s_part;     // [n_qgroups_max, H_kv, max_block]
   float* s_exact;    // [H_kv, max_block]
-  int32_t* cnt;      // [H_kv, max_block]
+  int32_t* cnt;      // [n_qgroups_max, H_kv, max_block] count parts
+  int32_t* cnt_sum;  // [H_kv, max_block] summed counts (stage output)
+  uint32_t* qhist;   // [H_kv, L, 2^K / 2] or null when the tables are too large to keep zeroed
+  int qhist_words_per_head;
   uint16_t* sig_k;   // [H_kv, max_block, L]
   uint16_t* sig_q;   // [H_q, max_window, L]
   int m_pad;
@@ -173,6 +176,10 @@ int laserkv_create(const laserkv_config* cfg, laserkv_ctx** out) {
   const int m_rows = group * c.max_window;
   ctx->m_pad = (m_rows + 255) / 256 * 256;
   const int n_qg_max = (m_rows + 127) / 128;
+  // query-code histograms stay resident (and zeroed between blocks) when a head's tables fit 512 KiB
+  const size_t hist_bytes_head = ((size_t)c.lsh_tables << c.lsh_bits) * 2;
+  const bool use_qhist = hist_bytes_head <= 512 * 1024 && hist_bytes_head % 16 == 0 && env_int("LASERKV_NO_QHIST", 0) == 0;
+  ctx->qhist_words_per_head = use_qhist ? (int)(hist_bytes_head / 4) : 0;
   // ranges of at most score_max_range() keys, plus one for the look-back keys, and room for finer splits
   ctx->max_ranges = (c.max_block + c.max_ctx_keys) / lkv::score_max_range() + 2;
   if (ctx->max_ranges < 64) ctx->max_ranges = 64;
@@ -181,7 +188,8 @@ int laserkv_create(const laserkv_config* cfg, laserkv_ctx** out) {
       {(void**)&ctx->part, hk * ctx->max_ranges * ctx->m_pad * sizeof(float2)},
       {(void**)&ctx->s_part, (size_t)n_qg_max * hk * sb * sizeof(float)},
       {(void**)&ctx->s_exact, hk * sb * sizeof(float)},
-      {(void**)&ctx->cnt, hk * sb * sizeof(int32_t)},
+      {(void**)&ctx->cnt, (size_t)n_qg_max * hk * sb * sizeof(int32_t)},
+      {(void**)&ctx->cnt_sum, hk * sb * sizeof(int32_t)},
       {(void**)&ctx->sig_k, hk * sb * c.lsh_tables * sizeof(uint16_t)},
       {(void**)&ctx->sig_q, (size_t)c.n_q_heads * c.max_window * c.lsh_tables * sizeof(uint16_t)},
   };
@@ -192,13 +200,21 @@ int laserkv_create(const laserkv_config* cfg, laserkv_ctx** out) {
       return fail(nullptr, LKV_ENOMEM, "create: hipMalloc of %zu bytes failed: %s", al.bytes, hipGetErrorString(e));
     }
   }
+  if (use_qhist) {
+    e = hipMalloc((void**)&ctx->qhist, hk * hist_bytes_head);
+    if (e == hipSuccess) e = hipMemset(ctx->qhist, 0, hk * hist_bytes_head);
+    if (e != hipSuccess) {
+      laserkv_destroy(ctx);
+      return fail(nullptr, LKV_ENOMEM, "create: histogram workspace: %s", hipGetErrorString(e));
+    }
+  }
   *out = ctx;
   return LKV_OK;
 }
 
 void laserkv_destroy(laserkv_ctx* ctx) {
   if (!ctx) return;
-  void* ptrs[] = {ctx->part, ctx->s_part, ctx->s_exact, ctx->cnt, ctx->sig_k, ctx->sig_q};
+  void* ptrs[] = {ctx->part, ctx->s_part, ctx->s_exact, ctx->cnt, ctx->cnt_sum, ctx->qhist, ctx->sig_k, ctx->sig_q};
   for (void* p : ptrs)
     if (p) (void)hipFree(p);
   if (ctx->ev_pool)
@@ -208,17 +224,22 @@ void laserkv_destroy(laserkv_ctx* ctx) {
   delete ctx;
 }
 
-int laserkv_select_block(laserkv_ctx* ctx,
-                         const void* q_win, int64_t q_stride_head, int64_t q_stride_tok,
-                         const void* k_blk, int64_t k_stride_head, int64_t k_stride_tok,
-                         const void* k_ctx, int64_t c_stride_head, int64_t c_stride_tok,
-                         const void* hyperplanes,
-                         int32_t s_t, int32_t w, int32_t t_ctx,
-                         int64_t block_pos0, int64_t q_pos0, int32_t causal,
-                         int32_t n_anchor, int32_t n_local, int32_t k_exact, int32_t k_lsh,
-                         int32_t* keep_idx,
-                         float* dbg_s_exact, uint16_t* dbg_sig_k, uint16_t* dbg_sig_q, int32_t* dbg_count,
-                         void* hip_stream) {
+}  // extern "C"
+
+namespace {
+
+// Steps a1-a4, and a5 in the same last kernel when `fused` is given.
+int select_impl(laserkv_ctx* ctx,
+                const void* q_win, int64_t q_stride_head, int64_t q_stride_tok,
+                const void* k_blk, int64_t k_stride_head, int64_t k_stride_tok,
+                const void* k_ctx, int64_t c_stride_head, int64_t c_stride_tok,
+                const void* hyperplanes,
+                int32_t s_t, int32_t w, int32_t t_ctx,
+                int64_t block_pos0, int64_t q_pos0, int32_t causal,
+                int32_t n_anchor, int32_t n_local, int32_t k_exact, int32_t k_lsh,
+                int32_t* keep_idx,
+                float* dbg_s_exact, uint16_t* dbg_sig_k, uint16_t* dbg_sig_q, int32_t* dbg_count,
+                const lkv::AppendParams* fused, void* hip_stream) {
   if (!ctx) return fail(nullptr, LKV_EINVAL, "select_block: null context");
   const laserkv_config& c = ctx->cfg;
   const int es = ctx->elem_size, d = c.head_dim, G = ctx->group;
@@ -291,6 +312,7 @@ int laserkv_select_block(laserkv_ctx* ctx,
   sp.sig_k = ctx->sig_k;
   sp.sig_q = ctx->sig_q;
   sp.cnt = ctx->cnt;
+  sp.qhist = ctx->qhist;
 
   lkv::CountParams cp;
   cp.sig_k = ctx->sig_k;
@@ -320,6 +342,10 @@ int laserkv_select_block(laserkv_ctx* ctx,
   lp.n_kv_heads = c.n_kv_heads;
   lp.inv_m = 1.0f / (float)m_rows;
   lp.cnt = ctx->cnt;
+  lp.n_cnt_parts = ctx->qhist ? n_qg : 1;
+  lp.cnt_out = ctx->cnt_sum;
+  lp.qhist = ctx->qhist;
+  lp.qhist_words_per_head = ctx->qhist_words_per_head;
   lp.s_t = s_t;
   lp.n_anchor = n_anchor;
   lp.n_local = n_local;
@@ -335,10 +361,17 @@ int laserkv_select_block(laserkv_ctx* ctx,
     return fail_hip(ctx, e, "select_block: sweep 1 (row statistics + SimHash codes)");
   if ((e = timed(ctx, LKV_KERN_SWEEP2, st, [&] { return lkv::launch_sweep2(dt, d, sp, st); })) != hipSuccess)
     return fail_hip(ctx, e, "select_block: sweep 2 (pooled probabilities)");
-  if ((e = timed(ctx, LKV_KERN_COUNT, st, [&] { return lkv::launch_count(cp, nh, st); })) != hipSuccess)
+  if (!ctx->qhist && (e = timed(ctx, LKV_KERN_COUNT, st, [&] { return lkv::launch_count(cp, nh, st); })) != hipSuccess)
     return fail_hip(ctx, e, "select_block: count kernel");
-  if ((e = timed(ctx, LKV_KERN_SELECT, st, [&] { return lkv::launch_select(lp, st); })) != hipSuccess)
+  if (fused) {
+    lkv::AppendParams ap = *fused;
+    ap.keep = keep_idx;
+    const int n_cu = ctx->n_cu;
+    if ((e = timed(ctx, LKV_KERN_SELECT, st, [&] { return lkv::launch_select_append(lp, ap, n_cu, st); })) != hipSuccess)
+      return fail_hip(ctx, e, "compress_block: select + append kernel");
+  } else if ((e = timed(ctx, LKV_KERN_SELECT, st, [&] { return lkv::launch_select(lp, st); })) != hipSuccess) {
     return fail_hip(ctx, e, "select_block: select kernel");
+  }
 
   const size_t hk = c.n_kv_heads;
   if (dbg_s_exact && (e = hipMemcpyAsync(dbg_s_exact, ctx->s_exact, hk * s_t * sizeof(float), hipMemcpyDeviceToDevice, st)) != hipSuccess)
@@ -347,9 +380,67 @@ int laserkv_select_block(laserkv_ctx* ctx,
     return fail_hip(ctx, e, "select_block: copy of key signatures");
   if (dbg_sig_q && (e = hipMemcpyAsync(dbg_sig_q, ctx->sig_q, (size_t)c.n_q_heads * w * c.lsh_tables * sizeof(uint16_t), hipMemcpyDeviceToDevice, st)) != hipSuccess)
     return fail_hip(ctx, e, "select_block: copy of query signatures");
-  if (dbg_count && (e = hipMemcpyAsync(dbg_count, ctx->cnt, hk * s_t * sizeof(int32_t), hipMemcpyDeviceToDevice, st)) != hipSuccess)
+  if (dbg_count && (e = hipMemcpyAsync(dbg_count, ctx->cnt_sum, hk * s_t * sizeof(int32_t), hipMemcpyDeviceToDevice, st)) != hipSuccess)
     return fail_hip(ctx, e, "select_block: copy of counts");
   return LKV_OK;
+}
+
+// Checks the append arguments and fills the kernel parameter block (keep is set by the caller).
+int append_params(laserkv_ctx* ctx,
+                  const void* k_blk, int64_t k_stride_head, int64_t k_stride_tok,
+                  const void* v_blk, int64_t v_stride_head, int64_t v_stride_tok,
+                  int32_t b_t, int32_t s_t, int64_t block_pos0,
+                  void* k_cache, void* v_cache, int64_t cache_stride_head,
+                  int64_t* cache_pos, int64_t pos_stride_head,
+                  int64_t cache_len, int64_t cache_cap, lkv::AppendParams& ap) {
+  const laserkv_config& c = ctx->cfg;
+  const int es = ctx->elem_size, d = c.head_dim;
+  if (!k_blk || !v_blk || !k_cache || !v_cache || !cache_pos) return fail(ctx, LKV_EINVAL, "append: null tensor");
+  if (s_t < 1 || b_t < 0 || b_t > s_t) return fail(ctx, LKV_EINVAL, "append: need 0 <= b_t <= s_t");
+  if (cache_len < 0 || cache_cap < 0) return fail(ctx, LKV_EINVAL, "append: negative cache length or capacity");
+  if (cache_len + b_t > cache_cap) return fail(ctx, LKV_ECAP, "append: %lld + %d rows exceed the capacity %lld", (long long)cache_len, b_t, (long long)cache_cap);
+  auto bad_stride = [&](int64_t sh, int64_t st) { return st < d || sh < 0 || ((st * es) & 15) || ((sh * es) & 15); };
+  if (bad_stride(k_stride_head, k_stride_tok) || bad_stride(v_stride_head, v_stride_tok))
+    return fail(ctx, LKV_EINVAL, "append: strides must cover a row and keep rows 16-byte aligned");
+  if (cache_stride_head < cache_cap * d || ((cache_stride_head * es) & 15)) return fail(ctx, LKV_EINVAL, "append: cache head stride too small or misaligned");
+  if (pos_stride_head < cache_cap) return fail(ctx, LKV_EINVAL, "append: position head stride below the capacity");
+  if (!aligned16(k_blk) || !aligned16(v_blk) || !aligned16(k_cache) || !aligned16(v_cache))
+    return fail(ctx, LKV_EINVAL, "append: tensors must be 16-byte aligned");
+  ap.kb = {(const char*)k_blk, k_stride_head * es, k_stride_tok * es};
+  ap.vb = {(const char*)v_blk, v_stride_head * es, v_stride_tok * es};
+  ap.keep = nullptr;
+  ap.b_t = b_t;
+  ap.s_t = s_t;
+  ap.row_bytes = d * es;
+  ap.k_cache = (char*)k_cache;
+  ap.v_cache = (char*)v_cache;
+  ap.cache_stride_head = cache_stride_head * es;
+  ap.cache_pos = cache_pos;
+  ap.pos_stride_head = pos_stride_head;
+  ap.cache_len = cache_len;
+  ap.block_pos0 = block_pos0;
+  return LKV_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int laserkv_select_block(laserkv_ctx* ctx,
+                         const void* q_win, int64_t q_stride_head, int64_t q_stride_tok,
+                         const void* k_blk, int64_t k_stride_head, int64_t k_stride_tok,
+                         const void* k_ctx, int64_t c_stride_head, int64_t c_stride_tok,
+                         const void* hyperplanes,
+                         int32_t s_t, int32_t w, int32_t t_ctx,
+                         int64_t block_pos0, int64_t q_pos0, int32_t causal,
+                         int32_t n_anchor, int32_t n_local, int32_t k_exact, int32_t k_lsh,
+                         int32_t* keep_idx,
+                         float* dbg_s_exact, uint16_t* dbg_sig_k, uint16_t* dbg_sig_q, int32_t* dbg_count,
+                         void* hip_stream) {
+  return select_impl(ctx, q_win, q_stride_head, q_stride_tok, k_blk, k_stride_head, k_stride_tok,
+                     k_ctx, c_stride_head, c_stride_tok, hyperplanes, s_t, w, t_ctx, block_pos0, q_pos0, causal,
+                     n_anchor, n_local, k_exact, k_lsh, keep_idx, dbg_s_exact, dbg_sig_k, dbg_sig_q, dbg_count,
+                     nullptr, hip_stream);
 }
 
 int laserkv_append(laserkv_ctx* ctx,
@@ -361,38 +452,45 @@ int laserkv_append(laserkv_ctx* ctx,
                    int64_t cache_len, int64_t cache_cap,
                    void* hip_stream) {
   if (!ctx) return fail(nullptr, LKV_EINVAL, "append: null context");
-  const laserkv_config& c = ctx->cfg;
-  const int es = ctx->elem_size, d = c.head_dim;
-  if (!k_blk || !v_blk || !keep_idx || !k_cache || !v_cache || !cache_pos) return fail(ctx, LKV_EINVAL, "append: null tensor");
-  if (s_t < 1 || b_t < 0 || b_t > s_t) return fail(ctx, LKV_EINVAL, "append: need 0 <= b_t <= s_t");
-  if (cache_len < 0 || cache_cap < 0) return fail(ctx, LKV_EINVAL, "append: negative cache length or capacity");
-  if (cache_len + b_t > cache_cap) return fail(ctx, LKV_ECAP, "append: %lld + %d rows exceed the capacity %lld", (long long)cache_len, b_t, (long long)cache_cap);
-  auto bad_stride = [&](int64_t sh, int64_t st) { return st < d || sh < 0 || ((st * es) & 15) || ((sh * es) & 15); };
-  if (bad_stride(k_stride_head, k_stride_tok) || bad_stride(v_stride_head, v_stride_tok))
-    return fail(ctx, LKV_EINVAL, "append: strides must cover a row and keep rows 16-byte aligned");
-  if (cache_stride_head < cache_cap * d || ((cache_stride_head * es) & 15)) return fail(ctx, LKV_EINVAL, "append: cache head stride too small or misaligned");
-  if (pos_stride_head < cache_cap) return fail(ctx, LKV_EINVAL, "append: position head stride below the capacity");
-  if (!aligned16(k_blk) || !aligned16(v_blk) || !aligned16(k_cache) || !aligned16(v_cache))
-    return fail(ctx, LKV_EINVAL, "append: tensors must be 16-byte aligned");
+  if (!keep_idx) return fail(ctx, LKV_EINVAL, "append: null tensor");
   lkv::AppendParams ap;
-  ap.kb = {(const char*)k_blk, k_stride_head * es, k_stride_tok * es};
-  ap.vb = {(const char*)v_blk, v_stride_head * es, v_stride_tok * es};
+  const int rc = append_params(ctx, k_blk, k_stride_head, k_stride_tok, v_blk, v_stride_head, v_stride_tok, b_t, s_t,
+                               block_pos0, k_cache, v_cache, cache_stride_head, cache_pos, pos_stride_head, cache_len,
+                               cache_cap, ap);
+  if (rc != LKV_OK) return rc;
   ap.keep = keep_idx;
-  ap.b_t = b_t;
-  ap.s_t = s_t;
-  ap.row_bytes = d * es;
-  ap.k_cache = (char*)k_cache;
-  ap.v_cache = (char*)v_cache;
-  ap.cache_stride_head = cache_stride_head * es;
-  ap.cache_pos = cache_pos;
-  ap.pos_stride_head = pos_stride_head;
-  ap.cache_len = cache_len;
-  ap.block_pos0 = block_pos0;
   hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
-  const int nh = c.n_kv_heads;
+  const int nh = ctx->cfg.n_kv_heads;
   hipError_t e = timed(ctx, LKV_KERN_APPEND, st, [&] { return lkv::launch_append(ap, nh, st); });
   if (e != hipSuccess) return fail_hip(ctx, e, "append: gather kernel");
   return LKV_OK;
+}
+
+int laserkv_compress_block(laserkv_ctx* ctx,
+                           const void* q_win, int64_t q_stride_head, int64_t q_stride_tok,
+                           const void* k_blk, int64_t k_stride_head, int64_t k_stride_tok,
+                           const void* v_blk, int64_t v_stride_head, int64_t v_stride_tok,
+                           const void* k_ctx, int64_t c_stride_head, int64_t c_stride_tok,
+                           const void* hyperplanes,
+                           int32_t s_t, int32_t w, int32_t t_ctx,
+                           int64_t block_pos0, int64_t q_pos0, int32_t causal,
+                           int32_t n_anchor, int32_t n_local, int32_t k_exact, int32_t k_lsh,
+                           int32_t* keep_idx,
+                           void* k_cache, void* v_cache, int64_t cache_stride_head,
+                           int64_t* cache_pos, int64_t pos_stride_head,
+                           int64_t cache_len, int64_t cache_cap,
+                           void* hip_stream) {
+  if (!ctx) return fail(nullptr, LKV_EINVAL, "compress_block: null context");
+  const int64_t b_t = (int64_t)n_anchor + n_local + k_exact + k_lsh;
+  if (n_anchor < 0 || n_local < 0 || k_exact < 0 || k_lsh < 0 || b_t > s_t) return fail(ctx, LKV_EINVAL, "compress_block: budget does not fit the block");
+  lkv::AppendParams ap;
+  const int rc = append_params(ctx, k_blk, k_stride_head, k_stride_tok, v_blk, v_stride_head, v_stride_tok, (int32_t)b_t, s_t,
+                               block_pos0, k_cache, v_cache, cache_stride_head, cache_pos, pos_stride_head, cache_len,
+                               cache_cap, ap);
+  if (rc != LKV_OK) return rc;
+  return select_impl(ctx, q_win, q_stride_head, q_stride_tok, k_blk, k_stride_head, k_stride_tok,
+                     k_ctx, c_stride_head, c_stride_tok, hyperplanes, s_t, w, t_ctx, block_pos0, q_pos0, causal,
+                     n_anchor, n_local, k_exact, k_lsh, keep_idx, nullptr, nullptr, nullptr, nullptr, &ap, hip_stream);
 }
 
 int laserkv_profile_begin(laserkv_ctx* ctx) {

@@ -42,7 +42,9 @@ struct PassParams {
   int tables_per_split; // tables hashed by one query-row group's workgroups: ceil(L / n_qgroups)
   uint16_t* sig_k;      // [H_kv, S, L]
   uint16_t* sig_q;      // [H_q, W, L] = [H_kv, M, L]
-  int32_t* cnt;         // [H_kv, S]: zeroed in sweep 1 for the count kernel's atomics
+  int32_t* cnt;         // with qhist: [n_qgroups, H_kv, S] written by sweep 2; else [H_kv, S] zeroed in sweep 1
+                        // for the count kernel's atomics
+  uint32_t* qhist;      // [H_kv, L, 2^K / 2] query-code histograms, two 16-bit bins per word; null: separate count kernel
 };
 
 struct CountParams {
@@ -60,7 +62,11 @@ struct SelectParams {
   int n_qgroups;
   int n_kv_heads;
   float inv_m;          // 1 / (G * W)
-  const int32_t* cnt;   // [H_kv, S]
+  const int32_t* cnt;   // [n_cnt_parts, H_kv, S]
+  int n_cnt_parts;
+  int32_t* cnt_out;     // [H_kv, S] summed counts (optional, for the stage outputs)
+  uint32_t* qhist;      // cleared here for the next block when not null
+  int qhist_words_per_head;
   int s_t;
   int n_anchor, n_local, k_exact, k_lsh;
   int cnt_bits;         // bits needed to hold G * W * L
@@ -87,6 +93,7 @@ hipError_t launch_sweep1(int dtype, int head_dim, const PassParams& p, hipStream
 hipError_t launch_sweep2(int dtype, int head_dim, const PassParams& p, hipStream_t st);
 hipError_t launch_count(const CountParams& p, int n_kv_heads, hipStream_t st);
 hipError_t launch_select(const SelectParams& p, hipStream_t st);
+hipError_t launch_select_append(const SelectParams& p, const AppendParams& ap, int n_cu, hipStream_t st);
 hipError_t launch_append(const AppendParams& p, int n_kv_heads, hipStream_t st);
 hipError_t init_kernel_attributes();
 size_t sweep_lds_bytes(int dtype, int head_dim, bool pass2, int range_keys, int q_rows_per_wg);

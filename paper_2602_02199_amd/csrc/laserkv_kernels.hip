@@ -271,6 +271,50 @@ __global__ __launch_bounds__(PASS_WAVES * 64) void pass_kernel(PassParams p) {
   __syncthreads();
   LKV_TS(1);
 
+  if (PASS2 && p.qhist && !in_ctx) {
+    // collision counts (Alg. 1 step 6) of this range's keys over this workgroup's share of the
+    // tables: four lanes per key, each eight tables at a time from the L2-resident query histograms
+    const int tab0c = qg * p.tables_per_split;
+    const int n_tabc = max(0, min(p.tables_per_split, p.n_tables - tab0c));
+    // lanes per key: as many groups of eight tables as there are, at most four, and one pass over the keys
+    int lpk_log = n_tabc > 16 ? 2 : (n_tabc > 8 ? 1 : 0);
+    while (lpk_log > 0 && (n_keys_wg << lpk_log) > NTHR) --lpk_log;
+    const int lpk = 1 << lpk_log;
+    for (int kq = tid; kq < (n_keys_wg << lpk_log); kq += NTHR) {
+      const int key = kq >> lpk_log, sub = kq & (lpk - 1);
+      const uint16_t* sk = p.sig_k + ((size_t)h * p.s_t + seg_row0 + key) * p.n_tables + tab0c;
+      int sum = 0;
+      for (int tb = sub * 8; tb < n_tabc; tb += 8 * lpk) {
+        uint32_t cw[4];
+        const bool vec = tb + 8 <= n_tabc && ((reinterpret_cast<uintptr_t>(sk + tb) & 15) == 0);
+        if (vec) {
+          const uint4 v = *reinterpret_cast<const uint4*>(sk + tb);
+          cw[0] = v.x; cw[1] = v.y; cw[2] = v.z; cw[3] = v.w;
+        } else {
+#pragma unroll
+          for (int u = 0; u < 4; ++u) {
+            const uint32_t lo = tb + 2 * u < n_tabc ? sk[tb + 2 * u] : 0u;
+            const uint32_t hi = tb + 2 * u + 1 < n_tabc ? sk[tb + 2 * u + 1] : 0u;
+            cw[u] = lo | (hi << 16);
+          }
+        }
+        uint32_t hv[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+          const uint32_t code = (cw[u >> 1] >> ((u & 1) * 16)) & 0xffffu;
+          const int t = min(tb + u, n_tabc - 1);
+          const uint32_t idx = ((uint32_t)(h * p.n_tables + tab0c + t) << p.n_bits) | code;
+          hv[u] = (p.qhist[idx >> 1] >> ((idx & 1u) * 16)) & 0xffffu;
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) sum += (tb + u < n_tabc) ? (int)hv[u] : 0;
+      }
+      if (lpk > 1) sum += __shfl_xor(sum, 1);
+      if (lpk > 2) sum += __shfl_xor(sum, 2);
+      if (sub == 0) p.cnt[((size_t)qg * p.n_kv_heads + h) * p.s_t + seg_row0 + key] = sum;
+    }
+  }
+
   if (!hash_wave) {
     float ref[16], sum[16];  // sweep 1: (reference, sum); sweep 2: ref holds the row lse
 #pragma unroll
@@ -440,8 +484,17 @@ __global__ __launch_bounds__(PASS_WAVES * 64) void pass_kernel(PassParams p) {
         for (int u = 0; u < 8; ++u)
           if (tb + u < n_tab) dst[u] = (uint16_t)codes[u];
       }
+      if (!is_key && p.qhist) {
+        // per-(head, table) histogram of the query codes, two 16-bit bins per word (a bin holds <= G*W <= 1024)
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+          if (tb + u < n_tab) {
+            const uint32_t idx = ((uint32_t)(h * p.n_tables + tab0 + tb + u) << p.n_bits) | codes[u];
+            atomicAdd(p.qhist + (idx >> 1), 1u << ((idx & 1u) * 16));
+          }
+      }
     }
-    if (!in_ctx && qg == 0)
+    if (!p.qhist && !in_ctx && qg == 0)  // the separate count kernel accumulates with atomics
       for (int t = tid; t < n_keys_wg; t += NTHR) p.cnt[(size_t)h * p.s_t + seg_row0 + t] = 0;
   }
   LKV_TS(4);
@@ -489,13 +542,30 @@ __global__ __launch_bounds__(256) void count_kernel(CountParams p) {
 // address atomics), which also yields how many keys equal to the threshold are still needed; those
 // are taken in index order via a prefix count.
 // ---------------------------------------------------------------------------------------------
-template <int EPT>
-__global__ __launch_bounds__(1024) void select_kernel(SelectParams p) {
+//
+// FUSED = true also appends: a head's selection is then computed redundantly by `split` workgroups
+// (the inputs are L2-resident and the compute units would idle otherwise), and each of them copies
+// its share of the kept K/V rows to the cache tail.  That saves a kernel boundary, which on this
+// chip costs about as much as the whole copy.
+template <int EPT, bool FUSED>
+__global__ __launch_bounds__(1024) void select_kernel(SelectParams p, AppendParams ap, int split) {
   __shared__ uint32_t sHist[4][256];
   __shared__ int sWave[16];
   __shared__ int sPick[2];  // digit chosen in this round, keys still needed below it
+  __shared__ int sKeep[FUSED ? 1024 : 1];  // FUSED: the kept indices this workgroup copies
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-  const int h = blockIdx.x;
+  const int n_sel_wg = p.n_kv_heads * split;
+  const int h = FUSED ? blockIdx.x / split : blockIdx.x;
+  const int part = FUSED ? blockIdx.x - h * split : 0;
+  if ((int)blockIdx.x >= n_sel_wg) {
+    // extra workgroups: the query histograms have been consumed by the sweep before this kernel;
+    // clear them for the next block, a slice each
+    const int n_z = gridDim.x - n_sel_wg, z = blockIdx.x - n_sel_wg;
+    const size_t n_vec = (size_t)p.n_kv_heads * p.qhist_words_per_head / 4;
+    uint4* hz = reinterpret_cast<uint4*>(p.qhist);
+    for (size_t i = (size_t)z * 1024 + tid; i < n_vec; i += (size_t)n_z * 1024) hz[i] = make_uint4(0u, 0u, 0u, 0u);
+    return;
+  }
 
   uint32_t key[EPT], c2[EPT];
   bool inr[EPT], cand[EPT], sel[EPT];
@@ -511,11 +581,15 @@ __global__ __launch_bounds__(1024) void select_kernel(SelectParams p) {
       float s = 0.0f;
       for (int qg = 0; qg < p.n_qgroups; ++qg) s += p.s_part[((size_t)qg * p.n_kv_heads + h) * p.s_t + i];
       s *= p.inv_m;
-      p.s_exact[(size_t)h * p.s_t + i] = s;
+      if (part == 0) p.s_exact[(size_t)h * p.s_t + i] = s;
       key[e] = __float_as_uint(s);  // scores are >= 0: their bit patterns order like the values
-      c2[e] = (uint32_t)p.cnt[(size_t)h * p.s_t + i];
+      int c = 0;
+      for (int q = 0; q < p.n_cnt_parts; ++q) c += p.cnt[((size_t)q * p.n_kv_heads + h) * p.s_t + i];
+      c2[e] = (uint32_t)c;
+      if (p.cnt_out && part == 0) p.cnt_out[(size_t)h * p.s_t + i] = c;
     }
   }
+
 
   // exclusive prefix of per-thread counts over the block, in thread (= index) order
   auto block_excl_scan = [&](int v) -> int {
@@ -604,11 +678,32 @@ __global__ __launch_bounds__(1024) void select_kernel(SelectParams p) {
   }
   int pos = block_excl_scan(n_keep);
   const int b_t = p.n_anchor + p.n_local + p.k_exact + p.k_lsh;
+  // FUSED: this workgroup copies output ranks [r0, r1)
+  const int per = (b_t + split - 1) / split;
+  const int r0 = FUSED ? min(part * per, b_t) : 0, r1 = FUSED ? min(r0 + per, b_t) : b_t;
 #pragma unroll
   for (int e = 0; e < EPT; ++e) {
     if (sel[e]) {
-      if (pos < b_t) p.keep[(size_t)h * b_t + pos] = tid * EPT + e;
+      if (pos >= r0 && pos < r1) {
+        p.keep[(size_t)h * b_t + pos] = tid * EPT + e;
+        if (FUSED) sKeep[pos - r0] = tid * EPT + e;
+      }
       ++pos;
+    }
+  }
+  if (FUSED) {
+    __syncthreads();
+    const int cpr = ap.row_bytes / 16;
+    const int n_copy = (r1 - r0) * cpr;
+    for (int t = tid; t < n_copy; t += 1024) {
+      const int row = t / cpr, c = t - row * cpr;
+      const int src = sKeep[row];
+      const int64_t dst_off = (int64_t)h * ap.cache_stride_head + (ap.cache_len + r0 + row) * (int64_t)ap.row_bytes + c * 16;
+      const uint4 kv = ld16(ap.kb.base + (int64_t)h * ap.kb.stride_head + (int64_t)src * ap.kb.stride_row + c * 16);
+      const uint4 vv = ld16(ap.vb.base + (int64_t)h * ap.vb.stride_head + (int64_t)src * ap.vb.stride_row + c * 16);
+      *reinterpret_cast<uint4*>(ap.k_cache + dst_off) = kv;
+      *reinterpret_cast<uint4*>(ap.v_cache + dst_off) = vv;
+      if (c == 0) ap.cache_pos[(int64_t)h * ap.pos_stride_head + ap.cache_len + r0 + row] = ap.block_pos0 + src;
     }
   }
 }
@@ -708,16 +803,34 @@ hipError_t launch_count(const CountParams& p, int n_kv_heads, hipStream_t st) {
   return hipGetLastError();
 }
 
-hipError_t launch_select(const SelectParams& p, hipStream_t st) {
+template <bool FUSED>
+static hipError_t launch_select_t(const SelectParams& p, const AppendParams& ap, int split, hipStream_t st) {
   const int ept = (p.s_t + 1023) / 1024;
-  dim3 grid(p.n_kv_heads);
-  if (ept <= 1) hipLaunchKernelGGL((select_kernel<1>), grid, dim3(1024), 0, st, p);
-  else if (ept <= 2) hipLaunchKernelGGL((select_kernel<2>), grid, dim3(1024), 0, st, p);
-  else if (ept <= 4) hipLaunchKernelGGL((select_kernel<4>), grid, dim3(1024), 0, st, p);
-  else if (ept <= 8) hipLaunchKernelGGL((select_kernel<8>), grid, dim3(1024), 0, st, p);
-  else if (ept <= 16) hipLaunchKernelGGL((select_kernel<16>), grid, dim3(1024), 0, st, p);
+  // `split` workgroups per head select (and, fused, copy); with resident query histograms, extra ones
+  // clear them (16 KiB each)
+  const int n_zero = p.qhist ? (int)(((size_t)p.n_kv_heads * p.qhist_words_per_head * 4 + 16383) / 16384) : 0;
+  dim3 grid(p.n_kv_heads * split + n_zero);
+  if (ept <= 1) hipLaunchKernelGGL((select_kernel<1, FUSED>), grid, dim3(1024), 0, st, p, ap, split);
+  else if (ept <= 2) hipLaunchKernelGGL((select_kernel<2, FUSED>), grid, dim3(1024), 0, st, p, ap, split);
+  else if (ept <= 4) hipLaunchKernelGGL((select_kernel<4, FUSED>), grid, dim3(1024), 0, st, p, ap, split);
+  else if (ept <= 8) hipLaunchKernelGGL((select_kernel<8, FUSED>), grid, dim3(1024), 0, st, p, ap, split);
+  else if (ept <= 16) hipLaunchKernelGGL((select_kernel<16, FUSED>), grid, dim3(1024), 0, st, p, ap, split);
   else return hipErrorInvalidValue;
   return hipGetLastError();
+}
+
+hipError_t launch_select(const SelectParams& p, hipStream_t st) {
+  AppendParams none = {};
+  return launch_select_t<false>(p, none, 1, st);
+}
+
+hipError_t launch_select_append(const SelectParams& p, const AppendParams& ap, int n_cu, hipStream_t st) {
+  // enough workgroups per head to fill the chip, each copying at most 1024 rows
+  const int b_t = p.n_anchor + p.n_local + p.k_exact + p.k_lsh;
+  int split = n_cu / p.n_kv_heads;
+  if (split < 1) split = 1;
+  while ((b_t + split - 1) / split > 1024) ++split;
+  return launch_select_t<true>(p, ap, split, st);
 }
 
 hipError_t launch_append(const AppendParams& p, int n_kv_heads, hipStream_t st) {

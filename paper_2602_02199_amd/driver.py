@@ -82,12 +82,13 @@ class LayerCompressor:
         return self.cache_len
 
     # ---- pre-marshalled call lists: one ctypes call per library entry point, nothing else ----
-    def plan_layer(self, data, n_blocks=None):
+    def plan_layer(self, data, n_blocks=None, fused=True):
         """Builds the layer's call list once: [(c_function, argument tuple without the stream)].
 
         The tensors in `data`, the cache and the keep buffer must stay alive and in place while the
         plan is used.  run_plan() then issues the calls back to back with no per-call Python work
-        beyond the foreign call itself (and can be captured into a HIP graph).
+        beyond the foreign call itself (and can be captured into a HIP graph).  fused=True uses
+        laserkv_compress_block (one call per block), else laserkv_select_block + laserkv_append.
         """
         import ctypes as C
         wl, lib = self.wl, self.lib._lib
@@ -108,15 +109,24 @@ class LayerCompressor:
             q, k, v = data["q_win"][t], data["k"][:, lo:hi], data["v"][:, lo:hi]
             t_ctx = prev_local if cache_len else 0
             ctx_ptr = vp(self.k_cache.data_ptr() + (cache_len - t_ctx) * kc_st * es) if t_ctx else None
-            calls.append((lib.laserkv_select_block, (
-                ctx, vp(q.data_ptr()), q.stride(0), q.stride(1), vp(k.data_ptr()), k.stride(0), k.stride(1),
-                ctx_ptr, kc_sh if t_ctx else 0, kc_st if t_ctx else 0, vp(data["planes"].data_ptr()),
-                s_t, wl.window, t_ctx, lo, lo + s_t - wl.window, 1, na, nl, ke, kl,
-                vp(self.keep.data_ptr()), None, None, None, None)))
-            calls.append((lib.laserkv_append, (
-                ctx, vp(k.data_ptr()), k.stride(0), k.stride(1), vp(v.data_ptr()), v.stride(0), v.stride(1),
-                vp(self.keep.data_ptr()), b_t, s_t, lo, vp(self.k_cache.data_ptr()), vp(self.v_cache.data_ptr()),
-                kc_sh, vp(self.cache_pos.data_ptr()), self.cache_pos.stride(0), cache_len, self.cap)))
+            if fused:
+                calls.append((lib.laserkv_compress_block, (
+                    ctx, vp(q.data_ptr()), q.stride(0), q.stride(1), vp(k.data_ptr()), k.stride(0), k.stride(1),
+                    vp(v.data_ptr()), v.stride(0), v.stride(1),
+                    ctx_ptr, kc_sh if t_ctx else 0, kc_st if t_ctx else 0, vp(data["planes"].data_ptr()),
+                    s_t, wl.window, t_ctx, lo, lo + s_t - wl.window, 1, na, nl, ke, kl,
+                    vp(self.keep.data_ptr()), vp(self.k_cache.data_ptr()), vp(self.v_cache.data_ptr()), kc_sh,
+                    vp(self.cache_pos.data_ptr()), self.cache_pos.stride(0), cache_len, self.cap)))
+            else:
+                calls.append((lib.laserkv_select_block, (
+                    ctx, vp(q.data_ptr()), q.stride(0), q.stride(1), vp(k.data_ptr()), k.stride(0), k.stride(1),
+                    ctx_ptr, kc_sh if t_ctx else 0, kc_st if t_ctx else 0, vp(data["planes"].data_ptr()),
+                    s_t, wl.window, t_ctx, lo, lo + s_t - wl.window, 1, na, nl, ke, kl,
+                    vp(self.keep.data_ptr()), None, None, None, None)))
+                calls.append((lib.laserkv_append, (
+                    ctx, vp(k.data_ptr()), k.stride(0), k.stride(1), vp(v.data_ptr()), v.stride(0), v.stride(1),
+                    vp(self.keep.data_ptr()), b_t, s_t, lo, vp(self.k_cache.data_ptr()), vp(self.v_cache.data_ptr()),
+                    kc_sh, vp(self.cache_pos.data_ptr()), self.cache_pos.stride(0), cache_len, self.cap)))
             cache_len += b_t
             prev_local = nl
         self._plan_len = cache_len

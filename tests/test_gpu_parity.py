@@ -231,3 +231,23 @@ def test_graph_replay_matches_eager_every_time():
             comp.run_plan(plan)          # eager work between replays
             stream.synchronize()
             assert torch.equal(comp.cache_pos, ref[0])
+
+
+@pytest.mark.parametrize("name,n_blocks", [("tiny", 3), ("llama8b-16k", 2), ("gqa8-128k", 1)])
+def test_compress_block_equals_select_then_append(name, n_blocks):
+    """The one-call entry point must leave exactly the cache the two separate calls leave."""
+    wl = synth.WORKLOADS[name]
+    B = O.budget(wl.s_block, wl.l_ctx, wl.r_num, wl.r_den)
+    na = O.partition(B, wl.n_div, wl.alpha, wl.s_block)[0]
+    dev = to_dev(synth.make_layer(wl, 2, na, n_blocks=n_blocks))
+    results = []
+    for fused in (False, True):
+        comp = LayerCompressor(wl, DEV, max_blocks=n_blocks)
+        plan = comp.plan_layer(dev, fused=fused)
+        comp.run_plan(plan)
+        torch.cuda.synchronize()
+        results.append((comp.cache_pos.clone(), comp.k_cache.clone(), comp.v_cache.clone(), comp.keep.clone()))
+        assert comp.cache_len == n_blocks * min(B, wl.s_block)
+    for a, b in zip(*results):
+        assert torch.equal(a, b)
+    assert bool((results[1][0][:, :n_blocks * min(B, wl.s_block)] >= 0).all())
