@@ -11,6 +11,7 @@
 #include "laserkv_kernels.h"
 
 #include <limits.h>
+#include <stdlib.h>
 
 // Timestamp hook for bench harnesses that include this file with their own definition; nothing in the library build.
 #ifndef LKV_TS
@@ -567,6 +568,7 @@ __global__ __launch_bounds__(1024) void select_kernel(SelectParams p, AppendPara
     return;
   }
 
+  LKV_TS(0);
   uint32_t key[EPT], c2[EPT];
   bool inr[EPT], cand[EPT], sel[EPT];
 #pragma unroll
@@ -664,11 +666,14 @@ __global__ __launch_bounds__(1024) void select_kernel(SelectParams p, AppendPara
 
   sHist[tid >> 8][tid & 255] = 0u;
   __syncthreads();
+  LKV_TS(1);
   take_top(key, cand, p.k_exact, 4);
+  LKV_TS(2);
   bool act2[EPT];
 #pragma unroll
   for (int e = 0; e < EPT; ++e) act2[e] = cand[e] && !sel[e];
   take_top(c2, act2, p.k_lsh, (p.cnt_bits + 7) >> 3);
+  LKV_TS(3);
 
   int n_keep = 0;
 #pragma unroll
@@ -691,6 +696,7 @@ __global__ __launch_bounds__(1024) void select_kernel(SelectParams p, AppendPara
       ++pos;
     }
   }
+  LKV_TS(4);
   if (FUSED) {
     __syncthreads();
     const int cpr = ap.row_bytes / 16;
@@ -706,6 +712,7 @@ __global__ __launch_bounds__(1024) void select_kernel(SelectParams p, AppendPara
       if (c == 0) ap.cache_pos[(int64_t)h * ap.pos_stride_head + ap.cache_len + r0 + row] = ap.block_pos0 + src;
     }
   }
+  LKV_TS(5);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -828,6 +835,7 @@ hipError_t launch_select_append(const SelectParams& p, const AppendParams& ap, i
   // enough workgroups per head to fill the chip, each copying at most 1024 rows
   const int b_t = p.n_anchor + p.n_local + p.k_exact + p.k_lsh;
   int split = n_cu / p.n_kv_heads;
+  if (const char* e = getenv("LASERKV_APPEND_SPLIT")) split = atoi(e);
   if (split < 1) split = 1;
   while ((b_t + split - 1) / split > 1024) ++split;
   return launch_select_t<true>(p, ap, split, st);
