@@ -571,27 +571,56 @@ __global__ __launch_bounds__(1024) void select_kernel(SelectParams p, AppendPara
   LKV_TS(0);
   uint32_t key[EPT], c2[EPT];
   bool inr[EPT], cand[EPT], sel[EPT];
+  {
+    // scores and counts arrive in up to two parts in the common cases: issue every load before the
+    // first use (a loop with a run-time part count would serialise one memory round trip per load)
+    float sc[EPT];
+    int cc[EPT];
+    const size_t hoff = (size_t)h * p.s_t, poff = (size_t)p.n_kv_heads * p.s_t;
+    if (p.n_qgroups <= 2 && p.n_cnt_parts <= 2) {
+      const bool s2 = p.n_qgroups > 1, c2p = p.n_cnt_parts > 1;
+      float a0[EPT], a1[EPT];
+      int b0[EPT], b1[EPT];
 #pragma unroll
-  for (int e = 0; e < EPT; ++e) {
-    const int i = tid * EPT + e;
-    inr[e] = i < p.s_t;
-    cand[e] = inr[e] && i >= p.n_anchor && i < p.s_t - p.n_local;
-    sel[e] = false;
-    key[e] = 0u;
-    c2[e] = 0u;
-    if (inr[e]) {
-      float s = 0.0f;
-      for (int qg = 0; qg < p.n_qgroups; ++qg) s += p.s_part[((size_t)qg * p.n_kv_heads + h) * p.s_t + i];
-      s *= p.inv_m;
-      if (part == 0) p.s_exact[(size_t)h * p.s_t + i] = s;
-      key[e] = __float_as_uint(s);  // scores are >= 0: their bit patterns order like the values
-      int c = 0;
-      for (int q = 0; q < p.n_cnt_parts; ++q) c += p.cnt[((size_t)q * p.n_kv_heads + h) * p.s_t + i];
-      c2[e] = (uint32_t)c;
-      if (p.cnt_out && part == 0) p.cnt_out[(size_t)h * p.s_t + i] = c;
+      for (int e = 0; e < EPT; ++e) {
+        const int i = min(tid * EPT + e, p.s_t - 1);
+        a0[e] = p.s_part[hoff + i];
+        a1[e] = s2 ? p.s_part[poff + hoff + i] : 0.0f;
+        b0[e] = p.cnt[hoff + i];
+        b1[e] = c2p ? p.cnt[poff + hoff + i] : 0;
+      }
+#pragma unroll
+      for (int e = 0; e < EPT; ++e) {
+        sc[e] = a0[e] + a1[e];
+        cc[e] = b0[e] + b1[e];
+      }
+    } else {
+#pragma unroll
+      for (int e = 0; e < EPT; ++e) {
+        const int i = min(tid * EPT + e, p.s_t - 1);
+        float sacc = 0.0f;
+        int cacc = 0;
+        for (int q = 0; q < p.n_qgroups; ++q) sacc += p.s_part[(size_t)q * poff + hoff + i];
+        for (int q = 0; q < p.n_cnt_parts; ++q) cacc += p.cnt[(size_t)q * poff + hoff + i];
+        sc[e] = sacc;
+        cc[e] = cacc;
+      }
+    }
+#pragma unroll
+    for (int e = 0; e < EPT; ++e) {
+      const int i = tid * EPT + e;
+      inr[e] = i < p.s_t;
+      cand[e] = inr[e] && i >= p.n_anchor && i < p.s_t - p.n_local;
+      sel[e] = false;
+      const float sv = sc[e] * p.inv_m;
+      key[e] = inr[e] ? __float_as_uint(sv) : 0u;  // scores are >= 0: their bit patterns order like the values
+      c2[e] = inr[e] ? (uint32_t)cc[e] : 0u;
+      if (inr[e] && part == 0) {
+        p.s_exact[hoff + i] = sv;
+        if (p.cnt_out) p.cnt_out[hoff + i] = cc[e];
+      }
     }
   }
-
 
   // exclusive prefix of per-thread counts over the block, in thread (= index) order
   auto block_excl_scan = [&](int v) -> int {
