@@ -51,6 +51,8 @@ def main():
     ap.add_argument("--mode", choices=["graph", "eager"], default="graph")
     ap.add_argument("--profile-steps", type=int, default=3)
     ap.add_argument("--unfused", action="store_true", help="laserkv_select_block + laserkv_append instead of laserkv_compress_block")
+    ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MIB",
+                    help="also run one plain device copy of this many MiB (a known-size reference for HBM byte counters)")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="lower bound of oracle work for cpu_baseline; 0 skips")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -71,6 +73,15 @@ def main():
     print(f"[bench] workload {wl.name}: inputs generated and resident in {time.time() - t_gen:.1f}s "
           f"(B={comp.B}, parts={comp.parts})", file=sys.stderr, flush=True)
 
+    if args.calibrate_copy:
+        n = args.calibrate_copy << 20
+        src = torch.ones(n, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)   # reads n bytes, writes n bytes
+        torch.cuda.synchronize()
+        print(f"[bench] calibration copy: {n} bytes read and written", file=sys.stderr, flush=True)
+        del src, dst
     plan = comp.plan_layer(ddev, fused=not args.unfused)
     stream = torch.cuda.Stream()
     graph = None
