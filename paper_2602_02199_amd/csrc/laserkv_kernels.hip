@@ -1,12 +1,16 @@
 // HIP kernels of the LASER-KV block-selection path for gfx950 (wave64, MFMA, LDS).
 //
-//   score_kernel<PASS2=false>  Alg. 1 step 3, first sweep: per window row, partial (max, sum) of
-//                              2^(logit) over each key range                      [MFMA]
-//   score_kernel<PASS2=true>   second sweep: pooled softmax probability per key    [MFMA]
-//   sig_kernel                 SimHash codes of keys and window queries            [MFMA + ballot-free bit packing]
-//   count_kernel               Alg. 1 step 6: collision counts via per-table LDS histograms of the query codes
-//   select_kernel              Alg. 1 steps 4-8 + Sec. 3.1 partition: two rank selections and compaction
-//   append_kernel              gather of the kept K/V rows onto the cache tail
+//   pass_kernel<PASS2=false>   sweep 1: per window row, partial (reference, sum) of 2^(logit) over each
+//                              key range (Alg. 1 step 3, normaliser), and in the same workgroups the
+//                              SimHash codes of keys and window queries (Sec. 3.3 "Recall") plus the
+//                              per-table histograms of the query codes                          [MFMA]
+//   pass_kernel<PASS2=true>    sweep 2: pooled softmax probability per key (Alg. 1 step 3), and the
+//                              collision counts by histogram lookup (Alg. 1 step 6)              [MFMA]
+//   count_kernel               collision counts via LDS histograms, for code widths whose histograms
+//                              are too large to keep resident in global memory
+//   select_kernel              Alg. 1 steps 4-8 + Sec. 3.1 partition: two rank selections and
+//                              compaction; FUSED also gathers the kept K/V rows onto the cache tail
+//   append_kernel              the gather alone
 #include "laserkv_device.h"
 #include "laserkv_kernels.h"
 
@@ -58,6 +62,12 @@ __host__ __device__ constexpr int row_pitch_chunks() { return D * (DT == DT_BF16
 
 __device__ __forceinline__ int div_w(int m, uint32_t magic) { return (int)__umulhi((uint32_t)m, magic); }
 
+// Workgroups are handed to the eight XCDs (each with its own L2) round-robin by linear id.  This maps
+// id to an index whose consecutive values stay on one XCD: XCD x gets indices [x*n/8, (x+1)*n/8).
+__device__ __forceinline__ int xcd_major(int id, int n) {
+  return (n & 7) == 0 ? (id & 7) * (n >> 3) + (id >> 3) : id;
+}
+
 template <int DT, int D, bool PASS2>
 __global__ __launch_bounds__(PASS_WAVES * 64) void pass_kernel(PassParams p) {
   constexpr int ES = DT == DT_BF16 ? 2 : 4;
@@ -70,23 +80,17 @@ __global__ __launch_bounds__(PASS_WAVES * 64) void pass_kernel(PassParams p) {
 
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, rl = lane & 31, kg = lane >> 5;
   LKV_TS(0);
-  // work item: consecutive linear ids land on different XCDs (id % 8), so the query-row groups of
-  // one (head, key range) are given ids that differ by a multiple of 8 and share an L2.
+  // work item: heads are the slow index of the XCD-major order, so one head's keys, queries and
+  // query histograms are fetched into one L2 (or as few as the head count allows)
   const int n_qg = p.n_qgroups;
   int kr, qg, h;
   {
-    const int id = blockIdx.x;
-    const int n_pairs = p.n_ranges * p.n_kv_heads;
-    const int xcd = id & 7, slot = id >> 3;
-    const int pair_hi = slot / n_qg;
-    int pair = pair_hi * 8 + xcd;
-    qg = slot - pair_hi * n_qg;
-    if ((n_pairs & 7) != 0) {  // plain order when the pairs do not tile the XCDs
-      pair = id / n_qg;
-      qg = id - pair * n_qg;
-    }
-    h = pair / p.n_ranges;
-    kr = pair - h * p.n_ranges;
+    const int per_head = p.n_ranges * n_qg;
+    const int lin = xcd_major(blockIdx.x, per_head * p.n_kv_heads);
+    h = lin / per_head;
+    const int rem = lin - h * per_head;
+    kr = rem / n_qg;
+    qg = rem - kr * n_qg;
   }
   const int nkr = p.keys_per_range;
   // a range lies entirely in the look-back keys or entirely in the block keys, so the source
@@ -556,8 +560,10 @@ __global__ __launch_bounds__(1024) void select_kernel(SelectParams p, AppendPara
   __shared__ int sKeep[FUSED ? 1024 : 1];  // FUSED: the kept indices this workgroup copies
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int n_sel_wg = p.n_kv_heads * split;
-  const int h = FUSED ? blockIdx.x / split : blockIdx.x;
-  const int part = FUSED ? blockIdx.x - h * split : 0;
+  // the workgroups that share a head (and read the same scores and counts) sit on one XCD
+  const int sel_id = (int)blockIdx.x < n_sel_wg ? xcd_major(blockIdx.x, n_sel_wg) : 0;
+  const int h = FUSED ? sel_id / split : sel_id;
+  const int part = FUSED ? sel_id - h * split : 0;
   if ((int)blockIdx.x >= n_sel_wg) {
     // extra workgroups: the query histograms have been consumed by the sweep before this kernel;
     // clear them for the next block, a slice each
