@@ -44,13 +44,15 @@ namespace lkv {
 // (<= 128 registers per lane): one wave alone issues a vector instruction only every ~10 clocks.
 //
 // Sweep 1 keeps, per window row, sum_i 2^(x_i - ref) against a reference ref shared by the 32 lanes
-// that hold the row; ref starts as the row maximum of the first tile and is raised (with the sum
-// rescaled) only when a logit exceeds it by more than 2^64, so the common case costs one fma, one
-// max, one exp and one add per logit.  Sweep 2 needs one fma, one exp and one add per logit.
+// that hold the row: the row maximum of the range's first tile.  The common case costs one fma, one
+// exp and one add per logit; a range whose later logits exceed that reference by more than 2^7
+// overflows the sum, which is detected after the loop and redone with a running-maximum reference.
+// Sweep 2 needs one fma, one exp and one add per logit.
 //
-// Hashing: lane = vector, accumulator register = plane, so 16 compares per tile give 16 sign bits of
-// the lane's vector and one exchange with the partner lane completes its 32-bit word for that
-// 32-plane tile.  With several query-row groups the tables are split between their workgroups.
+// Hashing: lane = vector, accumulator register = plane, with the planes fed in an order that makes
+// a lane's 16 registers 16 consecutive planes: one v_alignbit per register shifts its sign bit into
+// the lane's word, and one exchange with the partner lane completes the 32-bit word of that 32-plane
+// tile.  With several query-row groups the tables are split between their workgroups.
 // ---------------------------------------------------------------------------------------------
 constexpr int PASS_WAVES = 16;
 constexpr int PASS_ROWS = 256;        // window rows per workgroup: 8 row tiles
@@ -61,6 +63,11 @@ template <int DT, int D>
 __host__ __device__ constexpr int row_pitch_chunks() { return D * (DT == DT_BF16 ? 2 : 4) / 16 + 1; }
 
 __device__ __forceinline__ int div_w(int m, uint32_t magic) { return (int)__umulhi((uint32_t)m, magic); }
+
+// Plane (within a 32-plane tile) that a hashing wave feeds as row rho of its A operand.  Accumulator
+// register r of a lane in half kg is row 8*(r/4) + 4*kg + (r&3); with this order it is plane 16*kg + r,
+// so a lane's 16 registers are 16 consecutive sign bits.
+__device__ __forceinline__ int plane_row(int rho) { return 16 * ((rho >> 2) & 1) + 4 * (rho >> 3) + (rho & 3); }
 
 // Workgroups are handed to the eight XCDs (each with its own L2) round-robin by linear id.  This maps
 // id to an index whose consecutive values stay on one XCD: XCD x gets indices [x*n/8, (x+1)*n/8).
@@ -76,7 +83,6 @@ __global__ __launch_bounds__(PASS_WAVES * 64) void pass_kernel(PassParams p) {
   constexpr int CHP = CH + 1;      // LDS row pitch in chunks
   constexpr int NTHR = PASS_WAVES * 64;
   constexpr int MQ = PASS_ROWS;
-  constexpr float RESCALE_AT = 64.0f;
 
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, rl = lane & 31, kg = lane >> 5;
   LKV_TS(0);
@@ -207,7 +213,7 @@ __global__ __launch_bounds__(PASS_WAVES * 64) void pass_kernel(PassParams p) {
     }
     __syncthreads();
     {
-      const uint4* arow = smem + (size_t)((hash_wave ? MQ : 0) + rt * 32 + rl) * CHP + kg;
+      const uint4* arow = smem + (size_t)(hash_wave ? MQ + rt * 32 + plane_row(rl) : rt * 32 + rl) * CHP + kg;
 #pragma unroll
       for (int i = 0; i < NCH; ++i) a[i] = arow[2 * i];
     }
@@ -219,7 +225,7 @@ __global__ __launch_bounds__(PASS_WAVES * 64) void pass_kernel(PassParams p) {
     }
   } else {
     if (hash_wave) {
-      const int pm = min(plane0 + min(rt * 32 + rl, max(n_pl - 1, 0)), p.n_planes - 1);
+      const int pm = min(plane0 + min(rt * 32 + plane_row(rl), max(n_pl - 1, 0)), p.n_planes - 1);
       const char* ptr = p.planes + (size_t)pm * (D * ES);
 #pragma unroll
       for (int i = 0; i < NCH; ++i) a[i] = ld16(ptr + (2 * i + kg) * 16);
@@ -320,17 +326,14 @@ __global__ __launch_bounds__(PASS_WAVES * 64) void pass_kernel(PassParams p) {
     }
   }
 
-  if (!hash_wave) {
-    float ref[16], sum[16];  // sweep 1: (reference, sum); sweep 2: ref holds the row lse
+  if (PASS2) {
+    // lane = key column, registers = window rows: a key's pooled probability is an in-lane sum
+    float lse[16];
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      ref[r] = PASS2 ? sLse[rt * 32 + acc_row(r, kg)] : NEG_BIG;
-      sum[r] = 0.0f;
-    }
-    // sweep 1: all tiles of the range; sweep 2: this wave's half of them
-    const int t_half = (n_tiles + 1) >> 1;
-    const int nt_beg = PASS2 ? (wave >> 3) * t_half : 0;
-    const int nt_end = PASS2 ? min(n_tiles, nt_beg + t_half) : n_tiles;
+    for (int r = 0; r < 16; ++r) lse[r] = sLse[rt * 32 + acc_row(r, kg)];
+    const int t_half = (n_tiles + 1) >> 1;  // this wave's half of the tiles
+    const int nt_beg = (wave >> 3) * t_half;
+    const int nt_end = min(n_tiles, nt_beg + t_half);
     // rolled on purpose (microsecond kernels start from a cold instruction cache)
 #pragma unroll 1
     for (int nt = nt_beg; nt < nt_end; ++nt) {
@@ -343,79 +346,94 @@ __global__ __launch_bounds__(PASS_WAVES * 64) void pass_kernel(PassParams p) {
       for (int i = 0; i < NCH; ++i) Mma<DT>::run(acc, a[i], brow[2 * i]);
       const int kidx = kbase + rl;
       const bool partial = (kbase + 32 > k1) || (p.causal && (kbase + 31 > p.lim0));  // wave-uniform
-      if (PASS2) {
-        float col = 0.0f;
-        if (!partial) {
+      float col = 0.0f;
+      if (!partial) {
 #pragma unroll
-          for (int r = 0; r < 16; ++r) col += fast_exp2(fmaf(acc[r], p.scale2, -ref[r]));
-        } else {
-#pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            const bool vis = kidx < k1 && kidx <= sLim[rt * 32 + acc_row(r, kg)];
-            const float e = fast_exp2(fmaf(acc[r], p.scale2, -ref[r]));
-            col += vis ? e : 0.0f;
-          }
-        }
-        col += __shfl_xor(col, 32);
-        if (kg == 0) sCol[rt * nkr + nt * 32 + rl] = col;
+        for (int r = 0; r < 16; ++r) col += fast_exp2(fmaf(acc[r], p.scale2, -lse[r]));
       } else {
-        // acc is turned in place into t = x - ref (x = scaled logit, masked -> NEG_BIG)
-        if (nt == 0) {
-          // first tile of the range: the references start at this tile's row maxima
 #pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            float x = acc[r] * p.scale2;
-            if (partial) {
-              const bool vis = kidx < k1 && kidx <= sLim[rt * 32 + acc_row(r, kg)];
-              x = vis ? x : NEG_BIG;
-            }
-            ref[r] = half_allmax(x);
-            acc[r] = x - ref[r];
-            __builtin_amdgcn_sched_barrier(0);  // one row at a time: keeps register pressure low
-          }
-        } else {
-          float tmax = NEG_BIG;
-          if (!partial) {
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-              acc[r] = fmaf(acc[r], p.scale2, -ref[r]);
-              tmax = fmaxf(tmax, acc[r]);
-            }
-          } else {
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-              const bool vis = kidx < k1 && kidx <= sLim[rt * 32 + acc_row(r, kg)];
-              acc[r] = (vis ? acc[r] * p.scale2 : NEG_BIG) - ref[r];
-              tmax = fmaxf(tmax, acc[r]);
-            }
-          }
-          if (__any(tmax > RESCALE_AT)) {
-            // rare: raise the references of this wave's rows to the row maxima of this tile.
-            // (masks only ever hide the tail of a range, so a row whose reference is still unset
-            // has t = 0 here and never enters this branch with a visible key)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-              const float x = acc[r] + ref[r];
-              const float nref = fmaxf(ref[r], half_allmax(x));
-              sum[r] *= fast_exp2(ref[r] - nref);
-              ref[r] = nref;
-              acc[r] = x - nref;
-              __builtin_amdgcn_sched_barrier(0);
-            }
-          }
+        for (int r = 0; r < 16; ++r) {
+          const bool vis = kidx < k1 && kidx <= sLim[rt * 32 + acc_row(r, kg)];
+          const float e = fast_exp2(fmaf(acc[r], p.scale2, -lse[r]));
+          col += vis ? e : 0.0f;
         }
-#pragma unroll
-        for (int r = 0; r < 16; ++r) sum[r] += fast_exp2(acc[r]);
       }
+      col += __shfl_xor(col, 32);
+      if (kg == 0) sCol[rt * nkr + nt * 32 + rl] = col;
     }
-    if (!PASS2) {
+  } else if (!hash_wave) {
+    // Sweep 1 multiplies the other way round (keys as the A operand, window rows as B): lane = window
+    // row rt*32 + rl, registers = 16 keys of the tile, so a row's statistics never leave the lane.
+    // Each lane keeps (ref, sum) with sum = sum_i 2^(x_i - ref) over its keys; ref is the lane's
+    // maximum over the first tile and is not raised afterwards (see the overflow check below).
+    const int lim = sLim[rt * 32 + rl];
+    auto tile = [&](int nt, f32x16& acc) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
+      const uint4* krow = sK + (size_t)(nt * 32 + rl) * CHP + kg;
+#pragma unroll
+      for (int i = 0; i < NCH; ++i) Mma<DT>::run(acc, krow[2 * i], a[i]);
+    };
+    // scaled logits of a tile whose tail may be outside the range or hidden by the causal mask
+    auto masked = [&](int nt, f32x16& acc) {
+      const int kb0 = k0 + nt * 32 + 4 * kg;
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        const float s = half_allsum(sum[r]);
-        const int row = qg * MQ + rt * 32 + acc_row(r, kg);
-        if (rl == 0 && row < p.m_rows) p.part[((size_t)h * p.n_ranges + kr) * p.m_pad + row] = make_float2(ref[r], s);
+        const int kidx = kb0 + 8 * (r >> 2) + (r & 3);
+        acc[r] = (kidx < k1 && kidx <= lim) ? acc[r] * p.scale2 : NEG_BIG;
+      }
+    };
+    float ref, sum = 0.0f;
+    {
+      f32x16 acc;
+      tile(0, acc);
+      masked(0, acc);
+      float mx = acc[0];
+#pragma unroll
+      for (int r = 1; r < 16; ++r) mx = fmaxf(mx, acc[r]);
+      ref = mx;  // NEG_BIG when the row sees none of the lane's keys: its junk sum gets weight 0 in every merge
+#pragma unroll
+      for (int r = 0; r < 16; ++r) sum += fast_exp2(acc[r] - ref);
+    }
+#pragma unroll 1
+    for (int nt = 1; nt < n_tiles; ++nt) {
+      const int kbase = k0 + nt * 32;
+      f32x16 acc;
+      tile(nt, acc);
+      const bool partial = (kbase + 32 > k1) || (p.causal && (kbase + 31 > p.lim0));  // wave-uniform
+      if (!partial) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) sum += fast_exp2(fmaf(acc[r], p.scale2, -ref));
+      } else {
+        masked(nt, acc);
+#pragma unroll
+        for (int r = 0; r < 16; ++r) sum += fast_exp2(acc[r] - ref);
       }
     }
+    // A later logit more than 2^7 above the first tile's maximum (exp2 domain) overflows the sum.
+    // The wave then redoes its rows with a reference that follows the running maximum.
+    if (__any(!(sum < 3.0e38f))) {
+      ref = NEG_BIG;
+      sum = 0.0f;
+#pragma unroll 1
+      for (int nt = 0; nt < n_tiles; ++nt) {
+        f32x16 acc;
+        tile(nt, acc);
+        masked(nt, acc);
+        float mx = ref;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) mx = fmaxf(mx, acc[r]);
+        float add = 0.0f;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) add += fast_exp2(acc[r] - mx);
+        sum = sum * fast_exp2(ref - mx) + add;
+        ref = mx;
+      }
+    }
+    // the two halves of the wave hold the same rows over different keys
+    lse_merge(ref, sum, __shfl_xor(ref, 32), __shfl_xor(sum, 32));
+    const int row = qg * MQ + rt * 32 + rl;
+    if (kg == 0 && row < p.m_rows) p.part[((size_t)h * p.n_ranges + kr) * p.m_pad + row] = make_float2(ref, sum);
   } else {
     // hashing waves: SimHash sign bits of the range's block keys and of this workgroup's queries
     const int n_ktiles_h = in_ctx ? 0 : n_tiles;  // look-back keys are never candidates: not hashed
@@ -423,7 +441,7 @@ __global__ __launch_bounds__(PASS_WAVES * 64) void pass_kernel(PassParams p) {
 #pragma unroll 1
     for (int mt = rt; mt < n_mt; mt += 8) {
       if (mt != rt) {
-        const int pm = plane0 + min(mt * 32 + rl, n_pl - 1);
+        const int pm = plane0 + min(mt * 32 + plane_row(rl), n_pl - 1);
         const char* ptr = p.planes + (size_t)pm * (D * ES);
 #pragma unroll
         for (int i = 0; i < NCH; ++i) a[i] = ld16(ptr + (2 * i + kg) * 16);
@@ -437,10 +455,13 @@ __global__ __launch_bounds__(PASS_WAVES * 64) void pass_kernel(PassParams p) {
         const uint4* brow = sK + (size_t)(base + rl) * CHP + kg;
 #pragma unroll
         for (int i = 0; i < NCH; ++i) Mma<DT>::run(acc, a[i], brow[2 * i]);
-        uint32_t mask = 0u;
+        // the lane's 16 accumulators are planes 16*kg .. 16*kg+15 of the tile in register order (see
+        // plane_row); shifting their sign bits in from the top register down leaves plane r at bit r
+        uint32_t neg = 0u;
 #pragma unroll
-        for (int r = 0; r < 16; ++r) mask |= (acc[r] >= 0.0f ? 1u : 0u) << acc_row(r, kg);
-        mask |= (uint32_t)__shfl_xor((int)mask, 32);
+        for (int r = 15; r >= 0; --r) neg = __builtin_amdgcn_alignbit(neg, __float_as_uint(acc[r]), 31);
+        const uint32_t pos = ~neg & 0xffffu;  // bit = projection >= 0 (an accumulator is never -0)
+        const uint32_t mask = pos | ((uint32_t)__shfl_xor((int)pos, 32) << 16);
         if (kg == 0) sBits[(size_t)(base + rl) * BITS_PITCH + mt] = mask;
       }
     }

@@ -46,12 +46,15 @@ def gpu_stage(dbg, keep):
     )
 
 
-def run_and_check(wl, layer=0, n_blocks=None, check_blocks=None, label=""):
+def run_and_check(wl, layer=0, n_blocks=None, check_blocks=None, label="", mutate=None):
     """Run the layer's blocks on the GPU in the benchmark's launch configuration; check the listed
-    blocks stage by stage against the oracle, and whole-run invariants on the cache."""
+    blocks stage by stage against the oracle, and whole-run invariants on the cache.
+    mutate(data) may alter the generated inputs in place (both sides then see the altered values)."""
     B = O.budget(wl.s_block, wl.l_ctx, wl.r_num, wl.r_den)
     parts_full = O.partition(B, wl.n_div, wl.alpha, wl.s_block)
     data = synth.make_layer(wl, layer, parts_full[0], n_blocks=n_blocks)
+    if mutate is not None:
+        mutate(data)
     nb = data["q_win"].shape[0]
     check_blocks = list(range(nb)) if check_blocks is None else check_blocks
     dev = to_dev(data)
@@ -131,6 +134,31 @@ def test_ragged_shapes(case):
     base = synth.WORKLOADS["tiny"]
     wl = synth.shrink(base, index=7, needles_per_block=2, outlier_channels=2, **case)
     run_and_check(wl, label=case["name"])
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_dominant_late_key(dtype):
+    """Keys deep inside a key range whose logit for one window row lies ~120 nats above everything the
+    row has seen before: the first sweep's running sums overflow against the first tile's maximum and
+    the kernel has to redo those rows with a reference that follows the maximum."""
+    wl = synth.shrink(synth.WORKLOADS["llama8b-16k"], index=9, l_ctx=4096, dtype=dtype, needles_per_block=2)
+    d, g = wl.head_dim, wl.group
+    planted = []
+
+    def mutate(data):
+        k = data["k"].to(torch.float32)
+        for t in range(data["q_win"].shape[0]):
+            for h in range(wl.n_kv_heads):
+                for i, (gi, j) in ((360 + 7 * h, (h % g, 5)), (1201 + 3 * h, ((h + 1) % g, wl.window - 1))):
+                    qv = data["q_win"][t, h * g + gi, j].to(torch.float32)
+                    k[h, t * wl.s_block + i] = qv * (120.0 * d ** 0.5 / float(qv @ qv))
+                    planted.append((t, h, i))
+        data["k"] = k.to(wl.torch_dtype).contiguous()
+
+    _, comp, reps = run_and_check(wl, label=f"dominant-late-key-{dtype}", mutate=mutate)
+    kept = {(int(p) // wl.s_block, h, int(p) % wl.s_block) for h in range(wl.n_kv_heads)
+            for p in comp.cache_pos[h, :comp.cache_len].cpu().tolist()}
+    assert all(x in kept for x in planted)
 
 
 @pytest.mark.parametrize("alpha", [0.0, 1.0, 0.5])
