@@ -30,7 +30,7 @@ struct laserkv_ctx {
   int elem_size;
   // device workspace
   int max_ranges;    // key ranges per (head, query-row group) the workspace is sized for
-  float2* part;      // [H_kv, max_ranges, m_pad]
+  float2* part;      // [H_kv, m_pad, max_ranges]
   float* s_part;     // [n_qgroups_max, H_kv, max_block]
   float* s_exact;    // [H_kv, max_block]
   int32_t* cnt;      // [n_qgroups_max, H_kv, max_block] count parts
@@ -183,6 +183,7 @@ int laserkv_create(const laserkv_config* cfg, laserkv_ctx** out) {
   // ranges of at most score_max_range() keys, plus one for the look-back keys, and room for finer splits
   ctx->max_ranges = (c.max_block + c.max_ctx_keys) / lkv::score_max_range() + 2;
   if (ctx->max_ranges < 64) ctx->max_ranges = 64;
+  ctx->max_ranges = (ctx->max_ranges + 7) & ~7;
   const size_t hk = c.n_kv_heads, sb = c.max_block;
   struct { void** p; size_t bytes; } allocs[] = {
       {(void**)&ctx->part, hk * ctx->max_ranges * ctx->m_pad * sizeof(float2)},
@@ -304,6 +305,7 @@ int select_impl(laserkv_ctx* ctx,
   sp.scale2 = (float)(1.4426950408889634 / std::sqrt((double)d));
   sp.part = ctx->part;
   sp.m_pad = ctx->m_pad;
+  sp.r_pad = (sp.n_ranges + 7) & ~7;
   sp.s_part = ctx->s_part;
   sp.n_tables = c.lsh_tables;
   sp.n_bits = c.lsh_bits;

@@ -32,8 +32,9 @@ struct PassParams {
   int causal;
   int lim0;        // key index kidx is visible to window row j iff kidx <= lim0 + j (when causal)
   float scale2;    // log2(e) / sqrt(d)
-  float2* part;    // [H_kv, NR, m_pad] sweep-1 partials (reference, sum) in the exp2 domain
-  int m_pad;       // row pitch of part
+  float2* part;    // [H_kv, m_pad, r_pad] sweep-1 partials (reference, sum) in the exp2 domain
+  int m_pad;       // rows per head in part
+  int r_pad;       // partials per row in part: n_ranges rounded up to a multiple of 8
   int lds_tail_offset;  // byte offset of the per-row LDS arrays (set by the launcher)
   float* s_part;   // [n_qgroups, H_kv, S] sweep-2 pooled probabilities (sum over the group's rows)
   // hashing (sweep 1)

@@ -162,21 +162,17 @@ __global__ __launch_bounds__(PASS_WAVES * 64) void pass_kernel(PassParams p) {
     return (nkr + qq / CH) * CHP + qq % CH;
   };
 
-  float2 pv[PASS2 ? 8 : 1];  // sweep 2: this thread's share of the row's sweep-1 partials
-  int pr_beg = 0, pr_end = 0;
+  // sweep 2: four threads per window row, each a quarter of the row's sweep-1 partials (consecutive in
+  // memory); the first eight are prefetched here
+  uint4 pv[PASS2 ? 4 : 1];
+  const int pr_per = p.r_pad >> 2;  // partials per thread, even
+  const int pr_beg = (tid & 3) * pr_per;
+  const float2* pr_ptr = nullptr;
   if (PASS2) {
-    // four threads per row, a quarter of the ranges each; the first eight are prefetched here
-    const int t = tid >> 2, part = tid & 3;
-    const int m = qg * MQ + t;
-    const int per = (p.n_ranges + 3) >> 2;
-    pr_beg = min(part * per, p.n_ranges);
-    pr_end = (m < p.m_rows) ? min(pr_beg + per, p.n_ranges) : pr_beg;
-    const float2* pp = p.part + (size_t)h * p.n_ranges * p.m_pad + min(m, p.m_rows - 1);
+    const int m = min(qg * MQ + (tid >> 2), p.m_rows - 1);
+    pr_ptr = p.part + ((size_t)h * p.m_pad + m) * p.r_pad + pr_beg;
 #pragma unroll
-    for (int u = 0; u < 8; ++u) {
-      const int r = min(pr_beg + u, p.n_ranges - 1);
-      pv[u] = pp[(size_t)r * p.m_pad];
-    }
+    for (int u = 0; u < 4; ++u) pv[u] = ld16(pr_ptr + min(2 * u, pr_per - 2));
   }
   uint4 a[NCH];  // A operand: this wave's 32 window rows, or (hashing waves) its first 32 planes
   if (STAGE_A) {
@@ -212,6 +208,7 @@ __global__ __launch_bounds__(PASS_WAVES * 64) void pass_kernel(PassParams p) {
       if (!PASS2) smem[(MQ + q / CH) * CHP + q % CH] = ppre[u];
     }
     __syncthreads();
+    LKV_TS(7);
     {
       const uint4* arow = smem + (size_t)(hash_wave ? MQ + rt * 32 + plane_row(rl) : rt * 32 + rl) * CHP + kg;
 #pragma unroll
@@ -262,14 +259,14 @@ __global__ __launch_bounds__(PASS_WAVES * 64) void pass_kernel(PassParams p) {
     // row log-sum-exp from the sweep-1 partials
     float mm = NEG_BIG, ss = 0.0f;
 #pragma unroll
-    for (int u = 0; u < 8; ++u)
-      if (pr_beg + u < pr_end) lse_merge(mm, ss, pv[u].x, pv[u].y);
-    if (pr_end - pr_beg > 8) {  // more than 32 ranges per head: the rest, not prefetched
-      const float2* pp = p.part + (size_t)h * p.n_ranges * p.m_pad + qg * MQ + (tid >> 2);
-      for (int r = pr_beg + 8; r < pr_end; ++r) {
-        const float2 v = pp[(size_t)r * p.m_pad];
-        lse_merge(mm, ss, v.x, v.y);
-      }
+    for (int u = 0; u < 4; ++u) {
+      const int r = pr_beg + 2 * u;
+      if (2 * u < pr_per && r < p.n_ranges) lse_merge(mm, ss, __uint_as_float(pv[u].x), __uint_as_float(pv[u].y));
+      if (2 * u < pr_per && r + 1 < p.n_ranges) lse_merge(mm, ss, __uint_as_float(pv[u].z), __uint_as_float(pv[u].w));
+    }
+    for (int e = 8; e < pr_per; ++e) {  // more than 32 ranges per head: the rest, not prefetched
+      const float2 v = pr_ptr[e];
+      if (pr_beg + e < p.n_ranges) lse_merge(mm, ss, v.x, v.y);
     }
 #pragma unroll
     for (int off = 1; off < 4; off <<= 1) {
@@ -433,7 +430,7 @@ __global__ __launch_bounds__(PASS_WAVES * 64) void pass_kernel(PassParams p) {
     // the two halves of the wave hold the same rows over different keys
     lse_merge(ref, sum, __shfl_xor(ref, 32), __shfl_xor(sum, 32));
     const int row = qg * MQ + rt * 32 + rl;
-    if (kg == 0 && row < p.m_rows) p.part[((size_t)h * p.n_ranges + kr) * p.m_pad + row] = make_float2(ref, sum);
+    if (kg == 0 && row < p.m_rows) p.part[((size_t)h * p.m_pad + row) * p.r_pad + kr] = make_float2(ref, sum);
   } else {
     // hashing waves: SimHash sign bits of the range's block keys and of this workgroup's queries
     const int n_ktiles_h = in_ctx ? 0 : n_tiles;  // look-back keys are never candidates: not hashed
