@@ -35,8 +35,7 @@ struct laserkv_ctx {
   float* s_exact;    // [H_kv, max_block]
   int32_t* cnt;      // [n_qgroups_max, H_kv, max_block] count parts
   int32_t* cnt_sum;  // [H_kv, max_block] summed counts (stage output)
-  uint32_t* qhist;   // [H_kv, L, 2^K / 2] or null when the tables are too large to keep zeroed
-  int qhist_words_per_head;
+  uint32_t* qhist;   // [H_kv, L, 2^K / 2, n_qgroups] or null when the tables are too large
   uint16_t* sig_k;   // [H_kv, max_block, L]
   uint16_t* sig_q;   // [H_q, max_window, L]
   int m_pad;
@@ -176,10 +175,10 @@ int laserkv_create(const laserkv_config* cfg, laserkv_ctx** out) {
   const int m_rows = group * c.max_window;
   ctx->m_pad = (m_rows + 255) / 256 * 256;
   const int n_qg_max = (m_rows + 127) / 128;
-  // query-code histograms stay resident (and zeroed between blocks) when a head's tables fit 512 KiB
+  // histograms of the query codes (one per query-row group) are kept in global memory between the two
+  // sweeps when a head's tables fit 512 KiB per group
   const size_t hist_bytes_head = ((size_t)c.lsh_tables << c.lsh_bits) * 2;
-  const bool use_qhist = hist_bytes_head <= 512 * 1024 && hist_bytes_head % 16 == 0 && env_int("LASERKV_NO_QHIST", 0) == 0;
-  ctx->qhist_words_per_head = use_qhist ? (int)(hist_bytes_head / 4) : 0;
+  const bool use_qhist = hist_bytes_head <= 512 * 1024 && env_int("LASERKV_NO_QHIST", 0) == 0;
   // ranges of at most score_max_range() keys, plus one for the look-back keys, and room for finer splits
   ctx->max_ranges = (c.max_block + c.max_ctx_keys) / lkv::score_max_range() + 2;
   if (ctx->max_ranges < 64) ctx->max_ranges = 64;
@@ -202,8 +201,7 @@ int laserkv_create(const laserkv_config* cfg, laserkv_ctx** out) {
     }
   }
   if (use_qhist) {
-    e = hipMalloc((void**)&ctx->qhist, hk * hist_bytes_head);
-    if (e == hipSuccess) e = hipMemset(ctx->qhist, 0, hk * hist_bytes_head);
+    e = hipMalloc((void**)&ctx->qhist, (size_t)n_qg_max * hk * hist_bytes_head);
     if (e != hipSuccess) {
       laserkv_destroy(ctx);
       return fail(nullptr, LKV_ENOMEM, "create: histogram workspace: %s", hipGetErrorString(e));
@@ -289,12 +287,18 @@ int select_impl(laserkv_ctx* ctx,
   if (nr > ctx->max_ranges - 1) nr = ctx->max_ranges - 1;
   int nk = ((n_keys + nr - 1) / nr + 31) / 32 * 32;
   if (nk > lkv::score_max_range()) nk = lkv::score_max_range();
+  // the query-code job of a workgroup: ceil(L / n_ranges) tables, floor(32 / K) whole tables per plane
+  // tile, and (when they fit 32 KiB of LDS) their histograms
+  sp.q_tab_per_tile = 32 / c.lsh_bits;
   for (;;) {
     sp.keys_per_range = nk;
     sp.n_ctx_ranges = (t_ctx + nk - 1) / nk;
     sp.n_ranges = sp.n_ctx_ranges + (s_t + nk - 1) / nk;
-    sp.q_rows_per_wg = (m_rows + sp.n_ranges - 1) / sp.n_ranges;
-    if (nk <= 32 || lkv::sweep_lds_bytes(c.dtype, d, false, nk, sp.q_rows_per_wg) <= 150 * 1024) break;
+    sp.q_tab_per_wg = (c.lsh_tables + sp.n_ranges - 1) / sp.n_ranges;
+    sp.q_tiles = (sp.q_tab_per_wg + sp.q_tab_per_tile - 1) / sp.q_tab_per_tile;
+    const size_t hist_words = ((size_t)sp.q_tab_per_wg << c.lsh_bits) / 2;
+    sp.hist_lds_words = (ctx->qhist && hist_words * 4 <= 32 * 1024) ? (int)(hist_words ? hist_words : 1) : 0;
+    if (nk <= 32 || lkv::sweep_lds_bytes(c.dtype, d, false, nk, sp.q_tiles, sp.hist_lds_words) <= 150 * 1024) break;
     nk -= 32;
   }
   if (sp.n_ranges > ctx->max_ranges) return fail(ctx, LKV_EINVAL, "select_block: internal range split too fine");
@@ -314,7 +318,7 @@ int select_impl(laserkv_ctx* ctx,
   sp.sig_k = ctx->sig_k;
   sp.sig_q = ctx->sig_q;
   sp.cnt = ctx->cnt;
-  sp.qhist = ctx->qhist;
+  sp.qhist = sp.hist_lds_words ? ctx->qhist : nullptr;
 
   lkv::CountParams cp;
   cp.sig_k = ctx->sig_k;
@@ -344,10 +348,8 @@ int select_impl(laserkv_ctx* ctx,
   lp.n_kv_heads = c.n_kv_heads;
   lp.inv_m = 1.0f / (float)m_rows;
   lp.cnt = ctx->cnt;
-  lp.n_cnt_parts = ctx->qhist ? n_qg : 1;
+  lp.n_cnt_parts = sp.qhist ? n_qg : 1;
   lp.cnt_out = ctx->cnt_sum;
-  lp.qhist = ctx->qhist;
-  lp.qhist_words_per_head = ctx->qhist_words_per_head;
   lp.s_t = s_t;
   lp.n_anchor = n_anchor;
   lp.n_local = n_local;
@@ -363,7 +365,7 @@ int select_impl(laserkv_ctx* ctx,
     return fail_hip(ctx, e, "select_block: sweep 1 (row statistics + SimHash codes)");
   if ((e = timed(ctx, LKV_KERN_SWEEP2, st, [&] { return lkv::launch_sweep2(dt, d, sp, st); })) != hipSuccess)
     return fail_hip(ctx, e, "select_block: sweep 2 (pooled probabilities)");
-  if (!ctx->qhist && (e = timed(ctx, LKV_KERN_COUNT, st, [&] { return lkv::launch_count(cp, nh, st); })) != hipSuccess)
+  if (!sp.qhist && (e = timed(ctx, LKV_KERN_COUNT, st, [&] { return lkv::launch_count(cp, nh, st); })) != hipSuccess)
     return fail_hip(ctx, e, "select_block: count kernel");
   if (fused) {
     lkv::AppendParams ap = *fused;

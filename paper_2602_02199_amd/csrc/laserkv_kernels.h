@@ -39,13 +39,17 @@ struct PassParams {
   float* s_part;   // [n_qgroups, H_kv, S] sweep-2 pooled probabilities (sum over the group's rows)
   // hashing (sweep 1)
   int n_tables, n_bits, n_planes;  // L, K, L*K (<= 512)
-  int q_rows_per_wg;    // window rows of the head hashed by each key range's workgroup
-  int tables_per_split; // tables hashed by one query-row group's workgroups: ceil(L / n_qgroups)
+  int tables_per_split; // tables of the KEY codes computed by one query-row group's workgroups: ceil(L / n_qgroups)
+  int q_tab_per_wg;     // tables of the QUERY codes (of its own window rows) owned by workgroup (range, group): ceil(L / NR)
+  int q_tab_per_tile;   // whole tables per 32-plane tile of that job: floor(32 / K)
+  int q_tiles;          // ceil(q_tab_per_wg / q_tab_per_tile)
+  int hist_lds_words;   // q_tab_per_wg * 2^K / 2 when the query histograms are built, else 0
   uint16_t* sig_k;      // [H_kv, S, L]
   uint16_t* sig_q;      // [H_q, W, L] = [H_kv, M, L]
   int32_t* cnt;         // with qhist: [n_qgroups, H_kv, S] written by sweep 2; else [H_kv, S] zeroed in sweep 1
                         // for the count kernel's atomics
-  uint32_t* qhist;      // [H_kv, L, 2^K / 2] query-code histograms, two 16-bit bins per word; null: separate count kernel
+  uint32_t* qhist;      // [H_kv, L, 2^K / 2, n_qgroups] histograms of the query codes of each row group, two 16-bit
+                        // bins per word, every word rewritten by sweep 1; null: separate count kernel
 };
 
 struct CountParams {
@@ -66,8 +70,6 @@ struct SelectParams {
   const int32_t* cnt;   // [n_cnt_parts, H_kv, S]
   int n_cnt_parts;
   int32_t* cnt_out;     // [H_kv, S] summed counts (optional, for the stage outputs)
-  uint32_t* qhist;      // cleared here for the next block when not null
-  int qhist_words_per_head;
   int s_t;
   int n_anchor, n_local, k_exact, k_lsh;
   int cnt_bits;         // bits needed to hold G * W * L
@@ -97,7 +99,7 @@ hipError_t launch_select(const SelectParams& p, hipStream_t st);
 hipError_t launch_select_append(const SelectParams& p, const AppendParams& ap, int n_cu, hipStream_t st);
 hipError_t launch_append(const AppendParams& p, int n_kv_heads, hipStream_t st);
 hipError_t init_kernel_attributes();
-size_t sweep_lds_bytes(int dtype, int head_dim, bool pass2, int range_keys, int q_rows_per_wg);
+size_t sweep_lds_bytes(int dtype, int head_dim, bool pass2, int range_keys, int q_tiles, int hist_lds_words);
 int sweep_rows_per_group();  // window rows one sweep workgroup covers
 int score_max_range();  // most keys one score workgroup takes (its LDS holds the whole range)
 

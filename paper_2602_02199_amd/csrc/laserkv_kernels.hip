@@ -111,11 +111,11 @@ __global__ __launch_bounds__(PASS_WAVES * 64) void pass_kernel(PassParams p) {
   const char* kbase_ptr = ksrc.base + (int64_t)h * ksrc.stride_head;
   const int kstride = (int)ksrc.stride_row;
   const int n_tiles = (n_keys_wg + 31) >> 5;
-  // window queries this workgroup hashes (sweep 1) and its share of the tables
-  const int hq0 = kr * p.q_rows_per_wg;
-  const int n_hq = PASS2 ? 0 : max(0, min(p.q_rows_per_wg, p.m_rows - hq0));
-  const int n_hq_tiles = (n_hq + 31) >> 5;
-  const int q_tile_rows = PASS2 ? 0 : ((p.q_rows_per_wg + 31) & ~31);
+  // sweep 1: the tables whose QUERY codes (for the window rows of group qg) this workgroup owns ...
+  const int qt0 = kr * p.q_tab_per_wg;
+  const int n_qt = PASS2 ? 0 : max(0, min(p.q_tab_per_wg, p.n_tables - qt0));
+  const int n_qpt = (n_qt + p.q_tab_per_tile - 1) / p.q_tab_per_tile;  // 32-plane tiles of whole tables
+  // ... and its share of the tables of the KEY codes
   const int tab0 = qg * p.tables_per_split;
   const int n_tab = PASS2 ? 0 : max(0, min(p.tables_per_split, p.n_tables - tab0));
   const int plane0 = tab0 * p.n_bits;
@@ -126,10 +126,12 @@ __global__ __launch_bounds__(PASS_WAVES * 64) void pass_kernel(PassParams p) {
   const int rt = wave & 7;  // row tile of a score wave; index of a hashing wave
 
   extern __shared__ uint4 smem[];
-  uint4* sK = smem;                                                    // [nkr + q_tile_rows][CHP]
-  char* after_rows = reinterpret_cast<char*>(smem + (size_t)(nkr + q_tile_rows) * CHP);
+  uint4* sK = smem;                                                    // [nkr][CHP]
+  uint4* after_rows = smem + (size_t)nkr * CHP;
   float* sCol = reinterpret_cast<float*>(after_rows);                  // sweep 2: [8][nkr]
-  uint32_t* sBits = reinterpret_cast<uint32_t*>(after_rows);           // sweep 1: [nkr + q_tile_rows][BITS_PITCH]
+  uint32_t* sBits = reinterpret_cast<uint32_t*>(after_rows);           // sweep 1: [nkr][BITS_PITCH]
+  uint4* sQP = after_rows + (nkr * BITS_PITCH + 3) / 4;                // sweep 1: [q_tiles * 32][CHP] planes of the query job
+  uint32_t* sHist = reinterpret_cast<uint32_t*>(sQP + (size_t)p.q_tiles * 32 * CHP);  // sweep 1: [hist_lds_words]
   // row limits and lse sit past both the steady-state arrays and the A-operand staging area
   int* sLim = reinterpret_cast<int*>(reinterpret_cast<char*>(smem) + p.lds_tail_offset);  // [MQ]
   float* sLse = reinterpret_cast<float*>(sLim + MQ);                   // [MQ]
@@ -141,25 +143,28 @@ __global__ __launch_bounds__(PASS_WAVES * 64) void pass_kernel(PassParams p) {
   // meanwhile and then take over the same LDS space.
   constexpr bool STAGE_A = CH <= 16;                 // wider rows: fragments straight from memory
   constexpr int QL = STAGE_A ? MQ * CH / NTHR : 1;   // 16-byte chunks per thread: query panel
-  constexpr int KL = STAGE_A ? ((SCORE_MAX_RANGE + 32) * CH + NTHR - 1) / NTHR : 1;  // keys + hashed queries
+  constexpr int KL = STAGE_A ? ((SCORE_MAX_RANGE + 32) * CH + NTHR - 1) / NTHR : 1;  // keys + one tile of planes
   const int n_kchunks = n_tiles * 32 * CH;           // rows past the range are clamped copies, masked later
-  const int n_chunks = n_kchunks + n_hq_tiles * 32 * CH;
+  const int n_chunks = n_kchunks + n_qpt * 32 * CH;
   auto key_chunk = [&](int q) -> uint4 {
     if (q < n_kchunks) {
       const int row = q / CH, c = q % CH;
       const int lrow = min(seg_row0 + row, seg_rows - 1);
       return ld16(kbase_ptr + (uint32_t)(lrow * kstride + c * 16));
     }
+    // planes of the query job: tile t holds the planes of whole tables qt0 + t*q_tab_per_tile ..., padded
+    // with copies of its last plane
     const int qq = q - n_kchunks;
     const int row = qq / CH, c = qq % CH;
-    const int m = min(hq0 + row, p.m_rows - 1);
-    const int g = div_w(m, p.w_magic), j = m - g * p.w;
-    return ld16(p.q.base + (int64_t)(h * p.group + g) * p.q.stride_head + (int64_t)j * p.q.stride_row + c * 16);
+    const int t_tab0 = qt0 + (row >> 5) * p.q_tab_per_tile;
+    const int t_planes = min(p.q_tab_per_tile, qt0 + n_qt - t_tab0) * p.n_bits;
+    const int pm = t_tab0 * p.n_bits + min(row & 31, t_planes - 1);
+    return ld16(p.planes + (size_t)pm * (D * ES) + c * 16);
   };
   auto key_slot = [&](int q) -> int {
     if (q < n_kchunks) return (q / CH) * CHP + q % CH;
     const int qq = q - n_kchunks;
-    return (nkr + qq / CH) * CHP + qq % CH;
+    return (int)(sQP - smem) + (qq / CH) * CHP + qq % CH;
   };
 
   // sweep 2: four threads per window row, each a quarter of the row's sweep-1 partials (consecutive in
@@ -220,6 +225,7 @@ __global__ __launch_bounds__(PASS_WAVES * 64) void pass_kernel(PassParams p) {
       const int q = tid + NTHR * u;
       if (q < n_chunks) sK[key_slot(q)] = kpre[u];
     }
+    for (int q = tid + NTHR * KL; q < n_chunks; q += NTHR) sK[key_slot(q)] = key_chunk(q);  // further plane tiles
   } else {
     if (hash_wave) {
       const int pm = min(plane0 + min(rt * 32 + plane_row(rl), max(n_pl - 1, 0)), p.n_planes - 1);
@@ -250,6 +256,8 @@ __global__ __launch_bounds__(PASS_WAVES * 64) void pass_kernel(PassParams p) {
     }
   }
   LKV_TS(6);
+  if (!PASS2)
+    for (int i = tid; i < p.hist_lds_words; i += NTHR) sHist[i] = 0u;
   for (int t = tid; t < MQ; t += NTHR) {
     const int m = min(qg * MQ + t, p.m_rows - 1);
     const int j = m - div_w(m, p.w_magic) * p.w;
@@ -306,16 +314,35 @@ __global__ __launch_bounds__(PASS_WAVES * 64) void pass_kernel(PassParams p) {
             cw[u] = lo | (hi << 16);
           }
         }
-        uint32_t hv[8];
+        const size_t hist_w = (size_t)(1 << p.n_bits) >> 1;
+        // a bin's counts over the query-row groups sit in consecutive words
+        const uint32_t* hist = p.qhist + (size_t)h * p.n_tables * hist_w * n_qg;
+        if (n_qg == 2) {
+          uint2 hv[8];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) {
-          const uint32_t code = (cw[u >> 1] >> ((u & 1) * 16)) & 0xffffu;
-          const int t = min(tb + u, n_tabc - 1);
-          const uint32_t idx = ((uint32_t)(h * p.n_tables + tab0c + t) << p.n_bits) | code;
-          hv[u] = (p.qhist[idx >> 1] >> ((idx & 1u) * 16)) & 0xffffu;
+          for (int u = 0; u < 8; ++u) {
+            const uint32_t code = (cw[u >> 1] >> ((u & 1) * 16)) & 0xffffu;
+            const size_t at = (size_t)(tab0c + min(tb + u, n_tabc - 1)) * hist_w + (code >> 1);
+            hv[u] = *reinterpret_cast<const uint2*>(hist + at * 2);
+          }
+#pragma unroll
+          for (int u = 0; u < 8; ++u) {
+            const uint32_t sh = (cw[u >> 1] >> ((u & 1) * 16)) & 1u ? 16 : 0;
+            sum += (tb + u < n_tabc) ? (int)(((hv[u].x >> sh) & 0xffffu) + ((hv[u].y >> sh) & 0xffffu)) : 0;
+          }
+        } else {
+          for (int g2 = 0; g2 < n_qg; ++g2) {
+            uint32_t hv[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+              const uint32_t code = (cw[u >> 1] >> ((u & 1) * 16)) & 0xffffu;
+              const size_t at = (size_t)(tab0c + min(tb + u, n_tabc - 1)) * hist_w + (code >> 1);
+              hv[u] = (hist[at * n_qg + g2] >> ((code & 1u) * 16)) & 0xffffu;
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) sum += (tb + u < n_tabc) ? (int)hv[u] : 0;
+          }
         }
-#pragma unroll
-        for (int u = 0; u < 8; ++u) sum += (tb + u < n_tabc) ? (int)hv[u] : 0;
       }
       if (lpk > 1) sum += __shfl_xor(sum, 1);
       if (lpk > 2) sum += __shfl_xor(sum, 2);
@@ -431,10 +458,40 @@ __global__ __launch_bounds__(PASS_WAVES * 64) void pass_kernel(PassParams p) {
     lse_merge(ref, sum, __shfl_xor(ref, 32), __shfl_xor(sum, 32));
     const int row = qg * MQ + rt * 32 + rl;
     if (kg == 0 && row < p.m_rows) p.part[((size_t)h * p.m_pad + row) * p.r_pad + kr] = make_float2(ref, sum);
+
+    // SimHash codes of this wave's 32 window rows for the tables this workgroup owns (Sec. 3.3 "Recall"):
+    // planes as the A operand (in plane_row order), the rows already in registers as B, so lane = row
+    // and a lane's registers are 16 consecutive planes.  The codes go to sig_q and into the workgroup's
+    // LDS histograms of (table, code) over the 256 rows of its query-row group.
+    const uint32_t code_mask = (1u << p.n_bits) - 1u;
+    const int hist_w = p.hist_lds_words ? (1 << p.n_bits) >> 1 : 0;  // words per table, 0: no histograms
+#pragma unroll 1
+    for (int t = 0; t < n_qpt; ++t) {
+      f32x16 acc;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
+      const uint4* prow = sQP + (size_t)(t * 32 + plane_row(rl)) * CHP + kg;
+#pragma unroll
+      for (int i = 0; i < NCH; ++i) Mma<DT>::run(acc, prow[2 * i], a[i]);
+      uint32_t neg = 0u;
+#pragma unroll
+      for (int r = 15; r >= 0; --r) neg = __builtin_amdgcn_alignbit(neg, __float_as_uint(acc[r]), 31);
+      const uint32_t pos = ~neg & 0xffffu;
+      const uint32_t other = (uint32_t)__shfl_xor((int)pos, 32);
+      const uint32_t word = kg ? (other | (pos << 16)) : (pos | (other << 16));
+      // the tile's tables alternate between the two lanes that hold the row
+      const int t_tab0 = qt0 + t * p.q_tab_per_tile;
+      const int t_tabs = min(p.q_tab_per_tile, qt0 + n_qt - t_tab0);
+      if (row < p.m_rows)
+        for (int tt = kg; tt < t_tabs; tt += 2) {
+          const uint32_t code = (word >> (tt * p.n_bits)) & code_mask;
+          p.sig_q[((size_t)h * p.m_rows + row) * p.n_tables + t_tab0 + tt] = (uint16_t)code;
+          if (hist_w) atomicAdd(sHist + (t_tab0 + tt - qt0) * hist_w + (code >> 1), 1u << ((code & 1u) * 16));
+        }
+    }
   } else {
-    // hashing waves: SimHash sign bits of the range's block keys and of this workgroup's queries
-    const int n_ktiles_h = in_ctx ? 0 : n_tiles;  // look-back keys are never candidates: not hashed
-    const int n_vt = n_ktiles_h + n_hq_tiles;
+    // hashing waves: SimHash sign bits of the range's block keys
+    const int n_vt = in_ctx ? 0 : n_tiles;  // look-back keys are never candidates: not hashed
 #pragma unroll 1
     for (int mt = rt; mt < n_mt; mt += 8) {
       if (mt != rt) {
@@ -445,7 +502,7 @@ __global__ __launch_bounds__(PASS_WAVES * 64) void pass_kernel(PassParams p) {
       }
 #pragma unroll 1
       for (int vt = 0; vt < n_vt; ++vt) {
-        const int base = vt < n_ktiles_h ? vt * 32 : nkr + (vt - n_ktiles_h) * 32;
+        const int base = vt * 32;
         f32x16 acc;
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
@@ -479,16 +536,13 @@ __global__ __launch_bounds__(PASS_WAVES * 64) void pass_kernel(PassParams p) {
   } else {
     __syncthreads();
     LKV_TS(3);
-    // codes: one item = (vector row, group of 8 tables) -> one 16-byte store where aligned
+    // key codes: one item = (key, group of 8 tables) -> one 16-byte store where aligned
     const uint32_t code_mask = (1u << p.n_bits) - 1u;
     const int n_tg8 = (n_tab + 7) >> 3;
-    const int n_krows_h = in_ctx ? 0 : n_keys_wg;
-    const int n_items = (n_krows_h + n_hq) * n_tg8;
+    const int n_items = (in_ctx ? 0 : n_keys_wg) * n_tg8;
     for (int it = tid; it < n_items; it += NTHR) {
       const int vr = it / n_tg8, tb = (it - vr * n_tg8) * 8;
-      const bool is_key = vr < n_krows_h;
-      const int lrow = is_key ? vr : nkr + (vr - n_krows_h);
-      const uint32_t* bits = sBits + (size_t)lrow * BITS_PITCH;
+      const uint32_t* bits = sBits + (size_t)vr * BITS_PITCH;
       uint32_t codes[8];
 #pragma unroll
       for (int u = 0; u < 8; ++u) {
@@ -497,8 +551,7 @@ __global__ __launch_bounds__(PASS_WAVES * 64) void pass_kernel(PassParams p) {
         const uint64_t two = (uint64_t)bits[w0] | ((uint64_t)bits[w0 + 1] << 32);
         codes[u] = (uint32_t)(two >> sh) & code_mask;
       }
-      uint16_t* dst = is_key ? p.sig_k + ((size_t)h * p.s_t + seg_row0 + vr) * p.n_tables + tab0 + tb
-                             : p.sig_q + ((size_t)h * p.m_rows + hq0 + (vr - n_krows_h)) * p.n_tables + tab0 + tb;
+      uint16_t* dst = p.sig_k + ((size_t)h * p.s_t + seg_row0 + vr) * p.n_tables + tab0 + tb;
       if (tb + 8 <= n_tab && ((reinterpret_cast<uintptr_t>(dst) & 15) == 0)) {
         *reinterpret_cast<uint4*>(dst) = make_uint4(codes[0] | (codes[1] << 16), codes[2] | (codes[3] << 16),
                                                     codes[4] | (codes[5] << 16), codes[6] | (codes[7] << 16));
@@ -507,15 +560,14 @@ __global__ __launch_bounds__(PASS_WAVES * 64) void pass_kernel(PassParams p) {
         for (int u = 0; u < 8; ++u)
           if (tb + u < n_tab) dst[u] = (uint16_t)codes[u];
       }
-      if (!is_key && p.qhist) {
-        // per-(head, table) histogram of the query codes, two 16-bit bins per word (a bin holds <= G*W <= 1024)
-#pragma unroll
-        for (int u = 0; u < 8; ++u)
-          if (tb + u < n_tab) {
-            const uint32_t idx = ((uint32_t)(h * p.n_tables + tab0 + tb + u) << p.n_bits) | codes[u];
-            atomicAdd(p.qhist + (idx >> 1), 1u << ((idx & 1u) * 16));
-          }
-      }
+    }
+    // the finished histograms of this workgroup's (row group, tables), interleaved with the other
+    // groups' word by word: every word is rewritten each block, so nothing has to be cleared and no
+    // global atomics are needed
+    if (p.hist_lds_words && n_qt > 0) {
+      const int hist_w = (1 << p.n_bits) >> 1;
+      uint32_t* dst = p.qhist + ((size_t)h * p.n_tables + qt0) * hist_w * n_qg + qg;
+      for (int i = tid; i < n_qt * hist_w; i += NTHR) dst[(size_t)i * n_qg] = sHist[i];
     }
     if (!p.qhist && !in_ctx && qg == 0)  // the separate count kernel accumulates with atomics
       for (int t = tid; t < n_keys_wg; t += NTHR) p.cnt[(size_t)h * p.s_t + seg_row0 + t] = 0;
@@ -579,19 +631,9 @@ __global__ __launch_bounds__(1024) void select_kernel(SelectParams p, AppendPara
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int n_sel_wg = p.n_kv_heads * split;
   // the workgroups that share a head (and read the same scores and counts) sit on one XCD
-  const int sel_id = (int)blockIdx.x < n_sel_wg ? xcd_major(blockIdx.x, n_sel_wg) : 0;
+  const int sel_id = xcd_major(blockIdx.x, n_sel_wg);
   const int h = FUSED ? sel_id / split : sel_id;
   const int part = FUSED ? sel_id - h * split : 0;
-  if ((int)blockIdx.x >= n_sel_wg) {
-    // extra workgroups: the query histograms have been consumed by the sweep before this kernel;
-    // clear them for the next block, a slice each
-    const int n_z = gridDim.x - n_sel_wg, z = blockIdx.x - n_sel_wg;
-    const size_t n_vec = (size_t)p.n_kv_heads * p.qhist_words_per_head / 4;
-    uint4* hz = reinterpret_cast<uint4*>(p.qhist);
-    for (size_t i = (size_t)z * 1024 + tid; i < n_vec; i += (size_t)n_z * 1024) hz[i] = make_uint4(0u, 0u, 0u, 0u);
-    return;
-  }
-
   LKV_TS(0);
   uint32_t key[EPT], c2[EPT];
   bool inr[EPT], cand[EPT], sel[EPT];
@@ -790,27 +832,27 @@ __global__ __launch_bounds__(256) void append_kernel(AppendParams p) {
 // launchers
 // ---------------------------------------------------------------------------------------------
 // offset of the small per-row arrays = size of the larger of the two big LDS layouts of a sweep
-size_t sweep_lds_tail_offset(int dtype, int head_dim, bool pass2, int range_keys, int q_rows_per_wg) {
+size_t sweep_lds_tail_offset(int dtype, int head_dim, bool pass2, int range_keys, int q_tiles, int hist_lds_words) {
   const int es = dtype == DT_BF16 ? 2 : 4;
   const int ch = head_dim * es / 16;
   const size_t pitch = (size_t)(ch + 1) * 16;
-  const size_t qt = pass2 ? 0 : (size_t)((q_rows_per_wg + 31) & ~31);
-  const size_t rows = range_keys + qt;
-  const size_t steady = rows * pitch + (pass2 ? (size_t)8 * range_keys * 4 : rows * BITS_PITCH * 4);
+  const size_t bits = (((size_t)range_keys * BITS_PITCH + 3) / 4) * 16;
+  const size_t steady = range_keys * pitch + (pass2 ? (size_t)8 * range_keys * 4
+                                                     : bits + (size_t)q_tiles * 32 * pitch + (size_t)hist_lds_words * 4);
   const size_t staging = ch <= 16 ? (size_t)(pass2 ? 1 : 2) * PASS_ROWS * pitch : 0;
   return ((steady > staging ? steady : staging) + 15) & ~(size_t)15;
 }
 
-size_t sweep_lds_bytes(int dtype, int head_dim, bool pass2, int range_keys, int q_rows_per_wg) {
-  return sweep_lds_tail_offset(dtype, head_dim, pass2, range_keys, q_rows_per_wg) + (size_t)PASS_ROWS * 8;
+size_t sweep_lds_bytes(int dtype, int head_dim, bool pass2, int range_keys, int q_tiles, int hist_lds_words) {
+  return sweep_lds_tail_offset(dtype, head_dim, pass2, range_keys, q_tiles, hist_lds_words) + (size_t)PASS_ROWS * 8;
 }
 
 template <int DT, int D, bool PASS2>
 static hipError_t launch_pass_t(const PassParams& p, hipStream_t st) {
   dim3 grid(p.n_ranges * p.n_qgroups * p.n_kv_heads);
   PassParams q = p;
-  q.lds_tail_offset = (int)sweep_lds_tail_offset(DT, D, PASS2, p.keys_per_range, p.q_rows_per_wg);
-  const size_t lds = sweep_lds_bytes(DT, D, PASS2, p.keys_per_range, p.q_rows_per_wg);
+  q.lds_tail_offset = (int)sweep_lds_tail_offset(DT, D, PASS2, p.keys_per_range, p.q_tiles, p.hist_lds_words);
+  const size_t lds = sweep_lds_bytes(DT, D, PASS2, p.keys_per_range, p.q_tiles, p.hist_lds_words);
   hipLaunchKernelGGL((pass_kernel<DT, D, PASS2>), grid, dim3(PASS_WAVES * 64), lds, st, q);
   return hipGetLastError();
 }
@@ -866,10 +908,8 @@ hipError_t launch_count(const CountParams& p, int n_kv_heads, hipStream_t st) {
 template <bool FUSED>
 static hipError_t launch_select_t(const SelectParams& p, const AppendParams& ap, int split, hipStream_t st) {
   const int ept = (p.s_t + 1023) / 1024;
-  // `split` workgroups per head select (and, fused, copy); with resident query histograms, extra ones
-  // clear them (16 KiB each)
-  const int n_zero = p.qhist ? (int)(((size_t)p.n_kv_heads * p.qhist_words_per_head * 4 + 16383) / 16384) : 0;
-  dim3 grid(p.n_kv_heads * split + n_zero);
+  // `split` workgroups per head select (and, fused, copy)
+  dim3 grid(p.n_kv_heads * split);
   if (ept <= 1) hipLaunchKernelGGL((select_kernel<1, FUSED>), grid, dim3(1024), 0, st, p, ap, split);
   else if (ept <= 2) hipLaunchKernelGGL((select_kernel<2, FUSED>), grid, dim3(1024), 0, st, p, ap, split);
   else if (ept <= 4) hipLaunchKernelGGL((select_kernel<4, FUSED>), grid, dim3(1024), 0, st, p, ap, split);
