@@ -49,7 +49,7 @@ def main():
     ap.add_argument("--workload", default="llama8b-128k")
     ap.add_argument("--layer", type=int, default=0)
     ap.add_argument("--mode", choices=["graph", "eager"], default="graph")
-    ap.add_argument("--profile-steps", type=int, default=3)
+    ap.add_argument("--profile-steps", type=int, default=5, help="replays per kernel kind for the per-kernel durations; 0 skips them")
     ap.add_argument("--unfused", action="store_true", help="laserkv_select_block + laserkv_append instead of laserkv_compress_block")
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MIB",
                     help="also run one plain device copy of this many MiB (a known-size reference for HBM byte counters)")
@@ -106,11 +106,42 @@ def main():
         torch.cuda.synchronize()
         t1 = time.perf_counter()
         ms_per_step = (t1 - t0) * 1e3 / args.steps
-        # per-kernel durations: the same calls with an event pair around every launch
+        # which kernels one layer launches, and how often: one pass with an event pair around every launch
         comp.lib.laserkv_profile_begin()
-        for _ in range(args.profile_steps):
-            comp.run_plan(plan)
+        comp.run_plan(plan)
         prof = comp.lib.laserkv_profile_end()
+        torch.cuda.synchronize()
+        # per-kernel durations: the layer's launches of ONE kernel kind, back to back (graph replays in
+        # graph mode), between two events on the launch stream; average = elapsed / launches.  Event pairs
+        # between consecutive kernels would add about 2 us to each.
+        kern = {}
+        for name, (_, n_launch) in prof.items():
+            if not n_launch or not args.profile_steps:
+                kern[name] = dict(avg_us=0.0, launches=0)
+                continue
+            comp.lib.laserkv_profile_isolate(name)
+            comp.run_plan(plan)
+            stream.synchronize()
+            g1 = None
+            if args.mode == "graph":
+                g1 = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(g1, stream=stream):
+                    comp.run_plan(plan)
+                g1.replay()
+                stream.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            for _ in range(args.profile_steps):
+                if g1 is not None:
+                    g1.replay()
+                else:
+                    comp.run_plan(plan)
+            e1.record(stream)
+            e1.synchronize()
+            kern[name] = dict(avg_us=1e3 * e0.elapsed_time(e1) / (args.profile_steps * n_launch), launches=n_launch)
+            del g1
+        comp.lib.laserkv_profile_isolate(None)
+        comp.run_plan(plan)   # leave the workspace and the cache in the state of a complete pass
         torch.cuda.synchronize()
     tokens = ddev["k"].shape[1]
     value = tokens / (ms_per_step * 1e-3)
@@ -118,7 +149,6 @@ def main():
     work = algorithmic_work(wl, comp.B)
     if not args.unfused:  # the last kernel selects and appends
         work["select"] = ("hbm", work["select"][1] + work["append"][1])
-    kern = {k: dict(avg_us=1e3 * ms / max(n, 1), launches=n) for k, (ms, n) in prof.items()}
     if not any(v["launches"] for v in kern.values()):
         print(json.dumps(dict(value=round(value, 1), unit="tokens/s/layer", ms_per_step=round(ms_per_step, 4),
                               note="no per-kernel timing requested: roofline omitted")), flush=True)

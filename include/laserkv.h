@@ -166,6 +166,13 @@ typedef enum {
 int laserkv_profile_begin(laserkv_ctx* ctx);
 int laserkv_profile_end(laserkv_ctx* ctx, double* ms_per_kernel, int64_t* launches);
 
+/* For benchmarks that time one kernel kind without event pairs between kernels: while kernel_id names a
+ * laserkv_kernel_id, every call on the context launches only kernels of that kind (all checks still run,
+ * outputs are NOT valid); a negative kernel_id restores normal operation.  The workspace keeps the
+ * intermediates of the last complete call, so an isolated kernel runs on valid inputs of the same shape.
+ * Errors: LKV_EINVAL (null context, kernel_id >= LKV_N_KERNELS). */
+int laserkv_profile_isolate(laserkv_ctx* ctx, int32_t kernel_id);
+
 #ifdef __cplusplus
 }
 #endif

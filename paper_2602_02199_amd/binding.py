@@ -19,7 +19,7 @@ LKV_OK, LKV_EINVAL, LKV_ECAP, LKV_ENOMEM, LKV_EHIP = 0, -1, -2, -3, -4
 EXPORTS = (
     "laserkv_create", "laserkv_destroy", "laserkv_last_error", "laserkv_budget",
     "laserkv_partition", "laserkv_select_block", "laserkv_append", "laserkv_compress_block",
-    "laserkv_profile_begin", "laserkv_profile_end",
+    "laserkv_profile_begin", "laserkv_profile_end", "laserkv_profile_isolate",
 )
 KERNEL_NAMES = ("sweep1", "sweep2", "count", "select", "append")
 
@@ -78,6 +78,8 @@ def load():
     lib.laserkv_profile_begin.restype = C.c_int
     lib.laserkv_profile_end.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(i64)]
     lib.laserkv_profile_end.restype = C.c_int
+    lib.laserkv_profile_isolate.argtypes = [vp, i32]
+    lib.laserkv_profile_isolate.restype = C.c_int
     _lib = lib
     return lib
 
@@ -203,3 +205,7 @@ class LaserKV:
         cnt = (C.c_int64 * n)()
         self._check(self._lib.laserkv_profile_end(self._ctx, ms, cnt))
         return {KERNEL_NAMES[i]: (float(ms[i]), int(cnt[i])) for i in range(n)}
+
+    def laserkv_profile_isolate(self, kernel):
+        """kernel: a name from KERNEL_NAMES, or None to launch every kernel again."""
+        self._check(self._lib.laserkv_profile_isolate(self._ctx, -1 if kernel is None else KERNEL_NAMES.index(kernel)))

@@ -39,6 +39,7 @@ struct laserkv_ctx {
   uint16_t* sig_k;   // [H_kv, max_block, L]
   uint16_t* sig_q;   // [H_q, max_window, L]
   int m_pad;
+  int only_kernel;   // >= 0: launch only this kernel kind (laserkv_profile_isolate); -1 normally
   char error[512];
   // per-kernel event timing (benchmarks only)
   bool profiling;
@@ -78,6 +79,7 @@ int bits_for(int64_t v) {
 // Runs `launch` bracketed by an event pair when the context is profiling.
 template <typename F>
 hipError_t timed(laserkv_ctx* ctx, int kind, hipStream_t st, F launch) {
+  if (ctx->only_kernel >= 0 && ctx->only_kernel != kind) return hipSuccess;  // benchmark isolation
   if (!ctx->profiling || ctx->ev_kind->size() >= LKV_PROFILE_MAX_LAUNCHES) return launch();
   const size_t i = ctx->ev_kind->size();
   while (ctx->ev_pool->size() < 2 * (i + 1)) {
@@ -144,6 +146,7 @@ int laserkv_create(const laserkv_config* cfg, laserkv_ctx** out) {
   laserkv_ctx* ctx = new (std::nothrow) laserkv_ctx();
   if (!ctx) return fail(nullptr, LKV_ENOMEM, "create: host allocation failed");
   memset(ctx, 0, sizeof(*ctx));
+  ctx->only_kernel = -1;
   ctx->cfg = c;
   ctx->ev_pool = new (std::nothrow) std::vector<hipEvent_t>();
   ctx->ev_kind = new (std::nothrow) std::vector<int>();
@@ -495,6 +498,13 @@ int laserkv_compress_block(laserkv_ctx* ctx,
   return select_impl(ctx, q_win, q_stride_head, q_stride_tok, k_blk, k_stride_head, k_stride_tok,
                      k_ctx, c_stride_head, c_stride_tok, hyperplanes, s_t, w, t_ctx, block_pos0, q_pos0, causal,
                      n_anchor, n_local, k_exact, k_lsh, keep_idx, nullptr, nullptr, nullptr, nullptr, &ap, hip_stream);
+}
+
+int laserkv_profile_isolate(laserkv_ctx* ctx, int32_t kernel_id) {
+  if (!ctx) return fail(nullptr, LKV_EINVAL, "profile_isolate: null context");
+  if (kernel_id >= LKV_N_KERNELS) return fail(ctx, LKV_EINVAL, "profile_isolate: no kernel kind %d", kernel_id);
+  ctx->only_kernel = kernel_id < 0 ? -1 : kernel_id;
+  return LKV_OK;
 }
 
 int laserkv_profile_begin(laserkv_ctx* ctx) {

@@ -279,3 +279,30 @@ def test_compress_block_equals_select_then_append(name, n_blocks):
     for a, b in zip(*results):
         assert torch.equal(a, b)
     assert bool((results[1][0][:, :n_blocks * min(B, wl.s_block)] >= 0).all())
+
+
+def test_profile_isolate_restores_normal_operation():
+    """laserkv_profile_isolate launches one kernel kind only (benchmarks); after it is switched off the
+    same calls must again give the results of a complete pass."""
+    wl = synth.WORKLOADS["llama8b-16k"]
+    B = O.budget(wl.s_block, wl.l_ctx, wl.r_num, wl.r_den)
+    na = O.partition(B, wl.n_div, wl.alpha, wl.s_block)[0]
+    dev = to_dev(synth.make_layer(wl, 3, na, n_blocks=2))
+    comp = LayerCompressor(wl, DEV, max_blocks=2)
+    plan = comp.plan_layer(dev, fused=True)
+    comp.run_plan(plan)
+    torch.cuda.synchronize()
+    want = (comp.cache_pos.clone(), comp.k_cache.clone(), comp.v_cache.clone())
+    for name in ("sweep1", "sweep2", "select"):
+        comp.lib.laserkv_profile_isolate(name)
+        comp.run_plan(plan)
+    comp.lib.laserkv_profile_isolate(None)
+    with pytest.raises(binding.LaserKVError):
+        comp.lib._check(comp.lib._lib.laserkv_profile_isolate(comp.lib._ctx, 99))
+    comp.cache_pos.fill_(-1)
+    comp.k_cache.zero_()
+    comp.v_cache.zero_()
+    comp.run_plan(plan)
+    torch.cuda.synchronize()
+    for a, b in zip(want, (comp.cache_pos, comp.k_cache, comp.v_cache)):
+        assert torch.equal(a, b)
