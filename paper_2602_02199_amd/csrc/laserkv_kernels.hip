@@ -627,6 +627,7 @@ __global__ __launch_bounds__(1024) void select_kernel(SelectParams p, AppendPara
   __shared__ uint32_t sHist[4][256];
   __shared__ int sWave[16];
   __shared__ int sPick[2];  // digit chosen in this round, keys still needed below it
+  __shared__ uint32_t sMaxCnt;  // largest collision count among the candidates
   __shared__ int sKeep[FUSED ? 1024 : 1];  // FUSED: the kept indices this workgroup copies
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int n_sel_wg = p.n_kv_heads * split;
@@ -760,14 +761,28 @@ __global__ __launch_bounds__(1024) void select_kernel(SelectParams p, AppendPara
   };
 
   sHist[tid >> 8][tid & 255] = 0u;
+  if (tid == 0) sMaxCnt = 0u;
   __syncthreads();
   LKV_TS(1);
+  {
+    // Collision counts are mostly tiny, so their top byte is usually zero for every candidate: the
+    // block-wide maximum (one LDS atomic per wave, ordered by the barriers of the first stage) tells
+    // how many digits the second stage really needs.
+    uint32_t mx = 0u;
+#pragma unroll
+    for (int e = 0; e < EPT; ++e) mx = max(mx, cand[e] ? c2[e] : 0u);
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) mx = max(mx, (uint32_t)__shfl_xor((int)mx, off));
+    if (lane == 0 && mx) atomicMax(&sMaxCnt, mx);
+  }
   take_top(key, cand, p.k_exact, 4);
   LKV_TS(2);
   bool act2[EPT];
 #pragma unroll
   for (int e = 0; e < EPT; ++e) act2[e] = cand[e] && !sel[e];
-  take_top(c2, act2, p.k_lsh, (p.cnt_bits + 7) >> 3);
+  if (p.k_exact <= 0) __syncthreads();  // otherwise the first stage's barriers already order the atomicMax above
+  const int cnt_digits = sMaxCnt < 256u ? 1 : (sMaxCnt < 65536u ? 2 : (sMaxCnt < (1u << 24) ? 3 : 4));
+  take_top(c2, act2, p.k_lsh, min(cnt_digits, (p.cnt_bits + 7) >> 3));
   LKV_TS(3);
 
   int n_keep = 0;
