@@ -644,7 +644,34 @@ __global__ __launch_bounds__(1024) void select_kernel(SelectParams p, AppendPara
     float sc[EPT];
     int cc[EPT];
     const size_t hoff = (size_t)h * p.s_t, poff = (size_t)p.n_kv_heads * p.s_t;
-    if (p.n_qgroups <= 2 && p.n_cnt_parts <= 2) {
+    // 16-byte loads when a thread's EPT positions are whole aligned quads inside the block
+    const bool quads = EPT % 4 == 0 && (p.s_t & 3) == 0 && (tid + 1) * EPT <= p.s_t;
+    if (p.n_qgroups <= 2 && p.n_cnt_parts <= 2 && __all(quads)) {
+      constexpr int NQ = EPT >= 4 ? EPT / 4 : 1;
+      const bool s2 = p.n_qgroups > 1, c2p = p.n_cnt_parts > 1;
+      uint4 a0[NQ], a1[NQ], b0[NQ], b1[NQ];
+      const uint4* ps = reinterpret_cast<const uint4*>(p.s_part + hoff + (size_t)tid * EPT);
+      const uint4* pc = reinterpret_cast<const uint4*>(p.cnt + hoff + (size_t)tid * EPT);
+      const size_t pq = poff / 4;
+#pragma unroll
+      for (int v = 0; v < NQ; ++v) {
+        a0[v] = ps[v];
+        a1[v] = s2 ? ps[pq + v] : make_uint4(0u, 0u, 0u, 0u);
+        b0[v] = pc[v];
+        b1[v] = c2p ? pc[pq + v] : make_uint4(0u, 0u, 0u, 0u);
+      }
+#pragma unroll
+      for (int v = 0; v < NQ; ++v) {
+        const uint32_t x0[4] = {a0[v].x, a0[v].y, a0[v].z, a0[v].w}, x1[4] = {a1[v].x, a1[v].y, a1[v].z, a1[v].w};
+        const uint32_t y0[4] = {b0[v].x, b0[v].y, b0[v].z, b0[v].w}, y1[4] = {b1[v].x, b1[v].y, b1[v].z, b1[v].w};
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+          if (4 * v + u < EPT) {
+            sc[4 * v + u] = __uint_as_float(x0[u]) + __uint_as_float(x1[u]);
+            cc[4 * v + u] = (int)(y0[u] + y1[u]);
+          }
+      }
+    } else if (p.n_qgroups <= 2 && p.n_cnt_parts <= 2) {
       const bool s2 = p.n_qgroups > 1, c2p = p.n_cnt_parts > 1;
       float a0[EPT], a1[EPT];
       int b0[EPT], b1[EPT];
