@@ -352,14 +352,14 @@ int select_impl(laserkv_ctx* ctx,
   lp.inv_m = 1.0f / (float)m_rows;
   lp.cnt = ctx->cnt;
   lp.n_cnt_parts = sp.qhist ? n_qg : 1;
-  lp.cnt_out = ctx->cnt_sum;
+  lp.cnt_out = dbg_count ? ctx->cnt_sum : nullptr;      // stage outputs are written only on request
   lp.s_t = s_t;
   lp.n_anchor = n_anchor;
   lp.n_local = n_local;
   lp.k_exact = k_exact;
   lp.k_lsh = k_lsh;
   lp.cnt_bits = bits_for((int64_t)m_rows * c.lsh_tables);
-  lp.s_exact = ctx->s_exact;
+  lp.s_exact = dbg_s_exact ? ctx->s_exact : nullptr;
   lp.keep = keep_idx;
 
   hipError_t e;

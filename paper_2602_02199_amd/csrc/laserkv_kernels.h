@@ -73,7 +73,7 @@ struct SelectParams {
   int s_t;
   int n_anchor, n_local, k_exact, k_lsh;
   int cnt_bits;         // bits needed to hold G * W * L
-  float* s_exact;       // [H_kv, S] final scores (always written)
+  float* s_exact;       // [H_kv, S] final scores (optional, for the stage outputs)
   int32_t* keep;        // [H_kv, B_t]
 };
 

@@ -710,7 +710,7 @@ __global__ __launch_bounds__(1024) void select_kernel(SelectParams p, AppendPara
       key[e] = inr[e] ? __float_as_uint(sv) : 0u;  // scores are >= 0: their bit patterns order like the values
       c2[e] = inr[e] ? (uint32_t)cc[e] : 0u;
       if (inr[e] && part == 0) {
-        p.s_exact[hoff + i] = sv;
+        if (p.s_exact) p.s_exact[hoff + i] = sv;
         if (p.cnt_out) p.cnt_out[hoff + i] = cc[e];
       }
     }
