@@ -264,13 +264,19 @@ __global__ __launch_bounds__(PASS_WAVES * 64) void pass_kernel(PassParams p) {
     sLim[t] = p.causal ? p.lim0 + j : INT_MAX;
   }
   if (PASS2) {
-    // row log-sum-exp from the sweep-1 partials
+    // row log-sum-exp from the sweep-1 partials: maximum reference first, then one exp per partial
     float mm = NEG_BIG, ss = 0.0f;
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
       const int r = pr_beg + 2 * u;
-      if (2 * u < pr_per && r < p.n_ranges) lse_merge(mm, ss, __uint_as_float(pv[u].x), __uint_as_float(pv[u].y));
-      if (2 * u < pr_per && r + 1 < p.n_ranges) lse_merge(mm, ss, __uint_as_float(pv[u].z), __uint_as_float(pv[u].w));
+      if (2 * u < pr_per && r < p.n_ranges) mm = fmaxf(mm, __uint_as_float(pv[u].x));
+      if (2 * u < pr_per && r + 1 < p.n_ranges) mm = fmaxf(mm, __uint_as_float(pv[u].z));
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int r = pr_beg + 2 * u;
+      if (2 * u < pr_per && r < p.n_ranges) ss = fmaf(__uint_as_float(pv[u].y), fast_exp2(__uint_as_float(pv[u].x) - mm), ss);
+      if (2 * u < pr_per && r + 1 < p.n_ranges) ss = fmaf(__uint_as_float(pv[u].w), fast_exp2(__uint_as_float(pv[u].z) - mm), ss);
     }
     for (int e = 8; e < pr_per; ++e) {  // more than 32 ranges per head: the rest, not prefetched
       const float2 v = pr_ptr[e];

@@ -129,6 +129,9 @@ def test_llama16k_bf16_all_blocks():
          window=40, n_div=4, lsh_tables=31, lsh_bits=16),
     dict(name="one-table-one-bit", n_q_heads=2, n_kv_heads=2, head_dim=64, dtype="f32", l_ctx=130, s_block=65,
          window=3, n_div=2, lsh_tables=1, lsh_bits=1),
+    # 768 window rows = three query-row groups, with the histogram path (K <= 12)
+    dict(name="three-row-groups", n_q_heads=12, n_kv_heads=1, head_dim=128, dtype="bf16", l_ctx=1800, s_block=900,
+         window=64, n_div=4, lsh_tables=6, lsh_bits=9),
     # 512 window rows x 4 tables of 2 bits: collision counts in the hundreds (two radix digits in stage 2)
     dict(name="big-counts", n_q_heads=8, n_kv_heads=1, head_dim=64, dtype="bf16", l_ctx=1200, s_block=600,
          window=64, n_div=4, lsh_tables=4, lsh_bits=2),
