@@ -339,9 +339,16 @@ int select_impl(laserkv_ctx* ctx,
     if (tg > c.lsh_tables) tg = c.lsh_tables;
     cp.tables_per_group = tg;
     const int n_tg = (c.lsh_tables + tg - 1) / tg;
-    int n_kr = wg_target / (c.n_kv_heads * n_tg);
+    // Several table groups per workgroup (taken one after the other) save global atomics; as many as
+    // still leave about one workgroup per compute unit with key ranges of at least 1024 keys.
+    int gpw = 1;
+    while (gpw * 2 <= n_tg && (int64_t)c.n_kv_heads * ((n_tg + 2 * gpw - 1) / (2 * gpw)) * ((s_t + 1023) / 1024) >= wg_target) gpw *= 2;
+    cp.groups_per_wg = gpw;
+    const int n_wg_t = (n_tg + gpw - 1) / gpw;
+    int n_kr = wg_target / (c.n_kv_heads * n_wg_t);
     if (n_kr < 1) n_kr = 1;
-    int kpr = ((s_t + n_kr - 1) / n_kr + 255) / 256 * 256;
+    int kpr = ((s_t + n_kr - 1) / n_kr + 1023) / 1024 * 1024;
+    if (kpr > lkv::count_max_keys_per_range()) kpr = lkv::count_max_keys_per_range();
     cp.keys_per_range = kpr;
   }
 

@@ -58,8 +58,9 @@ struct CountParams {
   int32_t* cnt;           // [H_kv, S]
   int group, w, s_t;
   int n_tables, n_bits;
-  int tables_per_group;   // TG
-  int keys_per_range;
+  int tables_per_group;   // TG: tables whose histograms share the LDS at one time
+  int groups_per_wg;      // table groups a workgroup takes one after the other
+  int keys_per_range;     // <= count_max_keys_per_range()
 };
 
 struct SelectParams {
@@ -102,5 +103,6 @@ hipError_t init_kernel_attributes();
 size_t sweep_lds_bytes(int dtype, int head_dim, bool pass2, int range_keys, int q_tiles, int hist_lds_words);
 int sweep_rows_per_group();  // window rows one sweep workgroup covers
 int score_max_range();  // most keys one score workgroup takes (its LDS holds the whole range)
+int count_max_keys_per_range();
 
 }  // namespace lkv

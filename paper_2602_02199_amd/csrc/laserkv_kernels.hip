@@ -586,33 +586,68 @@ __global__ __launch_bounds__(PASS_WAVES * 64) void pass_kernel(PassParams p) {
 // table in the group are histogrammed into LDS (two 16-bit bins per word); each key then looks
 // its own code up per table.  Partial sums over table groups meet in integer atomics.
 // ---------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void count_kernel(CountParams p) {
+constexpr int COUNT_THREADS = 1024;
+constexpr int COUNT_KEYS_PER_THREAD = 8;  // keys_per_range <= COUNT_THREADS * COUNT_KEYS_PER_THREAD
+__global__ __launch_bounds__(COUNT_THREADS) void count_kernel(CountParams p) {
   extern __shared__ uint32_t bins[];
   const int tid = threadIdx.x;
-  const int kr = blockIdx.x, tg = blockIdx.y, h = blockIdx.z;
-  const int t0 = tg * p.tables_per_group;
-  const int tga = min(p.tables_per_group, p.n_tables - t0);
-  const int n_words = (tga << p.n_bits) >> 1;
-  for (int i = tid; i < n_words; i += 256) bins[i] = 0u;
-  __syncthreads();
+  const int kr = blockIdx.x, h = blockIdx.z;
   const int nq = p.group * p.w;
-  const uint16_t* sq = p.sig_q + (size_t)h * nq * p.n_tables + t0;
-  for (int e = tid; e < nq * tga; e += 256) {
-    const int qrow = e / tga, tl = e - qrow * tga;
-    const uint32_t idx = ((uint32_t)tl << p.n_bits) | sq[(size_t)qrow * p.n_tables + tl];
-    atomicAdd(&bins[idx >> 1], 1u << ((idx & 1u) * 16));
-  }
-  __syncthreads();
   const int i0 = kr * p.keys_per_range;
   const int i1 = min(i0 + p.keys_per_range, p.s_t);
-  for (int i = i0 + tid; i < i1; i += 256) {
-    const uint16_t* sk = p.sig_k + ((size_t)h * p.s_t + i) * p.n_tables + t0;
-    int sum = 0;
-    for (int tl = 0; tl < tga; ++tl) {
-      const uint32_t idx = ((uint32_t)tl << p.n_bits) | sk[tl];
-      sum += (bins[idx >> 1] >> ((idx & 1u) * 16)) & 0xffffu;
+  int sum[COUNT_KEYS_PER_THREAD];
+#pragma unroll
+  for (int k = 0; k < COUNT_KEYS_PER_THREAD; ++k) sum[k] = 0;
+  // the workgroup's table groups one after the other through the same LDS histogram, so a key's
+  // counts over all of them meet in a register and cost one global atomic
+  for (int pass = 0; pass < p.groups_per_wg; ++pass) {
+    const int t0 = (blockIdx.y * p.groups_per_wg + pass) * p.tables_per_group;
+    const int tga = min(p.tables_per_group, p.n_tables - t0);
+    if (tga <= 0) break;  // block-uniform
+    const uint16_t* sq = p.sig_q + (size_t)h * nq * p.n_tables + t0;
+    if (pass == 0) {
+      const int n_words = (tga << p.n_bits) >> 1;
+      if ((n_words & 3) == 0) {
+        uint4* b4 = reinterpret_cast<uint4*>(bins);
+        for (int i = tid; i < n_words / 4; i += COUNT_THREADS) b4[i] = make_uint4(0u, 0u, 0u, 0u);
+      } else {
+        for (int i = tid; i < n_words; i += COUNT_THREADS) bins[i] = 0u;
+      }
+    } else {
+      // only the bins of the previous group's query codes are non-zero
+      const int tp = t0 - p.tables_per_group;
+      const uint16_t* sp = p.sig_q + (size_t)h * nq * p.n_tables + tp;
+      for (int e = tid; e < nq * p.tables_per_group; e += COUNT_THREADS) {
+        const int qrow = e / p.tables_per_group, tl = e - qrow * p.tables_per_group;
+        const uint32_t idx = ((uint32_t)tl << p.n_bits) | sp[(size_t)qrow * p.n_tables + tl];
+        bins[idx >> 1] = 0u;
+      }
     }
-    atomicAdd(&p.cnt[(size_t)h * p.s_t + i], sum);
+    __syncthreads();
+    for (int e = tid; e < nq * tga; e += COUNT_THREADS) {
+      const int qrow = e / tga, tl = e - qrow * tga;
+      const uint32_t idx = ((uint32_t)tl << p.n_bits) | sq[(size_t)qrow * p.n_tables + tl];
+      atomicAdd(&bins[idx >> 1], 1u << ((idx & 1u) * 16));
+    }
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < COUNT_KEYS_PER_THREAD; ++k) {
+      const int i = i0 + tid + k * COUNT_THREADS;
+      if (i < i1) {
+        const uint16_t* sk = p.sig_k + ((size_t)h * p.s_t + i) * p.n_tables + t0;
+        for (int tl = 0; tl < tga; ++tl) {
+          const uint32_t code = sk[tl];
+          const uint32_t idx = ((uint32_t)tl << p.n_bits) | code;
+          sum[k] += (bins[idx >> 1] >> ((idx & 1u) * 16)) & 0xffffu;
+        }
+      }
+    }
+    __syncthreads();  // lookups done before the next pass clears and refills the bins
+  }
+#pragma unroll
+  for (int k = 0; k < COUNT_KEYS_PER_THREAD; ++k) {
+    const int i = i0 + tid + k * COUNT_THREADS;
+    if (i < i1) atomicAdd(&p.cnt[(size_t)h * p.s_t + i], sum[k]);
   }
 }
 
@@ -946,12 +981,16 @@ int sweep_rows_per_group() { return PASS_ROWS; }
 
 hipError_t launch_count(const CountParams& p, int n_kv_heads, hipStream_t st) {
   const int n_tg = (p.n_tables + p.tables_per_group - 1) / p.tables_per_group;
+  const int n_wg_t = (n_tg + p.groups_per_wg - 1) / p.groups_per_wg;
   const int n_kr = (p.s_t + p.keys_per_range - 1) / p.keys_per_range;
+  if (p.keys_per_range > COUNT_THREADS * COUNT_KEYS_PER_THREAD) return hipErrorInvalidValue;
   const size_t lds = ((size_t)p.tables_per_group << p.n_bits) * 2;
-  dim3 grid(n_kr, n_tg, n_kv_heads);
-  hipLaunchKernelGGL(count_kernel, grid, dim3(256), lds, st, p);
+  dim3 grid(n_kr, n_wg_t, n_kv_heads);
+  hipLaunchKernelGGL(count_kernel, grid, dim3(COUNT_THREADS), lds, st, p);
   return hipGetLastError();
 }
+
+int count_max_keys_per_range() { return COUNT_THREADS * COUNT_KEYS_PER_THREAD; }
 
 template <bool FUSED>
 static hipError_t launch_select_t(const SelectParams& p, const AppendParams& ap, int split, hipStream_t st) {

@@ -312,3 +312,13 @@ def test_profile_isolate_restores_normal_operation():
     torch.cuda.synchronize()
     for a, b in zip(want, (comp.cache_pos, comp.k_cache, comp.v_cache)):
         assert torch.equal(a, b)
+
+
+def test_separate_count_kernel_path(monkeypatch):
+    """LASERKV_NO_QHIST=1 (read when a context is created) forces the stand-alone count kernel, which is
+    otherwise used only when neither histograms nor code tables fit a call."""
+    monkeypatch.setenv("LASERKV_NO_QHIST", "1")
+    wl = synth.shrink(synth.WORKLOADS["llama8b-16k"], index=11, l_ctx=4096)
+    run_and_check(wl, label="count-kernel-16x10")
+    wl = synth.shrink(synth.WORKLOADS["tiny"], index=12, l_ctx=1024, lsh_tables=3, lsh_bits=16)
+    run_and_check(wl, label="count-kernel-3x16")
