@@ -29,6 +29,10 @@ Readings taken where the paper is silent (each is listed in the design notes):
   * TopK breaks ties towards the lower token index.
   * Every block keeps its first floor(B/n) and last floor(B/n) tokens.
 
+  * Global-consensus variant (consensus_block): Alg. 1 step 3 taken literally,
+    S_exact summed over every layer and head handed in, and likewise the
+    collision counts of step 6, then ONE selection shared by all of them.
+
 Pins: see tests/test_oracle_*.py.  The composition of the steps into one
 layer-level run (compress_layer) has no printed worked example in the paper:
 whole-path parity unpinned beyond the per-step pins and the invariants.
@@ -250,6 +254,36 @@ def select_block(q_win, k_blk, k_ctx, planes, n_tables, n_bits,
         k_l.append(kl)
     return dict(s_exact=s_ex, sig_k=sig_k, sig_q=sig_q, unsure_k=uns_k, unsure_q=uns_q,
                 cnt=cnt, keep=np.stack(keep), k_exact_set=k_ex, k_lsh_set=k_l)
+
+
+def consensus_block(layers, n_tables, n_bits, n_anchor, n_local, k_exact, k_lsh,
+                    block_pos0=0, q_pos0=None, causal=True):
+    """Alg. 1 steps 3-8 with the sum of step 3 taken over all layers and heads.
+
+    layers: sequence of dicts, one per layer, with q_win [H_q, W, d], k_blk [H_kv, S_t, d],
+    k_ctx [H_kv, T, d] or None, planes [L*K, d] (each layer may bring its own hyperplanes).
+    The exact score of a token is the plain sum of the per-head pooled probabilities
+    (Sec. 3.3 "Precision": aggregated "across all layers and heads"); its collision count is the
+    plain sum of the per-head counts (Alg. 1 step 6 averages the same indicator over r; the
+    sum over heads and layers keeps the order of that average).  One two-stage TopK (steps 4-8)
+    on the summed arrays gives one kept set for every layer and head.
+
+    Returns dict(score [S_t], count [S_t], keep [B_t], per_layer=[select_block-style stage dicts]).
+    """
+    score, count, stages = None, None, []
+    for lay in layers:
+        h_q = np.asarray(lay["q_win"]).shape[0]
+        h_kv = np.asarray(lay["k_blk"]).shape[0]
+        s_ex = exact_scores(lay["q_win"], lay["k_blk"], lay.get("k_ctx"), block_pos0, q_pos0, causal)
+        sig_k, uns_k = simhash(lay["k_blk"], lay["planes"], n_tables, n_bits)
+        sig_q, uns_q = simhash(lay["q_win"], lay["planes"], n_tables, n_bits)
+        cnt = collision_counts(sig_q, sig_k, h_q // h_kv)
+        stages.append(dict(s_exact=s_ex, sig_k=sig_k, sig_q=sig_q, unsure_k=uns_k, unsure_q=uns_q, cnt=cnt))
+        for h in range(h_kv):
+            score = s_ex[h].copy() if score is None else score + s_ex[h]
+            count = cnt[h].copy() if count is None else count + cnt[h]
+    keep, k_ex, k_l = select(score, count, n_anchor, n_local, k_exact, k_lsh)
+    return dict(score=score, count=count, keep=keep, k_exact_set=k_ex, k_lsh_set=k_l, per_layer=stages)
 
 
 def compress_layer(blocks, planes, n_tables, n_bits, B, n, alpha, cap, dtype=np.float64):
