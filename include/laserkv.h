@@ -146,6 +146,42 @@ int laserkv_compress_block(laserkv_ctx* ctx,
                            int64_t cache_len, int64_t cache_cap,
                            void* hip_stream);
 
+/* Global-consensus variant: Alg. 1 step 3 taken literally, with the exact score summed "across all
+ * layers and heads" (Sec. 3.3 "Precision") and, likewise, the collision counts of step 6, followed by
+ * ONE two-stage TopK (steps 4-8) whose kept set serves every layer and head.  Three calls:
+ *
+ * laserkv_score_block: steps a1-a3 of laserkv_select_block for one layer's tensors (same arguments,
+ *   same checks), then score_acc[i] (+)= sum over the layer's KV heads of S_exact[h, i] and
+ *   count_acc[i] (+)= sum over heads of the collision counts.  accumulate == 0 overwrites the
+ *   accumulators (first layer of a block), otherwise adds (every further layer, possibly through other
+ *   contexts of the same block length on the same stream).
+ *     score_acc  DEVICE [s_t] float, count_acc DEVICE [s_t] int32
+ * laserkv_select_consensus: steps a4 on the accumulators; keep_idx DEVICE out [B_t] int32 ascending.
+ * laserkv_append_shared: laserkv_append with one index list keep_idx DEVICE [b_t] for every KV head.
+ * Errors: as for laserkv_select_block / laserkv_append; LKV_EINVAL for null accumulators. */
+int laserkv_score_block(laserkv_ctx* ctx,
+                        const void* q_win, int64_t q_stride_head, int64_t q_stride_tok,
+                        const void* k_blk, int64_t k_stride_head, int64_t k_stride_tok,
+                        const void* k_ctx, int64_t c_stride_head, int64_t c_stride_tok,
+                        const void* hyperplanes,
+                        int32_t s_t, int32_t w, int32_t t_ctx,
+                        int64_t block_pos0, int64_t q_pos0, int32_t causal,
+                        float* score_acc, int32_t* count_acc, int32_t accumulate,
+                        void* hip_stream);
+
+int laserkv_select_consensus(laserkv_ctx* ctx, const float* score_acc, const int32_t* count_acc, int32_t s_t,
+                             int32_t n_anchor, int32_t n_local, int32_t k_exact, int32_t k_lsh,
+                             int32_t* keep_idx, void* hip_stream);
+
+int laserkv_append_shared(laserkv_ctx* ctx,
+                          const void* k_blk, int64_t k_stride_head, int64_t k_stride_tok,
+                          const void* v_blk, int64_t v_stride_head, int64_t v_stride_tok,
+                          const int32_t* keep_idx, int32_t b_t, int32_t s_t, int64_t block_pos0,
+                          void* k_cache, void* v_cache, int64_t cache_stride_head,
+                          int64_t* cache_pos, int64_t pos_stride_head,
+                          int64_t cache_len, int64_t cache_cap,
+                          void* hip_stream);
+
 /* Per-kernel timing for benchmarks.  Between laserkv_profile_begin and laserkv_profile_end every
  * kernel the context launches is bracketed by a pair of HIP events on the call's stream (which adds
  * a little time between kernels, so whole-path timings belong outside such a bracket).

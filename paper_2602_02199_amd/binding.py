@@ -20,6 +20,7 @@ EXPORTS = (
     "laserkv_create", "laserkv_destroy", "laserkv_last_error", "laserkv_budget",
     "laserkv_partition", "laserkv_select_block", "laserkv_append", "laserkv_compress_block",
     "laserkv_profile_begin", "laserkv_profile_end", "laserkv_profile_isolate",
+    "laserkv_score_block", "laserkv_select_consensus", "laserkv_append_shared",
 )
 KERNEL_NAMES = ("sweep1", "sweep2", "count", "select", "append")
 
@@ -74,6 +75,14 @@ def load():
         i32, i32, i32, i64, i64, i32, i32, i32, i32, i32,
         vp, vp, vp, i64, vp, i64, i64, i64, vp]
     lib.laserkv_compress_block.restype = C.c_int
+    lib.laserkv_score_block.argtypes = [
+        vp, vp, i64, i64, vp, i64, i64, vp, i64, i64, vp,
+        i32, i32, i32, i64, i64, i32, vp, vp, i32, vp]
+    lib.laserkv_score_block.restype = C.c_int
+    lib.laserkv_select_consensus.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, vp, vp]
+    lib.laserkv_select_consensus.restype = C.c_int
+    lib.laserkv_append_shared.argtypes = lib.laserkv_append.argtypes
+    lib.laserkv_append_shared.restype = C.c_int
     lib.laserkv_profile_begin.argtypes = [vp]
     lib.laserkv_profile_begin.restype = C.c_int
     lib.laserkv_profile_end.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(i64)]
@@ -193,6 +202,41 @@ class LaserKV:
             _ptr(k_ctx), cs[0], cs[1], _ptr(hyperplanes), s_t, w, t_ctx, block_pos0, q_pos0, 1 if causal else 0,
             n_anchor, n_local, k_exact, k_lsh, _ptr(keep_idx), _ptr(k_cache), _ptr(v_cache), k_cache.stride(0),
             _ptr(cache_pos), cache_pos.stride(0), cache_len, k_cache.shape[1], self._stream(stream))
+        self._check(rc)
+
+    def laserkv_score_block(self, q_win, k_blk, k_ctx, hyperplanes, *, block_pos0, q_pos0=None, causal=True,
+                            score_acc, count_acc, accumulate, stream=None):
+        d = self.cfg.head_dim
+        s_t, w = k_blk.shape[1], q_win.shape[1]
+        t_ctx = 0 if k_ctx is None else k_ctx.shape[1]
+        if q_pos0 is None:
+            q_pos0 = block_pos0 + s_t - w
+        qs, ks = _strides3(q_win, d), _strides3(k_blk, d)
+        cs = _strides3(k_ctx, d) if k_ctx is not None else (0, 0)
+        assert hyperplanes.is_contiguous() and score_acc.is_contiguous() and count_acc.is_contiguous()
+        assert score_acc.numel() >= s_t and count_acc.numel() >= s_t
+        rc = self._lib.laserkv_score_block(
+            self._ctx, _ptr(q_win), qs[0], qs[1], _ptr(k_blk), ks[0], ks[1], _ptr(k_ctx), cs[0], cs[1],
+            _ptr(hyperplanes), s_t, w, t_ctx, block_pos0, q_pos0, 1 if causal else 0,
+            _ptr(score_acc), _ptr(count_acc), 1 if accumulate else 0, self._stream(stream))
+        self._check(rc)
+
+    def laserkv_select_consensus(self, score_acc, count_acc, *, s_t, n_anchor, n_local, k_exact, k_lsh, keep_idx,
+                                 stream=None):
+        assert score_acc.is_contiguous() and count_acc.is_contiguous() and keep_idx.is_contiguous()
+        rc = self._lib.laserkv_select_consensus(self._ctx, _ptr(score_acc), _ptr(count_acc), s_t, n_anchor, n_local,
+                                                k_exact, k_lsh, _ptr(keep_idx), self._stream(stream))
+        self._check(rc)
+
+    def laserkv_append_shared(self, k_blk, v_blk, keep_idx, *, b_t, block_pos0, k_cache, v_cache, cache_pos,
+                              cache_len, stream=None):
+        d = self.cfg.head_dim
+        ks, vs = _strides3(k_blk, d), _strides3(v_blk, d)
+        assert k_cache.stride(2) == 1 and k_cache.stride(1) == d and v_cache.stride() == k_cache.stride()
+        rc = self._lib.laserkv_append_shared(
+            self._ctx, _ptr(k_blk), ks[0], ks[1], _ptr(v_blk), vs[0], vs[1], _ptr(keep_idx), b_t, k_blk.shape[1],
+            block_pos0, _ptr(k_cache), _ptr(v_cache), k_cache.stride(0), _ptr(cache_pos), cache_pos.stride(0),
+            cache_len, k_cache.shape[1], self._stream(stream))
         self._check(rc)
 
     def laserkv_profile_begin(self):

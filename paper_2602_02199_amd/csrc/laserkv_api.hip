@@ -241,11 +241,13 @@ int select_impl(laserkv_ctx* ctx,
                 int32_t n_anchor, int32_t n_local, int32_t k_exact, int32_t k_lsh,
                 int32_t* keep_idx,
                 float* dbg_s_exact, uint16_t* dbg_sig_k, uint16_t* dbg_sig_q, int32_t* dbg_count,
-                const lkv::AppendParams* fused, void* hip_stream) {
+                const lkv::AppendParams* fused, void* hip_stream,
+                float* acc_score = nullptr, int32_t* acc_count = nullptr, int accumulate = 0) {
+  // acc_score != null: scoring only (steps a1-a3), summed over the heads into the accumulators
   if (!ctx) return fail(nullptr, LKV_EINVAL, "select_block: null context");
   const laserkv_config& c = ctx->cfg;
   const int es = ctx->elem_size, d = c.head_dim, G = ctx->group;
-  if (!q_win || !k_blk || !hyperplanes || !keep_idx) return fail(ctx, LKV_EINVAL, "select_block: null tensor");
+  if (!q_win || !k_blk || !hyperplanes || (!keep_idx && !acc_score)) return fail(ctx, LKV_EINVAL, "select_block: null tensor");
   if (s_t < 1 || s_t > c.max_block) return fail(ctx, LKV_EINVAL, "select_block: s_t=%d outside 1..max_block=%d", s_t, c.max_block);
   if (w < 1 || w > c.max_window) return fail(ctx, LKV_EINVAL, "select_block: w=%d outside 1..max_window=%d", w, c.max_window);
   if (t_ctx < 0 || t_ctx > c.max_ctx_keys) return fail(ctx, LKV_EINVAL, "select_block: t_ctx=%d outside 0..max_ctx_keys=%d", t_ctx, c.max_ctx_keys);
@@ -377,7 +379,21 @@ int select_impl(laserkv_ctx* ctx,
     return fail_hip(ctx, e, "select_block: sweep 2 (pooled probabilities)");
   if (!sp.qhist && (e = timed(ctx, LKV_KERN_COUNT, st, [&] { return lkv::launch_count(cp, nh, st); })) != hipSuccess)
     return fail_hip(ctx, e, "select_block: count kernel");
-  if (fused) {
+  if (acc_score) {
+    lkv::AccumParams acp;
+    acp.s_part = ctx->s_part;
+    acp.cnt = ctx->cnt;
+    acp.n_qgroups = n_qg;
+    acp.n_cnt_parts = lp.n_cnt_parts;
+    acp.n_kv_heads = c.n_kv_heads;
+    acp.s_t = s_t;
+    acp.inv_m = lp.inv_m;
+    acp.score = acc_score;
+    acp.count = acc_count;
+    acp.accumulate = accumulate;
+    if ((e = timed(ctx, LKV_KERN_SELECT, st, [&] { return lkv::launch_accumulate(acp, st); })) != hipSuccess)
+      return fail_hip(ctx, e, "score_block: accumulation kernel");
+  } else if (fused) {
     lkv::AppendParams ap = *fused;
     ap.keep = keep_idx;
     const int n_cu = ctx->n_cu;
@@ -423,6 +439,7 @@ int append_params(laserkv_ctx* ctx,
   ap.kb = {(const char*)k_blk, k_stride_head * es, k_stride_tok * es};
   ap.vb = {(const char*)v_blk, v_stride_head * es, v_stride_tok * es};
   ap.keep = nullptr;
+  ap.keep_stride_head = b_t;
   ap.b_t = b_t;
   ap.s_t = s_t;
   ap.row_bytes = d * es;
@@ -505,6 +522,79 @@ int laserkv_compress_block(laserkv_ctx* ctx,
   return select_impl(ctx, q_win, q_stride_head, q_stride_tok, k_blk, k_stride_head, k_stride_tok,
                      k_ctx, c_stride_head, c_stride_tok, hyperplanes, s_t, w, t_ctx, block_pos0, q_pos0, causal,
                      n_anchor, n_local, k_exact, k_lsh, keep_idx, nullptr, nullptr, nullptr, nullptr, &ap, hip_stream);
+}
+
+int laserkv_score_block(laserkv_ctx* ctx,
+                        const void* q_win, int64_t q_stride_head, int64_t q_stride_tok,
+                        const void* k_blk, int64_t k_stride_head, int64_t k_stride_tok,
+                        const void* k_ctx, int64_t c_stride_head, int64_t c_stride_tok,
+                        const void* hyperplanes,
+                        int32_t s_t, int32_t w, int32_t t_ctx,
+                        int64_t block_pos0, int64_t q_pos0, int32_t causal,
+                        float* score_acc, int32_t* count_acc, int32_t accumulate,
+                        void* hip_stream) {
+  if (!ctx) return fail(nullptr, LKV_EINVAL, "score_block: null context");
+  if (!score_acc || !count_acc) return fail(ctx, LKV_EINVAL, "score_block: null accumulator");
+  return select_impl(ctx, q_win, q_stride_head, q_stride_tok, k_blk, k_stride_head, k_stride_tok,
+                     k_ctx, c_stride_head, c_stride_tok, hyperplanes, s_t, w, t_ctx, block_pos0, q_pos0, causal,
+                     0, 0, 0, 0, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, hip_stream,
+                     score_acc, count_acc, accumulate ? 1 : 0);
+}
+
+int laserkv_select_consensus(laserkv_ctx* ctx, const float* score_acc, const int32_t* count_acc, int32_t s_t,
+                             int32_t n_anchor, int32_t n_local, int32_t k_exact, int32_t k_lsh,
+                             int32_t* keep_idx, void* hip_stream) {
+  if (!ctx) return fail(nullptr, LKV_EINVAL, "select_consensus: null context");
+  if (!score_acc || !count_acc || !keep_idx) return fail(ctx, LKV_EINVAL, "select_consensus: null tensor");
+  if (s_t < 1 || s_t > ctx->cfg.max_block) return fail(ctx, LKV_EINVAL, "select_consensus: s_t=%d outside 1..max_block=%d", s_t, ctx->cfg.max_block);
+  if (n_anchor < 0 || n_local < 0 || k_exact < 0 || k_lsh < 0) return fail(ctx, LKV_EINVAL, "select_consensus: negative budget");
+  if ((int64_t)n_anchor + n_local > s_t) return fail(ctx, LKV_EINVAL, "select_consensus: protected sets exceed the block");
+  if ((int64_t)k_exact + k_lsh > (int64_t)s_t - n_anchor - n_local)
+    return fail(ctx, LKV_EINVAL, "select_consensus: recall budget exceeds the candidate set");
+  lkv::SelectParams lp;
+  lp.s_part = score_acc;
+  lp.n_qgroups = 1;
+  lp.n_kv_heads = 1;
+  lp.inv_m = 1.0f;
+  lp.cnt = count_acc;
+  lp.n_cnt_parts = 1;
+  lp.cnt_out = nullptr;
+  lp.s_t = s_t;
+  lp.n_anchor = n_anchor;
+  lp.n_local = n_local;
+  lp.k_exact = k_exact;
+  lp.k_lsh = k_lsh;
+  lp.cnt_bits = 31;  // the kernel reads the largest count and uses only the digits it needs
+  lp.s_exact = nullptr;
+  lp.keep = keep_idx;
+  hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
+  hipError_t e = timed(ctx, LKV_KERN_SELECT, st, [&] { return lkv::launch_select(lp, st); });
+  if (e != hipSuccess) return fail_hip(ctx, e, "select_consensus: select kernel");
+  return LKV_OK;
+}
+
+int laserkv_append_shared(laserkv_ctx* ctx,
+                          const void* k_blk, int64_t k_stride_head, int64_t k_stride_tok,
+                          const void* v_blk, int64_t v_stride_head, int64_t v_stride_tok,
+                          const int32_t* keep_idx, int32_t b_t, int32_t s_t, int64_t block_pos0,
+                          void* k_cache, void* v_cache, int64_t cache_stride_head,
+                          int64_t* cache_pos, int64_t pos_stride_head,
+                          int64_t cache_len, int64_t cache_cap,
+                          void* hip_stream) {
+  if (!ctx) return fail(nullptr, LKV_EINVAL, "append_shared: null context");
+  if (!keep_idx) return fail(ctx, LKV_EINVAL, "append_shared: null tensor");
+  lkv::AppendParams ap;
+  const int rc = append_params(ctx, k_blk, k_stride_head, k_stride_tok, v_blk, v_stride_head, v_stride_tok, b_t, s_t,
+                               block_pos0, k_cache, v_cache, cache_stride_head, cache_pos, pos_stride_head, cache_len,
+                               cache_cap, ap);
+  if (rc != LKV_OK) return rc;
+  ap.keep = keep_idx;
+  ap.keep_stride_head = 0;  // one index list for every head
+  hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
+  const int nh = ctx->cfg.n_kv_heads;
+  hipError_t e = timed(ctx, LKV_KERN_APPEND, st, [&] { return lkv::launch_append(ap, nh, st); });
+  if (e != hipSuccess) return fail_hip(ctx, e, "append_shared: gather kernel");
+  return LKV_OK;
 }
 
 int laserkv_profile_isolate(laserkv_ctx* ctx, int32_t kernel_id) {

@@ -78,9 +78,21 @@ struct SelectParams {
   int32_t* keep;        // [H_kv, B_t]
 };
 
+// Adds one layer's scores and counts, summed over its KV heads, into [S] accumulators.
+struct AccumParams {
+  const float* s_part;  // [n_qgroups, H_kv, S]
+  const int32_t* cnt;   // [n_cnt_parts, H_kv, S]
+  int n_qgroups, n_cnt_parts, n_kv_heads, s_t;
+  float inv_m;          // 1 / (G * W)
+  float* score;         // [S]
+  int32_t* count;       // [S]
+  int accumulate;       // 0: overwrite, else add
+};
+
 struct AppendParams {
   RowSrc kb, vb;        // [H_kv, S, d]
-  const int32_t* keep;  // [H_kv, B_t]
+  const int32_t* keep;  // [H_kv, B_t], or [B_t] shared by all heads when keep_stride_head == 0
+  int keep_stride_head; // elements between two heads' index lists
   int b_t;
   int s_t;              // rows in the block: indices are clamped into it
   int row_bytes;        // d * elem size
@@ -99,6 +111,7 @@ hipError_t launch_count(const CountParams& p, int n_kv_heads, hipStream_t st);
 hipError_t launch_select(const SelectParams& p, hipStream_t st);
 hipError_t launch_select_append(const SelectParams& p, const AppendParams& ap, int n_cu, hipStream_t st);
 hipError_t launch_append(const AppendParams& p, int n_kv_heads, hipStream_t st);
+hipError_t launch_accumulate(const AccumParams& p, hipStream_t st);
 hipError_t init_kernel_attributes();
 size_t sweep_lds_bytes(int dtype, int head_dim, bool pass2, int range_keys, int q_tiles, int hist_lds_words);
 int sweep_rows_per_group();  // window rows one sweep workgroup covers

@@ -902,13 +902,34 @@ __global__ __launch_bounds__(256) void append_kernel(AppendParams p) {
   const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
   const int row = (int)(t / cpr), c = (int)(t % cpr);
   if (row >= p.b_t) return;
-  const int src = min(max(p.keep[(size_t)h * p.b_t + row], 0), p.s_t - 1);
+  const int src = min(max(p.keep[(size_t)h * p.keep_stride_head + row], 0), p.s_t - 1);
   const int64_t dst_off = (int64_t)h * p.cache_stride_head + (p.cache_len + row) * (int64_t)p.row_bytes + c * 16;
   const uint4 kv = ld16(p.kb.base + (int64_t)h * p.kb.stride_head + (int64_t)src * p.kb.stride_row + c * 16);
   const uint4 vv = ld16(p.vb.base + (int64_t)h * p.vb.stride_head + (int64_t)src * p.vb.stride_row + c * 16);
   *reinterpret_cast<uint4*>(p.k_cache + dst_off) = kv;
   *reinterpret_cast<uint4*>(p.v_cache + dst_off) = vv;
   if (c == 0) p.cache_pos[(int64_t)h * p.pos_stride_head + p.cache_len + row] = p.block_pos0 + src;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Global-consensus accumulation (Alg. 1 step 3 summed over layers and heads; likewise the counts of
+// step 6): one layer's pooled scores and counts, summed over its KV heads in head order, are written
+// to or added onto [S] accumulators.
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void accumulate_kernel(AccumParams p) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i >= p.s_t) return;
+  const size_t poff = (size_t)p.n_kv_heads * p.s_t;
+  float s = 0.0f;
+  int c = 0;
+  for (int h = 0; h < p.n_kv_heads; ++h) {
+    float sh = 0.0f;
+    for (int q = 0; q < p.n_qgroups; ++q) sh += p.s_part[q * poff + (size_t)h * p.s_t + i];
+    s += sh * p.inv_m;
+    for (int q = 0; q < p.n_cnt_parts; ++q) c += p.cnt[q * poff + (size_t)h * p.s_t + i];
+  }
+  p.score[i] = p.accumulate ? p.score[i] + s : s;
+  p.count[i] = p.accumulate ? p.count[i] + c : c;
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -991,6 +1012,11 @@ hipError_t launch_count(const CountParams& p, int n_kv_heads, hipStream_t st) {
 }
 
 int count_max_keys_per_range() { return COUNT_THREADS * COUNT_KEYS_PER_THREAD; }
+
+hipError_t launch_accumulate(const AccumParams& p, hipStream_t st) {
+  hipLaunchKernelGGL(accumulate_kernel, dim3((p.s_t + 255) / 256), dim3(256), 0, st, p);
+  return hipGetLastError();
+}
 
 template <bool FUSED>
 static hipError_t launch_select_t(const SelectParams& p, const AppendParams& ap, int split, hipStream_t st) {
