@@ -54,6 +54,10 @@ def main():
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MIB",
                     help="also run one plain device copy of this many MiB (a known-size reference for HBM byte counters)")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="lower bound of oracle work for cpu_baseline; 0 skips")
+    ap.add_argument("--policy", choices=["per-head", "consensus"], default="per-head",
+                    help="consensus: the global-consensus variant (scores summed over --layers layers and all heads, one "
+                         "selection per block); prints its own JSON line, not the headline metric")
+    ap.add_argument("--layers", type=int, default=4, help="layers summed by --policy consensus")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no collectives, no sharding); --gpus must be 1", file=sys.stderr)
@@ -65,6 +69,8 @@ def main():
 
     wl = synth.WORKLOADS[args.workload]
     dev = "cuda:0"
+    if args.policy == "consensus":
+        return bench_consensus(args, wl, dev)
     comp = LayerCompressor(wl, dev)
     t_gen = time.time()
     data = synth.make_layer(wl, args.layer, comp.parts[0])
@@ -193,6 +199,74 @@ def main():
                            entry="laserkv_select_block+laserkv_append" if args.unfused else "laserkv_compress_block"),
                roofline=roofline, cpu_baseline=cpu)
     print(json.dumps(out), flush=True)
+    return 0
+
+
+def bench_consensus(args, wl, dev):
+    """Global-consensus variant: per block, every layer is scored into shared accumulators, one selection
+    is made, and every layer appends the shared rows.  A step covers all blocks of --layers layers; the
+    rate is context tokens per second per layer (step time divided by the layer count)."""
+    import torch
+    from paper_2602_02199_amd import binding, synth
+    B = binding.laserkv_budget(wl.s_block, wl.l_ctx, wl.r_num, wl.r_den)
+    na, nl, ke, kl = binding.laserkv_partition(B, wl.n_div, wl.alpha, wl.s_block)
+    b_t, s, nb, nl_layers = na + nl + ke + kl, wl.s_block, wl.n_blocks, args.layers
+    lib = binding.LaserKV(wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.dtype, wl.lsh_tables, wl.lsh_bits,
+                          max_block=s, max_window=wl.window, max_ctx_keys=nl)
+    data = []
+    for layer in range(nl_layers):
+        d = synth.make_layer(wl, layer, na)
+        data.append({k: v.to(dev) for k, v in d.items() if k != "needles"})
+    cap = nb * b_t
+    caches = [dict(k=torch.zeros(wl.n_kv_heads, cap, wl.head_dim, dtype=wl.torch_dtype, device=dev),
+                   v=torch.zeros(wl.n_kv_heads, cap, wl.head_dim, dtype=wl.torch_dtype, device=dev),
+                   pos=torch.full((wl.n_kv_heads, cap), -1, dtype=torch.int64, device=dev)) for _ in range(nl_layers)]
+    score = torch.empty(s, dtype=torch.float32, device=dev)
+    count = torch.empty(s, dtype=torch.int32, device=dev)
+    keep = torch.empty(b_t, dtype=torch.int32, device=dev)
+
+    def step():
+        cache_len = 0
+        for t in range(nb):
+            lo = t * s
+            n_ctx = nl if t else 0
+            for li in range(nl_layers):
+                k_ctx = caches[li]["k"][:, cache_len - n_ctx:cache_len] if n_ctx else None
+                lib.laserkv_score_block(data[li]["q_win"][t], data[li]["k"][:, lo:lo + s], k_ctx, data[li]["planes"],
+                                        block_pos0=lo, score_acc=score, count_acc=count, accumulate=li > 0)
+            lib.laserkv_select_consensus(score, count, s_t=s, n_anchor=na, n_local=nl, k_exact=ke, k_lsh=kl, keep_idx=keep)
+            for li in range(nl_layers):
+                lib.laserkv_append_shared(data[li]["k"][:, lo:lo + s], data[li]["v"][:, lo:lo + s], keep, b_t=b_t,
+                                          block_pos0=lo, k_cache=caches[li]["k"], v_cache=caches[li]["v"],
+                                          cache_pos=caches[li]["pos"], cache_len=cache_len)
+            cache_len += b_t
+
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        for _ in range(max(args.warmup, 1)):
+            step()
+        stream.synchronize()
+        graph = None
+        if args.mode == "graph":
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph, stream=stream):
+                step()
+            graph.replay()
+            stream.synchronize()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            graph.replay() if graph is not None else step()
+        stream.synchronize()
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    print(json.dumps(dict(metric="global-consensus variant: context tokens/s/layer (score over all layers and heads, one "
+                                 "selection per block, shared append)",
+                          value=round(wl.l_ctx / (ms * 1e-3 / nl_layers), 1), unit="tokens/s/layer", n_gpus=1,
+                          steps=args.steps, warmup=args.warmup, ms_per_step=round(ms, 4), higher_is_better=True,
+                          dtype=wl.dtype, data="synthetic",
+                          config=dict(workload=wl.name, layers=nl_layers, blocks=nb, budget_per_block=B, launch=args.mode))),
+          flush=True)
     return 0
 
 
