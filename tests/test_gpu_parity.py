@@ -129,6 +129,18 @@ def test_llama16k_bf16_all_blocks():
          window=40, n_div=4, lsh_tables=31, lsh_bits=16),
     dict(name="one-table-one-bit", n_q_heads=2, n_kv_heads=2, head_dim=64, dtype="f32", l_ctx=130, s_block=65,
          window=3, n_div=2, lsh_tables=1, lsh_bits=1),
+    # the longest block a context accepts (16384 keys: 16 positions per select thread)
+    dict(name="max-block", n_q_heads=1, n_kv_heads=1, head_dim=64, dtype="bf16", l_ctx=16384, s_block=16384,
+         window=8, n_div=8, lsh_tables=2, lsh_bits=5),
+    # the most window rows a head may have (G*W = 1024: four query-row groups)
+    dict(name="max-rows", n_q_heads=16, n_kv_heads=1, head_dim=64, dtype="f32", l_ctx=640, s_block=320,
+         window=64, n_div=4, lsh_tables=2, lsh_bits=6),
+    # protection divisor larger than the budget: no anchors, no local window, no look-back keys
+    dict(name="no-protected", n_q_heads=2, n_kv_heads=1, head_dim=64, dtype="f32", l_ctx=128, s_block=64,
+         window=4, n_div=32, lsh_tables=2, lsh_bits=3),
+    # one window query, one head, blocks shorter than a tile
+    dict(name="one-query", n_q_heads=1, n_kv_heads=1, head_dim=128, dtype="bf16", l_ctx=57, s_block=19,
+         window=1, n_div=2, lsh_tables=2, lsh_bits=2),
     # 768 window rows = three query-row groups, with the histogram path (K <= 12)
     dict(name="three-row-groups", n_q_heads=12, n_kv_heads=1, head_dim=128, dtype="bf16", l_ctx=1800, s_block=900,
          window=64, n_div=4, lsh_tables=6, lsh_bits=9),
