@@ -190,11 +190,13 @@ int laserkv_append_shared(laserkv_ctx* ctx,
  * LKV_N_KERNELS entries.  At most LKV_PROFILE_MAX_LAUNCHES launches are recorded per bracket;
  * later ones run untimed.  Errors: LKV_EINVAL (null / not begun), LKV_EHIP. */
 typedef enum {
-  LKV_KERN_SWEEP1 = 0, /* exact score sweep 1 (row maxima and sums) + SimHash codes of keys and queries */
-  LKV_KERN_SWEEP2 = 1, /* exact score sweep 2: pooled probabilities */
-  LKV_KERN_COUNT = 2,  /* collision counts */
-  LKV_KERN_SELECT = 3, /* two-stage TopK and compaction */
-  LKV_KERN_APPEND = 4, /* gather-append */
+  LKV_KERN_SWEEP1 = 0, /* exact score sweep 1 (row maxima and sums) + SimHash codes of keys and window queries
+                          + histograms of the query codes */
+  LKV_KERN_SWEEP2 = 1, /* exact score sweep 2 (pooled probabilities) + collision counts by histogram lookup */
+  LKV_KERN_COUNT = 2,  /* collision counts as a kernel of their own (codes wider than 12 bits) */
+  LKV_KERN_SELECT = 3, /* two-stage TopK and compaction (with the gather in laserkv_compress_block); also the
+                          accumulation kernel of laserkv_score_block */
+  LKV_KERN_APPEND = 4, /* gather-append as a kernel of its own */
   LKV_N_KERNELS = 5
 } laserkv_kernel_id;
 #define LKV_PROFILE_MAX_LAUNCHES 8192
