@@ -30,11 +30,13 @@ namespace lkv {
 //
 //   sweep 1 (PASS2 = false): waves 0-7 compute, per window row, partial softmax statistics over the
 //            range (Alg. 1 step 3, normaliser); waves 8-15 compute the SimHash sign bits of the
-//            range's keys and of this workgroup's share of the window queries (Sec. 3.3 "Recall")
-//            from the SAME LDS rows, so the block's keys are read from HBM once for both
-//            contractions and the two roles overlap on every SIMD.
+//            range's keys (Sec. 3.3 "Recall") from the SAME LDS rows, so the block's keys are read
+//            from HBM once for both contractions and the two roles overlap on every SIMD.  Waves 0-7
+//            then hash their own window rows (already in registers) for the few tables this workgroup
+//            owns and histogram the codes in LDS; the histograms leave as plain stores.
 //   sweep 2 (PASS2 = true):  pooled softmax probability of every key of the range (Alg. 1 step 3);
-//            wave = (row tile, half of the range).
+//            wave = (row tile, half of the range).  Before that loop: collision counts of the range's
+//            keys by lookup in the histograms (Alg. 1 step 6).
 //
 // The whole range (<= SCORE_MAX_RANGE keys) is fetched into LDS up front: a range is microseconds
 // of work, so what matters is having all of its loads in flight at once.  After one barrier each
@@ -43,11 +45,12 @@ namespace lkv {
 // 16-byte chunk: conflict-free reads at base + immediate addresses).  Four waves share a SIMD
 // (<= 128 registers per lane): one wave alone issues a vector instruction only every ~10 clocks.
 //
-// Sweep 1 keeps, per window row, sum_i 2^(x_i - ref) against a reference ref shared by the 32 lanes
-// that hold the row: the row maximum of the range's first tile.  The common case costs one fma, one
-// exp and one add per logit; a range whose later logits exceed that reference by more than 2^7
-// overflows the sum, which is detected after the loop and redone with a running-maximum reference.
-// Sweep 2 needs one fma, one exp and one add per logit.
+// Sweep 1 multiplies keys (A) by window rows (B), so a lane owns one window row and keeps its
+// sum_i 2^(x_i - ref) privately, ref being the lane's maximum over the range's first tile.  The common
+// case costs one fma, one exp and one add per logit; a range whose later logits exceed that reference
+// by more than 2^7 overflows the sum, which is detected after the loop and redone with a
+// running-maximum reference.  Sweep 2 multiplies window rows (A) by keys (B), so a lane owns one key
+// and its pooled probability is an in-lane sum: one fma, one exp and one add per logit.
 //
 // Hashing: lane = vector, accumulator register = plane, with the planes fed in an order that makes
 // a lane's 16 registers 16 consecutive planes: one v_alignbit per register shifts its sign bit into
@@ -295,7 +298,7 @@ __global__ __launch_bounds__(PASS_WAVES * 64) void pass_kernel(PassParams p) {
 
   if (PASS2 && p.qhist && !in_ctx) {
     // collision counts (Alg. 1 step 6) of this range's keys over this workgroup's share of the
-    // tables: four lanes per key, each eight tables at a time from the L2-resident query histograms
+    // tables: up to four lanes per key, each eight tables at a time from the L2-resident query histograms
     const int tab0c = qg * p.tables_per_split;
     const int n_tabc = max(0, min(p.tables_per_split, p.n_tables - tab0c));
     // lanes per key: as many groups of eight tables as there are, at most four, and one pass over the keys
@@ -582,9 +585,10 @@ __global__ __launch_bounds__(PASS_WAVES * 64) void pass_kernel(PassParams p) {
 }
 
 // ---------------------------------------------------------------------------------------------
-// Collision counts.  Workgroup = (key range, table group, KV head).  The G*W query codes of each
-// table in the group are histogrammed into LDS (two 16-bit bins per word); each key then looks
-// its own code up per table.  Partial sums over table groups meet in integer atomics.
+// Collision counts as a kernel of their own (codes too wide for resident histograms).  Workgroup =
+// (key range, set of table groups, KV head).  The G*W query codes of each table of a group are
+// histogrammed into LDS (two 16-bit bins per word); each key then looks its own code up per table.
+// Partial sums over the workgroups of a key meet in integer atomics.
 // ---------------------------------------------------------------------------------------------
 constexpr int COUNT_THREADS = 1024;
 constexpr int COUNT_KEYS_PER_THREAD = 8;  // keys_per_range <= COUNT_THREADS * COUNT_KEYS_PER_THREAD
