@@ -85,13 +85,17 @@ def partition(B: int, n: int, alpha: float, s_t: int):
 # --------------------------------------------------------------------------
 # a1  exact score (Sec. 3.3 "Precision"; Alg. 1 step 3, one layer / KV head)
 # --------------------------------------------------------------------------
-def exact_scores(q_win, k_blk, k_ctx=None, block_pos0=0, q_pos0=None, causal=True):
+def exact_scores(q_win, k_blk, k_ctx=None, block_pos0=0, q_pos0=None, causal=True, row_lse=None):
     """S_exact[h, i] for every block key i of every KV head h.
 
     q_win [H_q, W, d]  window queries, query head h*G+g belongs to KV head h
     k_blk [H_kv, S_t, d] block keys, key i sits at position block_pos0 + i
     k_ctx [H_kv, T, d] or None: look-back keys, always visible, normaliser only
     q_pos0: position of window query 0 (default: window = last W block tokens)
+    row_lse [H_q, W] or None: natural-log sum over keys OUTSIDE this call of exp(q . k / sqrt(d)) for
+        every window query (what an attention kernel over the rest of the cache reports); those keys
+        join the normaliser exactly as look-back keys do (Sec. 3.2 boundary smoothing, extended to
+        context that is not re-read).
 
     Row (g, j): logits l = q . k / sqrt(d) over the T + S_t keys, block key i
     masked when causal and block_pos0 + i > q_pos0 + j, p = softmax(l);
@@ -123,7 +127,11 @@ def exact_scores(q_win, k_blk, k_ctx=None, block_pos0=0, q_pos0=None, causal=Tru
             logits = np.where(vis, logits, -np.inf)
             row_max = logits.max(axis=1, keepdims=True)
             e = np.exp(logits - row_max)
-            p = e / e.sum(axis=1, keepdims=True)
+            denom = e.sum(axis=1, keepdims=True)
+            if row_lse is not None:
+                ext = np.asarray(row_lse, dtype=np.float64)[h * g_sz + g][:, None]
+                denom = denom + np.exp(ext - row_max)
+            p = e / denom
             out[h] += p[:, t_ctx:].sum(axis=0)
     return out / np.float64(g_sz * w)
 
@@ -237,12 +245,12 @@ def append(cache_k, cache_v, cache_pos, cache_len: int, k_blk, v_blk, keep, bloc
 # --------------------------------------------------------------------------
 def select_block(q_win, k_blk, k_ctx, planes, n_tables, n_bits,
                  n_anchor, n_local, k_exact, k_lsh,
-                 block_pos0=0, q_pos0=None, causal=True):
+                 block_pos0=0, q_pos0=None, causal=True, row_lse=None):
     """Steps a1-a4 for all KV heads of one block.  Returns a dict of every stage."""
     h_q = np.asarray(q_win).shape[0]
     h_kv = np.asarray(k_blk).shape[0]
     g_sz = h_q // h_kv
-    s_ex = exact_scores(q_win, k_blk, k_ctx, block_pos0, q_pos0, causal)
+    s_ex = exact_scores(q_win, k_blk, k_ctx, block_pos0, q_pos0, causal, row_lse)
     sig_k, uns_k = simhash(k_blk, planes, n_tables, n_bits)
     sig_q, uns_q = simhash(q_win, planes, n_tables, n_bits)
     cnt = collision_counts(sig_q, sig_k, g_sz)

@@ -102,3 +102,28 @@ def test_large_logits_are_stable():
     k = _rand((1, 12, 8), 15) * 300
     s = O.exact_scores(q, k, None, causal=False)
     assert np.isfinite(s).all() and abs(s.sum() - 1) < 1e-12
+
+
+def test_row_lse_equals_extra_context_keys():
+    """Keys summarised by their log-sum-exp must weigh in exactly as if they had been passed as
+    look-back keys (which enter the normaliser only)."""
+    from scipy.special import logsumexp
+    rng = np.random.default_rng(77)
+    h_q, h_kv, w, s_t, d, t_in, t_out = 4, 2, 5, 40, 16, 6, 23
+    q = rng.standard_normal((h_q, w, d)) * 1.5
+    k = rng.standard_normal((h_kv, s_t, d))
+    ctx_in = rng.standard_normal((h_kv, t_in, d))
+    ctx_out = rng.standard_normal((h_kv, t_out, d)) * 2.0
+    g = h_q // h_kv
+    row_lse = np.stack([logsumexp(q[hq] @ ctx_out[hq // g].T / np.sqrt(d), axis=1) for hq in range(h_q)])
+    a = O.exact_scores(q, k, ctx_in, block_pos0=100, causal=True, row_lse=row_lse)
+    b = O.exact_scores(q, k, np.concatenate([ctx_out, ctx_in], axis=1), block_pos0=100, causal=True)
+    assert np.allclose(a, b, rtol=1e-12, atol=0)
+    # and without look-back keys of its own
+    a = O.exact_scores(q, k, None, block_pos0=0, causal=False, row_lse=row_lse)
+    b = O.exact_scores(q, k, ctx_out, block_pos0=0, causal=False)
+    assert np.allclose(a, b, rtol=1e-12, atol=0)
+    # a vanishing outside mass changes nothing; a dominating one takes (almost) all of the probability
+    base = O.exact_scores(q, k, None, block_pos0=0)
+    assert np.allclose(O.exact_scores(q, k, None, block_pos0=0, row_lse=np.full((h_q, w), -1e4)), base, rtol=1e-13, atol=0)
+    assert O.exact_scores(q, k, None, block_pos0=0, row_lse=np.full((h_q, w), 60.0)).sum() < 1e-10
