@@ -146,6 +146,17 @@ int laserkv_compress_block(laserkv_ctx* ctx,
                            int64_t cache_len, int64_t cache_cap,
                            void* hip_stream);
 
+/* Boundary smoothing (Sec. 3.2) extended to context that is not re-read: keys outside a call (the rest
+ * of the compressed cache, say) can join the softmax normaliser of Alg. 1 step 3 through one number per
+ * window query, the natural-log sum of exp(q.k / sqrt(d)) over those keys, as an attention kernel
+ * reports it.  They weigh in exactly as if they had been passed as look-back keys.
+ *   row_lse  DEVICE [H_q, w] float, contiguous; NULL switches the feature off (the default).
+ * The pointer is remembered by the context and read by the kernels of EVERY following
+ * laserkv_select_block / laserkv_compress_block / laserkv_score_block call until it is replaced or reset;
+ * it must stay valid until those calls' kernels have run.  Errors: LKV_EINVAL (null context, pointer
+ * not 4-byte aligned). */
+int laserkv_set_row_lse(laserkv_ctx* ctx, const float* row_lse);
+
 /* Global-consensus variant: Alg. 1 step 3 taken literally, with the exact score summed "across all
  * layers and heads" (Sec. 3.3 "Precision") and, likewise, the collision counts of step 6, followed by
  * ONE two-stage TopK (steps 4-8) whose kept set serves every layer and head.  Three calls:

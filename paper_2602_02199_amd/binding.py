@@ -20,7 +20,7 @@ EXPORTS = (
     "laserkv_create", "laserkv_destroy", "laserkv_last_error", "laserkv_budget",
     "laserkv_partition", "laserkv_select_block", "laserkv_append", "laserkv_compress_block",
     "laserkv_profile_begin", "laserkv_profile_end", "laserkv_profile_isolate",
-    "laserkv_score_block", "laserkv_select_consensus", "laserkv_append_shared",
+    "laserkv_score_block", "laserkv_select_consensus", "laserkv_append_shared", "laserkv_set_row_lse",
 )
 KERNEL_NAMES = ("sweep1", "sweep2", "count", "select", "append")
 
@@ -83,6 +83,8 @@ def load():
     lib.laserkv_select_consensus.restype = C.c_int
     lib.laserkv_append_shared.argtypes = lib.laserkv_append.argtypes
     lib.laserkv_append_shared.restype = C.c_int
+    lib.laserkv_set_row_lse.argtypes = [vp, vp]
+    lib.laserkv_set_row_lse.restype = C.c_int
     lib.laserkv_profile_begin.argtypes = [vp]
     lib.laserkv_profile_begin.restype = C.c_int
     lib.laserkv_profile_end.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(i64)]
@@ -238,6 +240,14 @@ class LaserKV:
             block_pos0, _ptr(k_cache), _ptr(v_cache), k_cache.stride(0), _ptr(cache_pos), cache_pos.stride(0),
             cache_len, k_cache.shape[1], self._stream(stream))
         self._check(rc)
+
+    def laserkv_set_row_lse(self, row_lse):
+        """row_lse: contiguous float32 [H_q, w] device tensor, or None to switch the feature off.  The tensor
+        is kept alive by this object for as long as it is set."""
+        if row_lse is not None:
+            assert row_lse.is_contiguous() and row_lse.dtype == self._torch.float32
+        self._row_lse = row_lse
+        self._check(self._lib.laserkv_set_row_lse(self._ctx, _ptr(row_lse)))
 
     def laserkv_profile_begin(self):
         self._check(self._lib.laserkv_profile_begin(self._ctx))

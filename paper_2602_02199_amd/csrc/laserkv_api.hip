@@ -39,6 +39,7 @@ struct laserkv_ctx {
   uint16_t* sig_k;   // [H_kv, max_block, L]
   uint16_t* sig_q;   // [H_q, max_window, L]
   int m_pad;
+  const float* row_lse;  // laserkv_set_row_lse: applies to every following scoring call until reset
   int only_kernel;   // >= 0: launch only this kernel kind (laserkv_profile_isolate); -1 normally
   char error[512];
   // per-kernel event timing (benchmarks only)
@@ -316,6 +317,7 @@ int select_impl(laserkv_ctx* ctx,
   sp.m_pad = ctx->m_pad;
   sp.r_pad = (sp.n_ranges + 7) & ~7;
   sp.s_part = ctx->s_part;
+  sp.row_lse = ctx->row_lse;
   sp.n_tables = c.lsh_tables;
   sp.n_bits = c.lsh_bits;
   sp.n_planes = c.lsh_tables * c.lsh_bits;
@@ -522,6 +524,13 @@ int laserkv_compress_block(laserkv_ctx* ctx,
   return select_impl(ctx, q_win, q_stride_head, q_stride_tok, k_blk, k_stride_head, k_stride_tok,
                      k_ctx, c_stride_head, c_stride_tok, hyperplanes, s_t, w, t_ctx, block_pos0, q_pos0, causal,
                      n_anchor, n_local, k_exact, k_lsh, keep_idx, nullptr, nullptr, nullptr, nullptr, &ap, hip_stream);
+}
+
+int laserkv_set_row_lse(laserkv_ctx* ctx, const float* row_lse) {
+  if (!ctx) return fail(nullptr, LKV_EINVAL, "set_row_lse: null context");
+  if (row_lse && (reinterpret_cast<uintptr_t>(row_lse) & 3)) return fail(ctx, LKV_EINVAL, "set_row_lse: misaligned pointer");
+  ctx->row_lse = row_lse;
+  return LKV_OK;
 }
 
 int laserkv_score_block(laserkv_ctx* ctx,

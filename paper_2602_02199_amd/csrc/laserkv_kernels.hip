@@ -285,6 +285,10 @@ __global__ __launch_bounds__(PASS_WAVES * 64) void pass_kernel(PassParams p) {
       const float2 v = pr_ptr[e];
       if (pr_beg + e < p.n_ranges) lse_merge(mm, ss, v.x, v.y);
     }
+    // keys outside this call, summarised by the caller as one log-sum-exp per window row, join the
+    // normaliser like one more partial (natural log -> exp2 domain)
+    if (p.row_lse && (tid & 3) == 0 && qg * MQ + (tid >> 2) < p.m_rows)
+      lse_merge(mm, ss, p.row_lse[(size_t)h * p.m_rows + qg * MQ + (tid >> 2)] * 1.4426950408889634f, 1.0f);
 #pragma unroll
     for (int off = 1; off < 4; off <<= 1) {
       const float m2 = __shfl_xor(mm, off), s2 = __shfl_xor(ss, off);

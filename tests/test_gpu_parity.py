@@ -334,3 +334,39 @@ def test_separate_count_kernel_path(monkeypatch):
     run_and_check(wl, label="count-kernel-16x10")
     wl = synth.shrink(synth.WORKLOADS["tiny"], index=12, l_ctx=1024, lsh_tables=3, lsh_bits=16)
     run_and_check(wl, label="count-kernel-3x16")
+
+
+@pytest.mark.parametrize("name,kw", [("tiny", dict(l_ctx=1024)), ("llama8b-16k", dict(l_ctx=2048))])
+def test_row_lse_of_outside_keys(name, kw):
+    """laserkv_set_row_lse: keys outside the call, summarised as one log-sum-exp per window query, join the
+    normaliser; switching it off again restores the plain result."""
+    wl = synth.shrink(synth.WORKLOADS[name], index=13, **kw)
+    B = O.budget(wl.s_block, wl.l_ctx, wl.r_num, wl.r_den)
+    parts = O.partition(B, wl.n_div, wl.alpha, wl.s_block)
+    data = synth.make_layer(wl, 0, parts[0], n_blocks=1)
+    dev = to_dev(data)
+    s, d, g = wl.s_block, wl.head_dim, wl.group
+    gen = torch.Generator().manual_seed(5)
+    k_out = torch.randn(wl.n_kv_heads, 300, d, generator=gen, dtype=torch.float64) * 3.0
+    q64 = data["q_win"][0].to(torch.float64)
+    row_lse = torch.stack([torch.logsumexp(q64[hq] @ k_out[hq // g].T / d ** 0.5, dim=1) for hq in range(wl.n_q_heads)])
+    row_lse = row_lse.to(torch.float32).contiguous()            # both sides use these rounded values
+    lib = binding.LaserKV(wl.n_q_heads, wl.n_kv_heads, d, wl.dtype, wl.lsh_tables, wl.lsh_bits,
+                          max_block=s, max_window=wl.window, max_ctx_keys=0)
+    outs = {}
+    for tag, lse in (("with", row_lse.to(DEV)), ("without", None)):
+        lib.laserkv_set_row_lse(lse)
+        dbg = dbg_buffers(wl, s)
+        keep = torch.empty(wl.n_kv_heads, sum(parts), dtype=torch.int32, device=DEV)
+        lib.laserkv_select_block(dev["q_win"][0], dev["k"][:, :s], None, dev["planes"], block_pos0=0,
+                                 n_anchor=parts[0], n_local=parts[1], k_exact=parts[2], k_lsh=parts[3], keep_idx=keep,
+                                 dbg_s_exact=dbg["s_exact"], dbg_sig_k=dbg["sig_k"], dbg_sig_q=dbg["sig_q"], dbg_count=dbg["cnt"])
+        torch.cuda.synchronize()
+        outs[tag] = gpu_stage(dbg, keep)
+    for tag, lse in (("with", row_lse.to(torch.float64).numpy()), ("without", None)):
+        st = O.select_block(f64(data["q_win"][0]), f64(data["k"][:, :s]), None, f64(data["planes"]), wl.lsh_tables,
+                            wl.lsh_bits, *parts, block_pos0=0, row_lse=lse)
+        rep = check_block(st, outs[tag], parts, wl.dtype)
+        say(f"[row-lse {wl.name} {tag}] max score err/(s+s_k) {rep['max_rel']:.2e}, tolerated {rep['tolerated']}")
+    # the outside keys take a share of the probability mass
+    assert outs["with"]["s_exact"].sum() < 0.99 * outs["without"]["s_exact"].sum()
