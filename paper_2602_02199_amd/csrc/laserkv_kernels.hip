@@ -182,6 +182,22 @@ __global__ __launch_bounds__(PASS_WAVES * 64) void pass_kernel(PassParams p) {
 #pragma unroll
     for (int u = 0; u < 4; ++u) pv[u] = ld16(pr_ptr + min(2 * u, pr_per - 2));
   }
+  // Sweep 2, collision counts (Alg. 1 step 6) of this range's keys over this workgroup's share of the
+  // tables: 1, 2 or 4 lanes per key, eight tables per lane and step.  In the common shape (two row
+  // groups, one step per lane, aligned codes) the job rides along with the main loop: the key's eight
+  // codes are fetched here with the other loads, each loop iteration issues the histogram lookups of
+  // two tables and adds up those of the iteration before, so their latency costs nothing.
+  const int tab0c = qg * p.tables_per_split;
+  const int n_tabc = PASS2 && p.qhist && !in_ctx ? max(0, min(p.tables_per_split, p.n_tables - tab0c)) : 0;
+  int lpk_log = n_tabc > 16 ? 2 : (n_tabc > 8 ? 1 : 0);
+  while (lpk_log > 0 && (n_keys_wg << lpk_log) > NTHR) --lpk_log;
+  const bool cnt_piped = n_tabc > 0 && n_tabc == (8 << lpk_log) && (p.n_tables & 7) == 0 && (tab0c & 7) == 0 &&
+                         (n_keys_wg << lpk_log) <= NTHR && n_qg == 2;
+  const bool cnt_lane = cnt_piped && tid < (n_keys_wg << lpk_log);
+  const int cnt_key = tid >> lpk_log, cnt_tb = (tid & ((1 << lpk_log) - 1)) * 8;
+  uint4 cnt_codes = make_uint4(0u, 0u, 0u, 0u);  // two 16-bit codes per word, consumed from .x upwards
+  if (cnt_lane) cnt_codes = ld16(p.sig_k + ((size_t)h * p.s_t + seg_row0 + cnt_key) * p.n_tables + tab0c + cnt_tb);
+
   uint4 a[NCH];  // A operand: this wave's 32 window rows, or (hashing waves) its first 32 planes
   if (STAGE_A) {
     uint4 qpre[QL], ppre[QL], kpre[KL];
@@ -300,14 +316,9 @@ __global__ __launch_bounds__(PASS_WAVES * 64) void pass_kernel(PassParams p) {
   __syncthreads();
   LKV_TS(1);
 
-  if (PASS2 && p.qhist && !in_ctx) {
-    // collision counts (Alg. 1 step 6) of this range's keys over this workgroup's share of the
-    // tables: up to four lanes per key, each eight tables at a time from the L2-resident query histograms
-    const int tab0c = qg * p.tables_per_split;
-    const int n_tabc = max(0, min(p.tables_per_split, p.n_tables - tab0c));
-    // lanes per key: as many groups of eight tables as there are, at most four, and one pass over the keys
-    int lpk_log = n_tabc > 16 ? 2 : (n_tabc > 8 ? 1 : 0);
-    while (lpk_log > 0 && (n_keys_wg << lpk_log) > NTHR) --lpk_log;
+  if (PASS2 && n_tabc > 0 && !cnt_piped) {
+    // the general shape: the whole job before the main loop, eight tables at a time from the L2-resident
+    // query histograms
     const int lpk = 1 << lpk_log;
     for (int kq = tid; kq < (n_keys_wg << lpk_log); kq += NTHR) {
       const int key = kq >> lpk_log, sub = kq & (lpk - 1);
@@ -371,10 +382,35 @@ __global__ __launch_bounds__(PASS_WAVES * 64) void pass_kernel(PassParams p) {
     const int t_half = (n_tiles + 1) >> 1;  // this wave's half of the tiles
     const int nt_beg = (wave >> 3) * t_half;
     const int nt_end = min(n_tiles, nt_beg + t_half);
+    // pipelined count job: step s looks up tables cnt_tb + 2s and + 2s + 1 (both row groups' bins in one
+    // 8-byte word pair) and adds up the pair fetched by step s - 1
+    const uint32_t* cnt_hist =
+        cnt_piped ? p.qhist + ((size_t)h * p.n_tables + tab0c + cnt_tb) * ((size_t)(1 << p.n_bits) >> 1) * 2 : nullptr;
+    const uint32_t cnt_hw2 = (uint32_t)(1 << p.n_bits);  // words per table: 2^K / 2 bins x 2 row groups
+    uint2 cnt_pa = make_uint2(0u, 0u), cnt_pb = make_uint2(0u, 0u);
+    uint32_t cnt_psh = 0u;  // shifts (0 / 16) of the pending pair, packed
+    int cnt_sum = 0, cnt_step = 0;
+    auto cnt_advance = [&]() {
+      // add up the pending pair (zeros before the first step) ...
+      cnt_sum += (int)(((cnt_pa.x >> (cnt_psh & 31u)) & 0xffffu) + ((cnt_pa.y >> (cnt_psh & 31u)) & 0xffffu) +
+                       ((cnt_pb.x >> (cnt_psh >> 8)) & 0xffffu) + ((cnt_pb.y >> (cnt_psh >> 8)) & 0xffffu));
+      cnt_pa = make_uint2(0u, 0u);
+      cnt_pb = make_uint2(0u, 0u);
+      // ... and issue the next one
+      if (cnt_lane && cnt_step < 4) {
+        const uint32_t c0 = cnt_codes.x & 0xffffu, c1 = cnt_codes.x >> 16;
+        cnt_pa = *reinterpret_cast<const uint2*>(cnt_hist + (size_t)(2 * cnt_step) * cnt_hw2 + (c0 >> 1) * 2);
+        cnt_pb = *reinterpret_cast<const uint2*>(cnt_hist + (size_t)(2 * cnt_step + 1) * cnt_hw2 + (c1 >> 1) * 2);
+        cnt_psh = ((c0 & 1u) * 16u) | (((c1 & 1u) * 16u) << 8);
+        cnt_codes = make_uint4(cnt_codes.y, cnt_codes.z, cnt_codes.w, 0u);
+      }
+      ++cnt_step;
+    };
     // rolled on purpose (microsecond kernels start from a cold instruction cache)
 #pragma unroll 1
     for (int nt = nt_beg; nt < nt_end; ++nt) {
       const int kbase = k0 + nt * 32;
+      if (cnt_piped) cnt_advance();
       f32x16 acc;
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
@@ -397,6 +433,13 @@ __global__ __launch_bounds__(PASS_WAVES * 64) void pass_kernel(PassParams p) {
       }
       col += __shfl_xor(col, 32);
       if (kg == 0) sCol[rt * nkr + nt * 32 + rl] = col;
+    }
+    if (cnt_piped) {
+      while (cnt_step < 5) cnt_advance();  // steps the loop was too short for, and the last pending pair
+      if (lpk_log > 0) cnt_sum += __shfl_xor(cnt_sum, 1);
+      if (lpk_log > 1) cnt_sum += __shfl_xor(cnt_sum, 2);
+      if (cnt_lane && (tid & ((1 << lpk_log) - 1)) == 0)
+        p.cnt[((size_t)qg * p.n_kv_heads + h) * p.s_t + seg_row0 + cnt_key] = cnt_sum;
     }
   } else if (!hash_wave) {
     // Sweep 1 multiplies the other way round (keys as the A operand, window rows as B): lane = window
