@@ -304,7 +304,9 @@ int select_impl(laserkv_ctx* ctx,
     sp.q_tiles = (sp.q_tab_per_wg + sp.q_tab_per_tile - 1) / sp.q_tab_per_tile;
     const size_t hist_words = ((size_t)sp.q_tab_per_wg << c.lsh_bits) / 2;
     sp.hist_lds_words = (ctx->qhist && hist_words * 4 <= 32 * 1024) ? (int)(hist_words ? hist_words : 1) : 0;
-    if (nk <= 32 || lkv::sweep_lds_bytes(c.dtype, d, false, nk, sp.q_tiles, sp.hist_lds_words) <= 150 * 1024) break;
+    if (nk <= 32 || (lkv::sweep_lds_bytes(c.dtype, d, false, nk, sp.q_tiles, sp.hist_lds_words) <= 150 * 1024 &&
+                     lkv::sweep_lds_bytes(c.dtype, d, true, nk, 0, 0) <= 160 * 1024))
+      break;
     nk -= 32;
   }
   if (sp.n_ranges > ctx->max_ranges) return fail(ctx, LKV_EINVAL, "select_block: internal range split too fine");

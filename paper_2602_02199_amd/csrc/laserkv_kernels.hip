@@ -135,6 +135,7 @@ __global__ __launch_bounds__(PASS_WAVES * 64) void pass_kernel(PassParams p) {
   uint32_t* sBits = reinterpret_cast<uint32_t*>(after_rows);           // sweep 1: [nkr][BITS_PITCH]
   uint4* sQP = after_rows + (nkr * BITS_PITCH + 3) / 4;                // sweep 1: [q_tiles * 32][CHP] planes of the query job
   uint32_t* sHist = reinterpret_cast<uint32_t*>(sQP + (size_t)p.q_tiles * 32 * CHP);  // sweep 1: [hist_lds_words]
+  uint4* sQst = after_rows + 2 * nkr;                                  // sweep 2: [256][CHP] query panel (past sCol)
   // row limits and lse sit past both the steady-state arrays and the A-operand staging area
   int* sLim = reinterpret_cast<int*>(reinterpret_cast<char*>(smem) + p.lds_tail_offset);  // [MQ]
   float* sLse = reinterpret_cast<float*>(sLim + MQ);                   // [MQ]
@@ -224,21 +225,32 @@ __global__ __launch_bounds__(PASS_WAVES * 64) void pass_kernel(PassParams p) {
       if (q < n_chunks) kpre[u] = key_chunk(q);
     }
     LKV_TS(5);
-    // staging area: rows [0, 256) queries, rows [256, 512) planes, pitch CHP
+    if (PASS2) {
+      // sweep 2 has room for the query panel beside the keys: both go to their LDS places as they
+      // arrive and the fragments are read after the one barrier further down
 #pragma unroll
-    for (int u = 0; u < QL; ++u) {
-      const int q = tid + NTHR * u;
-      smem[(q / CH) * CHP + q % CH] = qpre[u];
-      if (!PASS2) smem[(MQ + q / CH) * CHP + q % CH] = ppre[u];
-    }
-    __syncthreads();
-    LKV_TS(7);
-    {
-      const uint4* arow = smem + (size_t)(hash_wave ? MQ + rt * 32 + plane_row(rl) : rt * 32 + rl) * CHP + kg;
+      for (int u = 0; u < QL; ++u) {
+        const int q = tid + NTHR * u;
+        sQst[(q / CH) * CHP + q % CH] = qpre[u];
+      }
+      LKV_TS(7);
+    } else {
+      // staging area: rows [0, 256) queries, rows [256, 512) planes, pitch CHP
 #pragma unroll
-      for (int i = 0; i < NCH; ++i) a[i] = arow[2 * i];
+      for (int u = 0; u < QL; ++u) {
+        const int q = tid + NTHR * u;
+        smem[(q / CH) * CHP + q % CH] = qpre[u];
+        smem[(MQ + q / CH) * CHP + q % CH] = ppre[u];
+      }
+      __syncthreads();
+      LKV_TS(7);
+      {
+        const uint4* arow = smem + (size_t)(hash_wave ? MQ + rt * 32 + plane_row(rl) : rt * 32 + rl) * CHP + kg;
+#pragma unroll
+        for (int i = 0; i < NCH; ++i) a[i] = arow[2 * i];
+      }
+      __syncthreads();  // fragments are in registers: the key rows may take the space
     }
-    __syncthreads();  // fragments are in registers: the key rows may take the space
 #pragma unroll
     for (int u = 0; u < KL; ++u) {
       const int q = tid + NTHR * u;
@@ -315,6 +327,11 @@ __global__ __launch_bounds__(PASS_WAVES * 64) void pass_kernel(PassParams p) {
   }
   __syncthreads();
   LKV_TS(1);
+  if (PASS2 && STAGE_A) {
+    const uint4* arow = sQst + (size_t)(rt * 32 + rl) * CHP + kg;
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) a[i] = arow[2 * i];
+  }
 
   if (PASS2 && n_tabc > 0 && !cnt_piped) {
     // the general shape: the whole job before the main loop, eight tables at a time from the L2-resident
@@ -992,9 +1009,12 @@ size_t sweep_lds_tail_offset(int dtype, int head_dim, bool pass2, int range_keys
   const int ch = head_dim * es / 16;
   const size_t pitch = (size_t)(ch + 1) * 16;
   const size_t bits = (((size_t)range_keys * BITS_PITCH + 3) / 4) * 16;
-  const size_t steady = range_keys * pitch + (pass2 ? (size_t)8 * range_keys * 4
+  // sweep 2 keeps its query panel beside the keys; sweep 1 stages queries and planes in the space its
+  // steady-state arrays take over afterwards
+  const size_t panel = ch <= 16 ? (size_t)PASS_ROWS * pitch : 0;
+  const size_t steady = range_keys * pitch + (pass2 ? (size_t)8 * range_keys * 4 + panel
                                                      : bits + (size_t)q_tiles * 32 * pitch + (size_t)hist_lds_words * 4);
-  const size_t staging = ch <= 16 ? (size_t)(pass2 ? 1 : 2) * PASS_ROWS * pitch : 0;
+  const size_t staging = pass2 ? 0 : 2 * panel;
   return ((steady > staging ? steady : staging) + 15) & ~(size_t)15;
 }
 
