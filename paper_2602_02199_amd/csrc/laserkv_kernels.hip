@@ -452,7 +452,32 @@ __global__ __launch_bounds__(PASS_WAVES * 64) void pass_kernel(PassParams p) {
       if (kg == 0) sCol[rt * nkr + nt * 32 + rl] = col;
     }
     if (cnt_piped) {
-      while (cnt_step < 5) cnt_advance();  // steps the loop was too short for, and the last pending pair
+      // the last pending pair, and the steps a short loop did not reach, all issued before any is added
+      cnt_advance();
+      uint2 ra[4], rb[4];
+      uint32_t rsh[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        ra[u] = cnt_pa;  // u == 0: what the call above may have issued; otherwise replaced or zero
+        rb[u] = cnt_pb;
+        rsh[u] = cnt_psh;
+        if (u > 0) {
+          ra[u] = make_uint2(0u, 0u);
+          rb[u] = make_uint2(0u, 0u);
+          if (cnt_lane && cnt_step < 4) {
+            const uint32_t c0 = cnt_codes.x & 0xffffu, c1 = cnt_codes.x >> 16;
+            ra[u] = *reinterpret_cast<const uint2*>(cnt_hist + (size_t)(2 * cnt_step) * cnt_hw2 + (c0 >> 1) * 2);
+            rb[u] = *reinterpret_cast<const uint2*>(cnt_hist + (size_t)(2 * cnt_step + 1) * cnt_hw2 + (c1 >> 1) * 2);
+            rsh[u] = ((c0 & 1u) * 16u) | (((c1 & 1u) * 16u) << 8);
+            cnt_codes = make_uint4(cnt_codes.y, cnt_codes.z, cnt_codes.w, 0u);
+          }
+          ++cnt_step;
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+        cnt_sum += (int)(((ra[u].x >> (rsh[u] & 31u)) & 0xffffu) + ((ra[u].y >> (rsh[u] & 31u)) & 0xffffu) +
+                         ((rb[u].x >> (rsh[u] >> 8)) & 0xffffu) + ((rb[u].y >> (rsh[u] >> 8)) & 0xffffu));
       if (lpk_log > 0) cnt_sum += __shfl_xor(cnt_sum, 1);
       if (lpk_log > 1) cnt_sum += __shfl_xor(cnt_sum, 2);
       if (cnt_lane && (tid & ((1 << lpk_log) - 1)) == 0)
