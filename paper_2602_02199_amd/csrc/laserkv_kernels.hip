@@ -805,6 +805,19 @@ __global__ __launch_bounds__(1024) void select_kernel(SelectParams p, AppendPara
             cc[4 * v + u] = (int)(y0[u] + y1[u]);
           }
       }
+    } else if (EPT == 2 && p.n_qgroups <= 2 && p.n_cnt_parts <= 2 &&
+               __all((p.s_t & 1) == 0 && (tid + 1) * EPT <= p.s_t)) {
+      // two positions per thread: 8-byte loads
+      const bool s2 = p.n_qgroups > 1, c2p = p.n_cnt_parts > 1;
+      const uint2* ps = reinterpret_cast<const uint2*>(p.s_part + hoff + (size_t)tid * 2);
+      const uint2* pc = reinterpret_cast<const uint2*>(p.cnt + hoff + (size_t)tid * 2);
+      const size_t pq = poff / 2;
+      const uint2 a0 = ps[0], a1 = s2 ? ps[pq] : make_uint2(0u, 0u);
+      const uint2 b0 = pc[0], b1 = c2p ? pc[pq] : make_uint2(0u, 0u);
+      sc[0] = __uint_as_float(a0.x) + __uint_as_float(a1.x);
+      sc[EPT - 1] = __uint_as_float(a0.y) + __uint_as_float(a1.y);
+      cc[0] = (int)(b0.x + b1.x);
+      cc[EPT - 1] = (int)(b0.y + b1.y);
     } else if (p.n_qgroups <= 2 && p.n_cnt_parts <= 2) {
       const bool s2 = p.n_qgroups > 1, c2p = p.n_cnt_parts > 1;
       float a0[EPT], a1[EPT];
