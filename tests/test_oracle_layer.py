@@ -55,3 +55,16 @@ def test_layer_run_invariants_tiny():
     kept = {(t, h, int(p)) for t, st in enumerate(stages) for h in range(wl.n_kv_heads) for p in st["keep"][h]}
     for blk, h, p in data["needles"].tolist():
         assert (blk, h, p) in kept                                        # sanity: needles are heavy hitters
+
+
+def test_tiny_kept_sets_match_the_stored_run():
+    """The oracle and the seeded generator still produce the kept sets stored by
+    tests/golden/make_tiny_keep.py (a drift guard, not an independent pin)."""
+    import importlib.util
+    import os
+    here = os.path.dirname(os.path.abspath(__file__))
+    spec = importlib.util.spec_from_file_location("make_tiny_keep", os.path.join(here, "golden", "make_tiny_keep.py"))
+    mod = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(mod)
+    stored = [ln.strip() for ln in open(os.path.join(here, "golden", "tiny_keep_sets.txt")) if ln.strip() and not ln.startswith("#")]
+    assert mod.compute() == stored
