@@ -141,6 +141,9 @@ def test_llama16k_bf16_all_blocks():
     # one window query, one head, blocks shorter than a tile
     dict(name="one-query", n_q_heads=1, n_kv_heads=1, head_dim=128, dtype="bf16", l_ctx=57, s_block=19,
          window=1, n_div=2, lsh_tables=2, lsh_bits=2),
+    # bit-wise scoring: 64 tables of one sign bit each (count = rows*tables - summed Hamming distance)
+    dict(name="bitwise-64x1", n_q_heads=4, n_kv_heads=2, head_dim=64, dtype="bf16", l_ctx=900, s_block=450,
+         window=16, n_div=4, lsh_tables=64, lsh_bits=1),
     # 768 window rows = three query-row groups, with the histogram path (K <= 12)
     dict(name="three-row-groups", n_q_heads=12, n_kv_heads=1, head_dim=128, dtype="bf16", l_ctx=1800, s_block=900,
          window=64, n_div=4, lsh_tables=6, lsh_bits=9),

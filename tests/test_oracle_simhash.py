@@ -142,3 +142,26 @@ def test_collision_rate_of_counts_matches_closed_form():
     assert np.all(np.abs(cr / n_tables - pr) < 4.5 * np.sqrt(pr * (1 - pr) / n_tables))
     s_lsh = O.lsh_scores(cnt, 1, 1, n_tables)
     assert 0 <= s_lsh.min() and s_lsh.max() <= 1 and abs(s_lsh.mean() - pk) < 0.01
+
+
+def test_one_bit_tables_give_the_hamming_score():
+    """With K = 1 every table is one sign bit, and the collision count of a key is
+    G*W*L minus the summed Hamming distance between its bit string and the window queries'
+    (the bit-wise reading of the hash score)."""
+    rng = np.random.default_rng(11)
+    h_q, h_kv, w, s_t, d, L = 4, 2, 5, 30, 16, 24
+    planes = rng.standard_normal((L, d))
+    q = rng.standard_normal((h_q, w, d))
+    k = rng.standard_normal((h_kv, s_t, d))
+    sig_q, _ = O.simhash(q, planes, L, 1)
+    sig_k, _ = O.simhash(k, planes, L, 1)
+    cnt = O.collision_counts(sig_q, sig_k, h_q // h_kv)
+    g = h_q // h_kv
+    for h in range(h_kv):
+        bits_k = (k[h] @ planes.T >= 0)
+        for i in range(s_t):
+            ham = 0
+            for gi in range(g):
+                bits_q = (q[h * g + gi] @ planes.T >= 0)
+                ham += int((bits_q != bits_k[i][None, :]).sum())
+            assert cnt[h, i] == g * w * L - ham
