@@ -192,7 +192,7 @@ __global__ __launch_bounds__(PASS_WAVES * 64) void pass_kernel(PassParams p) {
   const int n_tabc = PASS2 && p.qhist && !in_ctx ? max(0, min(p.tables_per_split, p.n_tables - tab0c)) : 0;
   int lpk_log = n_tabc > 16 ? 2 : (n_tabc > 8 ? 1 : 0);
   while (lpk_log > 0 && (n_keys_wg << lpk_log) > NTHR) --lpk_log;
-  const bool cnt_piped = n_tabc > 0 && n_tabc == (8 << lpk_log) && (p.n_tables & 7) == 0 && (tab0c & 7) == 0 &&
+  const bool cnt_piped = NCH <= 8 && n_tabc > 0 && n_tabc == (8 << lpk_log) && (p.n_tables & 7) == 0 && (tab0c & 7) == 0 &&
                          (n_keys_wg << lpk_log) <= NTHR && n_qg == 2;
   const bool cnt_lane = cnt_piped && tid < (n_keys_wg << lpk_log);
   const int cnt_key = tid >> lpk_log, cnt_tb = (tid & ((1 << lpk_log) - 1)) * 8;
