@@ -373,3 +373,55 @@ def test_row_lse_of_outside_keys(name, kw):
         say(f"[row-lse {wl.name} {tag}] max score err/(s+s_k) {rep['max_rel']:.2e}, tolerated {rep['tolerated']}")
     # the outside keys take a share of the probability mass
     assert outs["with"]["s_exact"].sum() < 0.99 * outs["without"]["s_exact"].sum()
+
+
+def test_bench_launch_configuration_full_size_against_oracle():
+    """Exactly what bench.py times (the 128k layer as one captured graph of laserkv_compress_block calls,
+    replayed): the rows in the cache for sampled blocks must be the oracle's kept rows, up to tokens at a
+    selection threshold."""
+    from tests.parity_util import TOL, count_interval
+    wl = synth.WORKLOADS["llama8b-128k"]
+    B = O.budget(wl.s_block, wl.l_ctx, wl.r_num, wl.r_den)
+    parts = O.partition(B, wl.n_div, wl.alpha, wl.s_block)
+    na, nl, ke, kl = parts
+    data = synth.make_layer(wl, 0, na)
+    dev = to_dev(data)
+    comp = LayerCompressor(wl, DEV)
+    plan = comp.plan_layer(dev, fused=True)
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        comp.run_plan(plan)
+        stream.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=stream):
+            comp.run_plan(plan)
+        comp.cache_pos.fill_(-1)
+        comp.k_cache.zero_()
+        stream.synchronize()
+        graph.replay()
+        graph.replay()
+        stream.synchronize()
+    s, b_t, tol = wl.s_block, sum(parts), TOL[wl.dtype]
+    k64, planes64 = f64(data["k"]), f64(data["planes"])
+    for t in (0, 17, 31):
+        lo = t * s
+        n_ctx = nl if t else 0
+        st = O.select_block(f64(data["q_win"][t]), k64[:, lo:lo + s], k64[:, lo - n_ctx:lo] if n_ctx else None, planes64,
+                            wl.lsh_tables, wl.lsh_bits, *parts, block_pos0=lo)
+        got = (comp.cache_pos[:, t * b_t:(t + 1) * b_t] - lo).cpu().numpy()
+        c_lo, c_hi = count_interval(st["sig_q"], st["sig_k"], st["unsure_q"], st["unsure_k"], wl.group)
+        n_diff = 0
+        for h in range(wl.n_kv_heads):
+            assert np.all(np.diff(got[h]) > 0)
+            diff = np.setxor1d(got[h], st["keep"][h])
+            if diff.size:
+                cand = np.arange(na, s - nl)
+                s_k = np.sort(st["s_exact"][h][cand])[::-1][ke - 1]
+                resid = np.setdiff1d(cand, st["k_exact_set"][h])
+                c_k = np.sort(st["cnt"][h][resid])[::-1][kl - 1]
+                for i in diff:
+                    assert abs(st["s_exact"][h][i] - s_k) <= 4 * tol * s_k or c_lo[h, i] <= c_k <= c_hi[h, i], (t, h, int(i))
+                n_diff += diff.size
+        say(f"[bench configuration blk {t}] kept rows differing from the oracle's at a threshold: {n_diff}")
+        pos = comp.cache_pos[:, t * b_t:(t + 1) * b_t]
+        assert torch.equal(comp.k_cache[:, t * b_t:(t + 1) * b_t], torch.gather(dev["k"], 1, pos[:, :, None].expand(-1, -1, wl.head_dim)))
