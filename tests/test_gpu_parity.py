@@ -425,3 +425,33 @@ def test_bench_launch_configuration_full_size_against_oracle():
         say(f"[bench configuration blk {t}] kept rows differing from the oracle's at a threshold: {n_diff}")
         pos = comp.cache_pos[:, t * b_t:(t + 1) * b_t]
         assert torch.equal(comp.k_cache[:, t * b_t:(t + 1) * b_t], torch.gather(dev["k"], 1, pos[:, :, None].expand(-1, -1, wl.head_dim)))
+
+
+@pytest.mark.parametrize("shift", [7, 40, 300])
+def test_window_positions_beyond_the_block(shift):
+    """Explicit window positions: a window that straddles the end of the block or lies wholly after it
+    (a trailing prompt; or the deferred-tail reading of the look-back, where a block's candidates end
+    `shift` tokens before its window does).  The causal mask then hides fewer keys, or none."""
+    wl = synth.shrink(synth.WORKLOADS["llama8b-16k"], index=14, l_ctx=2048)
+    B = O.budget(wl.s_block, wl.l_ctx, wl.r_num, wl.r_den)
+    parts = O.partition(B, wl.n_div, wl.alpha, wl.s_block)
+    data = synth.make_layer(wl, 1, parts[0], n_blocks=1)
+    dev = to_dev(data)
+    s = wl.s_block
+    lib = binding.LaserKV(wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.dtype, wl.lsh_tables, wl.lsh_bits,
+                          max_block=s, max_window=wl.window, max_ctx_keys=0)
+    block_pos0 = 5000
+    q_pos0 = block_pos0 + s - wl.window + shift
+    dbg = dbg_buffers(wl, s)
+    keep = torch.empty(wl.n_kv_heads, sum(parts), dtype=torch.int32, device=DEV)
+    lib.laserkv_select_block(dev["q_win"][0], dev["k"][:, :s], None, dev["planes"], block_pos0=block_pos0, q_pos0=q_pos0,
+                             n_anchor=parts[0], n_local=parts[1], k_exact=parts[2], k_lsh=parts[3], keep_idx=keep,
+                             dbg_s_exact=dbg["s_exact"], dbg_sig_k=dbg["sig_k"], dbg_sig_q=dbg["sig_q"], dbg_count=dbg["cnt"])
+    torch.cuda.synchronize()
+    st = O.select_block(f64(data["q_win"][0]), f64(data["k"][:, :s]), None, f64(data["planes"]), wl.lsh_tables,
+                        wl.lsh_bits, *parts, block_pos0=block_pos0, q_pos0=q_pos0)
+    rep = check_block(st, gpu_stage(dbg, keep), parts, wl.dtype)
+    say(f"[window shift {shift}] max score err/(s+s_k) {rep['max_rel']:.2e}, tolerated {rep['tolerated']}")
+    # the last keys of the block are visible to more queries than with the default window
+    base = O.exact_scores(f64(data["q_win"][0]), f64(data["k"][:, :s]), None, block_pos0=block_pos0)
+    assert (st["s_exact"][:, -1] > base[:, -1]).all()
