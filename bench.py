@@ -58,6 +58,9 @@ def main():
                     help="consensus: the global-consensus variant (scores summed over --layers layers and all heads, one "
                          "selection per block); prints its own JSON line, not the headline metric")
     ap.add_argument("--layers", type=int, default=4, help="layers summed by --policy consensus")
+    ap.add_argument("--batch", type=int, default=1,
+                    help="fold this many independent sequences into the head axis (heads x batch per call); the rate then "
+                         "counts batch x context tokens. 1 is the headline configuration")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no collectives, no sharding); --gpus must be 1", file=sys.stderr)
@@ -68,6 +71,9 @@ def main():
     from paper_2602_02199_amd.driver import LayerCompressor
 
     wl = synth.WORKLOADS[args.workload]
+    if args.batch > 1:
+        wl = synth.shrink(wl, name=f"{wl.name}-x{args.batch}", n_q_heads=wl.n_q_heads * args.batch,
+                          n_kv_heads=wl.n_kv_heads * args.batch)
     dev = "cuda:0"
     if args.policy == "consensus":
         return bench_consensus(args, wl, dev)
@@ -149,7 +155,7 @@ def main():
         comp.lib.laserkv_profile_isolate(None)
         comp.run_plan(plan)   # leave the workspace and the cache in the state of a complete pass
         torch.cuda.synchronize()
-    tokens = ddev["k"].shape[1]
+    tokens = ddev["k"].shape[1] * args.batch
     value = tokens / (ms_per_step * 1e-3)
 
     work = algorithmic_work(wl, comp.B)
@@ -195,7 +201,7 @@ def main():
                config=dict(workload=wl.name, l_ctx=wl.l_ctx, s_block=wl.s_block, window=wl.window, n=wl.n_div,
                            lsh_tables=wl.lsh_tables, lsh_bits=wl.lsh_bits, n_q_heads=wl.n_q_heads,
                            n_kv_heads=wl.n_kv_heads, head_dim=wl.head_dim, budget_per_block=comp.B,
-                           blocks=wl.n_blocks, layers_timed=1, launch=args.mode,
+                           blocks=wl.n_blocks, layers_timed=1, launch=args.mode, sequences=args.batch,
                            entry="laserkv_select_block+laserkv_append" if args.unfused else "laserkv_compress_block"),
                roofline=roofline, cpu_baseline=cpu)
     print(json.dumps(out), flush=True)
