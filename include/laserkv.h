@@ -39,6 +39,9 @@ typedef enum {
   LKV_EHIP = -4    /* a HIP runtime call failed; text in laserkv_last_error */
 } laserkv_status;
 
+/* q_pos0 value that places the window on the last w tokens of the block */
+#define LKV_WINDOW_AT_BLOCK_END INT64_MIN
+
 typedef struct {
   int32_t n_q_heads;   /* H_q */
   int32_t n_kv_heads;  /* H_kv, divides H_q */
@@ -81,8 +84,11 @@ int laserkv_partition(int32_t B, int32_t n, double alpha, int32_t s_t,
  *   k_ctx        DEVICE [H_kv, t_ctx, d] look-back keys (tail of the previous block, Sec. 3.2):
  *                always visible, they enter the softmax normaliser only; NULL iff t_ctx == 0
  *   hyperplanes  DEVICE [L*K, d] contiguous; row r*K + c decides bit c of table r (bit = proj >= 0)
- *   causal       non-zero: block key i is visible to query j iff block_pos0 + i <= q_pos0 + j.
- *                Every query must see at least one key (t_ctx > 0 or q_pos0 >= block_pos0).
+ *   q_pos0       position of window query 0, or LKV_WINDOW_AT_BLOCK_END: the window is the block's last w
+ *                tokens (q_pos0 = block_pos0 + s_t - w), the observation window of Sec. 3.3 "Precision"
+ *   causal       non-zero: block key i is visible to query j iff block_pos0 + i <= q_pos0 + j; then
+ *                q_pos0 >= block_pos0 is required (every query sees at least the block's first key).
+ *                Look-back keys are visible to every query either way.
  *   n_anchor, n_local   first / last positions of the block that are always kept
  *   k_exact      candidates taken by (S_exact descending, index ascending)
  *   k_lsh        remaining candidates taken by (collision count descending, index ascending)
@@ -94,7 +100,8 @@ int laserkv_partition(int32_t B, int32_t n, double alpha, int32_t s_t,
  *
  * S_exact[h, i] = mean over the G*w window rows of KV head h of softmax(q.k / sqrt(d)) at key i.
  * Errors: LKV_EINVAL for shapes beyond the context's configuration, w < 1, budgets that do
- * not fit the block, misaligned pointers/strides (16-byte rows required), invisible rows. */
+ * not fit the block, misaligned pointers/strides (16-byte rows required), a causal window that
+ * starts before the block, or a block with too few keys to spread the L tables' query-code job over. */
 int laserkv_select_block(laserkv_ctx* ctx,
                          const void* q_win, int64_t q_stride_head, int64_t q_stride_tok,
                          const void* k_blk, int64_t k_stride_head, int64_t k_stride_tok,
@@ -157,8 +164,8 @@ int laserkv_compress_block(laserkv_ctx* ctx,
  * not 4-byte aligned). */
 int laserkv_set_row_lse(laserkv_ctx* ctx, const float* row_lse);
 
-/* Global-consensus variant: Alg. 1 step 3 taken literally, with the exact score summed "across all
- * layers and heads" (Sec. 3.3 "Precision") and, likewise, the collision counts of step 6, followed by
+/* Global-consensus variant: Alg. 1 step 3 taken literally, with the exact score summed over every
+ * layer and head (Sec. 3.3 "Precision") and, likewise, the collision counts of step 6, followed by
  * ONE two-stage TopK (steps 4-8) whose kept set serves every layer and head.  Three calls:
  *
  * laserkv_score_block: steps a1-a3 of laserkv_select_block for one layer's tensors (same arguments,

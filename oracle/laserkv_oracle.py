@@ -271,7 +271,7 @@ def consensus_block(layers, n_tables, n_bits, n_anchor, n_local, k_exact, k_lsh,
     layers: sequence of dicts, one per layer, with q_win [H_q, W, d], k_blk [H_kv, S_t, d],
     k_ctx [H_kv, T, d] or None, planes [L*K, d] (each layer may bring its own hyperplanes).
     The exact score of a token is the plain sum of the per-head pooled probabilities
-    (Sec. 3.3 "Precision": aggregated "across all layers and heads"); its collision count is the
+    (Sec. 3.3 "Precision"; Alg. 1 step 3: the sum runs over every layer and head); its collision count is the
     plain sum of the per-head counts (Alg. 1 step 6 averages the same indicator over r; the
     sum over heads and layers keeps the order of that average).  One two-stage TopK (steps 4-8)
     on the summed arrays gives one kept set for every layer and head.

@@ -15,6 +15,7 @@ LIB_PATH = os.path.join(_HERE, "liblaserkv.so")
 
 LKV_F32, LKV_BF16 = 0, 1
 LKV_OK, LKV_EINVAL, LKV_ECAP, LKV_ENOMEM, LKV_EHIP = 0, -1, -2, -3, -4
+LKV_WINDOW_AT_BLOCK_END = -(1 << 63)   # q_pos0 sentinel of laserkv.h
 
 EXPORTS = (
     "laserkv_create", "laserkv_destroy", "laserkv_last_error", "laserkv_budget",
@@ -165,7 +166,7 @@ class LaserKV:
         s_t, w = k_blk.shape[1], q_win.shape[1]
         t_ctx = 0 if k_ctx is None else k_ctx.shape[1]
         if q_pos0 is None:
-            q_pos0 = block_pos0 + s_t - w
+            q_pos0 = LKV_WINDOW_AT_BLOCK_END
         qs, ks = _strides3(q_win, d), _strides3(k_blk, d)
         cs = _strides3(k_ctx, d) if k_ctx is not None else (0, 0)
         assert hyperplanes.is_contiguous()
@@ -194,7 +195,7 @@ class LaserKV:
         s_t, w = k_blk.shape[1], q_win.shape[1]
         t_ctx = 0 if k_ctx is None else k_ctx.shape[1]
         if q_pos0 is None:
-            q_pos0 = block_pos0 + s_t - w
+            q_pos0 = LKV_WINDOW_AT_BLOCK_END
         qs, ks, vs = _strides3(q_win, d), _strides3(k_blk, d), _strides3(v_blk, d)
         cs = _strides3(k_ctx, d) if k_ctx is not None else (0, 0)
         assert hyperplanes.is_contiguous()
@@ -212,7 +213,7 @@ class LaserKV:
         s_t, w = k_blk.shape[1], q_win.shape[1]
         t_ctx = 0 if k_ctx is None else k_ctx.shape[1]
         if q_pos0 is None:
-            q_pos0 = block_pos0 + s_t - w
+            q_pos0 = LKV_WINDOW_AT_BLOCK_END
         qs, ks = _strides3(q_win, d), _strides3(k_blk, d)
         cs = _strides3(k_ctx, d) if k_ctx is not None else (0, 0)
         assert hyperplanes.is_contiguous() and score_acc.is_contiguous() and count_acc.is_contiguous()

@@ -41,6 +41,9 @@ struct laserkv_ctx {
   int m_pad;
   const float* row_lse;  // laserkv_set_row_lse: applies to every following scoring call until reset
   int only_kernel;   // >= 0: launch only this kernel kind (laserkv_profile_isolate); -1 normally
+  // tuning switches, read from the environment once when the context is created
+  int sweep_wg_per_cu;   // LASERKV_SWEEP_WG_PER_CU: sweep workgroups aimed at per compute unit (default 1)
+  int append_split;      // LASERKV_APPEND_SPLIT: select+append workgroups per head (default: n_cu / heads)
   char error[512];
   // per-kernel event timing (benchmarks only)
   bool profiling;
@@ -183,9 +186,12 @@ int laserkv_create(const laserkv_config* cfg, laserkv_ctx** out) {
   // sweeps when a head's tables fit 512 KiB per group
   const size_t hist_bytes_head = ((size_t)c.lsh_tables << c.lsh_bits) * 2;
   const bool use_qhist = hist_bytes_head <= 512 * 1024 && env_int("LASERKV_NO_QHIST", 0) == 0;
-  // ranges of at most score_max_range() keys, plus one for the look-back keys, and room for finer splits
-  ctx->max_ranges = (c.max_block + c.max_ctx_keys) / lkv::score_max_range() + 2;
-  if (ctx->max_ranges < 64) ctx->max_ranges = 64;
+  ctx->sweep_wg_per_cu = env_int("LASERKV_SWEEP_WG_PER_CU", 1);
+  if (ctx->sweep_wg_per_cu < 1) ctx->sweep_wg_per_cu = 1;
+  ctx->append_split = env_int("LASERKV_APPEND_SPLIT", 0);
+  // a key range never has fewer than 32 keys (wide rows and many planes shrink it that far), and the
+  // look-back keys have ranges of their own
+  ctx->max_ranges = (c.max_block + 31) / 32 + (c.max_ctx_keys + 31) / 32;
   ctx->max_ranges = (ctx->max_ranges + 7) & ~7;
   const size_t hk = c.n_kv_heads, sb = c.max_block;
   struct { void** p; size_t bytes; } allocs[] = {
@@ -204,11 +210,24 @@ int laserkv_create(const laserkv_config* cfg, laserkv_ctx** out) {
       return fail(nullptr, LKV_ENOMEM, "create: hipMalloc of %zu bytes failed: %s", al.bytes, hipGetErrorString(e));
     }
   }
+  const size_t qhist_bytes = (size_t)n_qg_max * hk * hist_bytes_head;
   if (use_qhist) {
-    e = hipMalloc((void**)&ctx->qhist, (size_t)n_qg_max * hk * hist_bytes_head);
+    e = hipMalloc((void**)&ctx->qhist, qhist_bytes);
     if (e != hipSuccess) {
       laserkv_destroy(ctx);
       return fail(nullptr, LKV_ENOMEM, "create: histogram workspace: %s", hipGetErrorString(e));
+    }
+  }
+  // LASERKV_POISON_WORKSPACE=1 (tests): fill the fresh workspace with a non-zero pattern, so that a kernel
+  // reading what no kernel wrote shows up in the results instead of meeting zeros by luck
+  if (env_int("LASERKV_POISON_WORKSPACE", 0)) {
+    for (auto& al : allocs)
+      if (e == hipSuccess) e = hipMemset(*al.p, 0xA5, al.bytes);
+    if (e == hipSuccess && ctx->qhist) e = hipMemset(ctx->qhist, 0xA5, qhist_bytes);
+    if (e == hipSuccess) e = hipDeviceSynchronize();
+    if (e != hipSuccess) {
+      laserkv_destroy(ctx);
+      return fail_hip(nullptr, e, "create: workspace fill");
     }
   }
   *out = ctx;
@@ -257,6 +276,7 @@ int select_impl(laserkv_ctx* ctx,
   if ((int64_t)n_anchor + n_local > s_t) return fail(ctx, LKV_EINVAL, "select_block: protected sets exceed the block");
   if ((int64_t)k_exact + k_lsh > (int64_t)s_t - n_anchor - n_local)
     return fail(ctx, LKV_EINVAL, "select_block: recall budget exceeds the candidate set");
+  if (q_pos0 == LKV_WINDOW_AT_BLOCK_END) q_pos0 = block_pos0 + s_t - w;
   if (causal && q_pos0 < block_pos0) return fail(ctx, LKV_EINVAL, "select_block: causal window must not start before the block");
   const int64_t row_elems = d;
   auto bad_stride = [&](int64_t sh, int64_t st) { return st < row_elems || sh < 0 || ((st * es) & 15) || ((sh * es) & 15); };
@@ -287,7 +307,7 @@ int select_impl(laserkv_ctx* ctx,
   sp.n_qgroups = n_qg;
   sp.n_kv_heads = c.n_kv_heads;
   // key ranges: about one workgroup per compute unit per query-row group, each range in one source
-  const int wg_target = ctx->n_cu * env_int("LASERKV_SWEEP_WG_PER_CU", 1);
+  const int wg_target = ctx->n_cu * ctx->sweep_wg_per_cu;
   int nr = wg_target / (c.n_kv_heads * n_qg);
   if (nr < 1) nr = 1;
   if (nr > ctx->max_ranges - 1) nr = ctx->max_ranges - 1;
@@ -309,6 +329,9 @@ int select_impl(laserkv_ctx* ctx,
       break;
     nk -= 32;
   }
+  if (lkv::sweep_lds_bytes(c.dtype, d, false, nk, sp.q_tiles, sp.hist_lds_words) > 160 * 1024)
+    return fail(ctx, LKV_EINVAL, "select_block: s_t + t_ctx = %d keys are too few to spread %d tables of %d bits over "
+                "(the query-code job of one key range exceeds the LDS)", n_keys, c.lsh_tables, c.lsh_bits);
   if (sp.n_ranges > ctx->max_ranges) return fail(ctx, LKV_EINVAL, "select_block: internal range split too fine");
   sp.causal = causal ? 1 : 0;
   int64_t lim0 = (int64_t)t_ctx + (q_pos0 - block_pos0);
@@ -364,7 +387,9 @@ int select_impl(laserkv_ctx* ctx,
   lp.n_kv_heads = c.n_kv_heads;
   lp.inv_m = 1.0f / (float)m_rows;
   lp.cnt = ctx->cnt;
-  lp.n_cnt_parts = sp.qhist ? n_qg : 1;
+  // sweep 2 writes a count part only for the query-row groups that own tables (the first ones); the
+  // stand-alone count kernel sums into part 0
+  lp.n_cnt_parts = sp.qhist ? (c.lsh_tables + sp.tables_per_split - 1) / sp.tables_per_split : 1;
   lp.cnt_out = dbg_count ? ctx->cnt_sum : nullptr;      // stage outputs are written only on request
   lp.s_t = s_t;
   lp.n_anchor = n_anchor;
@@ -400,8 +425,8 @@ int select_impl(laserkv_ctx* ctx,
   } else if (fused) {
     lkv::AppendParams ap = *fused;
     ap.keep = keep_idx;
-    const int n_cu = ctx->n_cu;
-    if ((e = timed(ctx, LKV_KERN_SELECT, st, [&] { return lkv::launch_select_append(lp, ap, n_cu, st); })) != hipSuccess)
+    const int n_cu = ctx->n_cu, split = ctx->append_split;
+    if ((e = timed(ctx, LKV_KERN_SELECT, st, [&] { return lkv::launch_select_append(lp, ap, n_cu, split, st); })) != hipSuccess)
       return fail_hip(ctx, e, "compress_block: select + append kernel");
   } else if ((e = timed(ctx, LKV_KERN_SELECT, st, [&] { return lkv::launch_select(lp, st); })) != hipSuccess) {
     return fail_hip(ctx, e, "select_block: select kernel");
@@ -562,6 +587,7 @@ int laserkv_select_consensus(laserkv_ctx* ctx, const float* score_acc, const int
   if ((int64_t)n_anchor + n_local > s_t) return fail(ctx, LKV_EINVAL, "select_consensus: protected sets exceed the block");
   if ((int64_t)k_exact + k_lsh > (int64_t)s_t - n_anchor - n_local)
     return fail(ctx, LKV_EINVAL, "select_consensus: recall budget exceeds the candidate set");
+  if (!aligned16(score_acc) || !aligned16(count_acc)) return fail(ctx, LKV_EINVAL, "select_consensus: accumulators must be 16-byte aligned");
   lkv::SelectParams lp;
   lp.s_part = score_acc;
   lp.n_qgroups = 1;

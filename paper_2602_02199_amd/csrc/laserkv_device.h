@@ -52,31 +52,6 @@ __device__ __forceinline__ float fast_log2(float x) { return __builtin_amdgcn_lo
 
 __device__ __forceinline__ uint4 ld16(const void* p) { return *reinterpret_cast<const uint4*>(p); }
 
-// Cross-lane helpers.  A 32x32 accumulator row is spread over the 32 lanes that share kg, i.e. over
-// one half of the wave: two DPP rows of 16 lanes.
-template <int CTRL>
-__device__ __forceinline__ float dpp_mov(float v) {
-  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, false));
-}
-__device__ __forceinline__ float swizzle_xor16(float v) {
-  return __int_as_float(__builtin_amdgcn_ds_swizzle(__float_as_int(v), 0x401F));  // lane ^ 16
-}
-// max / sum over the 32 lanes of a wave half; every lane of the half gets the result
-__device__ __forceinline__ float half_allmax(float v) {
-  v = fmaxf(v, dpp_mov<0xB1>(v));   // quad_perm [1,0,3,2]
-  v = fmaxf(v, dpp_mov<0x4E>(v));   // quad_perm [2,3,0,1]
-  v = fmaxf(v, dpp_mov<0x124>(v));  // row_ror:4
-  v = fmaxf(v, dpp_mov<0x128>(v));  // row_ror:8
-  return fmaxf(v, swizzle_xor16(v));
-}
-__device__ __forceinline__ float half_allsum(float v) {
-  v += dpp_mov<0xB1>(v);
-  v += dpp_mov<0x4E>(v);
-  v += dpp_mov<0x124>(v);
-  v += dpp_mov<0x128>(v);
-  return v + swizzle_xor16(v);
-}
-
 // inclusive prefix sum over the 64 lanes of a wave (DPP row shifts, then row broadcasts)
 __device__ __forceinline__ int wave_incl_scan(int v) {
   v += __builtin_amdgcn_update_dpp(0, v, 0x111, 0xf, 0xf, true);  // row_shr:1
@@ -93,13 +68,6 @@ __device__ __forceinline__ void lse_merge(float& m, float& s, float m2, float s2
   float mn = fmaxf(m, m2);
   s = s * fast_exp2(m - mn) + s2 * fast_exp2(m2 - mn);
   m = mn;
-}
-
-__device__ __forceinline__ void lse_push(float& m, float& s, float x) {
-  float dlt = x - m;
-  float e = fast_exp2(-fabsf(dlt));
-  s = dlt > 0.0f ? fmaf(s, e, 1.0f) : s + e;
-  m = fmaxf(m, x);
 }
 
 }  // namespace lkv

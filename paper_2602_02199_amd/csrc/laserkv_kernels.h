@@ -110,7 +110,8 @@ hipError_t launch_sweep1(int dtype, int head_dim, const PassParams& p, hipStream
 hipError_t launch_sweep2(int dtype, int head_dim, const PassParams& p, hipStream_t st);
 hipError_t launch_count(const CountParams& p, int n_kv_heads, hipStream_t st);
 hipError_t launch_select(const SelectParams& p, hipStream_t st);
-hipError_t launch_select_append(const SelectParams& p, const AppendParams& ap, int n_cu, hipStream_t st);
+// split_override > 0: workgroups per head (tuning); otherwise n_cu / heads
+hipError_t launch_select_append(const SelectParams& p, const AppendParams& ap, int n_cu, int split_override, hipStream_t st);
 hipError_t launch_append(const AppendParams& p, int n_kv_heads, hipStream_t st);
 hipError_t launch_accumulate(const AccumParams& p, hipStream_t st);
 hipError_t init_kernel_attributes();

@@ -15,12 +15,6 @@
 #include "laserkv_kernels.h"
 
 #include <limits.h>
-#include <stdlib.h>
-
-// Timestamp hook for bench harnesses that include this file with their own definition; nothing in the library build.
-#ifndef LKV_TS
-#define LKV_TS(n)
-#endif
 
 namespace lkv {
 
@@ -88,7 +82,6 @@ __global__ __launch_bounds__(PASS_WAVES * 64) void pass_kernel(PassParams p) {
   constexpr int MQ = PASS_ROWS;
 
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, rl = lane & 31, kg = lane >> 5;
-  LKV_TS(0);
   // work item: heads are the slow index of the XCD-major order, so one head's keys, queries and
   // query histograms are fetched into one L2 (or as few as the head count allows)
   const int n_qg = p.n_qgroups;
@@ -224,7 +217,6 @@ __global__ __launch_bounds__(PASS_WAVES * 64) void pass_kernel(PassParams p) {
       const int q = tid + NTHR * u;
       if (q < n_chunks) kpre[u] = key_chunk(q);
     }
-    LKV_TS(5);
     if (PASS2) {
       // sweep 2 has room for the query panel beside the keys: both go to their LDS places as they
       // arrive and the fragments are read after the one barrier further down
@@ -233,7 +225,6 @@ __global__ __launch_bounds__(PASS_WAVES * 64) void pass_kernel(PassParams p) {
         const int q = tid + NTHR * u;
         sQst[(q / CH) * CHP + q % CH] = qpre[u];
       }
-      LKV_TS(7);
     } else {
       // staging area: rows [0, 256) queries, rows [256, 512) planes, pitch CHP
 #pragma unroll
@@ -243,7 +234,6 @@ __global__ __launch_bounds__(PASS_WAVES * 64) void pass_kernel(PassParams p) {
         smem[(MQ + q / CH) * CHP + q % CH] = ppre[u];
       }
       __syncthreads();
-      LKV_TS(7);
       {
         const uint4* arow = smem + (size_t)(hash_wave ? MQ + rt * 32 + plane_row(rl) : rt * 32 + rl) * CHP + kg;
 #pragma unroll
@@ -270,7 +260,6 @@ __global__ __launch_bounds__(PASS_WAVES * 64) void pass_kernel(PassParams p) {
 #pragma unroll
       for (int i = 0; i < NCH; ++i) a[i] = ld16(ptr + (2 * i + kg) * 16);
     }
-    LKV_TS(5);
     constexpr int LDB = 4;
     for (int c0 = 0; c0 < n_chunks; c0 += NTHR * LDB) {
       uint4 pre[LDB];
@@ -286,7 +275,6 @@ __global__ __launch_bounds__(PASS_WAVES * 64) void pass_kernel(PassParams p) {
       }
     }
   }
-  LKV_TS(6);
   if (!PASS2)
     for (int i = tid; i < p.hist_lds_words; i += NTHR) sHist[i] = 0u;
   for (int t = tid; t < MQ; t += NTHR) {
@@ -326,7 +314,6 @@ __global__ __launch_bounds__(PASS_WAVES * 64) void pass_kernel(PassParams p) {
     if ((tid & 3) == 0) sLse[t] = (qg * MQ + t < p.m_rows) ? mm + fast_log2(ss) : 1.0e30f;  // padding rows: probability 0
   }
   __syncthreads();
-  LKV_TS(1);
   if (PASS2 && STAGE_A) {
     const uint4* arow = sQst + (size_t)(rt * 32 + rl) * CHP + kg;
 #pragma unroll
@@ -618,7 +605,6 @@ __global__ __launch_bounds__(PASS_WAVES * 64) void pass_kernel(PassParams p) {
       }
     }
   }
-  LKV_TS(2);
 
   if (PASS2) {
     __syncthreads();
@@ -633,7 +619,6 @@ __global__ __launch_bounds__(PASS_WAVES * 64) void pass_kernel(PassParams p) {
     }
   } else {
     __syncthreads();
-    LKV_TS(3);
     // key codes: one item = (key, group of 8 tables) -> one 16-byte store where aligned
     const uint32_t code_mask = (1u << p.n_bits) - 1u;
     const int n_tg8 = (n_tab + 7) >> 3;
@@ -670,7 +655,6 @@ __global__ __launch_bounds__(PASS_WAVES * 64) void pass_kernel(PassParams p) {
     if (!p.qhist && !in_ctx && qg == 0)  // the separate count kernel accumulates with atomics
       for (int t = tid; t < n_keys_wg; t += NTHR) p.cnt[(size_t)h * p.s_t + seg_row0 + t] = 0;
   }
-  LKV_TS(4);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -769,7 +753,6 @@ __global__ __launch_bounds__(1024) void select_kernel(SelectParams p, AppendPara
   const int sel_id = xcd_major(blockIdx.x, n_sel_wg);
   const int h = FUSED ? sel_id / split : sel_id;
   const int part = FUSED ? sel_id - h * split : 0;
-  LKV_TS(0);
   uint32_t key[EPT], c2[EPT];
   bool inr[EPT], cand[EPT], sel[EPT];
   {
@@ -937,7 +920,6 @@ __global__ __launch_bounds__(1024) void select_kernel(SelectParams p, AppendPara
   sHist[tid >> 8][tid & 255] = 0u;
   if (tid == 0) sMaxCnt = 0u;
   __syncthreads();
-  LKV_TS(1);
   {
     // Collision counts are mostly tiny, so their top byte is usually zero for every candidate: the
     // block-wide maximum (one LDS atomic per wave, ordered by the barriers of the first stage) tells
@@ -950,14 +932,12 @@ __global__ __launch_bounds__(1024) void select_kernel(SelectParams p, AppendPara
     if (lane == 0 && mx) atomicMax(&sMaxCnt, mx);
   }
   take_top(key, cand, p.k_exact, 4);
-  LKV_TS(2);
   bool act2[EPT];
 #pragma unroll
   for (int e = 0; e < EPT; ++e) act2[e] = cand[e] && !sel[e];
   if (p.k_exact <= 0) __syncthreads();  // otherwise the first stage's barriers already order the atomicMax above
   const int cnt_digits = sMaxCnt < 256u ? 1 : (sMaxCnt < 65536u ? 2 : (sMaxCnt < (1u << 24) ? 3 : 4));
   take_top(c2, act2, p.k_lsh, min(cnt_digits, (p.cnt_bits + 7) >> 3));
-  LKV_TS(3);
 
   int n_keep = 0;
 #pragma unroll
@@ -980,7 +960,6 @@ __global__ __launch_bounds__(1024) void select_kernel(SelectParams p, AppendPara
       ++pos;
     }
   }
-  LKV_TS(4);
   if (FUSED) {
     __syncthreads();
     const int cpr = ap.row_bytes / 16;
@@ -996,7 +975,6 @@ __global__ __launch_bounds__(1024) void select_kernel(SelectParams p, AppendPara
       if (c == 0) ap.cache_pos[(int64_t)h * ap.pos_stride_head + ap.cache_len + r0 + row] = ap.block_pos0 + src;
     }
   }
-  LKV_TS(5);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -1146,11 +1124,10 @@ hipError_t launch_select(const SelectParams& p, hipStream_t st) {
   return launch_select_t<false>(p, none, 1, st);
 }
 
-hipError_t launch_select_append(const SelectParams& p, const AppendParams& ap, int n_cu, hipStream_t st) {
+hipError_t launch_select_append(const SelectParams& p, const AppendParams& ap, int n_cu, int split_override, hipStream_t st) {
   // enough workgroups per head to fill the chip, each copying at most 1024 rows
   const int b_t = p.n_anchor + p.n_local + p.k_exact + p.k_lsh;
-  int split = n_cu / p.n_kv_heads;
-  if (const char* e = getenv("LASERKV_APPEND_SPLIT")) split = atoi(e);
+  int split = split_override > 0 ? split_override : n_cu / p.n_kv_heads;
   if (split < 1) split = 1;
   while ((b_t + split - 1) / split > 1024) ++split;
   return launch_select_t<true>(p, ap, split, st);

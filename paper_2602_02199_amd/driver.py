@@ -114,14 +114,14 @@ class LayerCompressor:
                     ctx, vp(q.data_ptr()), q.stride(0), q.stride(1), vp(k.data_ptr()), k.stride(0), k.stride(1),
                     vp(v.data_ptr()), v.stride(0), v.stride(1),
                     ctx_ptr, kc_sh if t_ctx else 0, kc_st if t_ctx else 0, vp(data["planes"].data_ptr()),
-                    s_t, wl.window, t_ctx, lo, lo + s_t - wl.window, 1, na, nl, ke, kl,
+                    s_t, wl.window, t_ctx, lo, binding.LKV_WINDOW_AT_BLOCK_END, 1, na, nl, ke, kl,
                     vp(self.keep.data_ptr()), vp(self.k_cache.data_ptr()), vp(self.v_cache.data_ptr()), kc_sh,
                     vp(self.cache_pos.data_ptr()), self.cache_pos.stride(0), cache_len, self.cap)))
             else:
                 calls.append((lib.laserkv_select_block, (
                     ctx, vp(q.data_ptr()), q.stride(0), q.stride(1), vp(k.data_ptr()), k.stride(0), k.stride(1),
                     ctx_ptr, kc_sh if t_ctx else 0, kc_st if t_ctx else 0, vp(data["planes"].data_ptr()),
-                    s_t, wl.window, t_ctx, lo, lo + s_t - wl.window, 1, na, nl, ke, kl,
+                    s_t, wl.window, t_ctx, lo, binding.LKV_WINDOW_AT_BLOCK_END, 1, na, nl, ke, kl,
                     vp(self.keep.data_ptr()), None, None, None, None)))
                 calls.append((lib.laserkv_append, (
                     ctx, vp(k.data_ptr()), k.stride(0), k.stride(1), vp(v.data_ptr()), v.stride(0), v.stride(1),

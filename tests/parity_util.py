@@ -5,15 +5,20 @@ Rules (per block, per KV head):
   * collision counts equal to a recount from the HIP path's own codes, inside the interval the
     unsure codes allow, and equal to the oracle's where nothing was unsure;
   * S_exact: |gpu - oracle| <= tol * oracle + tol * s_k, s_k = oracle's k_exact-th candidate score;
+  * the observed score error stays far inside that bar: max |gpu - oracle| / (oracle + s_k) <= OBSERVED
+    (inputs are exact in both, products of two bf16 are exact in fp32, sums run in fp32), so a kernel
+    mistake of a fraction of a percent cannot hide behind the bf16 bar;
   * kept indices equal to Alg. 1 applied to the HIP path's own scores and counts (exact), and equal
-    to the oracle's except tokens at the stage-1 threshold (within the score tolerance) or at the
-    stage-2 count threshold.
+    to the oracle's except tokens whose oracle score lies within tol * s_k of the stage-1 threshold s_k,
+    tokens whose count interval contains the stage-2 threshold count, and, when stage 1 differed by such
+    tokens, tokens at the stage-2 threshold count (the residual changed).
 """
 import numpy as np
 
 from oracle import laserkv_oracle as O
 
 TOL = {"f32": 1e-5, "bf16": 2e-2}
+OBSERVED = {"f32": 1e-5, "bf16": 1e-4}   # regression bound on the score error actually seen (about 2e-6)
 
 
 def count_interval(sig_q, sig_k, uns_q, uns_k, g):
@@ -68,6 +73,7 @@ def check_block(st, gpu, parts, dtype, report=None):
         assert np.all(err <= bound), f"head {h}: S_exact off by up to {float((err - bound).max()):.3e} beyond tolerance"
         big = o > 0
         rep["max_rel"] = max(rep["max_rel"], float((err[big] / (o[big] + s_k)).max()))
+        assert rep["max_rel"] <= OBSERVED[dtype], f"head {h}: score error {rep['max_rel']:.2e} of (score + s_k) exceeds the regression bound"
         keep = gpu["keep"][h].astype(np.int64)
         assert keep.shape[0] == na + nl + ke + kl
         assert np.all(np.diff(keep) > 0), "kept indices not strictly ascending"
@@ -81,7 +87,7 @@ def check_block(st, gpu, parts, dtype, report=None):
             own_ex = O.select(gsc, gpu["cnt"][h], na, nl, ke, 0)[1] if ke > 0 else np.array([], dtype=np.int64)
             stage1_swap = np.setxor1d(own_ex, st["k_exact_set"][h])
             for i in diff:
-                near_s = abs(o[i] - s_k) <= 4 * tol * s_k
+                near_s = abs(o[i] - s_k) <= tol * s_k
                 near_c = c_k is not None and lo[h, i] - 0 <= c_k <= hi[h, i]
                 knock_on = stage1_swap.size > 0 and c_k is not None and abs(int(st["cnt"][h][i]) - int(c_k)) <= 0
                 assert near_s or near_c or knock_on, (

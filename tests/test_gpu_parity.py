@@ -150,6 +150,14 @@ def test_llama16k_bf16_all_blocks():
     # 512 window rows x 4 tables of 2 bits: collision counts in the hundreds (two radix digits in stage 2)
     dict(name="big-counts", n_q_heads=8, n_kv_heads=1, head_dim=64, dtype="bf16", l_ctx=1200, s_block=600,
          window=64, n_div=4, lsh_tables=4, lsh_bits=2),
+    # more query-row groups than tables: the groups without a table contribute no count part
+    dict(name="two-row-groups-one-table", n_q_heads=5, n_kv_heads=1, head_dim=64, dtype="bf16", l_ctx=1000, s_block=500,
+         window=64, n_div=4, lsh_tables=1, lsh_bits=5),
+    dict(name="four-row-groups-three-tables", n_q_heads=16, n_kv_heads=1, head_dim=128, dtype="bf16", l_ctx=800,
+         s_block=400, window=64, n_div=4, lsh_tables=3, lsh_bits=4),
+    # the widest rows with the longest block a context accepts: the finest key-range split
+    dict(name="max-block-f32-d128", n_q_heads=2, n_kv_heads=1, head_dim=128, dtype="f32", l_ctx=16384, s_block=16384,
+         window=8, n_div=8, lsh_tables=4, lsh_bits=8),
 ])
 def test_ragged_shapes(case):
     base = synth.WORKLOADS["tiny"]
@@ -188,9 +196,9 @@ def test_alpha_end_points(alpha):
     run_and_check(wl, label=f"tiny-alpha{alpha}")
 
 
-def test_llama128k_full_size_sampled_blocks():
+def test_llama128k_full_size_every_block():
     wl = synth.WORKLOADS["llama8b-128k"]
-    run_and_check(wl, check_blocks=[0, 13, 31])
+    run_and_check(wl)
 
 
 def test_gqa8_128k_full_size_sampled_blocks():
@@ -198,10 +206,26 @@ def test_gqa8_128k_full_size_sampled_blocks():
     run_and_check(wl, check_blocks=[0, 15])
 
 
-def test_llama64k_two_layers_sampled_blocks():
+def test_llama64k_four_layers_sampled_blocks():
     wl = synth.WORKLOADS["llama8b-64k"]
-    for layer in (0, 31):
-        run_and_check(wl, layer=layer, check_blocks=[0, 31])
+    for layer in (0, 10, 21, 31):
+        run_and_check(wl, layer=layer, check_blocks=[0, 16, 31])
+
+
+def test_count_parts_on_a_poisoned_workspace(monkeypatch):
+    """LASERKV_POISON_WORKSPACE=1 (read when a context is created) fills the fresh workspace with a non-zero
+    pattern.  With more query-row groups than tables some groups write no count part; the selection must
+    not read those parts, whatever the workspace held before."""
+    monkeypatch.setenv("LASERKV_POISON_WORKSPACE", "1")
+    base = synth.WORKLOADS["tiny"]
+    for case in (dict(name="poison-2-groups-1-table", n_q_heads=5, n_kv_heads=1, head_dim=64, dtype="bf16", l_ctx=1000,
+                      s_block=500, window=64, n_div=4, lsh_tables=1, lsh_bits=5),
+                 dict(name="poison-4-groups-2-tables", n_q_heads=16, n_kv_heads=1, head_dim=64, dtype="f32", l_ctx=640,
+                      s_block=320, window=64, n_div=4, lsh_tables=2, lsh_bits=6),
+                 dict(name="poison-4-groups-3-tables", n_q_heads=16, n_kv_heads=2, head_dim=128, dtype="bf16", l_ctx=800,
+                      s_block=400, window=64, n_div=4, lsh_tables=3, lsh_bits=4)):
+        wl = synth.shrink(base, index=23, needles_per_block=2, outlier_channels=2, **case)
+        run_and_check(wl, label=case["name"])
 
 
 def test_repeat_runs_are_bit_identical():
@@ -420,7 +444,7 @@ def test_bench_launch_configuration_full_size_against_oracle():
                 resid = np.setdiff1d(cand, st["k_exact_set"][h])
                 c_k = np.sort(st["cnt"][h][resid])[::-1][kl - 1]
                 for i in diff:
-                    assert abs(st["s_exact"][h][i] - s_k) <= 4 * tol * s_k or c_lo[h, i] <= c_k <= c_hi[h, i], (t, h, int(i))
+                    assert abs(st["s_exact"][h][i] - s_k) <= tol * s_k or c_lo[h, i] <= c_k <= c_hi[h, i], (t, h, int(i))
                 n_diff += diff.size
         say(f"[bench configuration blk {t}] kept rows differing from the oracle's at a threshold: {n_diff}")
         pos = comp.cache_pos[:, t * b_t:(t + 1) * b_t]
