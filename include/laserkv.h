@@ -21,6 +21,7 @@
 #ifndef LASERKV_H
 #define LASERKV_H
 
+#include <stddef.h>
 #include <stdint.h>
 
 #ifdef __cplusplus
@@ -152,6 +153,40 @@ int laserkv_compress_block(laserkv_ctx* ctx,
                            int64_t* cache_pos, int64_t pos_stride_head,
                            int64_t cache_len, int64_t cache_cap,
                            void* hip_stream);
+
+/* laserkv_compress_block for callers that cannot allocate device memory or hold a context: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, checks, kernels
+ * and results as laserkv_compress_block on a context created from *cfg, but the workspace is a fixed
+ * LKV_STATIC_SCRATCH_BYTES array inside the library (one copy per GPU, held until the process ends).
+ * The call allocates nothing (no hipMalloc / hipFree, no events).  cfg is a HOST pointer read during the
+ * call only.
+ *   - Configurations whose workspace exceeds the array (laserkv_static_workspace_bytes(cfg) >
+ *     LKV_STATIC_SCRATCH_BYTES) are rejected with LKV_EINVAL and a message; nothing is launched.
+ *   - Every call on a GPU shares that GPU's array, which keeps the previous call's intermediates: each call
+ *     rewrites all it reads, so no clearing is needed, but calls that overlap in time on one GPU (two
+ *     streams, two threads) race.  Issue them on one stream.
+ *   - laserkv_static_init does the once-per-device set-up (address of the array on the current device,
+ *     kernel attributes) ahead of time, e.g. before a graph capture begins; otherwise the first
+ *     laserkv_compress_block_static call on a device does it.
+ *   - errors are reported through laserkv_last_error(NULL); the external log-sum-exp of
+ *     laserkv_set_row_lse is not available here. */
+#define LKV_STATIC_SCRATCH_BYTES (32u << 20)
+int laserkv_static_init(void);
+size_t laserkv_static_workspace_bytes(const laserkv_config* cfg); /* 0 for an invalid configuration */
+int laserkv_compress_block_static(const laserkv_config* cfg,
+                                  const void* q_win, int64_t q_stride_head, int64_t q_stride_tok,
+                                  const void* k_blk, int64_t k_stride_head, int64_t k_stride_tok,
+                                  const void* v_blk, int64_t v_stride_head, int64_t v_stride_tok,
+                                  const void* k_ctx, int64_t c_stride_head, int64_t c_stride_tok,
+                                  const void* hyperplanes,
+                                  int32_t s_t, int32_t w, int32_t t_ctx,
+                                  int64_t block_pos0, int64_t q_pos0, int32_t causal,
+                                  int32_t n_anchor, int32_t n_local, int32_t k_exact, int32_t k_lsh,
+                                  int32_t* keep_idx,
+                                  void* k_cache, void* v_cache, int64_t cache_stride_head,
+                                  int64_t* cache_pos, int64_t pos_stride_head,
+                                  int64_t cache_len, int64_t cache_cap,
+                                  void* hip_stream);
 
 /* Boundary smoothing (Sec. 3.2) extended to context that is not re-read: keys outside a call (the rest
  * of the compressed cache, say) can join the softmax normaliser of Alg. 1 step 3 through one number per

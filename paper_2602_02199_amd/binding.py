@@ -22,7 +22,9 @@ EXPORTS = (
     "laserkv_partition", "laserkv_select_block", "laserkv_append", "laserkv_compress_block",
     "laserkv_profile_begin", "laserkv_profile_end", "laserkv_profile_isolate",
     "laserkv_score_block", "laserkv_select_consensus", "laserkv_append_shared", "laserkv_set_row_lse",
+    "laserkv_static_init", "laserkv_static_workspace_bytes", "laserkv_compress_block_static",
 )
+LKV_STATIC_SCRATCH_BYTES = 32 << 20
 KERNEL_NAMES = ("sweep1", "sweep2", "count", "select", "append")
 
 
@@ -76,6 +78,12 @@ def load():
         i32, i32, i32, i64, i64, i32, i32, i32, i32, i32,
         vp, vp, vp, i64, vp, i64, i64, i64, vp]
     lib.laserkv_compress_block.restype = C.c_int
+    lib.laserkv_static_init.argtypes = []
+    lib.laserkv_static_init.restype = C.c_int
+    lib.laserkv_static_workspace_bytes.argtypes = [C.POINTER(Config)]
+    lib.laserkv_static_workspace_bytes.restype = C.c_size_t
+    lib.laserkv_compress_block_static.argtypes = [C.POINTER(Config)] + lib.laserkv_compress_block.argtypes[1:]
+    lib.laserkv_compress_block_static.restype = C.c_int
     lib.laserkv_score_block.argtypes = [
         vp, vp, i64, i64, vp, i64, i64, vp, i64, i64, vp,
         i32, i32, i32, i64, i64, i32, vp, vp, i32, vp]
@@ -110,6 +118,40 @@ def laserkv_partition(B: int, n: int, alpha: float, s_t: int):
     if rc != LKV_OK:
         raise LaserKVError(rc, lib.laserkv_last_error(None).decode())
     return tuple(int(o.value) for o in out)
+
+
+def laserkv_static_init():
+    lib = load()
+    rc = lib.laserkv_static_init()
+    if rc != LKV_OK:
+        raise LaserKVError(rc, lib.laserkv_last_error(None).decode())
+
+
+def laserkv_static_workspace_bytes(cfg: Config) -> int:
+    return int(load().laserkv_static_workspace_bytes(C.byref(cfg)))
+
+
+def laserkv_compress_block_static(cfg: Config, q_win, k_blk, v_blk, k_ctx, hyperplanes, *, block_pos0, q_pos0=None,
+                                  causal=True, n_anchor, n_local, k_exact, k_lsh, keep_idx, k_cache, v_cache, cache_pos,
+                                  cache_len, stream):
+    """laserkv_compress_block on the library's static scratch (no context, no allocation).  stream: raw handle."""
+    lib = load()
+    d = cfg.head_dim
+    s_t, w = k_blk.shape[1], q_win.shape[1]
+    t_ctx = 0 if k_ctx is None else k_ctx.shape[1]
+    if q_pos0 is None:
+        q_pos0 = LKV_WINDOW_AT_BLOCK_END
+    qs, ks, vs = _strides3(q_win, d), _strides3(k_blk, d), _strides3(v_blk, d)
+    cs = _strides3(k_ctx, d) if k_ctx is not None else (0, 0)
+    assert hyperplanes.is_contiguous()
+    assert k_cache.stride(2) == 1 and k_cache.stride(1) == d and v_cache.stride() == k_cache.stride()
+    rc = lib.laserkv_compress_block_static(
+        C.byref(cfg), _ptr(q_win), qs[0], qs[1], _ptr(k_blk), ks[0], ks[1], _ptr(v_blk), vs[0], vs[1],
+        _ptr(k_ctx), cs[0], cs[1], _ptr(hyperplanes), s_t, w, t_ctx, block_pos0, q_pos0, 1 if causal else 0,
+        n_anchor, n_local, k_exact, k_lsh, _ptr(keep_idx), _ptr(k_cache), _ptr(v_cache), k_cache.stride(0),
+        _ptr(cache_pos), cache_pos.stride(0), cache_len, k_cache.shape[1], C.c_void_p(stream))
+    if rc != LKV_OK:
+        raise LaserKVError(rc, lib.laserkv_last_error(None).decode())
 
 
 def _ptr(t):

@@ -9,6 +9,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -20,7 +21,13 @@ constexpr int kMaxPlanes = 512;  // L * K
 
 char g_error[512] = "";
 
+constexpr int kMaxDevices = 64;
+
 }  // namespace
+
+// Workspace of laserkv_compress_block_static: one copy per GPU, held until the process ends.  The name is
+// a host-side stand-in; host code uses the per-device address from hipGetSymbolAddress (static_device()).
+static __device__ __align__(256) unsigned char scratch[LKV_STATIC_SCRATCH_BYTES];
 
 struct laserkv_ctx {
   laserkv_config cfg;
@@ -39,6 +46,7 @@ struct laserkv_ctx {
   uint16_t* sig_k;   // [H_kv, max_block, L]
   uint16_t* sig_q;   // [H_q, max_window, L]
   int m_pad;
+  bool owns_workspace;   // the buffers above came from hipMalloc and are freed by laserkv_destroy
   const float* row_lse;  // laserkv_set_row_lse: applies to every following scoring call until reset
   int only_kernel;   // >= 0: launch only this kernel kind (laserkv_profile_isolate); -1 normally
   // tuning switches, read from the environment once when the context is created
@@ -102,6 +110,80 @@ hipError_t timed(laserkv_ctx* ctx, int kind, hipStream_t st, F launch) {
   return hipSuccess;
 }
 
+
+// Configuration limits shared by every entry point that takes a laserkv_config.
+int check_config(const laserkv_config& c, const char* who) {
+  if (c.n_kv_heads < 1 || c.n_q_heads < c.n_kv_heads || c.n_q_heads % c.n_kv_heads)
+    return fail(nullptr, LKV_EINVAL, "%s: n_kv_heads must divide n_q_heads", who);
+  if (c.head_dim != 64 && c.head_dim != 128) return fail(nullptr, LKV_EINVAL, "%s: head_dim must be 64 or 128", who);
+  if (c.dtype != LKV_F32 && c.dtype != LKV_BF16) return fail(nullptr, LKV_EINVAL, "%s: unknown dtype", who);
+  if (c.lsh_tables < 1 || c.lsh_bits < 1 || c.lsh_bits > 16 || c.lsh_tables * c.lsh_bits > kMaxPlanes)
+    return fail(nullptr, LKV_EINVAL, "%s: need 1 <= K <= 16 and L*K <= %d", who, kMaxPlanes);
+  if (c.max_block < 1 || c.max_block > kMaxBlock) return fail(nullptr, LKV_EINVAL, "%s: max_block must be 1..%d", who, kMaxBlock);
+  if (c.max_window < 1 || (int64_t)(c.n_q_heads / c.n_kv_heads) * c.max_window > kMaxRows)
+    return fail(nullptr, LKV_EINVAL, "%s: G * max_window must be 1..%d", who, kMaxRows);
+  if (c.max_ctx_keys < 0) return fail(nullptr, LKV_EINVAL, "%s: max_ctx_keys < 0", who);
+  return LKV_OK;
+}
+
+// The device workspace of a configuration: eight buffers, in the order of WsIndex.
+constexpr int kWsBuffers = 8;
+enum WsIndex { WS_PART, WS_S_PART, WS_S_EXACT, WS_CNT, WS_CNT_SUM, WS_SIG_K, WS_SIG_Q, WS_QHIST };
+struct WsPlan {
+  int m_pad, max_ranges;
+  size_t bytes[kWsBuffers];  // 0: buffer not used by this configuration
+  size_t total() const {
+    size_t t = 0;
+    for (size_t b : bytes) t += (b + 255) & ~(size_t)255;
+    return t;
+  }
+};
+
+void plan_workspace(const laserkv_config& c, bool allow_qhist, WsPlan& w) {
+  const int group = c.n_q_heads / c.n_kv_heads;
+  const int m_rows = group * c.max_window;
+  const int rows_per_group = lkv::sweep_rows_per_group();
+  w.m_pad = (m_rows + rows_per_group - 1) / rows_per_group * rows_per_group;
+  const size_t n_qg_max = w.m_pad / rows_per_group;
+  // a key range never has fewer than 32 keys (wide rows and many planes shrink it that far), and the
+  // look-back keys have ranges of their own
+  w.max_ranges = ((c.max_block + 31) / 32 + (c.max_ctx_keys + 31) / 32 + 7) & ~7;
+  // histograms of the query codes (one per query-row group) are kept in global memory between the two
+  // sweeps when a head's tables fit 512 KiB per group
+  const size_t hist_bytes_head = ((size_t)c.lsh_tables << c.lsh_bits) * 2;
+  const bool use_qhist = allow_qhist && hist_bytes_head <= 512 * 1024;
+  const size_t hk = c.n_kv_heads, sb = c.max_block;
+  w.bytes[WS_PART] = hk * w.max_ranges * w.m_pad * sizeof(float2);
+  w.bytes[WS_S_PART] = n_qg_max * hk * sb * sizeof(float);
+  w.bytes[WS_S_EXACT] = hk * sb * sizeof(float);
+  w.bytes[WS_CNT] = n_qg_max * hk * sb * sizeof(int32_t);
+  w.bytes[WS_CNT_SUM] = hk * sb * sizeof(int32_t);
+  w.bytes[WS_SIG_K] = hk * sb * c.lsh_tables * sizeof(uint16_t);
+  w.bytes[WS_SIG_Q] = (size_t)c.n_q_heads * c.max_window * c.lsh_tables * sizeof(uint16_t);
+  w.bytes[WS_QHIST] = use_qhist ? n_qg_max * hk * hist_bytes_head : 0;
+}
+
+void init_ctx_fields(laserkv_ctx* ctx, const laserkv_config& c) {
+  ctx->cfg = c;
+  ctx->only_kernel = -1;
+  ctx->group = c.n_q_heads / c.n_kv_heads;
+  ctx->elem_size = c.dtype == LKV_BF16 ? 2 : 4;
+  ctx->sweep_wg_per_cu = 1;
+}
+
+void bind_workspace(laserkv_ctx* ctx, const WsPlan& w, void* const ptr[kWsBuffers]) {
+  ctx->m_pad = w.m_pad;
+  ctx->max_ranges = w.max_ranges;
+  ctx->part = (float2*)ptr[WS_PART];
+  ctx->s_part = (float*)ptr[WS_S_PART];
+  ctx->s_exact = (float*)ptr[WS_S_EXACT];
+  ctx->cnt = (int32_t*)ptr[WS_CNT];
+  ctx->cnt_sum = (int32_t*)ptr[WS_CNT_SUM];
+  ctx->sig_k = (uint16_t*)ptr[WS_SIG_K];
+  ctx->sig_q = (uint16_t*)ptr[WS_SIG_Q];
+  ctx->qhist = (uint32_t*)ptr[WS_QHIST];
+}
+
 }  // namespace
 
 extern "C" {
@@ -135,95 +217,53 @@ int laserkv_partition(int32_t B, int32_t n, double alpha, int32_t s_t,
 int laserkv_create(const laserkv_config* cfg, laserkv_ctx** out) {
   if (!cfg || !out) return fail(nullptr, LKV_EINVAL, "create: null argument");
   const laserkv_config& c = *cfg;
-  if (c.n_kv_heads < 1 || c.n_q_heads < c.n_kv_heads || c.n_q_heads % c.n_kv_heads)
-    return fail(nullptr, LKV_EINVAL, "create: n_kv_heads must divide n_q_heads");
-  if (c.head_dim != 64 && c.head_dim != 128) return fail(nullptr, LKV_EINVAL, "create: head_dim must be 64 or 128");
-  if (c.dtype != LKV_F32 && c.dtype != LKV_BF16) return fail(nullptr, LKV_EINVAL, "create: unknown dtype");
-  if (c.lsh_tables < 1 || c.lsh_bits < 1 || c.lsh_bits > 16 || c.lsh_tables * c.lsh_bits > kMaxPlanes)
-    return fail(nullptr, LKV_EINVAL, "create: need 1 <= K <= 16 and L*K <= %d", kMaxPlanes);
-  if (c.max_block < 1 || c.max_block > kMaxBlock) return fail(nullptr, LKV_EINVAL, "create: max_block must be 1..%d", kMaxBlock);
-  const int group = c.n_q_heads / c.n_kv_heads;
-  if (c.max_window < 1 || (int64_t)group * c.max_window > kMaxRows)
-    return fail(nullptr, LKV_EINVAL, "create: G * max_window must be 1..%d", kMaxRows);
-  if (c.max_ctx_keys < 0) return fail(nullptr, LKV_EINVAL, "create: max_ctx_keys < 0");
+  int rc = check_config(c, "create");
+  if (rc != LKV_OK) return rc;
 
   laserkv_ctx* ctx = new (std::nothrow) laserkv_ctx();
   if (!ctx) return fail(nullptr, LKV_ENOMEM, "create: host allocation failed");
   memset(ctx, 0, sizeof(*ctx));
-  ctx->only_kernel = -1;
-  ctx->cfg = c;
+  init_ctx_fields(ctx, c);
   ctx->ev_pool = new (std::nothrow) std::vector<hipEvent_t>();
   ctx->ev_kind = new (std::nothrow) std::vector<int>();
   if (!ctx->ev_pool || !ctx->ev_kind) {
-    delete ctx->ev_pool;
-    delete ctx->ev_kind;
-    delete ctx;
+    laserkv_destroy(ctx);
     return fail(nullptr, LKV_ENOMEM, "create: host allocation failed");
   }
-  ctx->group = group;
-  ctx->elem_size = c.dtype == LKV_BF16 ? 2 : 4;
   hipError_t e = hipGetDevice(&ctx->device);
-  hipDeviceProp_t prop;
-  if (e == hipSuccess) e = hipGetDeviceProperties(&prop, ctx->device);
+  if (e == hipSuccess) e = hipDeviceGetAttribute(&ctx->n_cu, hipDeviceAttributeMultiprocessorCount, ctx->device);
   if (e != hipSuccess) {
-    delete ctx->ev_pool;
-    delete ctx->ev_kind;
-    delete ctx;
+    laserkv_destroy(ctx);
     return fail_hip(nullptr, e, "create: device query");
   }
-  ctx->n_cu = prop.multiProcessorCount;
   e = lkv::init_kernel_attributes();
   if (e != hipSuccess) {
-    delete ctx->ev_pool;
-    delete ctx->ev_kind;
-    delete ctx;
+    laserkv_destroy(ctx);
     return fail_hip(nullptr, e, "create: kernel attribute");
   }
-  const int m_rows = group * c.max_window;
-  ctx->m_pad = (m_rows + 255) / 256 * 256;
-  const int n_qg_max = (m_rows + 127) / 128;
-  // histograms of the query codes (one per query-row group) are kept in global memory between the two
-  // sweeps when a head's tables fit 512 KiB per group
-  const size_t hist_bytes_head = ((size_t)c.lsh_tables << c.lsh_bits) * 2;
-  const bool use_qhist = hist_bytes_head <= 512 * 1024 && env_int("LASERKV_NO_QHIST", 0) == 0;
   ctx->sweep_wg_per_cu = env_int("LASERKV_SWEEP_WG_PER_CU", 1);
   if (ctx->sweep_wg_per_cu < 1) ctx->sweep_wg_per_cu = 1;
   ctx->append_split = env_int("LASERKV_APPEND_SPLIT", 0);
-  // a key range never has fewer than 32 keys (wide rows and many planes shrink it that far), and the
-  // look-back keys have ranges of their own
-  ctx->max_ranges = (c.max_block + 31) / 32 + (c.max_ctx_keys + 31) / 32;
-  ctx->max_ranges = (ctx->max_ranges + 7) & ~7;
-  const size_t hk = c.n_kv_heads, sb = c.max_block;
-  struct { void** p; size_t bytes; } allocs[] = {
-      {(void**)&ctx->part, hk * ctx->max_ranges * ctx->m_pad * sizeof(float2)},
-      {(void**)&ctx->s_part, (size_t)n_qg_max * hk * sb * sizeof(float)},
-      {(void**)&ctx->s_exact, hk * sb * sizeof(float)},
-      {(void**)&ctx->cnt, (size_t)n_qg_max * hk * sb * sizeof(int32_t)},
-      {(void**)&ctx->cnt_sum, hk * sb * sizeof(int32_t)},
-      {(void**)&ctx->sig_k, hk * sb * c.lsh_tables * sizeof(uint16_t)},
-      {(void**)&ctx->sig_q, (size_t)c.n_q_heads * c.max_window * c.lsh_tables * sizeof(uint16_t)},
-  };
-  for (auto& al : allocs) {
-    e = hipMalloc(al.p, al.bytes);
+  WsPlan ws;
+  plan_workspace(c, env_int("LASERKV_NO_QHIST", 0) == 0, ws);
+  void* ptr[kWsBuffers] = {};
+  for (int i = 0; i < kWsBuffers; ++i) {
+    if (!ws.bytes[i]) continue;
+    e = hipMalloc(&ptr[i], ws.bytes[i]);
     if (e != hipSuccess) {
+      for (int j = 0; j < i; ++j)
+        if (ptr[j]) (void)hipFree(ptr[j]);
       laserkv_destroy(ctx);
-      return fail(nullptr, LKV_ENOMEM, "create: hipMalloc of %zu bytes failed: %s", al.bytes, hipGetErrorString(e));
+      return fail(nullptr, LKV_ENOMEM, "create: hipMalloc of %zu bytes failed: %s", ws.bytes[i], hipGetErrorString(e));
     }
   }
-  const size_t qhist_bytes = (size_t)n_qg_max * hk * hist_bytes_head;
-  if (use_qhist) {
-    e = hipMalloc((void**)&ctx->qhist, qhist_bytes);
-    if (e != hipSuccess) {
-      laserkv_destroy(ctx);
-      return fail(nullptr, LKV_ENOMEM, "create: histogram workspace: %s", hipGetErrorString(e));
-    }
-  }
+  bind_workspace(ctx, ws, ptr);
+  ctx->owns_workspace = true;
   // LASERKV_POISON_WORKSPACE=1 (tests): fill the fresh workspace with a non-zero pattern, so that a kernel
   // reading what no kernel wrote shows up in the results instead of meeting zeros by luck
   if (env_int("LASERKV_POISON_WORKSPACE", 0)) {
-    for (auto& al : allocs)
-      if (e == hipSuccess) e = hipMemset(*al.p, 0xA5, al.bytes);
-    if (e == hipSuccess && ctx->qhist) e = hipMemset(ctx->qhist, 0xA5, qhist_bytes);
+    for (int i = 0; i < kWsBuffers; ++i)
+      if (e == hipSuccess && ptr[i]) e = hipMemset(ptr[i], 0xA5, ws.bytes[i]);
     if (e == hipSuccess) e = hipDeviceSynchronize();
     if (e != hipSuccess) {
       laserkv_destroy(ctx);
@@ -237,8 +277,9 @@ int laserkv_create(const laserkv_config* cfg, laserkv_ctx** out) {
 void laserkv_destroy(laserkv_ctx* ctx) {
   if (!ctx) return;
   void* ptrs[] = {ctx->part, ctx->s_part, ctx->s_exact, ctx->cnt, ctx->cnt_sum, ctx->qhist, ctx->sig_k, ctx->sig_q};
-  for (void* p : ptrs)
-    if (p) (void)hipFree(p);
+  if (ctx->owns_workspace)
+    for (void* p : ptrs)
+      if (p) (void)hipFree(p);
   if (ctx->ev_pool)
     for (hipEvent_t ev : *ctx->ev_pool) (void)hipEventDestroy(ev);
   delete ctx->ev_pool;
@@ -669,6 +710,108 @@ int laserkv_profile_end(laserkv_ctx* ctx, double* ms_per_kernel, int64_t* launch
   }
   ctx->ev_kind->clear();
   return LKV_OK;
+}
+
+}  // extern "C"
+
+namespace {
+
+struct StaticDevice {
+  bool ready;
+  unsigned char* scratch;  // device address of this GPU's copy of the scratch array
+  int n_cu;
+};
+StaticDevice g_static[kMaxDevices];
+std::mutex g_static_mutex;
+
+// Once per device, with that device current: the address of its scratch array, its compute-unit count and
+// the kernels' LDS attributes.  Nothing here allocates device memory.
+int static_device(StaticDevice** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return fail_hip(nullptr, e, "compress_block_static: hipGetDevice");
+  if (dev < 0 || dev >= kMaxDevices) return fail(nullptr, LKV_EINVAL, "compress_block_static: device %d not supported", dev);
+  std::lock_guard<std::mutex> lock(g_static_mutex);
+  StaticDevice& sd = g_static[dev];
+  if (!sd.ready) {
+    void* ptr = nullptr;
+    e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !ptr) return fail_hip(nullptr, e, "compress_block_static: hipGetSymbolAddress");
+    int n_cu = 0;
+    e = hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev);
+    if (e != hipSuccess) return fail_hip(nullptr, e, "compress_block_static: device query");
+    e = lkv::init_kernel_attributes();
+    if (e != hipSuccess) return fail_hip(nullptr, e, "compress_block_static: kernel attribute");
+    sd.scratch = static_cast<unsigned char*>(ptr);
+    sd.n_cu = n_cu;
+    sd.ready = true;
+  }
+  *out = &sd;
+  return LKV_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int laserkv_static_init(void) {
+  StaticDevice* sd = nullptr;
+  return static_device(&sd);
+}
+
+size_t laserkv_static_workspace_bytes(const laserkv_config* cfg) {
+  if (!cfg || check_config(*cfg, "static_workspace_bytes") != LKV_OK) return 0;
+  WsPlan ws;
+  plan_workspace(*cfg, true, ws);
+  return ws.total();
+}
+
+int laserkv_compress_block_static(const laserkv_config* cfg,
+                                  const void* q_win, int64_t q_stride_head, int64_t q_stride_tok,
+                                  const void* k_blk, int64_t k_stride_head, int64_t k_stride_tok,
+                                  const void* v_blk, int64_t v_stride_head, int64_t v_stride_tok,
+                                  const void* k_ctx, int64_t c_stride_head, int64_t c_stride_tok,
+                                  const void* hyperplanes,
+                                  int32_t s_t, int32_t w, int32_t t_ctx,
+                                  int64_t block_pos0, int64_t q_pos0, int32_t causal,
+                                  int32_t n_anchor, int32_t n_local, int32_t k_exact, int32_t k_lsh,
+                                  int32_t* keep_idx,
+                                  void* k_cache, void* v_cache, int64_t cache_stride_head,
+                                  int64_t* cache_pos, int64_t pos_stride_head,
+                                  int64_t cache_len, int64_t cache_cap,
+                                  void* hip_stream) {
+  if (!cfg) return fail(nullptr, LKV_EINVAL, "compress_block_static: null configuration");
+  int rc = check_config(*cfg, "compress_block_static");
+  if (rc != LKV_OK) return rc;
+  WsPlan ws;
+  plan_workspace(*cfg, true, ws);
+  if (ws.total() > LKV_STATIC_SCRATCH_BYTES)
+    return fail(nullptr, LKV_EINVAL, "compress_block_static: this configuration needs %zu bytes of workspace, the static "
+                "scratch holds %zu (use laserkv_create + laserkv_compress_block)", ws.total(), (size_t)LKV_STATIC_SCRATCH_BYTES);
+  StaticDevice* sd = nullptr;
+  rc = static_device(&sd);
+  if (rc != LKV_OK) return rc;
+  // a context on the stack whose workspace is carved out of this GPU's scratch array
+  laserkv_ctx ctx;
+  memset(&ctx, 0, sizeof(ctx));
+  init_ctx_fields(&ctx, *cfg);
+  hipError_t e = hipGetDevice(&ctx.device);
+  if (e != hipSuccess) return fail_hip(nullptr, e, "compress_block_static: hipGetDevice");
+  ctx.n_cu = sd->n_cu;
+  void* ptr[kWsBuffers];
+  size_t off = 0;
+  for (int i = 0; i < kWsBuffers; ++i) {
+    ptr[i] = ws.bytes[i] ? sd->scratch + off : nullptr;
+    off += (ws.bytes[i] + 255) & ~(size_t)255;
+  }
+  bind_workspace(&ctx, ws, ptr);
+  rc = laserkv_compress_block(&ctx, q_win, q_stride_head, q_stride_tok, k_blk, k_stride_head, k_stride_tok,
+                              v_blk, v_stride_head, v_stride_tok, k_ctx, c_stride_head, c_stride_tok, hyperplanes,
+                              s_t, w, t_ctx, block_pos0, q_pos0, causal, n_anchor, n_local, k_exact, k_lsh, keep_idx,
+                              k_cache, v_cache, cache_stride_head, cache_pos, pos_stride_head, cache_len, cache_cap,
+                              hip_stream);
+  if (rc != LKV_OK) memcpy(g_error, ctx.error, sizeof(g_error));  // the stack context is gone after return
+  return rc;
 }
 
 }  // extern "C"

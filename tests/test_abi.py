@@ -58,6 +58,18 @@ def test_create_rejects_bad_configs_without_touching_a_gpu(lib):
         assert not out.value and lib.laserkv_last_error(None)
 
 
+def test_static_workspace_size_is_reported_without_a_gpu(lib):
+    small = binding.Config(4, 2, 64, 0, 8, 8, 512, 32, 56)
+    bench = binding.Config(32, 8, 128, 1, 32, 12, 4096, 128, 248)
+    huge = binding.Config(64, 64, 128, 1, 32, 12, 16384, 16, 4096)
+    assert 0 < binding.laserkv_static_workspace_bytes(small) < binding.laserkv_static_workspace_bytes(bench)
+    assert binding.laserkv_static_workspace_bytes(bench) <= binding.LKV_STATIC_SCRATCH_BYTES
+    assert binding.laserkv_static_workspace_bytes(huge) > binding.LKV_STATIC_SCRATCH_BYTES
+    assert binding.laserkv_static_workspace_bytes(binding.Config(5, 2, 64, 0, 8, 8, 512, 32, 56)) == 0
+    header = open(os.path.join(ROOT, "include", "laserkv.h")).read()
+    assert re.search(r"#define LKV_STATIC_SCRATCH_BYTES \(32u << 20\)", header) and binding.LKV_STATIC_SCRATCH_BYTES == 32 << 20
+
+
 def test_missing_library_fails_loudly(monkeypatch):
     monkeypatch.setattr(binding, "_lib", None)
     monkeypatch.setattr(binding, "LIB_PATH", "/nonexistent/liblaserkv.so")
