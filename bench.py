@@ -41,42 +41,13 @@ def algorithmic_work(wl, B):
     }
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="llama8b-128k")
-    ap.add_argument("--layer", type=int, default=0)
-    ap.add_argument("--mode", choices=["graph", "eager"], default="graph")
-    ap.add_argument("--profile-steps", type=int, default=5, help="replays per kernel kind for the per-kernel durations; 0 skips them")
-    ap.add_argument("--unfused", action="store_true", help="laserkv_select_block + laserkv_append instead of laserkv_compress_block")
-    ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MIB",
-                    help="also run one plain device copy of this many MiB (a known-size reference for HBM byte counters)")
-    ap.add_argument("--cpu-seconds", type=float, default=12.0, help="lower bound of oracle work for cpu_baseline; 0 skips")
-    ap.add_argument("--policy", choices=["per-head", "consensus"], default="per-head",
-                    help="consensus: the global-consensus variant (scores summed over --layers layers and all heads, one "
-                         "selection per block); prints its own JSON line, not the headline metric")
-    ap.add_argument("--layers", type=int, default=4, help="layers summed by --policy consensus")
-    ap.add_argument("--batch", type=int, default=1,
-                    help="fold this many independent sequences into the head axis (heads x batch per call); the rate then "
-                         "counts batch x context tokens. 1 is the headline configuration")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU (no collectives, no sharding); --gpus must be 1", file=sys.stderr)
-        return 2
-
+def measure(wl, args, dev, cpu_seconds):
+    """Times one workload: returns the fields of the JSON line that depend on the workload."""
+    import statistics
     import torch
     from paper_2602_02199_amd import synth
     from paper_2602_02199_amd.driver import LayerCompressor
 
-    wl = synth.WORKLOADS[args.workload]
-    if args.batch > 1:
-        wl = synth.shrink(wl, name=f"{wl.name}-x{args.batch}", n_q_heads=wl.n_q_heads * args.batch,
-                          n_kv_heads=wl.n_kv_heads * args.batch)
-    dev = "cuda:0"
-    if args.policy == "consensus":
-        return bench_consensus(args, wl, dev)
     comp = LayerCompressor(wl, dev)
     t_gen = time.time()
     data = synth.make_layer(wl, args.layer, comp.parts[0])
@@ -107,17 +78,24 @@ def main():
                 comp.run_plan(plan)
             graph.replay()
             stream.synchronize()
+        # exactly `steps` timed steps between two synchronisations; an event on the launch stream after every
+        # step gives the per-step times, whose median is the reported step time
+        marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        for _ in range(args.steps):
+        marks[0].record(stream)
+        for i in range(args.steps):
             if graph is not None:
                 graph.replay()
             else:
                 comp.run_plan(plan)
+            marks[i + 1].record(stream)
         stream.synchronize()
         torch.cuda.synchronize()
         t1 = time.perf_counter()
-        ms_per_step = (t1 - t0) * 1e3 / args.steps
+        per_step = [marks[i].elapsed_time(marks[i + 1]) for i in range(args.steps)]
+        ms_mean = (t1 - t0) * 1e3 / args.steps
+        ms_per_step = statistics.median(per_step)
         # which kernels one layer launches, and how often: one pass with an event pair around every launch
         comp.lib.laserkv_profile_begin()
         comp.run_plan(plan)
@@ -157,53 +135,120 @@ def main():
         torch.cuda.synchronize()
     tokens = ddev["k"].shape[1] * args.batch
     value = tokens / (ms_per_step * 1e-3)
+    res = dict(value=round(value, 1), ms_per_step=round(ms_per_step, 4), ms_per_step_mean=round(ms_mean, 4),
+               ms_per_step_min=round(min(per_step), 4), ms_per_step_max=round(max(per_step), 4),
+               config=dict(workload=wl.name, l_ctx=wl.l_ctx, s_block=wl.s_block, window=wl.window, n=wl.n_div,
+                           lsh_tables=wl.lsh_tables, lsh_bits=wl.lsh_bits, n_q_heads=wl.n_q_heads,
+                           n_kv_heads=wl.n_kv_heads, head_dim=wl.head_dim, budget_per_block=comp.B,
+                           blocks=wl.n_blocks, layers_timed=1, launch=args.mode, sequences=args.batch,
+                           step_time="median of the timed steps",
+                           entry="laserkv_select_block+laserkv_append" if args.unfused else "laserkv_compress_block"),
+               roofline=None, cpu_baseline=None)
 
     work = algorithmic_work(wl, comp.B)
     if not args.unfused:  # the last kernel selects and appends
         work["select"] = ("hbm", work["select"][1] + work["append"][1])
     if not any(v["launches"] for v in kern.values()):
-        print(json.dumps(dict(value=round(value, 1), unit="tokens/s/layer", ms_per_step=round(ms_per_step, 4),
-                              note="no per-kernel timing requested: roofline omitted")), flush=True)
-        return 0
-    dom = max(kern, key=lambda k: kern[k]["avg_us"])
-    bound, amount = work[dom]
-    dur_s = kern[dom]["avg_us"] * 1e-6
-    if bound == "mfma":
-        peak = PEAK_MFMA_BF16_TFLOPS if wl.dtype == "bf16" else PEAK_MFMA_F32_TFLOPS
-        achieved, unit = amount / dur_s / 1e12, "TFLOP/s"
-    else:
-        peak, achieved, unit = PEAK_HBM_GBS, amount / dur_s / 1e9, "GB/s"
+        return res
+    peak_mfma = PEAK_MFMA_BF16_TFLOPS if wl.dtype == "bf16" else PEAK_MFMA_F32_TFLOPS
+    per_kernel = {}
+    for name, v in kern.items():
+        if not v["launches"]:
+            continue
+        bound, amount = work[name]
+        dur_s = v["avg_us"] * 1e-6
+        if bound == "mfma":
+            peak, achieved, unit = peak_mfma, amount / dur_s / 1e12, "TFLOP/s"
+        else:
+            peak, achieved, unit = PEAK_HBM_GBS, amount / dur_s / 1e9, "GB/s"
+        per_kernel[name] = dict(bound=bound, avg_us=round(v["avg_us"], 2), achieved=round(achieved, 3), peak=peak,
+                                unit=unit, frac=round(achieved / peak, 4), launches_per_step=v["launches"])
+    dom = max(per_kernel, key=lambda k: per_kernel[k]["avg_us"])
     traffic = None
     tpath = os.path.join(ROOT, "profiles", f"traffic_{wl.name}.json")
     if os.path.exists(tpath):
         traffic = json.load(open(tpath)).get(dom)
-    roofline = dict(bound=bound, kernel=dom, achieved=round(achieved, 3), peak=peak, unit=unit,
-                    frac=round(achieved / peak, 4), traffic=traffic,
-                    avg_us=round(kern[dom]["avg_us"], 2),
-                    per_kernel_us={k: round(v["avg_us"], 2) for k, v in kern.items()})
+    d = per_kernel[dom]
+    roofline = dict(bound=d["bound"], kernel=dom, achieved=d["achieved"], peak=d["peak"], unit=d["unit"],
+                    frac=d["frac"], traffic=traffic, avg_us=d["avg_us"], kernels=per_kernel,
+                    targets="score/projection kernels >= 0.50 of bf16 MFMA peak, hash/select/gather >= 0.60 of HBM peak: "
+                            + ("met" if all(v["frac"] >= (0.5 if v["bound"] == "mfma" else 0.6) for v in per_kernel.values())
+                               else "NOT met"))
     # whole-path roofline: serial sum of the contraction time at MFMA peak and the byte time at HBM peak
     es = 2 if wl.dtype == "bf16" else 4
     flops_blk = work["sweep1"][1]
     bytes_blk = wl.n_kv_heads * wl.s_block * wl.head_dim * es + wl.n_q_heads * wl.window * wl.head_dim * es \
         + work["append"][1]
-    peak_f = (PEAK_MFMA_BF16_TFLOPS if wl.dtype == "bf16" else PEAK_MFMA_F32_TFLOPS) * 1e12
-    t_roof = (flops_blk / peak_f + bytes_blk / (PEAK_HBM_GBS * 1e9)) * wl.n_blocks
+    t_roof = (flops_blk / (peak_mfma * 1e12) + bytes_blk / (PEAK_HBM_GBS * 1e9)) * wl.n_blocks
     roofline["path_frac_of_roofline"] = round(t_roof / (ms_per_step * 1e-3), 4)
+    res["roofline"] = roofline
+    if cpu_seconds > 0:
+        res["cpu_baseline"] = cpu_baseline(wl, data, comp.B, cpu_seconds)
+    del comp, ddev, data
+    torch.cuda.empty_cache()
+    return res
 
-    cpu = None
-    if args.cpu_seconds > 0:
-        cpu = cpu_baseline(wl, data, comp.B, args.cpu_seconds)
 
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="llama8b-128k")
+    ap.add_argument("--secondary", default="gqa8-128k",
+                    help="a second workload timed the same way and reported as the `secondary` object of the JSON line "
+                         "('none' skips it); not run with --batch, --calibrate-copy or --profile-steps 0")
+    ap.add_argument("--layer", type=int, default=0)
+    ap.add_argument("--mode", choices=["graph", "eager"], default="graph")
+    ap.add_argument("--profile-steps", type=int, default=5, help="replays per kernel kind for the per-kernel durations; 0 skips them")
+    ap.add_argument("--unfused", action="store_true", help="laserkv_select_block + laserkv_append instead of laserkv_compress_block")
+    ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MIB",
+                    help="also run one plain device copy of this many MiB (a known-size reference for HBM byte counters)")
+    ap.add_argument("--cpu-seconds", type=float, default=12.0, help="lower bound of oracle work for cpu_baseline; 0 skips")
+    ap.add_argument("--policy", choices=["per-head", "consensus"], default="per-head",
+                    help="consensus: the global-consensus variant (scores summed over --layers layers and all heads, one "
+                         "selection per block); prints its own JSON line, not the headline metric")
+    ap.add_argument("--layers", type=int, default=4, help="layers summed by --policy consensus")
+    ap.add_argument("--batch", type=int, default=1,
+                    help="fold this many independent sequences into the head axis (heads x batch per call); the rate then "
+                         "counts batch x context tokens. 1 is the headline configuration")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (no collectives, no sharding); --gpus must be 1", file=sys.stderr)
+        return 2
+    if args.steps < 1:
+        print("bench.py: --steps must be at least 1", file=sys.stderr)
+        return 2
+
+    from paper_2602_02199_amd import synth
+
+    wl = synth.WORKLOADS[args.workload]
+    if args.batch > 1:
+        wl = synth.shrink(wl, name=f"{wl.name}-x{args.batch}", n_q_heads=wl.n_q_heads * args.batch,
+                          n_kv_heads=wl.n_kv_heads * args.batch)
+    dev = "cuda:0"
+    if args.policy == "consensus":
+        return bench_consensus(args, wl, dev)
+    res = measure(wl, args, dev, args.cpu_seconds)
+    if res["roofline"] is None:
+        print(json.dumps(dict(value=res["value"], unit="tokens/s/layer", ms_per_step=res["ms_per_step"],
+                              note="no per-kernel timing requested: roofline omitted")), flush=True)
+        return 0
+    secondary = None
+    if args.secondary not in ("none", args.workload) and args.batch == 1 and not args.calibrate_copy:
+        sec = measure(synth.WORKLOADS[args.secondary], args, dev, 0.0)
+        r = sec["roofline"]
+        secondary = dict(workload=args.secondary, value=sec["value"], unit="tokens/s/layer", ms_per_step=sec["ms_per_step"],
+                         ms_per_step_mean=sec["ms_per_step_mean"], budget_per_block=sec["config"]["budget_per_block"],
+                         blocks=sec["config"]["blocks"], dominant_kernel=r["kernel"], bound=r["bound"], frac=r["frac"],
+                         avg_us=r["avg_us"], traffic=r["traffic"], kernels=r["kernels"],
+                         path_frac_of_roofline=r["path_frac_of_roofline"])
     out = dict(metric="prefill-compression tokens/s/layer (score+LSH+top-k+gather) @128k; % roofline",
-               value=round(value, 1), unit="tokens/s/layer", n_gpus=1, steps=args.steps, warmup=args.warmup,
-               ms_per_step=round(ms_per_step, 4), higher_is_better=True, scaling="weak", vs_baseline=None,
-               dtype=wl.dtype, data="synthetic",
-               config=dict(workload=wl.name, l_ctx=wl.l_ctx, s_block=wl.s_block, window=wl.window, n=wl.n_div,
-                           lsh_tables=wl.lsh_tables, lsh_bits=wl.lsh_bits, n_q_heads=wl.n_q_heads,
-                           n_kv_heads=wl.n_kv_heads, head_dim=wl.head_dim, budget_per_block=comp.B,
-                           blocks=wl.n_blocks, layers_timed=1, launch=args.mode, sequences=args.batch,
-                           entry="laserkv_select_block+laserkv_append" if args.unfused else "laserkv_compress_block"),
-               roofline=roofline, cpu_baseline=cpu)
+               value=res["value"], unit="tokens/s/layer", n_gpus=1, steps=args.steps, warmup=args.warmup,
+               ms_per_step=res["ms_per_step"], higher_is_better=True, scaling="weak", vs_baseline=None,
+               dtype=wl.dtype, data="synthetic", config=res["config"], roofline=res["roofline"],
+               cpu_baseline=res["cpu_baseline"], ms_per_step_mean=res["ms_per_step_mean"],
+               ms_per_step_min=res["ms_per_step_min"], ms_per_step_max=res["ms_per_step_max"], secondary=secondary)
     print(json.dumps(out), flush=True)
     return 0
 

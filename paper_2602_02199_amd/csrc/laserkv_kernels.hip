@@ -636,8 +636,9 @@ __global__ __launch_bounds__(PASS_WAVES * 64) void pass_kernel(PassParams p) {
       }
       uint16_t* dst = p.sig_k + ((size_t)h * p.s_t + seg_row0 + vr) * p.n_tables + tab0 + tb;
       if (tb + 8 <= n_tab && ((reinterpret_cast<uintptr_t>(dst) & 15) == 0)) {
-        *reinterpret_cast<uint4*>(dst) = make_uint4(codes[0] | (codes[1] << 16), codes[2] | (codes[3] << 16),
-                                                    codes[4] | (codes[5] << 16), codes[6] | (codes[7] << 16));
+        const uint4 cv = make_uint4(codes[0] | (codes[1] << 16), codes[2] | (codes[3] << 16),
+                                    codes[4] | (codes[5] << 16), codes[6] | (codes[7] << 16));
+        *reinterpret_cast<uint4*>(dst) = cv;
       } else {
 #pragma unroll
         for (int u = 0; u < 8; ++u)
@@ -734,17 +735,27 @@ __global__ __launch_bounds__(COUNT_THREADS) void count_kernel(CountParams p) {
 // descent over 8-bit digits from the top (LDS histogram, four interleaved copies against same-
 // address atomics), which also yields how many keys equal to the threshold are still needed; those
 // are taken in index order via a prefix count.
+//
+// The kernel is a chain of short workgroup-wide phases, so each round of the descent is kept to ONE
+// barrier: after the histogram is complete every wave scans it redundantly (lane l owns digits
+// 4l..4l+3) and learns the chosen digit through a wave broadcast; nothing goes back through LDS.  Three
+// histogram buffers rotate, the one read in round r being cleared during round r + 1 and reused in
+// round r + 3.
 // ---------------------------------------------------------------------------------------------
 //
 // FUSED = true also appends: a head's selection is then computed redundantly by `split` workgroups
 // (the inputs are L2-resident and the compute units would idle otherwise), and each of them copies
 // its share of the kept K/V rows to the cache tail.  That saves a kernel boundary, which on this
 // chip costs about as much as the whole copy.
+constexpr int SEL_COPIES = 4;
+constexpr int SEL_BUFFERS = 3;
+
 template <int EPT, bool FUSED>
 __global__ __launch_bounds__(1024) void select_kernel(SelectParams p, AppendParams ap, int split) {
-  __shared__ uint32_t sHist[4][256];
+  __shared__ __align__(16) uint32_t sHist[SEL_BUFFERS][SEL_COPIES][256];
   __shared__ int sWave[16];
-  __shared__ int sPick[2];  // digit chosen in this round, keys still needed below it
+  __shared__ uint32_t sList[64];  // keys that share the threshold's leading digits
+  __shared__ int sListN;
   __shared__ uint32_t sMaxCnt;  // largest collision count among the candidates
   __shared__ int sKeep[FUSED ? 1024 : 1];  // FUSED: the kept indices this workgroup copies
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
@@ -852,73 +863,91 @@ __global__ __launch_bounds__(1024) void select_kernel(SelectParams p, AppendPara
     __syncthreads();  // sWave free again
     if (lane == 63) sWave[wave] = inc;
     __syncthreads();
-    int base = 0;
-#pragma unroll
-    for (int w = 0; w < 16; ++w) base += (w < wave) ? sWave[w] : 0;
+    // the 16 wave totals, one per lane of every 16-lane row, prefix-summed inside the row
+    int wt = sWave[lane & 15];
+    wt += __builtin_amdgcn_update_dpp(0, wt, 0x111, 0xf, 0xf, true);  // row_shr:1
+    wt += __builtin_amdgcn_update_dpp(0, wt, 0x112, 0xf, 0xf, true);  // row_shr:2
+    wt += __builtin_amdgcn_update_dpp(0, wt, 0x114, 0xf, 0xf, true);  // row_shr:4
+    wt += __builtin_amdgcn_update_dpp(0, wt, 0x118, 0xf, 0xf, true);  // row_shr:8
+    const int base = wave ? __builtin_amdgcn_readlane(wt, wave - 1) : 0;
     return base + inc - v;
   };
-  // marks in sel[] the k active elements ranked first by (val descending, index ascending);
-  // val < 2^(8*n_digits)
-  auto take_top = [&](const uint32_t* val, const bool* active, int k, int n_digits) {
-    if (k <= 0) return;  // block-uniform
+  int round_no = 0;  // rounds of both descents so far: selects the histogram buffer
+  // The k-th largest value among the active elements (val < 2^(8*n_digits)): returns it in thr, with `need`
+  // = how many of the `in_bin` active elements equal to it belong to the top k.  All three block-uniform.
+  auto kth_largest = [&](const uint32_t* val, const bool* active, int k, int n_digits, uint32_t& thr, int& need, int& in_bin) {
     uint32_t prefix = 0u, pmask = 0u;
-    int need = k;
+    need = k;
+    in_bin = 0;
     for (int dg = n_digits - 1; dg >= 0; --dg) {
       const int shift = 8 * dg;
-      // the histogram is zero here: cleared before the first use and by wave 0 after every read
+      const int buf = round_no % SEL_BUFFERS;
+      // buffer `buf` is zero here: cleared at kernel start or two rounds ago
 #pragma unroll
       for (int e = 0; e < EPT; ++e)
-        if (active[e] && (val[e] & pmask) == prefix) atomicAdd(&sHist[lane & 3][(val[e] >> shift) & 255u], 1u);
+        if (active[e] && (val[e] & pmask) == prefix) atomicAdd(&sHist[buf][lane & 3][(val[e] >> shift) & 255u], 1u);
       __syncthreads();
-      if (wave == 0) {
-        // lane l owns digits 4l..4l+3; walk from the top digit down
-        uint4 q[4];
+      // the buffer of the round before has been read by every wave: clear it for the round after next
+      if (round_no > 0) sHist[(round_no - 1) % SEL_BUFFERS][tid >> 8][tid & 255] = 0u;
+      ++round_no;
+      // every wave: lane l owns digits 4l..4l+3; walk from the top digit down
+      uint4 q[SEL_COPIES];
 #pragma unroll
-        for (int b = 0; b < 4; ++b) {
-          q[b] = *reinterpret_cast<const uint4*>(&sHist[b][4 * lane]);
-          *reinterpret_cast<uint4*>(&sHist[b][4 * lane]) = make_uint4(0u, 0u, 0u, 0u);
-        }
-        const uint32_t c[4] = {q[0].x + q[1].x + q[2].x + q[3].x, q[0].y + q[1].y + q[2].y + q[3].y,
-                               q[0].z + q[1].z + q[2].z + q[3].z, q[0].w + q[1].w + q[2].w + q[3].w};
-        const int mine = (int)(c[0] + c[1] + c[2] + c[3]);
-        const int incl = wave_incl_scan(mine);
-        const int total = __builtin_amdgcn_readlane(incl, 63);
-        int above = total - incl;  // keys in digits owned by higher lanes
-        // the digit holding the need-th largest key: above < need <= above + count
+      for (int b = 0; b < SEL_COPIES; ++b) q[b] = *reinterpret_cast<const uint4*>(&sHist[buf][b][4 * lane]);
+      const uint32_t c[4] = {q[0].x + q[1].x + q[2].x + q[3].x, q[0].y + q[1].y + q[2].y + q[3].y,
+                             q[0].z + q[1].z + q[2].z + q[3].z, q[0].w + q[1].w + q[2].w + q[3].w};
+      const int mine = (int)(c[0] + c[1] + c[2] + c[3]);
+      const int incl = wave_incl_scan(mine);
+      const int total = __builtin_amdgcn_readlane(incl, 63);
+      int above = total - incl;  // keys in digits owned by higher lanes
+      // the digit holding the need-th largest key: above < need <= above + count (one lane, one digit)
+      int p_dig = -1, p_need = 0, p_cnt = 0;
 #pragma unroll
-        for (int b = 3; b >= 0; --b) {
-          if (above < need && need <= above + (int)c[b]) {
-            sPick[0] = 4 * lane + b;
-            sPick[1] = need - above;
-          }
-          above += (int)c[b];
-        }
+      for (int b = 3; b >= 0; --b) {
+        const bool hit = above < need && need <= above + (int)c[b];
+        p_dig = hit ? 4 * lane + b : p_dig;
+        p_need = hit ? need - above : p_need;
+        p_cnt = hit ? (int)c[b] : p_cnt;
+        above += (int)c[b];
       }
-      __syncthreads();
-      prefix |= (uint32_t)sPick[0] << shift;
+      const uint64_t hit_mask = __ballot(p_dig >= 0);
+      const int src = hit_mask ? __builtin_ctzll(hit_mask) : 0;
+      prefix |= (uint32_t)__builtin_amdgcn_readlane(p_dig, src) << shift;
       pmask |= 255u << shift;
-      need = sPick[1];
-    }
-    // prefix is the k-th largest value; `need` of the keys equal to it are taken, lowest index first
-    int n_eq = 0;
+      need = __builtin_amdgcn_readlane(p_need, src);
+      in_bin = __builtin_amdgcn_readlane(p_cnt, src);
+      if (dg > 0 && in_bin <= 64) {  // block-uniform
+        // few keys share the chosen digits: every wave ranks them against each other (one key per
+        // lane) instead of descending through the remaining digits
 #pragma unroll
-    for (int e = 0; e < EPT; ++e) n_eq += (active[e] && val[e] == prefix) ? 1 : 0;
-    int rank = block_excl_scan(n_eq);
-#pragma unroll
-    for (int e = 0; e < EPT; ++e) {
-      if (active[e]) {
-        if (val[e] > prefix) {
-          sel[e] = true;
-        } else if (val[e] == prefix) {
-          if (rank < need) sel[e] = true;
-          ++rank;
+        for (int e = 0; e < EPT; ++e)
+          if (active[e] && (val[e] & pmask) == prefix) sList[atomicAdd(&sListN, 1)] = val[e];
+        __syncthreads();
+        if (tid == 0) sListN = 0;  // next used after at least one more barrier
+        const uint32_t v = lane < in_bin ? sList[lane] : 0u;
+        int gt = 0, ge = 0;
+        for (int j = 0; j < in_bin; ++j) {
+          const uint32_t u = (uint32_t)__builtin_amdgcn_readlane((int)v, j);
+          gt += u > v ? 1 : 0;
+          ge += u >= v ? 1 : 0;
         }
+        const uint64_t m2 = __ballot(lane < in_bin && gt < need && need <= ge);  // equal keys agree on the values
+        const int s2 = m2 ? __builtin_ctzll(m2) : 0;
+        prefix = (uint32_t)__builtin_amdgcn_readlane((int)v, s2);
+        const int gt_s = __builtin_amdgcn_readlane(gt, s2), ge_s = __builtin_amdgcn_readlane(ge, s2);
+        need -= gt_s;
+        in_bin = ge_s - gt_s;
+        break;
       }
     }
+    thr = prefix;
   };
 
-  sHist[tid >> 8][tid & 255] = 0u;
-  if (tid == 0) sMaxCnt = 0u;
+  for (int i = tid; i < SEL_BUFFERS * SEL_COPIES * 256; i += 1024) (&sHist[0][0][0])[i] = 0u;
+  if (tid == 0) {
+    sMaxCnt = 0u;
+    sListN = 0;
+  }
   __syncthreads();
   {
     // Collision counts are mostly tiny, so their top byte is usually zero for every candidate: the
@@ -931,34 +960,74 @@ __global__ __launch_bounds__(1024) void select_kernel(SelectParams p, AppendPara
     for (int off = 32; off > 0; off >>= 1) mx = max(mx, (uint32_t)__shfl_xor((int)mx, off));
     if (lane == 0 && mx) atomicMax(&sMaxCnt, mx);
   }
-  take_top(key, cand, p.k_exact, 4);
+  // stage 1 (Alg. 1 step 4): the k_exact candidates ranked first by (score descending, index ascending)
+  if (p.k_exact > 0) {  // block-uniform
+    uint32_t thr;
+    int need, in_bin;
+    kth_largest(key, cand, p.k_exact, 4, thr, need, in_bin);
+    int rank = 0;
+    if (need < in_bin) {  // ties at the threshold (rare for scores): the lowest indices win
+      int n_eq = 0;
+#pragma unroll
+      for (int e = 0; e < EPT; ++e) n_eq += (cand[e] && key[e] == thr) ? 1 : 0;
+      rank = block_excl_scan(n_eq);
+    }
+#pragma unroll
+    for (int e = 0; e < EPT; ++e) {
+      if (cand[e]) {
+        if (key[e] > thr) {
+          sel[e] = true;
+        } else if (key[e] == thr) {
+          if (need >= in_bin || rank < need) sel[e] = true;
+          ++rank;
+        }
+      }
+    }
+  } else {
+    __syncthreads();  // orders the atomicMax above before its read below
+  }
+  // stage 2 (Alg. 1 steps 5-7): the k_lsh remaining candidates ranked first by (count descending, index
+  // ascending).  Only the threshold is found here; its ties are resolved inside the compaction below.
   bool act2[EPT];
 #pragma unroll
   for (int e = 0; e < EPT; ++e) act2[e] = cand[e] && !sel[e];
-  if (p.k_exact <= 0) __syncthreads();  // otherwise the first stage's barriers already order the atomicMax above
-  const int cnt_digits = sMaxCnt < 256u ? 1 : (sMaxCnt < 65536u ? 2 : (sMaxCnt < (1u << 24) ? 3 : 4));
-  take_top(c2, act2, p.k_lsh, min(cnt_digits, (p.cnt_bits + 7) >> 3));
+  uint32_t thr2 = 0xffffffffu;  // k_lsh == 0: nothing of the residual is kept
+  int need2 = 0, in2 = 0;
+  if (p.k_lsh > 0) {
+    const int cnt_digits = sMaxCnt < 256u ? 1 : (sMaxCnt < 65536u ? 2 : (sMaxCnt < (1u << 24) ? 3 : 4));
+    kth_largest(c2, act2, p.k_lsh, min(cnt_digits, (p.cnt_bits + 7) >> 3), thr2, need2, in2);
+  }
 
-  int n_keep = 0;
+  // Compaction (Alg. 1 step 8 and the Sec. 3.1 partition).  Kept for certain: protected positions, stage-1
+  // winners, residual candidates with a count above the threshold.  Of the residual candidates AT the
+  // threshold the first need2 in index order are kept.  One packed prefix count (certain << 16 | ties) gives
+  // every element its output rank: certain ones before it plus min(ties before it, need2).
+  int packed = 0;
 #pragma unroll
   for (int e = 0; e < EPT; ++e) {
-    sel[e] = inr[e] && (!cand[e] || sel[e]);
-    n_keep += sel[e] ? 1 : 0;
+    const bool tie = act2[e] && c2[e] == thr2;
+    sel[e] = inr[e] && (!cand[e] || sel[e] || (act2[e] && c2[e] > thr2 && p.k_lsh > 0));
+    act2[e] = tie;
+    packed += (sel[e] ? 1 << 16 : 0) + (tie ? 1 : 0);
   }
-  int pos = block_excl_scan(n_keep);
+  const int pre = block_excl_scan(packed);
+  int n_sure = pre >> 16, n_tie = pre & 0xffff;
   const int b_t = p.n_anchor + p.n_local + p.k_exact + p.k_lsh;
   // FUSED: this workgroup copies output ranks [r0, r1)
   const int per = (b_t + split - 1) / split;
   const int r0 = FUSED ? min(part * per, b_t) : 0, r1 = FUSED ? min(r0 + per, b_t) : b_t;
 #pragma unroll
   for (int e = 0; e < EPT; ++e) {
-    if (sel[e]) {
+    const bool kept = sel[e] || (act2[e] && n_tie < need2);
+    if (kept) {
+      const int pos = n_sure + min(n_tie, need2);
       if (pos >= r0 && pos < r1) {
         p.keep[(size_t)h * b_t + pos] = tid * EPT + e;
         if (FUSED) sKeep[pos - r0] = tid * EPT + e;
       }
-      ++pos;
     }
+    n_sure += sel[e] ? 1 : 0;
+    n_tie += act2[e] ? 1 : 0;
   }
   if (FUSED) {
     __syncthreads();
@@ -970,8 +1039,8 @@ __global__ __launch_bounds__(1024) void select_kernel(SelectParams p, AppendPara
       const int64_t dst_off = (int64_t)h * ap.cache_stride_head + (ap.cache_len + r0 + row) * (int64_t)ap.row_bytes + c * 16;
       const uint4 kv = ld16(ap.kb.base + (int64_t)h * ap.kb.stride_head + (int64_t)src * ap.kb.stride_row + c * 16);
       const uint4 vv = ld16(ap.vb.base + (int64_t)h * ap.vb.stride_head + (int64_t)src * ap.vb.stride_row + c * 16);
-      *reinterpret_cast<uint4*>(ap.k_cache + dst_off) = kv;
-      *reinterpret_cast<uint4*>(ap.v_cache + dst_off) = vv;
+      st16_stream(ap.k_cache + dst_off, kv);
+      st16_stream(ap.v_cache + dst_off, vv);
       if (c == 0) ap.cache_pos[(int64_t)h * ap.pos_stride_head + ap.cache_len + r0 + row] = ap.block_pos0 + src;
     }
   }
