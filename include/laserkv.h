@@ -199,6 +199,18 @@ int laserkv_compress_block_static(const laserkv_config* cfg,
  * not 4-byte aligned). */
 int laserkv_set_row_lse(laserkv_ctx* ctx, const float* row_lse);
 
+/* The window rows' softmax statistics taken from the model's own attention kernel (Sec. 3.3 "Precision":
+ * the exact score is the attention the model already computes; Sec. 3 first paragraph).  row_lse then
+ * holds, per window query, the COMPLETE natural-log sum of exp(q.k / sqrt(d)) over every key the row
+ * attends to (the block keys it sees, the look-back keys, the rest of the cache), exactly what a
+ * flash-attention forward reports for those rows.  S_exact[h, i] = mean over the rows of
+ * exp(q.k_i / sqrt(d) - row_lse) at the visible keys.  The library then computes no row statistics: the
+ * first sweep only hashes, and k_ctx / t_ctx of the following calls are accepted but not read.
+ *   row_lse  DEVICE [H_q, w] float, contiguous; NULL switches back to the library's own statistics.
+ * Lifetime and scope as for laserkv_set_row_lse, which it replaces (and which replaces it).
+ * Errors: LKV_EINVAL (null context, pointer not 4-byte aligned). */
+int laserkv_set_row_lse_complete(laserkv_ctx* ctx, const float* row_lse);
+
 /* Global-consensus variant: Alg. 1 step 3 taken literally, with the exact score summed over every
  * layer and head (Sec. 3.3 "Precision") and, likewise, the collision counts of step 6, followed by
  * ONE two-stage TopK (steps 4-8) whose kept set serves every layer and head.  Three calls:

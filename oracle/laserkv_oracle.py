@@ -85,7 +85,8 @@ def partition(B: int, n: int, alpha: float, s_t: int):
 # --------------------------------------------------------------------------
 # a1  exact score (Sec. 3.3 "Precision"; Alg. 1 step 3, one layer / KV head)
 # --------------------------------------------------------------------------
-def exact_scores(q_win, k_blk, k_ctx=None, block_pos0=0, q_pos0=None, causal=True, row_lse=None):
+def exact_scores(q_win, k_blk, k_ctx=None, block_pos0=0, q_pos0=None, causal=True, row_lse=None,
+                 row_lse_complete=None):
     """S_exact[h, i] for every block key i of every KV head h.
 
     q_win [H_q, W, d]  window queries, query head h*G+g belongs to KV head h
@@ -96,6 +97,11 @@ def exact_scores(q_win, k_blk, k_ctx=None, block_pos0=0, q_pos0=None, causal=Tru
         every window query (what an attention kernel over the rest of the cache reports); those keys
         join the normaliser exactly as look-back keys do (Sec. 3.2 boundary smoothing, extended to
         context that is not re-read).
+
+    row_lse_complete [H_q, W] or None: the COMPLETE natural-log normaliser of every window query, over all
+        keys the row attends to, as the model's own attention reports it (Sec. 3.3 "Precision": the score is
+        the attention the model computes).  Then p = exp(l - row_lse_complete) at the visible block keys;
+        k_ctx and row_lse are not used.
 
     Row (g, j): logits l = q . k / sqrt(d) over the T + S_t keys, block key i
     masked when causal and block_pos0 + i > q_pos0 + j, p = softmax(l);
@@ -116,6 +122,14 @@ def exact_scores(q_win, k_blk, k_ctx=None, block_pos0=0, q_pos0=None, causal=Tru
     if causal:
         visible = key_pos[None, :] <= qry_pos[:, None]
     out = np.zeros((h_kv, s_t), dtype=np.float64)
+    if row_lse_complete is not None:
+        lse = np.asarray(row_lse_complete, dtype=np.float64)
+        for h in range(h_kv):
+            for g in range(g_sz):
+                logits = (q_win[h * g_sz + g] @ k_blk[h].T) / np.sqrt(np.float64(d))
+                p = np.where(visible, np.exp(logits - lse[h * g_sz + g][:, None]), 0.0)
+                out[h] += p.sum(axis=0)
+        return out / np.float64(g_sz * w)
     for h in range(h_kv):
         if t_ctx:
             keys = np.concatenate([np.asarray(k_ctx[h], dtype=np.float64), k_blk[h]], axis=0)
@@ -245,12 +259,12 @@ def append(cache_k, cache_v, cache_pos, cache_len: int, k_blk, v_blk, keep, bloc
 # --------------------------------------------------------------------------
 def select_block(q_win, k_blk, k_ctx, planes, n_tables, n_bits,
                  n_anchor, n_local, k_exact, k_lsh,
-                 block_pos0=0, q_pos0=None, causal=True, row_lse=None):
+                 block_pos0=0, q_pos0=None, causal=True, row_lse=None, row_lse_complete=None):
     """Steps a1-a4 for all KV heads of one block.  Returns a dict of every stage."""
     h_q = np.asarray(q_win).shape[0]
     h_kv = np.asarray(k_blk).shape[0]
     g_sz = h_q // h_kv
-    s_ex = exact_scores(q_win, k_blk, k_ctx, block_pos0, q_pos0, causal, row_lse)
+    s_ex = exact_scores(q_win, k_blk, k_ctx, block_pos0, q_pos0, causal, row_lse, row_lse_complete)
     sig_k, uns_k = simhash(k_blk, planes, n_tables, n_bits)
     sig_q, uns_q = simhash(q_win, planes, n_tables, n_bits)
     cnt = collision_counts(sig_q, sig_k, g_sz)

@@ -22,6 +22,7 @@ EXPORTS = (
     "laserkv_partition", "laserkv_select_block", "laserkv_append", "laserkv_compress_block",
     "laserkv_profile_begin", "laserkv_profile_end", "laserkv_profile_isolate",
     "laserkv_score_block", "laserkv_select_consensus", "laserkv_append_shared", "laserkv_set_row_lse",
+    "laserkv_set_row_lse_complete",
     "laserkv_static_init", "laserkv_static_workspace_bytes", "laserkv_compress_block_static",
 )
 LKV_STATIC_SCRATCH_BYTES = 32 << 20
@@ -94,6 +95,8 @@ def load():
     lib.laserkv_append_shared.restype = C.c_int
     lib.laserkv_set_row_lse.argtypes = [vp, vp]
     lib.laserkv_set_row_lse.restype = C.c_int
+    lib.laserkv_set_row_lse_complete.argtypes = [vp, vp]
+    lib.laserkv_set_row_lse_complete.restype = C.c_int
     lib.laserkv_profile_begin.argtypes = [vp]
     lib.laserkv_profile_begin.restype = C.c_int
     lib.laserkv_profile_end.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(i64)]
@@ -291,6 +294,14 @@ class LaserKV:
             assert row_lse.is_contiguous() and row_lse.dtype == self._torch.float32
         self._row_lse = row_lse
         self._check(self._lib.laserkv_set_row_lse(self._ctx, _ptr(row_lse)))
+
+    def laserkv_set_row_lse_complete(self, row_lse):
+        """row_lse: contiguous float32 [H_q, w] device tensor holding every window row's complete log-sum-exp,
+        or None to let the library compute the statistics itself again."""
+        if row_lse is not None:
+            assert row_lse.is_contiguous() and row_lse.dtype == self._torch.float32
+        self._row_lse = row_lse
+        self._check(self._lib.laserkv_set_row_lse_complete(self._ctx, _ptr(row_lse)))
 
     def laserkv_profile_begin(self):
         self._check(self._lib.laserkv_profile_begin(self._ctx))

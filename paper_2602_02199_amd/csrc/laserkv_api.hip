@@ -48,6 +48,7 @@ struct laserkv_ctx {
   int m_pad;
   bool owns_workspace;   // the buffers above came from hipMalloc and are freed by laserkv_destroy
   const float* row_lse;  // laserkv_set_row_lse: applies to every following scoring call until reset
+  bool row_lse_complete; // the rows' complete log-sum-exp (laserkv_set_row_lse_complete) rather than outside keys only
   int only_kernel;   // >= 0: launch only this kernel kind (laserkv_profile_isolate); -1 normally
   // tuning switches, read from the environment once when the context is created
   int sweep_wg_per_cu;   // LASERKV_SWEEP_WG_PER_CU: sweep workgroups aimed at per compute unit (default 1)
@@ -331,6 +332,13 @@ int select_impl(laserkv_ctx* ctx,
 
   hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
   const int m_rows = G * w;
+  // With the rows' complete log-sum-exp from the caller the look-back keys have nothing left to contribute
+  // (they only ever entered the normaliser): they are not read.
+  const bool lse_complete = ctx->row_lse && ctx->row_lse_complete;
+  if (lse_complete) {
+    t_ctx = 0;
+    k_ctx = nullptr;
+  }
   const int n_keys = t_ctx + s_t;
 
   lkv::PassParams sp;
@@ -384,6 +392,7 @@ int select_impl(laserkv_ctx* ctx,
   sp.r_pad = (sp.n_ranges + 7) & ~7;
   sp.s_part = ctx->s_part;
   sp.row_lse = ctx->row_lse;
+  sp.lse_complete = lse_complete ? 1 : 0;
   sp.n_tables = c.lsh_tables;
   sp.n_bits = c.lsh_bits;
   sp.n_planes = c.lsh_tables * c.lsh_bits;
@@ -598,6 +607,15 @@ int laserkv_set_row_lse(laserkv_ctx* ctx, const float* row_lse) {
   if (!ctx) return fail(nullptr, LKV_EINVAL, "set_row_lse: null context");
   if (row_lse && (reinterpret_cast<uintptr_t>(row_lse) & 3)) return fail(ctx, LKV_EINVAL, "set_row_lse: misaligned pointer");
   ctx->row_lse = row_lse;
+  ctx->row_lse_complete = false;
+  return LKV_OK;
+}
+
+int laserkv_set_row_lse_complete(laserkv_ctx* ctx, const float* row_lse) {
+  if (!ctx) return fail(nullptr, LKV_EINVAL, "set_row_lse_complete: null context");
+  if (row_lse && (reinterpret_cast<uintptr_t>(row_lse) & 3)) return fail(ctx, LKV_EINVAL, "set_row_lse_complete: misaligned pointer");
+  ctx->row_lse = row_lse;
+  ctx->row_lse_complete = row_lse != nullptr;
   return LKV_OK;
 }
 

@@ -38,6 +38,7 @@ struct PassParams {
   int lds_tail_offset;  // byte offset of the per-row LDS arrays (set by the launcher)
   float* s_part;   // [n_qgroups, H_kv, S] sweep-2 pooled probabilities (sum over the group's rows)
   const float* row_lse;  // [H_kv, M] natural-log sum of exp(logit) over keys outside this call, or null
+  int lse_complete;      // row_lse is every window row's COMPLETE log-sum-exp: sweep 1 computes no row statistics
   // hashing (sweep 1)
   int n_tables, n_bits, n_planes;  // L, K, L*K (<= 512)
   int tables_per_split; // tables of the KEY codes computed by one query-row group's workgroups: ceil(L / n_qgroups)

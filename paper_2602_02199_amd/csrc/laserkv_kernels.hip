@@ -170,7 +170,7 @@ __global__ __launch_bounds__(PASS_WAVES * 64) void pass_kernel(PassParams p) {
   const int pr_per = p.r_pad >> 2;  // partials per thread, even
   const int pr_beg = (tid & 3) * pr_per;
   const float2* pr_ptr = nullptr;
-  if (PASS2) {
+  if (PASS2 && !p.lse_complete) {
     const int m = min(qg * MQ + (tid >> 2), p.m_rows - 1);
     pr_ptr = p.part + ((size_t)h * p.m_pad + m) * p.r_pad + pr_beg;
 #pragma unroll
@@ -282,7 +282,13 @@ __global__ __launch_bounds__(PASS_WAVES * 64) void pass_kernel(PassParams p) {
     const int j = m - div_w(m, p.w_magic) * p.w;
     sLim[t] = p.causal ? p.lim0 + j : INT_MAX;
   }
-  if (PASS2) {
+  if (PASS2 && p.lse_complete) {
+    // the caller knows every row's complete log-sum-exp (natural log -> exp2 domain): nothing to merge
+    if ((tid & 3) == 0) {
+      const int t = tid >> 2, m = qg * MQ + t;
+      sLse[t] = m < p.m_rows ? p.row_lse[(size_t)h * p.m_rows + m] * 1.4426950408889634f : 1.0e30f;
+    }
+  } else if (PASS2) {
     // row log-sum-exp from the sweep-1 partials: maximum reference first, then one exp per partial
     float mm = NEG_BIG, ss = 0.0f;
 #pragma unroll
@@ -476,6 +482,8 @@ __global__ __launch_bounds__(PASS_WAVES * 64) void pass_kernel(PassParams p) {
     // Each lane keeps (ref, sum) with sum = sum_i 2^(x_i - ref) over its keys; ref is the lane's
     // maximum over the first tile and is not raised afterwards (see the overflow check below).
     const int lim = sLim[rt * 32 + rl];
+    const int row = qg * MQ + rt * 32 + rl;
+    if (!p.lse_complete) {  // workgroup-uniform: with complete row statistics from the caller only the hashing remains
     auto tile = [&](int nt, f32x16& acc) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
@@ -541,8 +549,8 @@ __global__ __launch_bounds__(PASS_WAVES * 64) void pass_kernel(PassParams p) {
     }
     // the two halves of the wave hold the same rows over different keys
     lse_merge(ref, sum, __shfl_xor(ref, 32), __shfl_xor(sum, 32));
-    const int row = qg * MQ + rt * 32 + rl;
     if (kg == 0 && row < p.m_rows) p.part[((size_t)h * p.m_pad + row) * p.r_pad + kr] = make_float2(ref, sum);
+    }
 
     // SimHash codes of this wave's 32 window rows for the tables this workgroup owns (Sec. 3.3 "Recall"):
     // planes as the A operand (in plane_row order), the rows already in registers as B, so lane = row

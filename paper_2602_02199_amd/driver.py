@@ -82,13 +82,16 @@ class LayerCompressor:
         return self.cache_len
 
     # ---- pre-marshalled call lists: one ctypes call per library entry point, nothing else ----
-    def plan_layer(self, data, n_blocks=None, fused=True):
+    def plan_layer(self, data, n_blocks=None, fused=True, row_lse_complete=None):
         """Builds the layer's call list once: [(c_function, argument tuple without the stream)].
 
         The tensors in `data`, the cache and the keep buffer must stay alive and in place while the
         plan is used.  run_plan() then issues the calls back to back with no per-call Python work
         beyond the foreign call itself (and can be captured into a HIP graph).  fused=True uses
         laserkv_compress_block (one call per block), else laserkv_select_block + laserkv_append.
+        row_lse_complete: optional list of per-block float32 [H_q, W] device tensors with the window rows'
+        complete log-sum-exp (what the model's attention kernel reports); each block's call is then preceded
+        by laserkv_set_row_lse_complete, and look-back keys are not passed.
         """
         import ctypes as C
         wl, lib = self.wl, self.lib._lib
@@ -108,6 +111,11 @@ class LayerCompressor:
             assert b_t == self.keep.shape[1], "plans cover equal-sized blocks only"
             q, k, v = data["q_win"][t], data["k"][:, lo:hi], data["v"][:, lo:hi]
             t_ctx = prev_local if cache_len else 0
+            if row_lse_complete is not None:
+                lse = row_lse_complete[t]
+                assert lse.is_contiguous() and lse.dtype == torch.float32 and lse.shape == (wl.n_q_heads, wl.window)
+                calls.append((lib.laserkv_set_row_lse_complete, (ctx, vp(lse.data_ptr())), False))
+                t_ctx = 0
             ctx_ptr = vp(self.k_cache.data_ptr() + (cache_len - t_ctx) * kc_st * es) if t_ctx else None
             if fused:
                 calls.append((lib.laserkv_compress_block, (
@@ -116,19 +124,21 @@ class LayerCompressor:
                     ctx_ptr, kc_sh if t_ctx else 0, kc_st if t_ctx else 0, vp(data["planes"].data_ptr()),
                     s_t, wl.window, t_ctx, lo, binding.LKV_WINDOW_AT_BLOCK_END, 1, na, nl, ke, kl,
                     vp(self.keep.data_ptr()), vp(self.k_cache.data_ptr()), vp(self.v_cache.data_ptr()), kc_sh,
-                    vp(self.cache_pos.data_ptr()), self.cache_pos.stride(0), cache_len, self.cap)))
+                    vp(self.cache_pos.data_ptr()), self.cache_pos.stride(0), cache_len, self.cap), True))
             else:
                 calls.append((lib.laserkv_select_block, (
                     ctx, vp(q.data_ptr()), q.stride(0), q.stride(1), vp(k.data_ptr()), k.stride(0), k.stride(1),
                     ctx_ptr, kc_sh if t_ctx else 0, kc_st if t_ctx else 0, vp(data["planes"].data_ptr()),
                     s_t, wl.window, t_ctx, lo, binding.LKV_WINDOW_AT_BLOCK_END, 1, na, nl, ke, kl,
-                    vp(self.keep.data_ptr()), None, None, None, None)))
+                    vp(self.keep.data_ptr()), None, None, None, None), True))
                 calls.append((lib.laserkv_append, (
                     ctx, vp(k.data_ptr()), k.stride(0), k.stride(1), vp(v.data_ptr()), v.stride(0), v.stride(1),
                     vp(self.keep.data_ptr()), b_t, s_t, lo, vp(self.k_cache.data_ptr()), vp(self.v_cache.data_ptr()),
-                    kc_sh, vp(self.cache_pos.data_ptr()), self.cache_pos.stride(0), cache_len, self.cap)))
+                    kc_sh, vp(self.cache_pos.data_ptr()), self.cache_pos.stride(0), cache_len, self.cap), True))
             cache_len += b_t
             prev_local = nl
+        if row_lse_complete is not None:   # leave the context computing its own statistics again
+            calls.append((lib.laserkv_set_row_lse_complete, (ctx, None), False))
         self._plan_len = cache_len
         return calls
 
@@ -137,8 +147,8 @@ class LayerCompressor:
         if stream is None:
             stream = torch.cuda.current_stream().cuda_stream
         sp = C.c_void_p(stream)
-        for fn, args in calls:
-            rc = fn(*args, sp)
+        for fn, args, takes_stream in calls:
+            rc = fn(*args, sp) if takes_stream else fn(*args)
             if rc != 0:
                 self.lib._check(rc)
         self.cache_len = self._plan_len

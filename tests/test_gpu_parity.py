@@ -399,6 +399,69 @@ def test_row_lse_of_outside_keys(name, kw):
     assert outs["with"]["s_exact"].sum() < 0.99 * outs["without"]["s_exact"].sum()
 
 
+def complete_row_lse(q_win, k_blk, k_ctx, q_pos0_minus_block_pos0, d):
+    """float32 [H_q, W]: log-sum-exp of every window row over the look-back keys and the block keys it sees
+    (torch float64 on the CPU: stands in for what the model's attention kernel reports)."""
+    h_q, w, _ = q_win.shape
+    h_kv, s_t, _ = k_blk.shape
+    g = h_q // h_kv
+    vis = torch.arange(s_t)[None, :] <= (q_pos0_minus_block_pos0 + torch.arange(w))[:, None]
+    out = torch.empty(h_q, w, dtype=torch.float64)
+    for hq in range(h_q):
+        h = hq // g
+        l_blk = (q_win[hq].double() @ k_blk[h].double().T / d ** 0.5).masked_fill(~vis, float("-inf"))
+        parts = [l_blk] if k_ctx is None else [q_win[hq].double() @ k_ctx[h].double().T / d ** 0.5, l_blk]
+        out[hq] = torch.logsumexp(torch.cat(parts, dim=1), dim=1)
+    return out.to(torch.float32).contiguous()
+
+
+@pytest.mark.parametrize("name,kw", [("tiny", dict(l_ctx=1024)), ("llama8b-16k", dict(l_ctx=4096)),
+                                     ("llama8b-128k", dict(l_ctx=8192)), ("gqa8-128k", dict(l_ctx=8192))])
+def test_complete_row_lse_from_the_attention_kernel(name, kw):
+    """laserkv_set_row_lse_complete: with every window row's complete log-sum-exp supplied (as the model's
+    attention kernel reports it) the first sweep computes no row statistics and the look-back keys are not
+    read; scores, codes, counts and kept sets must still match the oracle, and the scores must match what the
+    library computes on its own from the same keys."""
+    wl = synth.shrink(synth.WORKLOADS[name], index=17, **kw)
+    B = O.budget(wl.s_block, wl.l_ctx, wl.r_num, wl.r_den)
+    parts = O.partition(B, wl.n_div, wl.alpha, wl.s_block)
+    na, nl, ke, kl = parts
+    nb = min(2, wl.n_blocks)
+    data = synth.make_layer(wl, 1, na, n_blocks=nb)
+    dev = to_dev(data)
+    s, d = wl.s_block, wl.head_dim
+    lib = binding.LaserKV(wl.n_q_heads, wl.n_kv_heads, d, wl.dtype, wl.lsh_tables, wl.lsh_bits,
+                          max_block=s, max_window=wl.window, max_ctx_keys=nl)
+    for t in range(nb):
+        lo = t * s
+        k_blk = data["k"][:, lo:lo + s]
+        k_ctx = data["k"][:, lo - nl:lo] if t else None
+        lse = complete_row_lse(data["q_win"][t], k_blk, k_ctx, s - wl.window, d)
+        outs = {}
+        for tag in ("own", "complete"):
+            lib.laserkv_set_row_lse_complete(lse.to(DEV) if tag == "complete" else None)
+            dbg = dbg_buffers(wl, s)
+            keep = torch.empty(wl.n_kv_heads, sum(parts), dtype=torch.int32, device=DEV)
+            # the complete mode gets no look-back keys at all: they are inside the log-sum-exp
+            ctx_dev = dev["k"][:, lo - nl:lo] if (t and tag == "own") else None
+            lib.laserkv_select_block(dev["q_win"][t], dev["k"][:, lo:lo + s], ctx_dev, dev["planes"], block_pos0=lo,
+                                     n_anchor=na, n_local=nl, k_exact=ke, k_lsh=kl, keep_idx=keep,
+                                     dbg_s_exact=dbg["s_exact"], dbg_sig_k=dbg["sig_k"], dbg_sig_q=dbg["sig_q"], dbg_count=dbg["cnt"])
+            torch.cuda.synchronize()
+            outs[tag] = gpu_stage(dbg, keep)
+        st = O.select_block(f64(data["q_win"][t]), f64(k_blk), None, f64(data["planes"]), wl.lsh_tables, wl.lsh_bits,
+                            *parts, block_pos0=lo, row_lse_complete=lse.to(torch.float64).numpy())
+        rep = check_block(st, outs["complete"], parts, wl.dtype)
+        say(f"[complete-lse {wl.name} blk {t}] max score err/(s+s_k) {rep['max_rel']:.2e}, tolerated {rep['tolerated']}")
+        # the library's own statistics over the same keys give the same scores up to the rounding of the
+        # float32 log-sum-exp handed in (relative 2^-24 of a value around 10: a few 1e-6 in the exponent)
+        own, comp = outs["own"]["s_exact"].astype(np.float64), outs["complete"]["s_exact"].astype(np.float64)
+        assert np.all(np.abs(own - comp) <= 2e-5 * np.maximum(own, comp) + 1e-30)
+        assert np.array_equal(outs["own"]["sig_k"], outs["complete"]["sig_k"]) and np.array_equal(outs["own"]["cnt"], outs["complete"]["cnt"])
+    lib.laserkv_set_row_lse_complete(None)
+    lib.close()
+
+
 def test_bench_launch_configuration_full_size_against_oracle():
     """Exactly what bench.py times (the 128k layer as one captured graph of laserkv_compress_block calls,
     replayed): the rows in the cache for sampled blocks must be the oracle's kept rows, up to tokens at a

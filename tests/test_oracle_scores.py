@@ -127,3 +127,46 @@ def test_row_lse_equals_extra_context_keys():
     base = O.exact_scores(q, k, None, block_pos0=0)
     assert np.allclose(O.exact_scores(q, k, None, block_pos0=0, row_lse=np.full((h_q, w), -1e4)), base, rtol=1e-13, atol=0)
     assert O.exact_scores(q, k, None, block_pos0=0, row_lse=np.full((h_q, w), 60.0)).sum() < 1e-10
+
+
+def test_complete_row_lse_reproduces_the_plain_path_and_library_attention():
+    """Sec. 3.3 "Precision": the exact score is the attention the model computes.  With every window row's
+    complete log-sum-exp (over the keys it sees in the block, the look-back keys and any further context)
+    the scores must equal the plain path's, and equal library attention weights taken with that normaliser."""
+    from scipy.special import logsumexp
+    rng = np.random.default_rng(91)
+    h_q, h_kv, w, s_t, d, t_in, t_far = 6, 2, 4, 33, 8, 5, 17
+    g = h_q // h_kv
+    q = rng.standard_normal((h_q, w, d)) * 1.3
+    k = rng.standard_normal((h_kv, s_t, d))
+    ctx_in = rng.standard_normal((h_kv, t_in, d))
+    far = rng.standard_normal((h_kv, t_far, d)) * 1.7       # the rest of the cache: never passed to the call
+    pos0, qpos0 = 200, 200 + s_t - w
+    vis = (pos0 + np.arange(s_t))[None, :] <= (qpos0 + np.arange(w))[:, None]
+    lse = np.zeros((h_q, w))
+    for hq in range(h_q):
+        h = hq // g
+        l_blk = np.where(vis, q[hq] @ k[h].T / np.sqrt(d), -np.inf)
+        l_all = np.concatenate([q[hq] @ far[h].T / np.sqrt(d), q[hq] @ ctx_in[h].T / np.sqrt(d), l_blk], axis=1)
+        lse[hq] = logsumexp(l_all, axis=1)
+    got = O.exact_scores(q, k, None, block_pos0=pos0, row_lse_complete=lse)
+    plain = O.exact_scores(q, k, np.concatenate([far, ctx_in], axis=1), block_pos0=pos0)
+    np.testing.assert_allclose(got, plain, rtol=1e-12, atol=0)
+    # look-back keys and an outside log-sum-exp passed along are ignored: the normaliser is already complete
+    same = O.exact_scores(q, k, ctx_in, block_pos0=pos0, row_lse=np.zeros((h_q, w)), row_lse_complete=lse)
+    np.testing.assert_array_equal(got, same)
+    # library attention over [far | look-back | block] with V = one-hot of the block keys gives the same weights
+    t = t_far + t_in
+    for h in range(h_kv):
+        keys = torch.from_numpy(np.concatenate([far[h], ctx_in[h], k[h]], axis=0))
+        mask = torch.from_numpy(np.concatenate([np.ones((w, t), dtype=bool), vis], axis=1))
+        v_onehot = torch.zeros(t + s_t, s_t, dtype=torch.float64)
+        v_onehot[t:] = torch.eye(s_t, dtype=torch.float64)
+        acc = np.zeros(s_t)
+        for gi in range(g):
+            out = torch.nn.functional.scaled_dot_product_attention(torch.from_numpy(q[h * g + gi])[None], keys[None], v_onehot[None],
+                                                                   attn_mask=mask[None])
+            acc += out[0].sum(0).numpy()
+        np.testing.assert_allclose(got[h], acc / (g * w), rtol=1e-10, atol=0)
+    # a normaliser that misses keys (too small) inflates the scores: the total mass exceeds what the block holds
+    assert O.exact_scores(q, k, None, block_pos0=pos0, row_lse_complete=lse - 1.0).sum() > got.sum() * 2.7
