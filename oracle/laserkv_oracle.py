@@ -337,3 +337,57 @@ def compress_layer(blocks, planes, n_tables, n_bits, B, n, alpha, cap, dtype=np.
         prev_local = nl
         stages.append(st)
     return cache_k, cache_v, cache_pos, cache_len, stages
+
+
+def compress_layer_deferred(blocks, planes, n_tables, n_bits, B, n, alpha, cap, tail, dtype=np.float64):
+    """The layer loop with the look-back of Sec. 3.2 read as DEFERRING a block's edge: the last `tail`
+    tokens of block t are not judged with block t (no later context has been seen for them) but join the
+    candidates of block t+1; the last block defers nothing, so every token is judged exactly once.
+
+    Segment t = [deferred tail of block t-1 | block t without its own tail], scored by block t's
+    observation window (its last W tokens, at their real positions: the window then reaches `tail`
+    tokens past the segment's end, and the causal mask follows positions).  Everything else is
+    compress_layer applied to the segments: budget B per segment (B_t = min(B, segment length)), the
+    Sec. 3.1 partition on the segment, and the previous SEGMENT's local window (the cache's last n_local
+    rows, the tokens just before the segment) as context-only keys.  tail = 0 is compress_layer.
+
+    blocks: iterable of (q_win, k_blk, v_blk, block_pos0), consecutive in position.
+    Returns (cache_k, cache_v, cache_pos, cache_len, per-segment stage dicts); each stage dict also
+    carries seg_pos0 and seg_len.
+    """
+    blocks = list(blocks)
+    cache_k = cache_v = cache_pos = None
+    cache_len = 0
+    prev_local = 0
+    pend_k = pend_v = None
+    stages = []
+    for t, (q_win, k_blk, v_blk, pos0) in enumerate(blocks):
+        k_blk = np.asarray(k_blk, dtype=np.float64)
+        v_blk = np.asarray(v_blk, dtype=np.float64)
+        h_kv, s_t, d = k_blk.shape
+        w = np.asarray(q_win).shape[1]
+        tail_t = 0 if t == len(blocks) - 1 else int(tail)
+        if tail_t > s_t:
+            raise ValueError("tail longer than a block")
+        if cache_k is None:
+            cache_k = np.zeros((h_kv, cap, d), dtype=dtype)
+            cache_v = np.zeros((h_kv, cap, d), dtype=dtype)
+            cache_pos = np.full((h_kv, cap), -1, dtype=np.int64)
+        n_pend = 0 if pend_k is None else pend_k.shape[1]
+        seg_k = k_blk[:, :s_t - tail_t] if n_pend == 0 else np.concatenate([pend_k, k_blk[:, :s_t - tail_t]], axis=1)
+        seg_v = v_blk[:, :s_t - tail_t] if n_pend == 0 else np.concatenate([pend_v, v_blk[:, :s_t - tail_t]], axis=1)
+        pend_k = k_blk[:, s_t - tail_t:] if tail_t else None
+        pend_v = v_blk[:, s_t - tail_t:] if tail_t else None
+        seg_pos0 = pos0 - n_pend
+        seg_len = seg_k.shape[1]
+        na, nl, ke, kl = partition(B, n, alpha, seg_len)
+        k_ctx = None
+        if cache_len and prev_local:
+            k_ctx = cache_k[:, cache_len - prev_local:cache_len].astype(np.float64)
+        st = select_block(q_win, seg_k, k_ctx, planes, n_tables, n_bits, na, nl, ke, kl,
+                          block_pos0=seg_pos0, q_pos0=pos0 + s_t - w)
+        cache_len = append(cache_k, cache_v, cache_pos, cache_len, seg_k, seg_v, st["keep"], seg_pos0)
+        prev_local = nl
+        st["seg_pos0"], st["seg_len"] = seg_pos0, seg_len
+        stages.append(st)
+    return cache_k, cache_v, cache_pos, cache_len, stages

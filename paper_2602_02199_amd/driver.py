@@ -13,15 +13,22 @@ from . import binding
 
 
 class LayerCompressor:
-    def __init__(self, wl, device="cuda:0", max_blocks=None):
+    def __init__(self, wl, device="cuda:0", max_blocks=None, budget=None, tail=0, lib=None):
+        """budget: per-block budget B of this layer (default: the App. B equation for the workload; a
+        per-layer schedule passes its own).  tail: tokens a block defers to the next one (run_layer_deferred);
+        blocks handed to the library are then up to s_block + tail long.  lib: an existing library context
+        of sufficient limits to share (its workspace does not depend on the budget)."""
         self.wl = wl
         self.device = torch.device(device)
-        self.B = binding.laserkv_budget(wl.s_block, wl.l_ctx, wl.r_num, wl.r_den)
+        self.B = binding.laserkv_budget(wl.s_block, wl.l_ctx, wl.r_num, wl.r_den) if budget is None else int(budget)
         self.parts = binding.laserkv_partition(self.B, wl.n_div, wl.alpha, wl.s_block)
         nb = wl.n_blocks if max_blocks is None else max_blocks
-        self.cap = nb * min(self.B, wl.s_block)
-        self.lib = binding.LaserKV(wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.dtype, wl.lsh_tables, wl.lsh_bits,
-                                   max_block=wl.s_block, max_window=wl.window, max_ctx_keys=self.parts[1])
+        self.tail = int(tail)
+        self.cap = nb * min(self.B, wl.s_block + self.tail)
+        max_local = binding.laserkv_partition(self.B, wl.n_div, wl.alpha, wl.s_block + self.tail)[1]
+        self.lib = lib if lib is not None else binding.LaserKV(
+            wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.dtype, wl.lsh_tables, wl.lsh_bits,
+            max_block=wl.s_block + self.tail, max_window=wl.window, max_ctx_keys=max_local)
         dt = wl.torch_dtype
         self.k_cache = torch.zeros(wl.n_kv_heads, self.cap, wl.head_dim, dtype=dt, device=self.device)
         self.v_cache = torch.zeros_like(self.k_cache)
@@ -31,6 +38,43 @@ class LayerCompressor:
 
     def reset(self):
         self.cache_len = 0
+
+    def run_layer_deferred(self, data, n_blocks=None, dbg_for=None):
+        """The layer loop with each block's last `tail` tokens deferred to the next block's call (the look-back
+        of Sec. 3.2 read as judging a block's edge only once later context exists): call t covers positions
+        [block start - tail, block end - tail) (the first starts with its block, the last ends with its block)
+        and is scored by the block's own last W tokens at their real positions.  Pointer arithmetic only.
+
+        dbg_for: optional callable(t, seg_len) -> (dbg dict or None, keep tensor or None) supplying stage-output
+        buffers for segment t.  Returns [(seg_lo, seg_hi, n_ctx, keep)] per segment."""
+        wl, tail = self.wl, self.tail
+        self.reset()
+        nb = data["q_win"].shape[0] if n_blocks is None else n_blocks
+        l_tot = data["k"].shape[1]
+        prev_local, out = 0, []
+        for t in range(nb):
+            blk_lo, blk_hi = t * wl.s_block, min((t + 1) * wl.s_block, l_tot)
+            lo = blk_lo - (tail if t else 0)
+            hi = blk_hi - (tail if t < nb - 1 else 0)
+            na, nl, ke, kl = binding.laserkv_partition(self.B, wl.n_div, wl.alpha, hi - lo)
+            b_t = na + nl + ke + kl
+            dbg, keep = dbg_for(t, hi - lo) if dbg_for else (None, None)
+            if keep is None:
+                keep = torch.empty(wl.n_kv_heads, b_t, dtype=torch.int32, device=self.device)
+            dbg = dbg or {}
+            k_ctx = self.k_cache[:, self.cache_len - prev_local:self.cache_len] if (self.cache_len and prev_local) else None
+            k_seg, v_seg = data["k"][:, lo:hi], data["v"][:, lo:hi]
+            self.lib.laserkv_select_block(data["q_win"][t], k_seg, k_ctx, data["planes"], block_pos0=lo,
+                                          q_pos0=blk_hi - wl.window, causal=True,
+                                          n_anchor=na, n_local=nl, k_exact=ke, k_lsh=kl, keep_idx=keep,
+                                          dbg_s_exact=dbg.get("s_exact"), dbg_sig_k=dbg.get("sig_k"),
+                                          dbg_sig_q=dbg.get("sig_q"), dbg_count=dbg.get("cnt"))
+            self.lib.laserkv_append(k_seg, v_seg, keep, b_t=b_t, block_pos0=lo, k_cache=self.k_cache,
+                                    v_cache=self.v_cache, cache_pos=self.cache_pos, cache_len=self.cache_len)
+            self.cache_len += b_t
+            out.append((lo, hi, prev_local, keep))
+            prev_local = nl
+        return out
 
     def block_budget(self, s_t):
         """(n_anchor, n_local, k_exact, k_lsh) of a block with s_t tokens."""

@@ -542,3 +542,82 @@ def test_window_positions_beyond_the_block(shift):
     # the last keys of the block are visible to more queries than with the default window
     base = O.exact_scores(f64(data["q_win"][0]), f64(data["k"][:, :s]), None, block_pos0=block_pos0)
     assert (st["s_exact"][:, -1] > base[:, -1]).all()
+
+
+@pytest.mark.parametrize("name,kw,tail", [("tiny", dict(l_ctx=2048), 40), ("llama8b-16k", dict(l_ctx=8192), 96),
+                                          ("llama8b-16k", dict(l_ctx=6144), 0)])
+def test_deferred_tail_layer_against_oracle(name, kw, tail):
+    """The look-back of Sec. 3.2 read as deferring a block's last `tail` tokens to the next block's call:
+    the driver's segment loop (pointer arithmetic into the resident tensors) against the oracle's
+    compress_layer_deferred, every segment stage by stage, and the final cache."""
+    wl = synth.shrink(synth.WORKLOADS[name], index=19, **kw)
+    B = O.budget(wl.s_block, wl.l_ctx, wl.r_num, wl.r_den)
+    na_full = O.partition(B, wl.n_div, wl.alpha, wl.s_block)[0]
+    data = synth.make_layer(wl, 2, na_full)
+    dev = to_dev(data)
+    nb, s = data["q_win"].shape[0], wl.s_block
+    comp = LayerCompressor(wl, DEV, tail=tail)
+    saved = {}
+
+    def dbg_for(t, seg_len):
+        dbg = dbg_buffers(wl, seg_len)
+        keep = torch.empty(wl.n_kv_heads, sum(O.partition(B, wl.n_div, wl.alpha, seg_len)), dtype=torch.int32, device=DEV)
+        saved[t] = (dbg, keep)
+        return dbg, keep
+
+    segs = comp.run_layer_deferred(dev, dbg_for=dbg_for)
+    torch.cuda.synchronize()
+    k64, v64, q64 = f64(data["k"]), f64(data["v"]), f64(data["q_win"])
+    blocks = [(q64[t], k64[:, t * s:(t + 1) * s], v64[:, t * s:(t + 1) * s], t * s) for t in range(nb)]
+    cap = sum(min(B, hi - lo) for lo, hi, _, _ in segs)
+    ck, cv, cp, clen, stages = O.compress_layer_deferred(blocks, f64(data["planes"]), wl.lsh_tables, wl.lsh_bits, B,
+                                                         wl.n_div, wl.alpha, cap=cap, tail=tail)
+    assert comp.cache_len == clen == cap
+    n_tol = 0
+    for t, (lo, hi, n_ctx, keep) in enumerate(segs):
+        assert (lo, hi - lo) == (stages[t]["seg_pos0"], stages[t]["seg_len"])
+        parts = O.partition(B, wl.n_div, wl.alpha, hi - lo)
+        # the oracle's stage used ITS cache rows as look-back keys; they are the raw keys before the segment
+        rep = check_block(stages[t], gpu_stage(*saved[t]), parts, wl.dtype)
+        n_tol += sum(c for _, c in rep["tolerated"])
+    say(f"[deferred-tail {wl.name} tail {tail}] {len(segs)} segments, tolerated index diffs {n_tol}")
+    pos = comp.cache_pos[:, :clen]
+    assert bool((pos[:, 1:] > pos[:, :-1]).all())
+    assert torch.equal(comp.k_cache[:, :clen], torch.gather(dev["k"], 1, pos[:, :, None].expand(-1, -1, wl.head_dim)))
+    assert torch.equal(comp.v_cache[:, :clen], torch.gather(dev["v"], 1, pos[:, :, None].expand(-1, -1, wl.head_dim)))
+    if n_tol == 0:
+        assert np.array_equal(pos.cpu().numpy(), cp[:, :clen])
+
+
+def test_layers_with_their_own_budgets_share_one_context():
+    """A per-layer budget schedule (a pyramid over depth, say) is a host-side choice of the four integers of
+    every call: two layers with different B run through ONE library context and each matches the oracle run
+    with its own budget."""
+    wl = synth.shrink(synth.WORKLOADS["llama8b-16k"], index=20, l_ctx=6144)
+    B0 = O.budget(wl.s_block, wl.l_ctx, wl.r_num, wl.r_den)
+    budgets = [B0, B0 // 3]
+    shared = None
+    for layer, B in enumerate(budgets):
+        parts = O.partition(B, wl.n_div, wl.alpha, wl.s_block)
+        data = synth.make_layer(wl, layer, parts[0])
+        dev = to_dev(data)
+        comp = LayerCompressor(wl, DEV, budget=B, lib=shared)
+        shared = comp.lib
+        nb, s = data["q_win"].shape[0], wl.s_block
+        prev_local, saved = 0, []
+        for t in range(nb):
+            dbg = dbg_buffers(wl, s)
+            keep = torch.empty(wl.n_kv_heads, sum(parts), dtype=torch.int32, device=DEV)
+            n_ctx = prev_local
+            prev_local, _ = comp.step(dev["q_win"][t], dev["k"][:, t * s:(t + 1) * s], dev["v"][:, t * s:(t + 1) * s],
+                                      dev["planes"], t * s, prev_local, dbg=dbg, keep_out=keep)
+            saved.append((dbg, keep, n_ctx))
+        torch.cuda.synchronize()
+        assert comp.cache_len == nb * sum(parts) == nb * B
+        k64 = f64(data["k"])
+        for t, (dbg, keep, n_ctx) in enumerate(saved):
+            lo = t * s
+            st = O.select_block(f64(data["q_win"][t]), k64[:, lo:lo + s], k64[:, lo - n_ctx:lo] if n_ctx else None,
+                                f64(data["planes"]), wl.lsh_tables, wl.lsh_bits, *parts, block_pos0=lo)
+            check_block(st, gpu_stage(dbg, keep), parts, wl.dtype)
+        say(f"[per-layer budget] layer {layer} B={B} parts={parts}: {nb} blocks match the oracle")

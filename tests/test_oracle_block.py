@@ -9,6 +9,7 @@ a power of two; all probabilities below are exact fractions.
 from fractions import Fraction as F
 
 import numpy as np
+import pytest
 
 from oracle import laserkv_oracle as O
 
@@ -133,3 +134,73 @@ def test_compress_layer_look_back_is_the_previous_blocks_local_window():
             np.testing.assert_array_equal(ck[h, off:off + b_t], k[h, lo + stages[t]["keep"][h]])
             np.testing.assert_array_equal(cv[h, off:off + b_t], v[h, lo + stages[t]["keep"][h]])
         off += b_t
+
+
+def _layer_inputs(seed, lens, h_q=4, h_kv=2, d=8, w=4, L=3, Kb=4):
+    rng = np.random.default_rng(seed)
+    total = sum(lens)
+    k = rng.standard_normal((h_kv, total, d))
+    v = rng.standard_normal((h_kv, total, d))
+    planes = rng.standard_normal((L * Kb, d))
+    qs = [rng.standard_normal((h_q, w, d)) * 2.0 for _ in lens]
+    starts = [int(x) for x in np.concatenate([[0], np.cumsum(lens)[:-1]])]
+    blocks = [(qs[t], k[:, lo:lo + s], v[:, lo:lo + s], lo) for t, (lo, s) in enumerate(zip(starts, lens))]
+    return k, v, planes, qs, starts, blocks, L, Kb, w
+
+
+def test_deferred_tail_of_zero_is_the_plain_layer_loop():
+    lens = [40, 16, 28, 40]
+    k, v, planes, qs, starts, blocks, L, Kb, w = _layer_inputs(5, lens)
+    B, n, alpha = 24, 4, 0.75
+    cap = sum(min(B, s) for s in lens)
+    a = O.compress_layer(blocks, planes, L, Kb, B, n, alpha, cap=cap)
+    b = O.compress_layer_deferred(blocks, planes, L, Kb, B, n, alpha, cap=cap, tail=0)
+    assert a[3] == b[3]
+    for x, y in zip(a[:3], b[:3]):
+        np.testing.assert_array_equal(x, y)
+    for sa, sb in zip(a[4], b[4]):
+        np.testing.assert_array_equal(sa["s_exact"], sb["s_exact"])
+        np.testing.assert_array_equal(sa["keep"], sb["keep"])
+
+
+def test_deferred_tail_segments_follow_sec_3_2():
+    """Every segment re-derived from the raw tensors: it starts `tail` tokens before its block, ends `tail`
+    tokens before the block's end (the last block ends with its block), is scored by the block's own last W
+    tokens at their real positions, and sees the previous segment's local window as context-only keys."""
+    lens, tail = [40, 24, 40, 32], 6
+    k, v, planes, qs, starts, blocks, L, Kb, w = _layer_inputs(6, lens)
+    B, n, alpha = 24, 4, 0.75
+    total = sum(lens)
+    seg_lo = [0] + [starts[t] - tail for t in range(1, len(lens))]
+    seg_hi = [starts[t] + lens[t] - tail for t in range(len(lens) - 1)] + [total]
+    cap = sum(min(B, hi - lo) for lo, hi in zip(seg_lo, seg_hi))
+    ck, cv, cp, clen, stages = O.compress_layer_deferred(blocks, planes, L, Kb, B, n, alpha, cap=cap, tail=tail)
+    assert clen == cap                                                   # kept count = budget of every segment
+    assert seg_hi[:-1] == seg_lo[1:]                                     # the segments tile the context: each token is judged once
+    n_local_prev = 0
+    off = 0
+    for t, (lo, hi) in enumerate(zip(seg_lo, seg_hi)):
+        parts = O.partition(B, n, alpha, hi - lo)
+        assert stages[t]["seg_pos0"] == lo and stages[t]["seg_len"] == hi - lo
+        k_ctx = k[:, lo - n_local_prev:lo] if t else None               # raw keys just before the segment
+        st = O.select_block(qs[t], k[:, lo:hi], k_ctx, planes, L, Kb, *parts, block_pos0=lo,
+                            q_pos0=starts[t] + lens[t] - w)
+        np.testing.assert_array_equal(st["s_exact"], stages[t]["s_exact"])
+        np.testing.assert_array_equal(st["cnt"], stages[t]["cnt"])
+        np.testing.assert_array_equal(st["keep"], stages[t]["keep"])
+        b_t = sum(parts)
+        for h in range(k.shape[0]):
+            np.testing.assert_array_equal(cp[h, off:off + b_t], lo + st["keep"][h])
+            np.testing.assert_array_equal(ck[h, off:off + b_t], k[h, lo + st["keep"][h]])
+            np.testing.assert_array_equal(cv[h, off:off + b_t], v[h, lo + st["keep"][h]])
+        if t < len(lens) - 1:
+            # the block's own tail is judged later: none of it is in the cache yet, and the window's last
+            # `tail` queries lie beyond the segment, so the mask hides fewer keys than in the plain loop
+            assert cp[:, :off + b_t].max() < hi
+            plain = O.exact_scores(qs[t], k[:, lo:hi], k_ctx, block_pos0=lo)   # window = the SEGMENT's last W tokens
+            assert np.abs(plain - st["s_exact"]).max() > 1e-6
+        off += b_t
+        n_local_prev = parts[1]
+    assert np.all(np.diff(cp[:, :clen], axis=1) > 0)                     # append-only order
+    with pytest.raises(ValueError):
+        O.compress_layer_deferred(blocks, planes, L, Kb, B, n, alpha, cap=cap, tail=25)
