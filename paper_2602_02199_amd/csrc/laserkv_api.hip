@@ -346,6 +346,7 @@ int select_impl(laserkv_ctx* ctx,
   sp.kb = {(const char*)k_blk, k_stride_head * es, k_stride_tok * es};
   sp.kc = {(const char*)k_ctx, c_stride_head * es, c_stride_tok * es};
   sp.planes = (const char*)hyperplanes;
+  sp.q_linear = (q_stride_head == (int64_t)w * q_stride_tok && (int64_t)G * w * q_stride_tok * es < (int64_t(1) << 31)) ? 1 : 0;
   sp.group = G;
   sp.w = w;
   sp.m_rows = m_rows;

@@ -52,6 +52,18 @@ __device__ __forceinline__ float fast_log2(float x) { return __builtin_amdgcn_lo
 
 __device__ __forceinline__ uint4 ld16(const void* p) { return *reinterpret_cast<const uint4*>(p); }
 
+// 16-byte loads through a buffer descriptor: the address is a uniform base plus a 32-bit per-lane byte
+// offset (no 64-bit address arithmetic per load), and offsets at or past `bytes` read as zero instead of
+// touching memory, so rows beyond the end of a tensor need no clamping.
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_srd(const void* base, uint32_t bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, (int)bytes, 0x00020000);
+}
+typedef uint32_t u32x4_ld __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint4 buf_ld16(__amdgpu_buffer_rsrc_t r, uint32_t byte_offset) {
+  const u32x4_ld v = __builtin_amdgcn_raw_buffer_load_b128(r, (int)byte_offset, 0, 0);
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
+
 // Streaming stores: data that no later instruction of the same kernel reads goes out without waiting
 // for the end-of-kernel write-back of the L2.
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));

@@ -18,6 +18,8 @@ struct PassParams {
   RowSrc kb;       // [H_kv, S, d]
   RowSrc kc;       // [H_kv, T, d] (base may be null when T == 0)
   const char* planes;   // [L*K, d] contiguous
+  int q_linear;    // q.stride_head == W * q.stride_row and the head's rows span < 2 GiB: window row m of KV head h
+                   // sits at q.base + (h*G*W + m) * q.stride_row
   int group;       // G
   int w;           // W
   uint32_t w_magic;  // ceil(2^32 / W): row / W == umulhi(row, w_magic) for row <= 1024

@@ -194,28 +194,44 @@ __global__ __launch_bounds__(PASS_WAVES * 64) void pass_kernel(PassParams p) {
 
   uint4 a[NCH];  // A operand: this wave's 32 window rows, or (hashing waves) its first 32 planes
   if (STAGE_A) {
+    // Load u of a thread is chunk tid % CH of row tid / CH + u * (NTHR / CH): one byte offset per thread
+    // and tensor, one add per load; rows past the end of a tensor read as zero (they are masked, or their
+    // results are never stored).
     uint4 qpre[QL], ppre[QL], kpre[KL];
+    constexpr int ROWS_PER_LOAD = NTHR / CH;
+    const uint32_t trow = tid / CH, tcol = (tid % CH) * 16;
+    if (p.q_linear) {
+      const uint32_t qstride = (uint32_t)p.q.stride_row;
+      const __amdgpu_buffer_rsrc_t qsrd =
+          make_srd(p.q.base + (int64_t)h * p.group * p.q.stride_head, (uint32_t)p.m_rows * qstride);
+      const uint32_t qoff = (qg * MQ + trow) * qstride + tcol;
 #pragma unroll
-    for (int u = 0; u < QL; ++u) {
-      const int q = tid + NTHR * u;
-      const int row = q / CH, c = q % CH;
-      const int m = min(qg * MQ + row, p.m_rows - 1);
-      const int g = div_w(m, p.w_magic), j = m - g * p.w;
-      qpre[u] = ld16(p.q.base + (int64_t)(h * p.group + g) * p.q.stride_head + (int64_t)j * p.q.stride_row + c * 16);
-    }
-    if (!PASS2) {
+      for (int u = 0; u < QL; ++u) qpre[u] = buf_ld16(qsrd, qoff + u * ROWS_PER_LOAD * qstride);
+    } else {
 #pragma unroll
       for (int u = 0; u < QL; ++u) {
         const int q = tid + NTHR * u;
         const int row = q / CH, c = q % CH;
-        const int pm = min(plane0 + min(row, max(n_pl - 1, 0)), p.n_planes - 1);
-        ppre[u] = ld16(p.planes + (size_t)pm * (D * ES) + c * 16);
+        const int m = min(qg * MQ + row, p.m_rows - 1);
+        const int g = div_w(m, p.w_magic), j = m - g * p.w;
+        qpre[u] = ld16(p.q.base + (int64_t)(h * p.group + g) * p.q.stride_head + (int64_t)j * p.q.stride_row + c * 16);
       }
     }
+    if (!PASS2) {
+      const __amdgpu_buffer_rsrc_t psrd = make_srd(p.planes, (uint32_t)p.n_planes * (D * ES));
+      const uint32_t poff = (plane0 + trow) * (D * ES) + tcol;
 #pragma unroll
-    for (int u = 0; u < KL; ++u) {
-      const int q = tid + NTHR * u;
-      if (q < n_chunks) kpre[u] = key_chunk(q);
+      for (int u = 0; u < QL; ++u) ppre[u] = buf_ld16(psrd, poff + u * ROWS_PER_LOAD * (D * ES));
+    }
+    {
+      const __amdgpu_buffer_rsrc_t ksrd = make_srd(kbase_ptr, (uint32_t)seg_rows * (uint32_t)kstride);
+      const uint32_t koff = (seg_row0 + trow) * (uint32_t)kstride + tcol;
+#pragma unroll
+      for (int u = 0; u < KL; ++u) {
+        const int q = tid + NTHR * u;
+        if (q < n_kchunks) kpre[u] = buf_ld16(ksrd, koff + u * ROWS_PER_LOAD * (uint32_t)kstride);
+        else if (q < n_chunks) kpre[u] = key_chunk(q);
+      }
     }
     if (PASS2) {
       // sweep 2 has room for the query panel beside the keys: both go to their LDS places as they
@@ -1041,15 +1057,29 @@ __global__ __launch_bounds__(1024) void select_kernel(SelectParams p, AppendPara
     __syncthreads();
     const int cpr = ap.row_bytes / 16;
     const int n_copy = (r1 - r0) * cpr;
-    for (int t = tid; t < n_copy; t += 1024) {
-      const int row = t / cpr, c = t - row * cpr;
-      const int src = sKeep[row];
-      const int64_t dst_off = (int64_t)h * ap.cache_stride_head + (ap.cache_len + r0 + row) * (int64_t)ap.row_bytes + c * 16;
-      const uint4 kv = ld16(ap.kb.base + (int64_t)h * ap.kb.stride_head + (int64_t)src * ap.kb.stride_row + c * 16);
-      const uint4 vv = ld16(ap.vb.base + (int64_t)h * ap.vb.stride_head + (int64_t)src * ap.vb.stride_row + c * 16);
-      st16_stream(ap.k_cache + dst_off, kv);
-      st16_stream(ap.v_cache + dst_off, vv);
-      if (c == 0) ap.cache_pos[(int64_t)h * ap.pos_stride_head + ap.cache_len + r0 + row] = ap.block_pos0 + src;
+    // two chunk pairs per thread and step, all four loads in flight before the first store
+    for (int t0 = tid; t0 < n_copy; t0 += 2048) {
+      const int t1 = t0 + 1024;
+      const bool two = t1 < n_copy;
+      const int row0 = t0 / cpr, c0 = t0 - row0 * cpr;
+      const int row1 = two ? t1 / cpr : row0, c1 = two ? t1 - row1 * cpr : c0;
+      const int src0 = sKeep[row0], src1 = sKeep[row1];
+      const char* kh = ap.kb.base + (int64_t)h * ap.kb.stride_head;
+      const char* vh = ap.vb.base + (int64_t)h * ap.vb.stride_head;
+      const uint4 k0v = ld16(kh + (int64_t)src0 * ap.kb.stride_row + c0 * 16);
+      const uint4 v0v = ld16(vh + (int64_t)src0 * ap.vb.stride_row + c0 * 16);
+      const uint4 k1v = ld16(kh + (int64_t)src1 * ap.kb.stride_row + c1 * 16);
+      const uint4 v1v = ld16(vh + (int64_t)src1 * ap.vb.stride_row + c1 * 16);
+      const int64_t dst_h = (int64_t)h * ap.cache_stride_head + (ap.cache_len + r0) * (int64_t)ap.row_bytes;
+      const int64_t pos_h = (int64_t)h * ap.pos_stride_head + ap.cache_len + r0;
+      st16_stream(ap.k_cache + dst_h + (int64_t)row0 * ap.row_bytes + c0 * 16, k0v);
+      st16_stream(ap.v_cache + dst_h + (int64_t)row0 * ap.row_bytes + c0 * 16, v0v);
+      if (c0 == 0) ap.cache_pos[pos_h + row0] = ap.block_pos0 + src0;
+      if (two) {
+        st16_stream(ap.k_cache + dst_h + (int64_t)row1 * ap.row_bytes + c1 * 16, k1v);
+        st16_stream(ap.v_cache + dst_h + (int64_t)row1 * ap.row_bytes + c1 * 16, v1v);
+        if (c1 == 0) ap.cache_pos[pos_h + row1] = ap.block_pos0 + src1;
+      }
     }
   }
 }

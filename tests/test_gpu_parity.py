@@ -621,3 +621,33 @@ def test_layers_with_their_own_budgets_share_one_context():
                                 f64(data["planes"]), wl.lsh_tables, wl.lsh_bits, *parts, block_pos0=lo)
             check_block(st, gpu_stage(dbg, keep), parts, wl.dtype)
         say(f"[per-layer budget] layer {layer} B={B} parts={parts}: {nb} blocks match the oracle")
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_padded_query_and_key_strides(dtype):
+    """Window queries whose head stride is not W rows (a slice of a longer tensor) and keys whose row stride
+    exceeds head_dim (a slice of a wider tensor): the general addressing paths of the sweeps' load phase."""
+    wl = synth.shrink(synth.WORKLOADS["llama8b-16k"], index=25, l_ctx=2048, s_block=1024, dtype=dtype, window=40)
+    B = O.budget(wl.s_block, wl.l_ctx, wl.r_num, wl.r_den)
+    parts = O.partition(B, wl.n_div, wl.alpha, wl.s_block)
+    data = synth.make_layer(wl, 0, parts[0], n_blocks=1)
+    s, d, w = wl.s_block, wl.head_dim, wl.window
+    q_pad = torch.zeros(wl.n_q_heads, w + 5, d, dtype=wl.torch_dtype, device=DEV)
+    q_pad[:, 2:2 + w] = data["q_win"][0].to(DEV)
+    k_wide = torch.zeros(wl.n_kv_heads, s, d + 64, dtype=wl.torch_dtype, device=DEV)
+    k_wide[:, :, 8:8 + d] = data["k"][:, :s].to(DEV)
+    q_view, k_view = q_pad[:, 2:2 + w], k_wide[:, :, 8:8 + d]
+    assert q_view.stride(0) != w * q_view.stride(1) and k_view.stride(1) == d + 64
+    lib = binding.LaserKV(wl.n_q_heads, wl.n_kv_heads, d, wl.dtype, wl.lsh_tables, wl.lsh_bits,
+                          max_block=s, max_window=w, max_ctx_keys=0)
+    dbg = dbg_buffers(wl, s)
+    keep = torch.empty(wl.n_kv_heads, sum(parts), dtype=torch.int32, device=DEV)
+    lib.laserkv_select_block(q_view, k_view, None, data["planes"].to(DEV), block_pos0=0,
+                             n_anchor=parts[0], n_local=parts[1], k_exact=parts[2], k_lsh=parts[3], keep_idx=keep,
+                             dbg_s_exact=dbg["s_exact"], dbg_sig_k=dbg["sig_k"], dbg_sig_q=dbg["sig_q"], dbg_count=dbg["cnt"])
+    torch.cuda.synchronize()
+    st = O.select_block(f64(data["q_win"][0]), f64(data["k"][:, :s]), None, f64(data["planes"]), wl.lsh_tables,
+                        wl.lsh_bits, *parts, block_pos0=0)
+    rep = check_block(st, gpu_stage(dbg, keep), parts, wl.dtype)
+    say(f"[padded strides {dtype}] max score err/(s+s_k) {rep['max_rel']:.2e}, tolerated {rep['tolerated']}")
+    lib.close()
