@@ -429,6 +429,11 @@ int select_impl(laserkv_ctx* ctx,
     if (n_kr < 1) n_kr = 1;
     int kpr = ((s_t + n_kr - 1) / n_kr + 1023) / 1024 * 1024;
     if (kpr > lkv::count_max_keys_per_range()) kpr = lkv::count_max_keys_per_range();
+    // the workgroup stages its tables' codes of all window queries and of its keys in LDS beside the histogram:
+    // fewer table groups per workgroup, then shorter key ranges, until that fits
+    while (lkv::count_lds_bytes(c.lsh_bits, tg, gpw, m_rows, kpr) > 156 * 1024 && gpw > 1) gpw /= 2;
+    while (lkv::count_lds_bytes(c.lsh_bits, tg, gpw, m_rows, kpr) > 156 * 1024 && kpr > 64) kpr /= 2;
+    cp.groups_per_wg = gpw;
     cp.keys_per_range = kpr;
   }
 

@@ -122,5 +122,7 @@ size_t sweep_lds_bytes(int dtype, int head_dim, bool pass2, int range_keys, int 
 int sweep_rows_per_group();  // window rows one sweep workgroup covers
 int score_max_range();  // most keys one score workgroup takes (its LDS holds the whole range)
 int count_max_keys_per_range();
+// LDS of a count workgroup: the histogram of one table group plus the staged query and key codes of all its tables
+size_t count_lds_bytes(int n_bits, int tables_per_group, int groups_per_wg, int n_query_rows, int keys_per_range);
 
 }  // namespace lkv

@@ -684,72 +684,100 @@ __global__ __launch_bounds__(PASS_WAVES * 64) void pass_kernel(PassParams p) {
 
 // ---------------------------------------------------------------------------------------------
 // Collision counts as a kernel of their own (codes too wide for resident histograms).  Workgroup =
-// (key range, set of table groups, KV head).  The G*W query codes of each table of a group are
-// histogrammed into LDS (two 16-bit bins per word); each key then looks its own code up per table.
-// Partial sums over the workgroups of a key meet in integer atomics.
+// (key range, set of table groups, KV head).  All codes the workgroup needs -- its tables' codes of
+// the G*W window queries and of the range's keys -- are fetched into LDS once, so that only one
+// round trip to memory lies on the kernel's critical path.  Then, one table group after the other
+// through the same LDS histogram (two 16-bit bins per word): the query codes are histogrammed, every
+// key looks its own codes up, and the bins that were touched are cleared again.  A key's count over
+// all the workgroup's tables meets in a register and costs one global atomic.
 // ---------------------------------------------------------------------------------------------
 constexpr int COUNT_THREADS = 1024;
 constexpr int COUNT_KEYS_PER_THREAD = 8;  // keys_per_range <= COUNT_THREADS * COUNT_KEYS_PER_THREAD
 __global__ __launch_bounds__(COUNT_THREADS) void count_kernel(CountParams p) {
-  extern __shared__ uint32_t bins[];
+  extern __shared__ uint32_t bins[];  // [tables_per_group << n_bits] / 2 words, then the staged codes
   const int tid = threadIdx.x;
   const int kr = blockIdx.x, h = blockIdx.z;
   const int nq = p.group * p.w;
   const int i0 = kr * p.keys_per_range;
   const int i1 = min(i0 + p.keys_per_range, p.s_t);
+  const int n_keys = i1 - i0;
+  const int t_first = blockIdx.y * p.groups_per_wg * p.tables_per_group;            // the workgroup's tables
+  const int ntw = min(p.groups_per_wg * p.tables_per_group, p.n_tables - t_first);  // > 0 by the grid's construction
+  const int n_bin_words = (p.tables_per_group << p.n_bits) >> 1;
+  uint16_t* sQ = reinterpret_cast<uint16_t*>(bins + ((n_bin_words + 3) & ~3));  // [ntw][nq]
+  uint16_t* sKc = sQ + ((ntw * nq + 7) & ~7);                                   // [n_keys][ntw]
+  // 1. everything from memory, issued back to back: query codes (transposed to table-major), key codes
+  const uint16_t* gq = p.sig_q + (size_t)h * nq * p.n_tables + t_first;
+  const uint16_t* gk = p.sig_k + ((size_t)h * p.s_t + i0) * p.n_tables + t_first;
+  const bool vec8 = (ntw & 7) == 0 && (p.n_tables & 7) == 0 && (t_first & 7) == 0;  // rows of whole aligned 16-byte groups
+  if (vec8) {
+    const int g8 = ntw >> 3;
+    for (int e = tid; e < nq * g8; e += COUNT_THREADS) {
+      const int qrow = e / g8, gi = e - qrow * g8;
+      const uint4 v = ld16(gq + (size_t)qrow * p.n_tables + gi * 8);
+      const uint32_t wv[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+      for (int u = 0; u < 8; ++u) sQ[(gi * 8 + u) * nq + qrow] = (uint16_t)(wv[u >> 1] >> ((u & 1) * 16));
+    }
+    for (int e = tid; e < n_keys * g8; e += COUNT_THREADS) {
+      const int key = e / g8, gi = e - key * g8;
+      *reinterpret_cast<uint4*>(sKc + (size_t)key * ntw + gi * 8) = ld16(gk + (size_t)key * p.n_tables + gi * 8);
+    }
+  } else {
+    for (int e = tid; e < nq * ntw; e += COUNT_THREADS) {
+      const int qrow = e / ntw, tl = e - qrow * ntw;
+      sQ[tl * nq + qrow] = gq[(size_t)qrow * p.n_tables + tl];
+    }
+    for (int e = tid; e < n_keys * ntw; e += COUNT_THREADS) {
+      const int key = e / ntw, tl = e - key * ntw;
+      sKc[(size_t)key * ntw + tl] = gk[(size_t)key * p.n_tables + tl];
+    }
+  }
+  if ((n_bin_words & 3) == 0) {
+    uint4* b4 = reinterpret_cast<uint4*>(bins);
+    for (int i = tid; i < n_bin_words / 4; i += COUNT_THREADS) b4[i] = make_uint4(0u, 0u, 0u, 0u);
+  } else {
+    for (int i = tid; i < n_bin_words; i += COUNT_THREADS) bins[i] = 0u;
+  }
   int sum[COUNT_KEYS_PER_THREAD];
 #pragma unroll
   for (int k = 0; k < COUNT_KEYS_PER_THREAD; ++k) sum[k] = 0;
-  // the workgroup's table groups one after the other through the same LDS histogram, so a key's
-  // counts over all of them meet in a register and cost one global atomic
-  for (int pass = 0; pass < p.groups_per_wg; ++pass) {
-    const int t0 = (blockIdx.y * p.groups_per_wg + pass) * p.tables_per_group;
-    const int tga = min(p.tables_per_group, p.n_tables - t0);
-    if (tga <= 0) break;  // block-uniform
-    const uint16_t* sq = p.sig_q + (size_t)h * nq * p.n_tables + t0;
-    if (pass == 0) {
-      const int n_words = (tga << p.n_bits) >> 1;
-      if ((n_words & 3) == 0) {
-        uint4* b4 = reinterpret_cast<uint4*>(bins);
-        for (int i = tid; i < n_words / 4; i += COUNT_THREADS) b4[i] = make_uint4(0u, 0u, 0u, 0u);
-      } else {
-        for (int i = tid; i < n_words; i += COUNT_THREADS) bins[i] = 0u;
-      }
-    } else {
-      // only the bins of the previous group's query codes are non-zero
-      const int tp = t0 - p.tables_per_group;
-      const uint16_t* sp = p.sig_q + (size_t)h * nq * p.n_tables + tp;
-      for (int e = tid; e < nq * p.tables_per_group; e += COUNT_THREADS) {
-        const int qrow = e / p.tables_per_group, tl = e - qrow * p.tables_per_group;
-        const uint32_t idx = ((uint32_t)tl << p.n_bits) | sp[(size_t)qrow * p.n_tables + tl];
-        bins[idx >> 1] = 0u;
-      }
-    }
-    __syncthreads();
+  __syncthreads();
+  // 2. the table groups, one after the other, in LDS only
+  for (int g0 = 0; g0 < ntw; g0 += p.tables_per_group) {
+    const int tga = min(p.tables_per_group, ntw - g0);
     for (int e = tid; e < nq * tga; e += COUNT_THREADS) {
-      const int qrow = e / tga, tl = e - qrow * tga;
-      const uint32_t idx = ((uint32_t)tl << p.n_bits) | sq[(size_t)qrow * p.n_tables + tl];
+      const int tl = e / nq, qrow = e - tl * nq;
+      const uint32_t idx = ((uint32_t)tl << p.n_bits) | sQ[(g0 + tl) * nq + qrow];
       atomicAdd(&bins[idx >> 1], 1u << ((idx & 1u) * 16));
     }
     __syncthreads();
 #pragma unroll
     for (int k = 0; k < COUNT_KEYS_PER_THREAD; ++k) {
-      const int i = i0 + tid + k * COUNT_THREADS;
-      if (i < i1) {
-        const uint16_t* sk = p.sig_k + ((size_t)h * p.s_t + i) * p.n_tables + t0;
+      const int key = tid + k * COUNT_THREADS;
+      if (key < n_keys) {
+        const uint16_t* kc = sKc + (size_t)key * ntw + g0;
         for (int tl = 0; tl < tga; ++tl) {
-          const uint32_t code = sk[tl];
-          const uint32_t idx = ((uint32_t)tl << p.n_bits) | code;
+          const uint32_t idx = ((uint32_t)tl << p.n_bits) | kc[tl];
           sum[k] += (bins[idx >> 1] >> ((idx & 1u) * 16)) & 0xffffu;
         }
       }
     }
-    __syncthreads();  // lookups done before the next pass clears and refills the bins
+    if (g0 + p.tables_per_group < ntw) {  // block-uniform: another group follows
+      __syncthreads();                    // lookups done before the bins are cleared
+      // only the bins of this group's query codes are non-zero
+      for (int e = tid; e < nq * tga; e += COUNT_THREADS) {
+        const int tl = e / nq, qrow = e - tl * nq;
+        const uint32_t idx = ((uint32_t)tl << p.n_bits) | sQ[(g0 + tl) * nq + qrow];
+        bins[idx >> 1] = 0u;
+      }
+      __syncthreads();
+    }
   }
 #pragma unroll
   for (int k = 0; k < COUNT_KEYS_PER_THREAD; ++k) {
-    const int i = i0 + tid + k * COUNT_THREADS;
-    if (i < i1) atomicAdd(&p.cnt[(size_t)h * p.s_t + i], sum[k]);
+    const int key = tid + k * COUNT_THREADS;
+    if (key < n_keys) atomicAdd(&p.cnt[(size_t)h * p.s_t + i0 + key], sum[k]);
   }
 }
 
@@ -1183,7 +1211,7 @@ static hipError_t pass_attrs() {
 
 hipError_t init_kernel_attributes() {
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&count_kernel),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024);
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
   if (e == hipSuccess) e = pass_attrs<DT_BF16, 128>();
   if (e == hipSuccess) e = pass_attrs<DT_BF16, 64>();
   if (e == hipSuccess) e = pass_attrs<DT_F32, 128>();
@@ -1194,12 +1222,19 @@ hipError_t init_kernel_attributes() {
 int score_max_range() { return SCORE_MAX_RANGE; }
 int sweep_rows_per_group() { return PASS_ROWS; }
 
+size_t count_lds_bytes(int n_bits, int tables_per_group, int groups_per_wg, int n_query_rows, int keys_per_range) {
+  const size_t bin_words = (((size_t)tables_per_group << n_bits) / 2 + 3) & ~(size_t)3;
+  const size_t ntw = (size_t)groups_per_wg * tables_per_group;
+  return bin_words * 4 + ((ntw * n_query_rows + 7) & ~(size_t)7) * 2 + ntw * keys_per_range * 2 + 16;
+}
+
 hipError_t launch_count(const CountParams& p, int n_kv_heads, hipStream_t st) {
   const int n_tg = (p.n_tables + p.tables_per_group - 1) / p.tables_per_group;
   const int n_wg_t = (n_tg + p.groups_per_wg - 1) / p.groups_per_wg;
   const int n_kr = (p.s_t + p.keys_per_range - 1) / p.keys_per_range;
   if (p.keys_per_range > COUNT_THREADS * COUNT_KEYS_PER_THREAD) return hipErrorInvalidValue;
-  const size_t lds = ((size_t)p.tables_per_group << p.n_bits) * 2;
+  const size_t lds = count_lds_bytes(p.n_bits, p.tables_per_group, p.groups_per_wg, p.group * p.w, p.keys_per_range);
+  if (lds > 160 * 1024) return hipErrorInvalidValue;
   dim3 grid(n_kr, n_wg_t, n_kv_heads);
   hipLaunchKernelGGL(count_kernel, grid, dim3(COUNT_THREADS), lds, st, p);
   return hipGetLastError();
