@@ -356,28 +356,41 @@ int select_impl(laserkv_ctx* ctx,
   const int n_qg = (m_rows + lkv::sweep_rows_per_group() - 1) / lkv::sweep_rows_per_group();
   sp.n_qgroups = n_qg;
   sp.n_kv_heads = c.n_kv_heads;
-  // key ranges: about one workgroup per compute unit per query-row group, each range in one source
+  // Key ranges, about one workgroup per compute unit and query-row group.  Sweep 1: ranges of nk keys, each
+  // entirely look-back keys or entirely block keys.  Sweep 2 scores block keys only and has ranges of its
+  // own: one round of workgroups if such ranges fit the LDS, else two, three, ... whole rounds.
   const int wg_target = ctx->n_cu * ctx->sweep_wg_per_cu;
-  int nr = wg_target / (c.n_kv_heads * n_qg);
-  if (nr < 1) nr = 1;
-  if (nr > ctx->max_ranges - 1) nr = ctx->max_ranges - 1;
-  int nk = ((n_keys + nr - 1) / nr + 31) / 32 * 32;
+  int nr0 = wg_target / (c.n_kv_heads * n_qg);
+  if (nr0 < 1) nr0 = 1;
+  int nk = ((n_keys + nr0 - 1) / nr0 + 31) / 32 * 32;
   if (nk > lkv::score_max_range()) nk = lkv::score_max_range();
-  // the query-code job of a workgroup: ceil(L / n_ranges) tables, floor(32 / K) whole tables per plane
-  // tile, and (when they fit 32 KiB of LDS) their histograms
+  // the query-code job of a sweep-1 workgroup: ceil(L / n_ranges) tables, floor(32 / K) whole tables per
+  // plane tile, and (when they fit 32 KiB of LDS) their histograms
   sp.q_tab_per_tile = 32 / c.lsh_bits;
   for (;;) {
-    sp.keys_per_range = nk;
+    sp.keys_per_range = sp.blk_per_range = sp.ctx_per_range = nk;
     sp.n_ctx_ranges = (t_ctx + nk - 1) / nk;
     sp.n_ranges = sp.n_ctx_ranges + (s_t + nk - 1) / nk;
     sp.q_tab_per_wg = (c.lsh_tables + sp.n_ranges - 1) / sp.n_ranges;
     sp.q_tiles = (sp.q_tab_per_wg + sp.q_tab_per_tile - 1) / sp.q_tab_per_tile;
     const size_t hist_words = ((size_t)sp.q_tab_per_wg << c.lsh_bits) / 2;
     sp.hist_lds_words = (ctx->qhist && hist_words * 4 <= 32 * 1024) ? (int)(hist_words ? hist_words : 1) : 0;
-    if (nk <= 32 || (lkv::sweep_lds_bytes(c.dtype, d, false, nk, sp.q_tiles, sp.hist_lds_words) <= 150 * 1024 &&
-                     lkv::sweep_lds_bytes(c.dtype, d, true, nk, 0, 0) <= 160 * 1024))
-      break;
+    if (nk <= 32 || lkv::sweep_lds_bytes(c.dtype, d, false, nk, sp.q_tiles, sp.hist_lds_words) <= 150 * 1024) break;
     nk -= 32;
+  }
+  sp.n_parts = sp.n_ranges;
+  {
+    auto fits2 = [&](int blk) { return blk <= lkv::score_max_range() && lkv::sweep_lds_bytes(c.dtype, d, true, blk, 0, 0) <= 160 * 1024; };
+    int blk = 32;
+    bool ok = false;
+    for (int rounds = 1; rounds <= 64 && !ok; ++rounds) {
+      blk = ((s_t + nr0 * rounds - 1) / (nr0 * rounds) + 31) / 32 * 32;
+      ok = fits2(blk);
+      if (blk == 32) break;
+    }
+    while (!ok && blk > 32) ok = fits2(blk -= 32);
+    sp.s2_blk_per_range = blk;
+    sp.s2_ranges = (s_t + blk - 1) / blk;
   }
   if (lkv::sweep_lds_bytes(c.dtype, d, false, nk, sp.q_tiles, sp.hist_lds_words) > 160 * 1024)
     return fail(ctx, LKV_EINVAL, "select_block: s_t + t_ctx = %d keys are too few to spread %d tables of %d bits over "

@@ -26,9 +26,16 @@ struct PassParams {
   int m_rows;      // M = G * W
   int s_t;         // S
   int t_ctx;       // T
-  int keys_per_range;   // NK (multiple of 32, <= score_max_range())
-  int n_ranges;         // NR = n_ctx_ranges + ranges over the block keys
-  int n_ctx_ranges;     // ranges that cover the look-back keys (each range lies in one source)
+  // key ranges of sweep 1: n_ctx_ranges ranges of ctx_per_range look-back keys, then ranges of blk_per_range block keys
+  int keys_per_range;   // key rows a workgroup's LDS holds (multiple of 32, <= score_max_range())
+  int blk_per_range;    // block keys per block range (multiple of 32)
+  int ctx_per_range;    // look-back keys per look-back range (multiple of 32)
+  int n_ctx_ranges;     // ceil(T / ctx_per_range)
+  int n_ranges;         // n_ctx_ranges + ceil(S / blk_per_range)
+  int n_parts;          // sweep-1 partials per window row (= sweep 1's n_ranges)
+  // key ranges of sweep 2 (block keys only); the launcher rewrites the fields above from these
+  int s2_blk_per_range; // multiple of 32
+  int s2_ranges;        // ceil(S / s2_blk_per_range)
   int n_qgroups;        // ceil(M / sweep_rows_per_group())
   int n_kv_heads;
   int causal;

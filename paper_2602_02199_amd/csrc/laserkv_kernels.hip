@@ -94,19 +94,22 @@ __global__ __launch_bounds__(PASS_WAVES * 64) void pass_kernel(PassParams p) {
     kr = rem / n_qg;
     qg = rem - kr * n_qg;
   }
-  const int nkr = p.keys_per_range;
-  // a range lies entirely in the look-back keys or entirely in the block keys, so the source
-  // base, stride and row offset are uniform over the workgroup
-  const bool in_ctx = kr < p.n_ctx_ranges;
-  const int seg_row0 = in_ctx ? kr * nkr : (kr - p.n_ctx_ranges) * nkr;
-  const int seg_rows = in_ctx ? p.t_ctx : p.s_t;
-  const int n_keys_wg = min(nkr, seg_rows - seg_row0);             // keys of this range
-  const int k0 = in_ctx ? seg_row0 : p.t_ctx + seg_row0;            // global key index of the range start
-  const int k1 = k0 + n_keys_wg;
-  const RowSrc ksrc = in_ctx ? p.kc : p.kb;
-  const char* kbase_ptr = ksrc.base + (int64_t)h * ksrc.stride_head;
-  const int kstride = (int)ksrc.stride_row;
-  const int n_tiles = (n_keys_wg + 31) >> 5;
+  const int nkr = p.keys_per_range;  // key rows the LDS holds
+  // The first n_ctx_ranges ranges of sweep 1 hold look-back keys (ctx_per_range each; they only enter the
+  // normaliser), the others blk_per_range consecutive block keys each; sweep 2 has block ranges only, of a
+  // length of its own.  In LDS, rows [0, nb) are block keys b0 .., rows [nb, nb + nc) look-back keys c0 ...
+  const int kb = kr - p.n_ctx_ranges;
+  const int b0 = max(kb, 0) * p.blk_per_range;
+  const int nb = kb < 0 ? 0 : min(p.blk_per_range, p.s_t - b0);    // block keys of this range
+  const int c0 = kr * p.ctx_per_range;
+  const int nc = kb < 0 ? min(p.ctx_per_range, p.t_ctx - c0) : 0;  // look-back keys of this range
+  const int n_rows = nb + nc;
+  const int k0 = p.t_ctx + b0;  // key index of block row 0 (look-back keys count first): key k is visible
+  const int k1 = k0 + nb;       // to window row j iff k <= lim0 + j
+  const char* kb_ptr = p.kb.base + (int64_t)h * p.kb.stride_head;
+  const char* kc_ptr = p.kc.base + (int64_t)h * p.kc.stride_head;  // null base when there are no look-back keys
+  const int kb_stride = (int)p.kb.stride_row, kc_stride = (int)p.kc.stride_row;
+  const int n_tiles = (n_rows + 31) >> 5;
   // sweep 1: the tables whose QUERY codes (for the window rows of group qg) this workgroup owns ...
   const int qt0 = kr * p.q_tab_per_wg;
   const int n_qt = PASS2 ? 0 : max(0, min(p.q_tab_per_wg, p.n_tables - qt0));
@@ -141,13 +144,13 @@ __global__ __launch_bounds__(PASS_WAVES * 64) void pass_kernel(PassParams p) {
   constexpr bool STAGE_A = CH <= 16;                 // wider rows: fragments straight from memory
   constexpr int QL = STAGE_A ? MQ * CH / NTHR : 1;   // 16-byte chunks per thread: query panel
   constexpr int KL = STAGE_A ? ((SCORE_MAX_RANGE + 32) * CH + NTHR - 1) / NTHR : 1;  // keys + one tile of planes
-  const int n_kchunks = n_tiles * 32 * CH;           // rows past the range are clamped copies, masked later
+  const int n_kchunks = n_tiles * 32 * CH;           // rows past the range: any readable row, masked later
   const int n_chunks = n_kchunks + n_qpt * 32 * CH;
   auto key_chunk = [&](int q) -> uint4 {
     if (q < n_kchunks) {
       const int row = q / CH, c = q % CH;
-      const int lrow = min(seg_row0 + row, seg_rows - 1);
-      return ld16(kbase_ptr + (uint32_t)(lrow * kstride + c * 16));
+      if (row < nb || nc == 0) return ld16(kb_ptr + (uint32_t)(min(b0 + row, p.s_t - 1) * kb_stride + c * 16));
+      return ld16(kc_ptr + (uint32_t)(min(c0 + row - nb, p.t_ctx - 1) * kc_stride + c * 16));
     }
     // planes of the query job: tile t holds the planes of whole tables qt0 + t*q_tab_per_tile ..., padded
     // with copies of its last plane
@@ -182,15 +185,15 @@ __global__ __launch_bounds__(PASS_WAVES * 64) void pass_kernel(PassParams p) {
   // codes are fetched here with the other loads, each loop iteration issues the histogram lookups of
   // two tables and adds up those of the iteration before, so their latency costs nothing.
   const int tab0c = qg * p.tables_per_split;
-  const int n_tabc = PASS2 && p.qhist && !in_ctx ? max(0, min(p.tables_per_split, p.n_tables - tab0c)) : 0;
+  const int n_tabc = PASS2 && p.qhist ? max(0, min(p.tables_per_split, p.n_tables - tab0c)) : 0;
   int lpk_log = n_tabc > 16 ? 2 : (n_tabc > 8 ? 1 : 0);
-  while (lpk_log > 0 && (n_keys_wg << lpk_log) > NTHR) --lpk_log;
+  while (lpk_log > 0 && (nb << lpk_log) > NTHR) --lpk_log;
   const bool cnt_piped = NCH <= 8 && n_tabc > 0 && n_tabc == (8 << lpk_log) && (p.n_tables & 7) == 0 && (tab0c & 7) == 0 &&
-                         (n_keys_wg << lpk_log) <= NTHR && n_qg == 2;
-  const bool cnt_lane = cnt_piped && tid < (n_keys_wg << lpk_log);
+                         (nb << lpk_log) <= NTHR && n_qg == 2;
+  const bool cnt_lane = cnt_piped && tid < (nb << lpk_log);
   const int cnt_key = tid >> lpk_log, cnt_tb = (tid & ((1 << lpk_log) - 1)) * 8;
   uint4 cnt_codes = make_uint4(0u, 0u, 0u, 0u);  // two 16-bit codes per word, consumed from .x upwards
-  if (cnt_lane) cnt_codes = ld16(p.sig_k + ((size_t)h * p.s_t + seg_row0 + cnt_key) * p.n_tables + tab0c + cnt_tb);
+  if (cnt_lane) cnt_codes = ld16(p.sig_k + ((size_t)h * p.s_t + b0 + cnt_key) * p.n_tables + tab0c + cnt_tb);
 
   uint4 a[NCH];  // A operand: this wave's 32 window rows, or (hashing waves) its first 32 planes
   if (STAGE_A) {
@@ -224,13 +227,19 @@ __global__ __launch_bounds__(PASS_WAVES * 64) void pass_kernel(PassParams p) {
       for (int u = 0; u < QL; ++u) ppre[u] = buf_ld16(psrd, poff + u * ROWS_PER_LOAD * (D * ES));
     }
     {
-      const __amdgpu_buffer_rsrc_t ksrd = make_srd(kbase_ptr, (uint32_t)seg_rows * (uint32_t)kstride);
-      const uint32_t koff = (seg_row0 + trow) * (uint32_t)kstride + tcol;
+      const __amdgpu_buffer_rsrc_t kb_srd = make_srd(kb_ptr, (uint32_t)p.s_t * (uint32_t)kb_stride);
+      const __amdgpu_buffer_rsrc_t kc_srd = make_srd(kc_ptr, (uint32_t)p.t_ctx * (uint32_t)kc_stride);
 #pragma unroll
       for (int u = 0; u < KL; ++u) {
         const int q = tid + NTHR * u;
-        if (q < n_kchunks) kpre[u] = buf_ld16(ksrd, koff + u * ROWS_PER_LOAD * (uint32_t)kstride);
-        else if (q < n_chunks) kpre[u] = key_chunk(q);
+        const int row = (int)trow + u * ROWS_PER_LOAD;  // LDS row of this chunk
+        if (q < n_kchunks) {
+          // two loads under complementary lane masks (a select between the descriptors would be looped over)
+          if (PASS2 || row < nb) kpre[u] = buf_ld16(kb_srd, (uint32_t)(b0 + row) * (uint32_t)kb_stride + tcol);
+          else kpre[u] = buf_ld16(kc_srd, (uint32_t)(c0 + row - nb) * (uint32_t)kc_stride + tcol);
+        } else if (q < n_chunks) {
+          kpre[u] = key_chunk(q);
+        }
       }
     }
     if (PASS2) {
@@ -310,18 +319,18 @@ __global__ __launch_bounds__(PASS_WAVES * 64) void pass_kernel(PassParams p) {
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
       const int r = pr_beg + 2 * u;
-      if (2 * u < pr_per && r < p.n_ranges) mm = fmaxf(mm, __uint_as_float(pv[u].x));
-      if (2 * u < pr_per && r + 1 < p.n_ranges) mm = fmaxf(mm, __uint_as_float(pv[u].z));
+      if (2 * u < pr_per && r < p.n_parts) mm = fmaxf(mm, __uint_as_float(pv[u].x));
+      if (2 * u < pr_per && r + 1 < p.n_parts) mm = fmaxf(mm, __uint_as_float(pv[u].z));
     }
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
       const int r = pr_beg + 2 * u;
-      if (2 * u < pr_per && r < p.n_ranges) ss = fmaf(__uint_as_float(pv[u].y), fast_exp2(__uint_as_float(pv[u].x) - mm), ss);
-      if (2 * u < pr_per && r + 1 < p.n_ranges) ss = fmaf(__uint_as_float(pv[u].w), fast_exp2(__uint_as_float(pv[u].z) - mm), ss);
+      if (2 * u < pr_per && r < p.n_parts) ss = fmaf(__uint_as_float(pv[u].y), fast_exp2(__uint_as_float(pv[u].x) - mm), ss);
+      if (2 * u < pr_per && r + 1 < p.n_parts) ss = fmaf(__uint_as_float(pv[u].w), fast_exp2(__uint_as_float(pv[u].z) - mm), ss);
     }
     for (int e = 8; e < pr_per; ++e) {  // more than 32 ranges per head: the rest, not prefetched
       const float2 v = pr_ptr[e];
-      if (pr_beg + e < p.n_ranges) lse_merge(mm, ss, v.x, v.y);
+      if (pr_beg + e < p.n_parts) lse_merge(mm, ss, v.x, v.y);
     }
     // keys outside this call, summarised by the caller as one log-sum-exp per window row, join the
     // normaliser like one more partial (natural log -> exp2 domain)
@@ -346,9 +355,9 @@ __global__ __launch_bounds__(PASS_WAVES * 64) void pass_kernel(PassParams p) {
     // the general shape: the whole job before the main loop, eight tables at a time from the L2-resident
     // query histograms
     const int lpk = 1 << lpk_log;
-    for (int kq = tid; kq < (n_keys_wg << lpk_log); kq += NTHR) {
+    for (int kq = tid; kq < (nb << lpk_log); kq += NTHR) {
       const int key = kq >> lpk_log, sub = kq & (lpk - 1);
-      const uint16_t* sk = p.sig_k + ((size_t)h * p.s_t + seg_row0 + key) * p.n_tables + tab0c;
+      const uint16_t* sk = p.sig_k + ((size_t)h * p.s_t + b0 + key) * p.n_tables + tab0c;
       int sum = 0;
       for (int tb = sub * 8; tb < n_tabc; tb += 8 * lpk) {
         uint32_t cw[4];
@@ -396,7 +405,7 @@ __global__ __launch_bounds__(PASS_WAVES * 64) void pass_kernel(PassParams p) {
       }
       if (lpk > 1) sum += __shfl_xor(sum, 1);
       if (lpk > 2) sum += __shfl_xor(sum, 2);
-      if (sub == 0) p.cnt[((size_t)qg * p.n_kv_heads + h) * p.s_t + seg_row0 + key] = sum;
+      if (sub == 0) p.cnt[((size_t)qg * p.n_kv_heads + h) * p.s_t + b0 + key] = sum;
     }
   }
 
@@ -450,11 +459,17 @@ __global__ __launch_bounds__(PASS_WAVES * 64) void pass_kernel(PassParams p) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) col += fast_exp2(fmaf(acc[r], p.scale2, -lse[r]));
       } else {
+        // registers 4g .. 4g+3 of a lane are four consecutive window rows: their limits come as one 16-byte read
+        const bool in_range = kidx < k1;
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const bool vis = kidx < k1 && kidx <= sLim[rt * 32 + acc_row(r, kg)];
-          const float e = fast_exp2(fmaf(acc[r], p.scale2, -lse[r]));
-          col += vis ? e : 0.0f;
+        for (int g4 = 0; g4 < 4; ++g4) {
+          const int4 lim4 = *reinterpret_cast<const int4*>(&sLim[rt * 32 + acc_row(4 * g4, kg)]);
+          const int lims[4] = {lim4.x, lim4.y, lim4.z, lim4.w};
+#pragma unroll
+          for (int u = 0; u < 4; ++u) {
+            const float e = fast_exp2(fmaf(acc[4 * g4 + u], p.scale2, -lse[4 * g4 + u]));
+            col += (in_range & (kidx <= lims[u])) ? e : 0.0f;
+          }
         }
       }
       col += __shfl_xor(col, 32);
@@ -490,7 +505,7 @@ __global__ __launch_bounds__(PASS_WAVES * 64) void pass_kernel(PassParams p) {
       if (lpk_log > 0) cnt_sum += __shfl_xor(cnt_sum, 1);
       if (lpk_log > 1) cnt_sum += __shfl_xor(cnt_sum, 2);
       if (cnt_lane && (tid & ((1 << lpk_log) - 1)) == 0)
-        p.cnt[((size_t)qg * p.n_kv_heads + h) * p.s_t + seg_row0 + cnt_key] = cnt_sum;
+        p.cnt[((size_t)qg * p.n_kv_heads + h) * p.s_t + b0 + cnt_key] = cnt_sum;
     }
   } else if (!hash_wave) {
     // Sweep 1 multiplies the other way round (keys as the A operand, window rows as B): lane = window
@@ -508,13 +523,21 @@ __global__ __launch_bounds__(PASS_WAVES * 64) void pass_kernel(PassParams p) {
       for (int i = 0; i < NCH; ++i) Mma<DT>::run(acc, krow[2 * i], a[i]);
     };
     // scaled logits of a tile whose tail may be outside the range or hidden by the causal mask
+    const int last_blk = min(lim - k0, nb - 1);  // last block row this window row may see (negative: none)
     auto masked = [&](int nt, f32x16& acc) {
-      const int kb0 = k0 + nt * 32 + 4 * kg;
+      // register r holds the key in LDS row rb + 8*(r/4) + (r&3); the look-back rows [nb, n_rows) are always visible
+      const int rb = nt * 32 + 4 * kg;
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        const int kidx = kb0 + 8 * (r >> 2) + (r & 3);
-        acc[r] = (kidx < k1 && kidx <= lim) ? acc[r] * p.scale2 : NEG_BIG;
+        const int row = rb + 8 * (r >> 2) + (r & 3);
+        const bool vis = (row <= last_blk) | ((unsigned)(row - nb) < (unsigned)nc);  // no short circuit: straight-line code
+        acc[r] = vis ? acc[r] * p.scale2 : NEG_BIG;
       }
+    };
+    // tiles that need the masks (wave-uniform): rows past the range, or block keys beyond the first window row's limit
+    auto needs_mask = [&](int nt) {
+      const int t0 = nt * 32;
+      return t0 + 32 > n_rows || (p.causal && t0 < nb && k0 + min(t0 + 31, nb - 1) > p.lim0);
     };
     float ref, sum = 0.0f;
     {
@@ -530,11 +553,9 @@ __global__ __launch_bounds__(PASS_WAVES * 64) void pass_kernel(PassParams p) {
     }
 #pragma unroll 1
     for (int nt = 1; nt < n_tiles; ++nt) {
-      const int kbase = k0 + nt * 32;
       f32x16 acc;
       tile(nt, acc);
-      const bool partial = (kbase + 32 > k1) || (p.causal && (kbase + 31 > p.lim0));  // wave-uniform
-      if (!partial) {
+      if (!needs_mask(nt)) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) sum += fast_exp2(fmaf(acc[r], p.scale2, -ref));
       } else {
@@ -600,7 +621,7 @@ __global__ __launch_bounds__(PASS_WAVES * 64) void pass_kernel(PassParams p) {
     }
   } else {
     // hashing waves: SimHash sign bits of the range's block keys
-    const int n_vt = in_ctx ? 0 : n_tiles;  // look-back keys are never candidates: not hashed
+    const int n_vt = (nb + 31) >> 5;  // look-back keys are never candidates: not hashed
 #pragma unroll 1
     for (int mt = rt; mt < n_mt; mt += 8) {
       if (mt != rt) {
@@ -632,21 +653,18 @@ __global__ __launch_bounds__(PASS_WAVES * 64) void pass_kernel(PassParams p) {
 
   if (PASS2) {
     __syncthreads();
-    for (int t = tid; t < n_keys_wg; t += NTHR) {
-      const int kidx = k0 + t;
-      if (kidx >= p.t_ctx) {
-        float v = 0.0f;
+    for (int t = tid; t < nb; t += NTHR) {
+      float v = 0.0f;
 #pragma unroll
-        for (int w = 0; w < 8; ++w) v += sCol[w * nkr + t];
-        p.s_part[((size_t)qg * p.n_kv_heads + h) * p.s_t + (kidx - p.t_ctx)] = v;
-      }
+      for (int w = 0; w < 8; ++w) v += sCol[w * nkr + t];
+      p.s_part[((size_t)qg * p.n_kv_heads + h) * p.s_t + b0 + t] = v;
     }
   } else {
     __syncthreads();
     // key codes: one item = (key, group of 8 tables) -> one 16-byte store where aligned
     const uint32_t code_mask = (1u << p.n_bits) - 1u;
     const int n_tg8 = (n_tab + 7) >> 3;
-    const int n_items = (in_ctx ? 0 : n_keys_wg) * n_tg8;
+    const int n_items = nb * n_tg8;
     for (int it = tid; it < n_items; it += NTHR) {
       const int vr = it / n_tg8, tb = (it - vr * n_tg8) * 8;
       const uint32_t* bits = sBits + (size_t)vr * BITS_PITCH;
@@ -658,7 +676,7 @@ __global__ __launch_bounds__(PASS_WAVES * 64) void pass_kernel(PassParams p) {
         const uint64_t two = (uint64_t)bits[w0] | ((uint64_t)bits[w0 + 1] << 32);
         codes[u] = (uint32_t)(two >> sh) & code_mask;
       }
-      uint16_t* dst = p.sig_k + ((size_t)h * p.s_t + seg_row0 + vr) * p.n_tables + tab0 + tb;
+      uint16_t* dst = p.sig_k + ((size_t)h * p.s_t + b0 + vr) * p.n_tables + tab0 + tb;
       if (tb + 8 <= n_tab && ((reinterpret_cast<uintptr_t>(dst) & 15) == 0)) {
         const uint4 cv = make_uint4(codes[0] | (codes[1] << 16), codes[2] | (codes[3] << 16),
                                     codes[4] | (codes[5] << 16), codes[6] | (codes[7] << 16));
@@ -677,8 +695,8 @@ __global__ __launch_bounds__(PASS_WAVES * 64) void pass_kernel(PassParams p) {
       uint32_t* dst = p.qhist + ((size_t)h * p.n_tables + qt0) * hist_w * n_qg + qg;
       for (int i = tid; i < n_qt * hist_w; i += NTHR) dst[(size_t)i * n_qg] = sHist[i];
     }
-    if (!p.qhist && !in_ctx && qg == 0)  // the separate count kernel accumulates with atomics
-      for (int t = tid; t < n_keys_wg; t += NTHR) p.cnt[(size_t)h * p.s_t + seg_row0 + t] = 0;
+    if (!p.qhist && qg == 0)  // the separate count kernel accumulates with atomics
+      for (int t = tid; t < nb; t += NTHR) p.cnt[(size_t)h * p.s_t + b0 + t] = 0;
   }
 }
 
@@ -1175,10 +1193,16 @@ size_t sweep_lds_bytes(int dtype, int head_dim, bool pass2, int range_keys, int 
 
 template <int DT, int D, bool PASS2>
 static hipError_t launch_pass_t(const PassParams& p, hipStream_t st) {
-  dim3 grid(p.n_ranges * p.n_qgroups * p.n_kv_heads);
+  dim3 grid((PASS2 ? p.s2_ranges : p.n_ranges) * p.n_qgroups * p.n_kv_heads);
   PassParams q = p;
-  q.lds_tail_offset = (int)sweep_lds_tail_offset(DT, D, PASS2, p.keys_per_range, p.q_tiles, p.hist_lds_words);
-  const size_t lds = sweep_lds_bytes(DT, D, PASS2, p.keys_per_range, p.q_tiles, p.hist_lds_words);
+  if (PASS2) {  // sweep 2 has its own ranges over the block keys only
+    q.n_ranges = p.s2_ranges;
+    q.n_ctx_ranges = 0;
+    q.blk_per_range = q.keys_per_range = p.s2_blk_per_range;
+    q.ctx_per_range = 0;
+  }
+  q.lds_tail_offset = (int)sweep_lds_tail_offset(DT, D, PASS2, q.keys_per_range, p.q_tiles, p.hist_lds_words);
+  const size_t lds = sweep_lds_bytes(DT, D, PASS2, q.keys_per_range, p.q_tiles, p.hist_lds_words);
   hipLaunchKernelGGL((pass_kernel<DT, D, PASS2>), grid, dim3(PASS_WAVES * 64), lds, st, q);
   return hipGetLastError();
 }

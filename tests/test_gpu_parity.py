@@ -651,3 +651,31 @@ def test_padded_query_and_key_strides(dtype):
     rep = check_block(st, gpu_stage(dbg, keep), parts, wl.dtype)
     say(f"[padded strides {dtype}] max score err/(s+s_k) {rep['max_rel']:.2e}, tolerated {rep['tolerated']}")
     lib.close()
+
+
+@pytest.mark.parametrize("s_t,t_ctx,dtype", [(96, 700, "bf16"), (40, 333, "f32"), (1024, 31, "bf16")])
+def test_look_back_keys_outnumbering_the_block(s_t, t_ctx, dtype):
+    """Look-back keys are spread evenly over the block's key ranges; when there are far more of them than
+    block keys, further ranges hold look-back keys only.  Scores must still carry their full weight."""
+    wl = synth.shrink(synth.WORKLOADS["llama8b-16k"], index=27, l_ctx=2 * s_t, s_block=s_t, dtype=dtype, window=8,
+                      n_q_heads=8, n_kv_heads=2)
+    parts = O.partition(s_t // 2, wl.n_div, wl.alpha, s_t)
+    data = synth.make_layer(wl, 0, parts[0], n_blocks=1)
+    gen = torch.Generator().manual_seed(99)
+    k_ctx = (torch.randn(wl.n_kv_heads, t_ctx, wl.head_dim, generator=gen) * 1.2).to(wl.torch_dtype)
+    lib = binding.LaserKV(wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.dtype, wl.lsh_tables, wl.lsh_bits,
+                          max_block=s_t, max_window=wl.window, max_ctx_keys=t_ctx)
+    dbg = dbg_buffers(wl, s_t)
+    keep = torch.empty(wl.n_kv_heads, sum(parts), dtype=torch.int32, device=DEV)
+    lib.laserkv_select_block(data["q_win"][0].to(DEV), data["k"][:, :s_t].to(DEV), k_ctx.to(DEV), data["planes"].to(DEV),
+                             block_pos0=4096, n_anchor=parts[0], n_local=parts[1], k_exact=parts[2], k_lsh=parts[3],
+                             keep_idx=keep, dbg_s_exact=dbg["s_exact"], dbg_sig_k=dbg["sig_k"], dbg_sig_q=dbg["sig_q"],
+                             dbg_count=dbg["cnt"])
+    torch.cuda.synchronize()
+    st = O.select_block(f64(data["q_win"][0]), f64(data["k"][:, :s_t]), f64(k_ctx), f64(data["planes"]), wl.lsh_tables,
+                        wl.lsh_bits, *parts, block_pos0=4096)
+    rep = check_block(st, gpu_stage(dbg, keep), parts, wl.dtype)
+    say(f"[look-back {t_ctx} keys, block {s_t}, {dtype}] max score err/(s+s_k) {rep['max_rel']:.2e}, tolerated {rep['tolerated']}")
+    if t_ctx > s_t:
+        assert st["s_exact"].sum(1).max() < 0.9  # the look-back keys hold a real share of the mass
+    lib.close()
