@@ -33,6 +33,9 @@ Readings taken where the paper is silent (each is listed in the design notes):
     S_exact summed over every layer and head handed in, and likewise the
     collision counts of step 6, then ONE selection shared by all of them.
 
+  * Attention over the compacted cache (attend_cache): plain softmax attention
+    of later queries over the kept rows, every kept row visible.
+
 Pins: see tests/test_oracle_*.py.  The composition of the steps into one
 layer-level run (compress_layer) has no printed worked example in the paper:
 whole-path parity unpinned beyond the per-step pins and the invariants.
@@ -252,6 +255,41 @@ def append(cache_k, cache_v, cache_pos, cache_len: int, k_blk, v_blk, keep, bloc
         cache_v[h, cache_len:cache_len + b_t] = v_blk[h, keep[h]]
         cache_pos[h, cache_len:cache_len + b_t] = block_pos0 + keep[h]
     return cache_len + b_t
+
+
+# --------------------------------------------------------------------------
+# attention over the compacted cache (Sec. 3 first paragraph: the kept tokens
+# are what later tokens attend to; Sec. 3.2 / 3.3: its row normaliser)
+# --------------------------------------------------------------------------
+def attend_cache(q, cache_k, cache_v, cache_len: int):
+    """Softmax attention of every query over the first cache_len rows of its KV head's cache.
+
+    q [H_q, n_q, d]; cache_k / cache_v [H_kv, cap, d]; query head h*G+g reads KV head h.  Every cached row
+    is visible: the cache holds earlier blocks only (append-only, Sec. 1 contribution 1).
+
+    Row (hq, j): l_i = q . k_i / sqrt(d) over i < cache_len, p = softmax(l), out = sum_i p_i v_i,
+    lse = log sum_i exp(l_i) (natural logarithm).  Returns (out [H_q, n_q, d], lse [H_q, n_q]).
+    With cache_len = 0 the output is zero and lse = -inf.  lse is what exact_scores takes as row_lse.
+    """
+    q = np.asarray(q, dtype=np.float64)
+    h_q, n_q, d = q.shape
+    h_kv = np.asarray(cache_k).shape[0]
+    assert h_q % h_kv == 0
+    g_sz = h_q // h_kv
+    out = np.zeros((h_q, n_q, d), dtype=np.float64)
+    lse = np.full((h_q, n_q), -np.inf, dtype=np.float64)
+    if cache_len == 0:
+        return out, lse
+    for hq in range(h_q):
+        keys = np.asarray(cache_k[hq // g_sz][:cache_len], dtype=np.float64)
+        vals = np.asarray(cache_v[hq // g_sz][:cache_len], dtype=np.float64)
+        logits = (q[hq] @ keys.T) / np.sqrt(np.float64(d))
+        row_max = logits.max(axis=1, keepdims=True)
+        e = np.exp(logits - row_max)
+        denom = e.sum(axis=1, keepdims=True)
+        out[hq] = (e / denom) @ vals
+        lse[hq] = (row_max + np.log(denom))[:, 0]
+    return out, lse
 
 
 # --------------------------------------------------------------------------
