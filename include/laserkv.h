@@ -211,6 +211,33 @@ int laserkv_set_row_lse(laserkv_ctx* ctx, const float* row_lse);
  * Errors: LKV_EINVAL (null context, pointer not 4-byte aligned). */
 int laserkv_set_row_lse_complete(laserkv_ctx* ctx, const float* row_lse);
 
+/* Attention over the compacted cache (Sec. 3 first paragraph: only the kept tokens remain for later tokens to
+ * attend to).  For every query head hq and each of its n_q queries: l_i = q.k_i / sqrt(d) over the first
+ * cache_len rows of KV head hq / G's cache (all visible: the cache holds earlier blocks only),
+ * out = sum_i softmax(l)_i v_i and out_lse = log sum_i exp(l_i) (natural logarithm).  Serves decoding
+ * (n_q = 1) and the window rows of the next block, whose out_lse is exactly what laserkv_set_row_lse takes:
+ * the whole compressed cache then joins the normaliser of Alg. 1 step 3 without being read again by the
+ * selection (Sec. 3.2); a caller merging this with its block-local attention uses out_lse as the weight.
+ *   q          DEVICE [H_q, n_q, d], strides in elements, d contiguous, rows 16-byte aligned
+ *   k_cache, v_cache  DEVICE [H_kv, cap, d] as written by laserkv_append (rows contiguous per head),
+ *              cache_stride_head in elements; cache_len rows per head are read, 0 <= cache_len,
+ *              cache_len * d * elem size < 2^31
+ *   n_q        1 .. max_window of the context's configuration
+ *   out        DEVICE [H_q, n_q, d] float, contiguous, 16-byte aligned; zero when cache_len == 0
+ *   out_lse    DEVICE [H_q, n_q] float, contiguous; -inf when cache_len == 0
+ *   workspace  DEVICE scratch of at least laserkv_attend_workspace_bytes(ctx, n_q, cache_len) bytes, 256-byte
+ *              aligned, owned by the caller; partial results of the key splits, dead after the call's kernels
+ * The call allocates nothing and is asynchronous on hip_stream.  Errors: LKV_EINVAL (null / misaligned
+ * tensor, n_q or cache_len out of range, workspace too small), LKV_EHIP.
+ * laserkv_attend_workspace_bytes returns -1 for arguments the call would reject. */
+int64_t laserkv_attend_workspace_bytes(const laserkv_ctx* ctx, int32_t n_q, int64_t cache_len);
+int laserkv_attend_cache(laserkv_ctx* ctx,
+                         const void* q, int64_t q_stride_head, int64_t q_stride_tok, int32_t n_q,
+                         const void* k_cache, const void* v_cache, int64_t cache_stride_head, int64_t cache_len,
+                         float* out, float* out_lse,
+                         void* workspace, int64_t workspace_bytes,
+                         void* hip_stream);
+
 /* Global-consensus variant: Alg. 1 step 3 taken literally, with the exact score summed over every
  * layer and head (Sec. 3.3 "Precision") and, likewise, the collision counts of step 6, followed by
  * ONE two-stage TopK (steps 4-8) whose kept set serves every layer and head.  Three calls:
@@ -262,7 +289,8 @@ typedef enum {
   LKV_KERN_SELECT = 3, /* two-stage TopK and compaction (with the gather in laserkv_compress_block); also the
                           accumulation kernel of laserkv_score_block */
   LKV_KERN_APPEND = 4, /* gather-append as a kernel of its own */
-  LKV_N_KERNELS = 5
+  LKV_KERN_ATTEND = 5, /* attention over the compacted cache (both of its kernels) */
+  LKV_N_KERNELS = 6
 } laserkv_kernel_id;
 #define LKV_PROFILE_MAX_LAUNCHES 8192
 

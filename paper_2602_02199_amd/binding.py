@@ -22,11 +22,11 @@ EXPORTS = (
     "laserkv_partition", "laserkv_select_block", "laserkv_append", "laserkv_compress_block",
     "laserkv_profile_begin", "laserkv_profile_end", "laserkv_profile_isolate",
     "laserkv_score_block", "laserkv_select_consensus", "laserkv_append_shared", "laserkv_set_row_lse",
-    "laserkv_set_row_lse_complete",
+    "laserkv_set_row_lse_complete", "laserkv_attend_workspace_bytes", "laserkv_attend_cache",
     "laserkv_static_init", "laserkv_static_workspace_bytes", "laserkv_compress_block_static",
 )
 LKV_STATIC_SCRATCH_BYTES = 32 << 20
-KERNEL_NAMES = ("sweep1", "sweep2", "count", "select", "append")
+KERNEL_NAMES = ("sweep1", "sweep2", "count", "select", "append", "attend")
 
 
 class LaserKVError(RuntimeError):
@@ -97,6 +97,10 @@ def load():
     lib.laserkv_set_row_lse.restype = C.c_int
     lib.laserkv_set_row_lse_complete.argtypes = [vp, vp]
     lib.laserkv_set_row_lse_complete.restype = C.c_int
+    lib.laserkv_attend_workspace_bytes.argtypes = [vp, i32, i64]
+    lib.laserkv_attend_workspace_bytes.restype = i64
+    lib.laserkv_attend_cache.argtypes = [vp, vp, i64, i64, i32, vp, vp, i64, i64, vp, vp, vp, i64, vp]
+    lib.laserkv_attend_cache.restype = C.c_int
     lib.laserkv_profile_begin.argtypes = [vp]
     lib.laserkv_profile_begin.restype = C.c_int
     lib.laserkv_profile_end.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(i64)]
@@ -302,6 +306,27 @@ class LaserKV:
             assert row_lse.is_contiguous() and row_lse.dtype == self._torch.float32
         self._row_lse = row_lse
         self._check(self._lib.laserkv_set_row_lse_complete(self._ctx, _ptr(row_lse)))
+
+    def laserkv_attend_workspace_bytes(self, n_q, cache_len):
+        n = int(self._lib.laserkv_attend_workspace_bytes(self._ctx, n_q, cache_len))
+        if n < 0:
+            raise LaserKVError(LKV_EINVAL, "attend_workspace_bytes: n_q or cache_len out of range")
+        return n
+
+    def laserkv_attend_cache(self, q, k_cache, v_cache, *, cache_len, out, out_lse, workspace, stream=None):
+        """q [H_q, n_q, d]; k_cache / v_cache [H_kv, cap, d]; out float32 [H_q, n_q, d], out_lse float32 [H_q, n_q];
+        workspace: uint8 device tensor of at least laserkv_attend_workspace_bytes(n_q, cache_len) bytes."""
+        d = self.cfg.head_dim
+        qs = _strides3(q, d)
+        assert k_cache.stride(2) == 1 and k_cache.stride(1) == d and v_cache.stride() == k_cache.stride()
+        f32 = self._torch.float32
+        assert out.is_contiguous() and out.dtype == f32 and out.shape == q.shape
+        assert out_lse.is_contiguous() and out_lse.dtype == f32 and out_lse.shape == q.shape[:2]
+        assert workspace.is_contiguous() and workspace.element_size() == 1
+        rc = self._lib.laserkv_attend_cache(
+            self._ctx, _ptr(q), qs[0], qs[1], q.shape[1], _ptr(k_cache), _ptr(v_cache), k_cache.stride(0), cache_len,
+            _ptr(out), _ptr(out_lse), _ptr(workspace), workspace.numel(), self._stream(stream))
+        self._check(rc)
 
     def laserkv_profile_begin(self):
         self._check(self._lib.laserkv_profile_begin(self._ctx))

@@ -238,6 +238,7 @@ int laserkv_create(const laserkv_config* cfg, laserkv_ctx** out) {
     return fail_hip(nullptr, e, "create: device query");
   }
   e = lkv::init_kernel_attributes();
+  if (e == hipSuccess) e = lkv::init_attend_attributes();
   if (e != hipSuccess) {
     laserkv_destroy(ctx);
     return fail_hip(nullptr, e, "create: kernel attribute");
@@ -635,6 +636,71 @@ int laserkv_set_row_lse_complete(laserkv_ctx* ctx, const float* row_lse) {
   if (row_lse && (reinterpret_cast<uintptr_t>(row_lse) & 3)) return fail(ctx, LKV_EINVAL, "set_row_lse_complete: misaligned pointer");
   ctx->row_lse = row_lse;
   ctx->row_lse_complete = row_lse != nullptr;
+  return LKV_OK;
+}
+
+int64_t laserkv_attend_workspace_bytes(const laserkv_ctx* ctx, int32_t n_q, int64_t cache_len) {
+  if (!ctx || n_q < 1 || n_q > ctx->cfg.max_window || cache_len < 0 ||
+      cache_len * ctx->cfg.head_dim * ctx->elem_size >= (int64_t(1) << 31))
+    return -1;
+  lkv::AttendPlan plan;
+  lkv::attend_plan(ctx->group * n_q, cache_len, ctx->cfg.n_kv_heads, ctx->n_cu, &plan);
+  return (int64_t)lkv::attend_workspace_bytes(plan, ctx->group * n_q, ctx->cfg.n_kv_heads, ctx->cfg.head_dim);
+}
+
+int laserkv_attend_cache(laserkv_ctx* ctx,
+                         const void* q, int64_t q_stride_head, int64_t q_stride_tok, int32_t n_q,
+                         const void* k_cache, const void* v_cache, int64_t cache_stride_head, int64_t cache_len,
+                         float* out, float* out_lse,
+                         void* workspace, int64_t workspace_bytes,
+                         void* hip_stream) {
+  if (!ctx) return fail(nullptr, LKV_EINVAL, "attend_cache: null context");
+  const laserkv_config& c = ctx->cfg;
+  const int es = ctx->elem_size, d = c.head_dim;
+  if (!q || !out || !out_lse || !workspace) return fail(ctx, LKV_EINVAL, "attend_cache: null tensor");
+  if (n_q < 1 || n_q > c.max_window) return fail(ctx, LKV_EINVAL, "attend_cache: n_q must be 1..max_window (%d)", c.max_window);
+  if (cache_len < 0 || cache_len * d * es >= (int64_t(1) << 31))
+    return fail(ctx, LKV_EINVAL, "attend_cache: cache_len must be >= 0 with cache_len * d * elem size < 2^31");
+  if (cache_len > 0 && (!k_cache || !v_cache)) return fail(ctx, LKV_EINVAL, "attend_cache: null cache");
+  if (q_stride_tok < d || q_stride_head < 0 || ((q_stride_tok * es) & 15) || ((q_stride_head * es) & 15))
+    return fail(ctx, LKV_EINVAL, "attend_cache: query strides must cover a row and keep rows 16-byte aligned");
+  if (cache_stride_head < cache_len * d || ((cache_stride_head * es) & 15))
+    return fail(ctx, LKV_EINVAL, "attend_cache: cache head stride too small or misaligned");
+  if (!aligned16(q) || !aligned16(k_cache) || !aligned16(v_cache) || !aligned16(out) ||
+      (reinterpret_cast<uintptr_t>(out_lse) & 3u) || (reinterpret_cast<uintptr_t>(workspace) & 255u))
+    return fail(ctx, LKV_EINVAL, "attend_cache: tensors must be 16-byte aligned (out_lse 4, workspace 256)");
+  const int m_rows = ctx->group * n_q;
+  lkv::AttendPlan plan;
+  lkv::attend_plan(m_rows, cache_len, c.n_kv_heads, ctx->n_cu, &plan);
+  const size_t need = lkv::attend_workspace_bytes(plan, m_rows, c.n_kv_heads, d);
+  if (workspace_bytes < (int64_t)need)
+    return fail(ctx, LKV_EINVAL, "attend_cache: workspace of %lld bytes, %zu needed", (long long)workspace_bytes, need);
+  lkv::AttendParams p = {};
+  p.q = {(const char*)q, q_stride_head * es, q_stride_tok * es};
+  p.group = ctx->group;
+  p.n_q = n_q;
+  p.nq_magic = (uint32_t)(((uint64_t(1) << 32) + n_q - 1) / n_q);
+  p.m_rows = m_rows;
+  p.k_cache = (const char*)k_cache;
+  p.v_cache = (const char*)v_cache;
+  p.cache_stride_head = cache_stride_head * es;
+  p.row_bytes = d * es;
+  p.cache_len = (int)cache_len;
+  p.keys_per_split = plan.keys_per_split;
+  p.n_splits = plan.n_splits;
+  p.wprt_log = plan.wprt_log;
+  p.n_parts = plan.n_parts;
+  p.n_qgroups = plan.n_qgroups;
+  p.n_kv_heads = c.n_kv_heads;
+  p.scale2 = (float)(1.4426950408889634 / sqrt((double)d));
+  const size_t rows = (size_t)c.n_kv_heads * plan.n_parts * m_rows;
+  p.part_o = reinterpret_cast<float*>(workspace);
+  p.part_ml = reinterpret_cast<float2*>(reinterpret_cast<char*>(workspace) + ((rows * d * 4 + 255) & ~(size_t)255));
+  p.out = out;
+  p.out_lse = out_lse;
+  hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
+  hipError_t e = timed(ctx, LKV_KERN_ATTEND, st, [&] { return lkv::launch_attend((int)c.dtype, d, p, st); });
+  if (e != hipSuccess) return fail_hip(ctx, e, "attend_cache: kernels");
   return LKV_OK;
 }
 

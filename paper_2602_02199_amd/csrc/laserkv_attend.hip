@@ -1,0 +1,319 @@
+// Attention over the compacted cache for gfx950 (Sec. 3 first paragraph: the kept tokens are what later
+// tokens attend to).  Every cached row is visible to every query: the cache holds earlier blocks only.
+//
+//   attend_kernel          workgroup = (key split, group of 256 query rows, KV head).  The split's keys and
+//                          values pass through LDS in chunks; each wave keeps 32 query rows in registers and
+//                          an online-softmax state (reference, sum, unnormalised output) per row, and leaves
+//                          one partial per (split, wave share)                                       [MFMA]
+//   attend_combine_kernel  merges the partials of a row through their references and writes the output and
+//                          the natural-log normaliser, the number laserkv_set_row_lse takes
+#include "laserkv_device.h"
+#include "laserkv_kernels.h"
+
+namespace lkv {
+
+constexpr int ATT_WAVES = 8;
+constexpr int ATT_THREADS = ATT_WAVES * 64;
+constexpr int ATT_ROWS = 256;      // query rows per workgroup: up to 8 row tiles
+constexpr int ATT_MAX_SPLITS = 64;
+
+template <int DT>
+__host__ __device__ constexpr int att_chunk_keys() { return DT == DT_BF16 ? 256 : 128; }
+
+// Transposes, inside groups of 8 consecutive lanes, the 8 x 8 matrix of 16-bit elements whose row i is lane
+// i's 16 bytes: afterwards lane i holds column i, element e of it being what lane e held at position i.
+// Three exchange steps, each swapping one bit of the lane index with one bit of the element index.
+__device__ __forceinline__ uint4 transpose_8x8_b16(const uint4& v, int lane) {
+  uint32_t x[4] = {v.x, v.y, v.z, v.w};
+  const bool i0 = lane & 1, i1 = lane & 2, i2 = lane & 4;
+#pragma unroll
+  for (int w = 0; w < 4; ++w) {  // lane bit 0 <-> half of the word
+    const uint32_t t = (uint32_t)__shfl_xor((int)x[w], 1);
+    x[w] = i0 ? ((t >> 16) | (x[w] & 0xffff0000u)) : ((x[w] & 0xffffu) | (t << 16));
+  }
+#pragma unroll
+  for (int a = 0; a < 4; a += 2) {  // lane bit 1 <-> word bit 0
+    const uint32_t recv = (uint32_t)__shfl_xor((int)(i1 ? x[a] : x[a + 1]), 2);
+    if (i1) x[a] = recv; else x[a + 1] = recv;
+  }
+#pragma unroll
+  for (int a = 0; a < 2; ++a) {  // lane bit 2 <-> word bit 1
+    const uint32_t recv = (uint32_t)__shfl_xor((int)(i2 ? x[a] : x[a + 2]), 4);
+    if (i2) x[a] = recv; else x[a + 2] = recv;
+  }
+  return make_uint4(x[0], x[1], x[2], x[3]);
+}
+
+// The same for 4 x 4 matrices of 32-bit elements inside groups of 4 consecutive lanes.
+__device__ __forceinline__ uint4 transpose_4x4_b32(const uint4& v, int lane) {
+  uint32_t x[4] = {v.x, v.y, v.z, v.w};
+  const bool i0 = lane & 1, i1 = lane & 2;
+#pragma unroll
+  for (int a = 0; a < 4; a += 2) {
+    const uint32_t recv = (uint32_t)__shfl_xor((int)(i0 ? x[a] : x[a + 1]), 1);
+    if (i0) x[a] = recv; else x[a + 1] = recv;
+  }
+#pragma unroll
+  for (int a = 0; a < 2; ++a) {
+    const uint32_t recv = (uint32_t)__shfl_xor((int)(i1 ? x[a] : x[a + 2]), 2);
+    if (i1) x[a] = recv; else x[a + 2] = recv;
+  }
+  return make_uint4(x[0], x[1], x[2], x[3]);
+}
+
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
+  typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+  bf16x2 t = {(__bf16)lo, (__bf16)hi};  // round to nearest even
+  return __builtin_bit_cast(uint32_t, t);
+}
+
+// One pass over the split's keys.  S^T = K Q^T puts a query row in a lane (column rl of the tile; the two
+// halves kg of the wave hold the same rows over different keys), so the softmax state is lane-private, and
+// the 16 accumulator registers are already the B operand of O^T += V^T P^T: register r of half kg is key
+// acc_row(r, kg), so a group of 8 (bf16) or 4 (f32) registers is one 16-byte operand chunk whose keys the A
+// operand matches by reading V^T at the same key offsets.  V is transposed in registers on its way into LDS.
+template <int DT, int D>
+__global__ __launch_bounds__(ATT_THREADS) void attend_kernel(AttendParams p) {
+  constexpr int ES = DT == DT_BF16 ? 2 : 4;
+  constexpr int CH = D * ES / 16;             // 16-byte chunks per row
+  constexpr int NCH = CH / 2;
+  constexpr int CHP = CH + 1;                 // K row pitch in chunks (odd)
+  constexpr int KC = att_chunk_keys<DT>();    // keys per LDS chunk
+  constexpr int EPC = 16 / ES;                // elements per 16-byte chunk
+  constexpr int VTP = KC / EPC + 1;           // V^T row pitch in chunks (odd)
+  constexpr int KL = KC * CH / ATT_THREADS;   // 16-byte loads per thread, tensor and chunk
+  constexpr int NDT = D / 32;                 // 32-wide tiles of the head dimension
+  constexpr int TPC = KC / 32;                // key tiles per chunk
+  constexpr int RUNS = 32 / (2 * EPC);        // operand chunks per lane and 32-key tile in P.V
+  constexpr int K_ROWS_PER_LOAD = ATT_THREADS / CH;
+  constexpr int V_GROUPS_PER_LOAD = ATT_THREADS / (EPC * CH);
+
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, rl = lane & 31, kg = lane >> 5;
+  const int split = blockIdx.x, qg = blockIdx.y, h = blockIdx.z;
+  const int k_lo = split * p.keys_per_split;
+  const int k_hi = min(k_lo + p.keys_per_split, p.cache_len);
+  const int wprt = 1 << p.wprt_log;           // waves that share a row tile, over different key tiles
+  const int rt = wave >> p.wprt_log, ks = wave & (wprt - 1);
+  const int row = qg * ATT_ROWS + rt * 32 + rl;
+
+  extern __shared__ uint4 smem[];
+  uint4* sK = smem;                           // [KC][CHP]
+  uint4* sVT = smem + KC * CHP;               // [D][VTP]: V^T, element (d, key) at chunk key / EPC of row d
+
+  // the wave's 32 query rows, as the B operand of S^T
+  uint4 a[NCH];
+  {
+    const int m = min(row, p.m_rows - 1);
+    const int g = (int)__umulhi((uint32_t)m, p.nq_magic), j = m - g * p.n_q;
+    const char* ptr = p.q.base + (int64_t)(h * p.group + g) * p.q.stride_head + (int64_t)j * p.q.stride_row;
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) a[i] = ld16(ptr + (2 * i + kg) * 16);
+  }
+
+  const uint32_t cache_bytes = (uint32_t)p.cache_len * (uint32_t)p.row_bytes;
+  const __amdgpu_buffer_rsrc_t ksrd = make_srd(p.k_cache + (int64_t)h * p.cache_stride_head, cache_bytes);
+  const __amdgpu_buffer_rsrc_t vsrd = make_srd(p.v_cache + (int64_t)h * p.cache_stride_head, cache_bytes);
+  // K: chunk tid % CH of row tid / CH (+ K_ROWS_PER_LOAD per load).  V: lane groups of EPC consecutive lanes
+  // hold EPC consecutive keys at the same chunk, the shape the register transpose wants.
+  const uint32_t k_row = tid / CH, k_col = tid % CH;
+  const uint32_t v_i = tid % EPC, v_c = (tid / EPC) % CH, v_grp = tid / (EPC * CH);
+  uint4 kpre[KL], vpre[KL];
+  auto prefetch = [&](int kc0) {
+#pragma unroll
+    for (int u = 0; u < KL; ++u) {
+      kpre[u] = buf_ld16(ksrd, (uint32_t)(kc0 + k_row + u * K_ROWS_PER_LOAD) * (uint32_t)p.row_bytes + k_col * 16);
+      const uint32_t key = (u * V_GROUPS_PER_LOAD + v_grp) * EPC + v_i;
+      vpre[u] = buf_ld16(vsrd, (uint32_t)(kc0 + key) * (uint32_t)p.row_bytes + v_c * 16);
+    }
+  };
+
+  float m_ref = NEG_BIG, l_sum = 0.0f;
+  f32x16 o[NDT];
+#pragma unroll
+  for (int dt = 0; dt < NDT; ++dt)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) o[dt][r] = 0.0f;
+
+  prefetch(k_lo);
+  for (int kc0 = k_lo; kc0 < k_hi; kc0 += KC) {
+    __syncthreads();  // every wave has finished with the previous chunk
+#pragma unroll
+    for (int u = 0; u < KL; ++u) {
+      sK[(k_row + u * K_ROWS_PER_LOAD) * CHP + k_col] = kpre[u];
+      const uint4 t = DT == DT_BF16 ? transpose_8x8_b16(vpre[u], lane) : transpose_4x4_b32(vpre[u], lane);
+      // the lane now holds head-dimension index v_c * EPC + v_i for the group's EPC keys
+      sVT[(v_c * EPC + v_i) * VTP + (u * V_GROUPS_PER_LOAD + v_grp)] = t;
+    }
+    if (kc0 + KC < k_hi) prefetch(kc0 + KC);  // in flight while this chunk is worked on
+    __syncthreads();
+
+#pragma unroll 1
+    for (int nt = ks; nt < TPC; nt += wprt) {
+      const int kbase = kc0 + nt * 32;
+      if (kbase >= k_hi) break;  // wave-uniform
+      f32x16 acc;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
+      const uint4* krow = sK + (size_t)(nt * 32 + rl) * CHP + kg;
+#pragma unroll
+      for (int i = 0; i < NCH; ++i) Mma<DT>::run(acc, krow[2 * i], a[i]);
+      const int n_vis = k_hi - kbase;  // keys of this tile inside the split (>= 32: all)
+      float mx = NEG_BIG;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        acc[r] = acc_row(r, kg) < n_vis ? acc[r] * p.scale2 : NEG_BIG;
+        mx = fmaxf(mx, acc[r]);
+      }
+      mx = fmaxf(mx, __shfl_xor(mx, 32));  // both halves of the wave use one reference per row
+      if (__any(mx > m_ref)) {
+        const float m_new = fmaxf(m_ref, mx);
+        const float alpha = fast_exp2(m_ref - m_new);
+        l_sum *= alpha;
+#pragma unroll
+        for (int dt = 0; dt < NDT; ++dt)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) o[dt][r] *= alpha;
+        m_ref = m_new;
+      }
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        acc[r] = fast_exp2(acc[r] - m_ref);
+        l_sum += acc[r];
+      }
+#pragma unroll
+      for (int s = 0; s < RUNS; ++s) {
+        uint4 pb;
+        if (DT == DT_BF16) {
+          pb = make_uint4(pack_bf16(acc[8 * s], acc[8 * s + 1]), pack_bf16(acc[8 * s + 2], acc[8 * s + 3]),
+                          pack_bf16(acc[8 * s + 4], acc[8 * s + 5]), pack_bf16(acc[8 * s + 6], acc[8 * s + 7]));
+        } else {
+          pb = make_uint4(__float_as_uint(acc[4 * s]), __float_as_uint(acc[4 * s + 1]),
+                          __float_as_uint(acc[4 * s + 2]), __float_as_uint(acc[4 * s + 3]));
+        }
+#pragma unroll
+        for (int dt = 0; dt < NDT; ++dt) {
+          const uint4* vrow = sVT + (size_t)(dt * 32 + rl) * VTP;
+          uint4 va;
+          if (DT == DT_BF16) {
+            // registers 8s .. 8s+3 are keys 16s + 4kg + (0..3), registers 8s+4 .. 8s+7 the same + 8
+            const uint2* v2 = reinterpret_cast<const uint2*>(vrow) + nt * 8 + 4 * s + kg;
+            const uint2 lo = v2[0], hi = v2[2];
+            va = make_uint4(lo.x, lo.y, hi.x, hi.y);
+          } else {
+            va = vrow[nt * 8 + 2 * s + kg];  // registers 4s .. 4s+3 are keys 8s + 4kg + (0..3)
+          }
+          Mma<DT>::run(o[dt], va, pb);
+        }
+      }
+    }
+  }
+
+  // one partial per (split, wave share of the row tile): reference, sum, unnormalised output
+  l_sum += __shfl_xor(l_sum, 32);
+  if (row < p.m_rows) {
+    const int part = split * wprt + ks;
+    const size_t at = ((size_t)h * p.n_parts + part) * p.m_rows + row;
+    if (kg == 0) p.part_ml[at] = make_float2(m_ref, l_sum);
+    float* dst = p.part_o + at * D;
+#pragma unroll
+    for (int dt = 0; dt < NDT; ++dt)
+#pragma unroll
+      for (int q4 = 0; q4 < 4; ++q4)
+        *reinterpret_cast<float4*>(dst + dt * 32 + 8 * q4 + 4 * kg) =
+            make_float4(o[dt][4 * q4], o[dt][4 * q4 + 1], o[dt][4 * q4 + 2], o[dt][4 * q4 + 3]);
+  }
+}
+
+// out = sum_p O_p 2^(m_p - M) / sum_p l_p 2^(m_p - M), lse = (M + log2 of that sum) ln 2; one row per group of
+// D / 4 lanes.  Without any partial (empty cache) the output is zero and the normaliser -inf.
+template <int D>
+__global__ __launch_bounds__(256) void attend_combine_kernel(AttendParams p) {
+  constexpr int LPR = D / 4;  // lanes per row
+  const int row_lin = blockIdx.x * (256 / LPR) + threadIdx.x / LPR;
+  const int d4 = threadIdx.x % LPR;
+  const int n_rows = p.n_kv_heads * p.m_rows;
+  if (row_lin >= n_rows) return;
+  const int h = row_lin / p.m_rows, m = row_lin - h * p.m_rows;
+  const float2* ml = p.part_ml + (size_t)h * p.n_parts * p.m_rows + m;
+  const float* po = p.part_o + ((size_t)h * p.n_parts * p.m_rows + m) * D + d4 * 4;
+  float mx = NEG_BIG;
+  for (int q = 0; q < p.n_parts; ++q) mx = fmaxf(mx, ml[(size_t)q * p.m_rows].x);
+  float l = 0.0f;
+  float4 acc = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+  for (int q = 0; q < p.n_parts; ++q) {
+    const float2 v = ml[(size_t)q * p.m_rows];
+    const float w = fast_exp2(v.x - mx);
+    const float4 ov = *reinterpret_cast<const float4*>(po + (size_t)q * p.m_rows * D);
+    l = fmaf(v.y, w, l);
+    acc.x = fmaf(ov.x, w, acc.x);
+    acc.y = fmaf(ov.y, w, acc.y);
+    acc.z = fmaf(ov.z, w, acc.z);
+    acc.w = fmaf(ov.w, w, acc.w);
+  }
+  const float inv = l > 0.0f ? 1.0f / l : 0.0f;
+  *reinterpret_cast<float4*>(p.out + (size_t)row_lin * D + d4 * 4) = make_float4(acc.x * inv, acc.y * inv, acc.z * inv, acc.w * inv);
+  if (d4 == 0) p.out_lse[row_lin] = l > 0.0f ? (mx + fast_log2(l)) * 0.6931471805599453f : -__builtin_inff();
+}
+
+// ---- host side ----
+void attend_plan(int m_rows, int64_t cache_len, int n_kv_heads, int n_cu, AttendPlan* plan) {
+  const int n_qg = (m_rows + ATT_ROWS - 1) / ATT_ROWS;
+  const int n_rt = (min(m_rows, ATT_ROWS) + 31) / 32;
+  int rt_pow2 = 1, wprt_log = 3;
+  while (rt_pow2 < n_rt) { rt_pow2 <<= 1; --wprt_log; }
+  int n_splits = n_cu / (n_kv_heads * n_qg);
+  n_splits = max(1, min(n_splits, ATT_MAX_SPLITS));
+  int64_t kps = (cache_len + n_splits - 1) / n_splits;
+  kps = max((int64_t)32, (kps + 31) / 32 * 32);
+  n_splits = cache_len > 0 ? (int)((cache_len + kps - 1) / kps) : 0;
+  plan->n_qgroups = n_qg;
+  plan->wprt_log = wprt_log;
+  plan->n_splits = n_splits;
+  plan->keys_per_split = (int)kps;
+  plan->n_parts = n_splits << wprt_log;
+}
+
+size_t attend_workspace_bytes(const AttendPlan& plan, int m_rows, int n_kv_heads, int head_dim) {
+  const size_t rows = (size_t)n_kv_heads * plan.n_parts * m_rows;
+  return ((rows * head_dim * 4 + 255) & ~(size_t)255) + rows * 8 + 256;
+}
+
+template <int DT, int D>
+static hipError_t launch_attend_t(const AttendParams& p, hipStream_t st) {
+  constexpr int ES = DT == DT_BF16 ? 2 : 4;
+  constexpr int KC = att_chunk_keys<DT>();
+  constexpr size_t lds = ((size_t)KC * (D * ES / 16 + 1) + (size_t)D * (KC / (16 / ES) + 1)) * 16;
+  static_assert(lds <= 160 * 1024, "attention chunk does not fit the LDS");
+  if (p.n_splits > 0) {
+    hipLaunchKernelGGL((attend_kernel<DT, D>), dim3(p.n_splits, p.n_qgroups, p.n_kv_heads), dim3(ATT_THREADS), lds, st, p);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
+  constexpr int rows_per_wg = 256 / (D / 4);
+  const int n_rows = p.n_kv_heads * p.m_rows;
+  hipLaunchKernelGGL((attend_combine_kernel<D>), dim3((n_rows + rows_per_wg - 1) / rows_per_wg), dim3(256), 0, st, p);
+  return hipGetLastError();
+}
+
+hipError_t launch_attend(int dtype, int head_dim, const AttendParams& p, hipStream_t st) {
+  if (dtype == DT_BF16 && head_dim == 128) return launch_attend_t<DT_BF16, 128>(p, st);
+  if (dtype == DT_BF16 && head_dim == 64) return launch_attend_t<DT_BF16, 64>(p, st);
+  if (dtype == DT_F32 && head_dim == 128) return launch_attend_t<DT_F32, 128>(p, st);
+  if (dtype == DT_F32 && head_dim == 64) return launch_attend_t<DT_F32, 64>(p, st);
+  return hipErrorInvalidValue;
+}
+
+template <int DT, int D>
+static hipError_t attend_attr() {
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(&attend_kernel<DT, D>), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+}
+
+hipError_t init_attend_attributes() {
+  hipError_t e = attend_attr<DT_BF16, 128>();
+  if (e == hipSuccess) e = attend_attr<DT_BF16, 64>();
+  if (e == hipSuccess) e = attend_attr<DT_F32, 128>();
+  if (e == hipSuccess) e = attend_attr<DT_F32, 64>();
+  return e;
+}
+
+}  // namespace lkv

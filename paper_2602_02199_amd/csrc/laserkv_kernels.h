@@ -116,6 +116,37 @@ struct AppendParams {
   int64_t block_pos0;
 };
 
+// Attention of n_q queries per query head over the first cache_len rows of each KV head's compacted cache.
+struct AttendParams {
+  RowSrc q;            // [H_q, n_q, d]
+  int group, n_q;
+  uint32_t nq_magic;   // ceil(2^32 / n_q): row / n_q == umulhi(row, nq_magic) for row <= 1024
+  int m_rows;          // M = G * n_q rows per KV head, row m = g * n_q + j
+  const char* k_cache; // [H_kv, cap, d] rows contiguous
+  const char* v_cache;
+  int64_t cache_stride_head;  // bytes
+  int row_bytes;       // d * elem size
+  int cache_len;       // rows
+  int keys_per_split;  // multiple of 32
+  int n_splits;        // ceil(cache_len / keys_per_split); 0: empty cache
+  int wprt_log;        // log2 of the waves that share a 32-row tile (over different key tiles)
+  int n_parts;         // n_splits << wprt_log partials per row
+  int n_qgroups;       // ceil(M / 256)
+  int n_kv_heads;
+  float scale2;        // log2(e) / sqrt(d)
+  float* part_o;       // [H_kv, n_parts, M, d] unnormalised partial outputs
+  float2* part_ml;     // [H_kv, n_parts, M] (reference, sum) in the exp2 domain
+  float* out;          // [H_kv * M, d]
+  float* out_lse;      // [H_kv * M] natural log
+};
+struct AttendPlan {
+  int n_qgroups, wprt_log, n_splits, keys_per_split, n_parts;
+};
+void attend_plan(int m_rows, int64_t cache_len, int n_kv_heads, int n_cu, AttendPlan* plan);
+size_t attend_workspace_bytes(const AttendPlan& plan, int m_rows, int n_kv_heads, int head_dim);  // part_o, then part_ml
+hipError_t launch_attend(int dtype, int head_dim, const AttendParams& p, hipStream_t st);
+hipError_t init_attend_attributes();
+
 hipError_t launch_sweep1(int dtype, int head_dim, const PassParams& p, hipStream_t st);
 hipError_t launch_sweep2(int dtype, int head_dim, const PassParams& p, hipStream_t st);
 hipError_t launch_count(const CountParams& p, int n_kv_heads, hipStream_t st);
