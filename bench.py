@@ -199,11 +199,46 @@ def measure(wl, args, dev, cpu_seconds):
     t_roof = (flops_blk / (peak_mfma * 1e12) + bytes_blk / (PEAK_HBM_GBS * 1e9)) * wl.n_blocks
     roofline["path_frac_of_roofline"] = round(t_roof / (ms_per_step * 1e-3), 4)
     res["roofline"] = roofline
+    if args.attend:
+        res["attend_cache"] = measure_attend(wl, comp, ddev, dev)
     if cpu_seconds > 0:
         res["cpu_baseline"] = cpu_baseline(wl, data, comp.B, cpu_seconds)
     del comp, ddev, data
     torch.cuda.empty_cache()
     return res
+
+
+def measure_attend(wl, comp, ddev, dev, reps=10):
+    """laserkv_attend_cache over the layer's finished cache (the rows the timed steps kept): one decode query
+    per head (bound by reading the cached K and V once) and the next block's window rows (bound by the two
+    contractions QK^T and PV).  Event times on the launch stream, average of `reps` launches after two."""
+    import torch
+    n = wl.n_blocks * min(comp.B, wl.s_block)
+    es = 2 if wl.dtype == "bf16" else 4
+    out = {}
+    stream = torch.cuda.current_stream()
+    for label, n_q in (("decode", 1), ("window", wl.window)):
+        q = ddev["q_win"][-1][:, :n_q].contiguous()
+        o = torch.empty(wl.n_q_heads, n_q, wl.head_dim, dtype=torch.float32, device=dev)
+        lse = torch.empty(wl.n_q_heads, n_q, dtype=torch.float32, device=dev)
+        ws = torch.empty(comp.lib.laserkv_attend_workspace_bytes(n_q, n), dtype=torch.uint8, device=dev)
+        run = lambda: comp.lib.laserkv_attend_cache(q, comp.k_cache, comp.v_cache, cache_len=n, out=o, out_lse=lse, workspace=ws)
+        run(); run()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for _ in range(reps):
+            run()
+        e1.record(stream)
+        e1.synchronize()
+        us = 1e3 * e0.elapsed_time(e1) / reps
+        nbytes = 2 * wl.n_kv_heads * n * wl.head_dim * es
+        flops = 4 * wl.n_q_heads * n_q * n * wl.head_dim
+        gbs, tfl = nbytes / us / 1e3, flops / us / 1e6
+        peak_mfma = PEAK_MFMA_BF16_TFLOPS if wl.dtype == "bf16" else PEAK_MFMA_F32_TFLOPS
+        out[label] = dict(n_q=n_q, cache_rows_per_head=n, avg_us=round(us, 2), hbm_gbs=round(gbs, 1),
+                          hbm_frac=round(gbs / PEAK_HBM_GBS, 4), tflops=round(tfl, 1), mfma_frac=round(tfl / peak_mfma, 4),
+                          bound="hbm" if gbs / PEAK_HBM_GBS > tfl / peak_mfma else "mfma")
+    return out
 
 
 def main():
@@ -229,6 +264,8 @@ def main():
     ap.add_argument("--lse", choices=["own", "complete"], default="own",
                     help="complete: the window rows' complete log-sum-exp is handed to the library (as the model's "
                          "attention kernel would report it), so the first sweep only hashes; not the headline configuration")
+    ap.add_argument("--no-attend", dest="attend", action="store_false",
+                    help="skip the timing of laserkv_attend_cache over the finished cache")
     ap.add_argument("--batch", type=int, default=1,
                     help="fold this many independent sequences into the head axis (heads x batch per call); the rate then "
                          "counts batch x context tokens. 1 is the headline configuration")
@@ -256,7 +293,9 @@ def main():
         return 0
     secondary = None
     if args.secondary not in ("none", args.workload) and args.batch == 1 and not args.calibrate_copy:
-        sec = measure(synth.WORKLOADS[args.secondary], args, dev, 0.0)
+        sec_args = argparse.Namespace(**vars(args))
+        sec_args.attend = False
+        sec = measure(synth.WORKLOADS[args.secondary], sec_args, dev, 0.0)
         r = sec["roofline"]
         secondary = dict(workload=args.secondary, value=sec["value"], unit="tokens/s/layer", ms_per_step=sec["ms_per_step"],
                          ms_per_step_mean=sec["ms_per_step_mean"], budget_per_block=sec["config"]["budget_per_block"],
@@ -268,7 +307,8 @@ def main():
                ms_per_step=res["ms_per_step"], higher_is_better=True, scaling="weak", vs_baseline=None,
                dtype=wl.dtype, data="synthetic", config=res["config"], roofline=res["roofline"],
                cpu_baseline=res["cpu_baseline"], ms_per_step_mean=res["ms_per_step_mean"],
-               ms_per_step_min=res["ms_per_step_min"], ms_per_step_max=res["ms_per_step_max"], secondary=secondary)
+               ms_per_step_min=res["ms_per_step_min"], ms_per_step_max=res["ms_per_step_max"], secondary=secondary,
+               attend_cache=res.get("attend_cache"))
     print(json.dumps(out), flush=True)
     return 0
 

@@ -61,6 +61,10 @@ __device__ __forceinline__ uint4 transpose_4x4_b32(const uint4& v, int lane) {
   return make_uint4(x[0], x[1], x[2], x[3]);
 }
 
+// Workgroup barrier for data exchanged through LDS only: waits for this wave's LDS traffic, not for its
+// global loads, so the next chunk's prefetch stays in flight across it (__syncthreads would wait for it).
+__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
 __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
   typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
   bf16x2 t = {(__bf16)lo, (__bf16)hi};  // round to nearest even
@@ -136,7 +140,7 @@ __global__ __launch_bounds__(ATT_THREADS) void attend_kernel(AttendParams p) {
 
   prefetch(k_lo);
   for (int kc0 = k_lo; kc0 < k_hi; kc0 += KC) {
-    __syncthreads();  // every wave has finished with the previous chunk
+    lds_barrier();  // every wave has finished with the previous chunk
 #pragma unroll
     for (int u = 0; u < KL; ++u) {
       sK[(k_row + u * K_ROWS_PER_LOAD) * CHP + k_col] = kpre[u];
@@ -145,7 +149,7 @@ __global__ __launch_bounds__(ATT_THREADS) void attend_kernel(AttendParams p) {
       sVT[(v_c * EPC + v_i) * VTP + (u * V_GROUPS_PER_LOAD + v_grp)] = t;
     }
     if (kc0 + KC < k_hi) prefetch(kc0 + KC);  // in flight while this chunk is worked on
-    __syncthreads();
+    lds_barrier();
 
 #pragma unroll 1
     for (int nt = ks; nt < TPC; nt += wprt) {
@@ -208,51 +212,116 @@ __global__ __launch_bounds__(ATT_THREADS) void attend_kernel(AttendParams p) {
     }
   }
 
-  // one partial per (split, wave share of the row tile): reference, sum, unnormalised output
   l_sum += __shfl_xor(l_sum, 32);
-  if (row < p.m_rows) {
-    const int part = split * wprt + ks;
-    const size_t at = ((size_t)h * p.n_parts + part) * p.m_rows + row;
-    if (kg == 0) p.part_ml[at] = make_float2(m_ref, l_sum);
-    float* dst = p.part_o + at * D;
+  if (p.wprt_log == 0) {
+    // a wave owns its row tile: its state is the split's partial (reference, sum, unnormalised output)
+    if (row < p.m_rows) {
+      const size_t at = ((size_t)h * p.n_parts + split) * p.m_rows + row;
+      if (kg == 0) p.part_ml[at] = make_float2(m_ref, l_sum);
+      float* dst = p.part_o + at * D;
+#pragma unroll
+      for (int dt = 0; dt < NDT; ++dt)
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4)
+          *reinterpret_cast<float4*>(dst + dt * 32 + 8 * q4 + 4 * kg) =
+              make_float4(o[dt][4 * q4], o[dt][4 * q4 + 1], o[dt][4 * q4 + 2], o[dt][4 * q4 + 3]);
+    }
+    return;
+  }
+  // several waves share a row tile over different key tiles: their states meet in LDS (rows padded by four
+  // floats against bank conflicts) and leave as one partial per split
+  constexpr int OP = D + 4;
+  float* sO = reinterpret_cast<float*>(smem);                       // [8 waves][32 rows][OP]
+  float2* sML = reinterpret_cast<float2*>(sO + ATT_WAVES * 32 * OP);  // [8 waves][32 rows]
+  lds_barrier();  // the chunk buffers are free
+  {
+    float* dst = sO + (size_t)(wave * 32 + rl) * OP;
 #pragma unroll
     for (int dt = 0; dt < NDT; ++dt)
 #pragma unroll
       for (int q4 = 0; q4 < 4; ++q4)
         *reinterpret_cast<float4*>(dst + dt * 32 + 8 * q4 + 4 * kg) =
             make_float4(o[dt][4 * q4], o[dt][4 * q4 + 1], o[dt][4 * q4 + 2], o[dt][4 * q4 + 3]);
+    if (kg == 0) sML[wave * 32 + rl] = make_float2(m_ref, l_sum);
+  }
+  lds_barrier();
+  const int n_rtw = ATT_WAVES >> p.wprt_log;  // row tiles of this workgroup
+  for (int e = tid; e < n_rtw * 32 * (D / 4); e += ATT_THREADS) {
+    const int d4 = e % (D / 4), rr = e / (D / 4);  // rr = row tile * 32 + row in tile
+    const int row2 = qg * ATT_ROWS + rr;
+    if (row2 >= p.m_rows) continue;
+    const int w0 = (rr >> 5) << p.wprt_log, r2 = rr & 31;  // first wave of the tile
+    float mx = NEG_BIG;
+    for (int k = 0; k < wprt; ++k) mx = fmaxf(mx, sML[(w0 + k) * 32 + r2].x);
+    float l = 0.0f;
+    float4 acc = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+    for (int k = 0; k < wprt; ++k) {
+      const float2 ml = sML[(w0 + k) * 32 + r2];
+      const float wgt = fast_exp2(ml.x - mx);
+      const float4 ov = *reinterpret_cast<const float4*>(sO + (size_t)((w0 + k) * 32 + r2) * OP + d4 * 4);
+      l = fmaf(ml.y, wgt, l);
+      acc.x = fmaf(ov.x, wgt, acc.x);
+      acc.y = fmaf(ov.y, wgt, acc.y);
+      acc.z = fmaf(ov.z, wgt, acc.z);
+      acc.w = fmaf(ov.w, wgt, acc.w);
+    }
+    const size_t at = ((size_t)h * p.n_parts + split) * p.m_rows + row2;
+    if (d4 == 0) p.part_ml[at] = make_float2(mx, l);
+    *reinterpret_cast<float4*>(p.part_o + at * D + d4 * 4) = acc;
   }
 }
 
-// out = sum_p O_p 2^(m_p - M) / sum_p l_p 2^(m_p - M), lse = (M + log2 of that sum) ln 2; one row per group of
-// D / 4 lanes.  Without any partial (empty cache) the output is zero and the normaliser -inf.
+// out = sum_p O_p 2^(m_p - M) / sum_p l_p 2^(m_p - M), lse = (M + log2 of that sum) ln 2.  One workgroup per row:
+// D / 4 lanes across the head dimension times COMB_SLICES slices of the partials, each slice merged on the fly
+// and the slices then through LDS.  Without any partial (empty cache) the output is zero, the normaliser -inf.
+constexpr int COMB_SLICES = 8;
 template <int D>
-__global__ __launch_bounds__(256) void attend_combine_kernel(AttendParams p) {
+__global__ __launch_bounds__((D / 4) * COMB_SLICES) void attend_combine_kernel(AttendParams p) {
   constexpr int LPR = D / 4;  // lanes per row
-  const int row_lin = blockIdx.x * (256 / LPR) + threadIdx.x / LPR;
-  const int d4 = threadIdx.x % LPR;
-  const int n_rows = p.n_kv_heads * p.m_rows;
-  if (row_lin >= n_rows) return;
+  __shared__ float4 sAcc[COMB_SLICES][LPR];
+  __shared__ float2 sMl[COMB_SLICES];
+  const int row_lin = blockIdx.x;
+  const int d4 = threadIdx.x % LPR, sl = threadIdx.x / LPR;
   const int h = row_lin / p.m_rows, m = row_lin - h * p.m_rows;
   const float2* ml = p.part_ml + (size_t)h * p.n_parts * p.m_rows + m;
   const float* po = p.part_o + ((size_t)h * p.n_parts * p.m_rows + m) * D + d4 * 4;
-  float mx = NEG_BIG;
-  for (int q = 0; q < p.n_parts; ++q) mx = fmaxf(mx, ml[(size_t)q * p.m_rows].x);
-  float l = 0.0f;
+  float mx = NEG_BIG, l = 0.0f;
   float4 acc = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
-  for (int q = 0; q < p.n_parts; ++q) {
+#pragma unroll 4
+  for (int q = sl; q < p.n_parts; q += COMB_SLICES) {
     const float2 v = ml[(size_t)q * p.m_rows];
-    const float w = fast_exp2(v.x - mx);
     const float4 ov = *reinterpret_cast<const float4*>(po + (size_t)q * p.m_rows * D);
-    l = fmaf(v.y, w, l);
-    acc.x = fmaf(ov.x, w, acc.x);
-    acc.y = fmaf(ov.y, w, acc.y);
-    acc.z = fmaf(ov.z, w, acc.z);
-    acc.w = fmaf(ov.w, w, acc.w);
+    const float mn = fmaxf(mx, v.x);
+    const float wa = fast_exp2(mx - mn), wb = fast_exp2(v.x - mn);
+    l = l * wa + v.y * wb;
+    acc.x = acc.x * wa + ov.x * wb;
+    acc.y = acc.y * wa + ov.y * wb;
+    acc.z = acc.z * wa + ov.z * wb;
+    acc.w = acc.w * wa + ov.w * wb;
+    mx = mn;
   }
-  const float inv = l > 0.0f ? 1.0f / l : 0.0f;
-  *reinterpret_cast<float4*>(p.out + (size_t)row_lin * D + d4 * 4) = make_float4(acc.x * inv, acc.y * inv, acc.z * inv, acc.w * inv);
-  if (d4 == 0) p.out_lse[row_lin] = l > 0.0f ? (mx + fast_log2(l)) * 0.6931471805599453f : -__builtin_inff();
+  sAcc[sl][d4] = acc;
+  if (d4 == 0) sMl[sl] = make_float2(mx, l);
+  __syncthreads();
+  if (sl != 0) return;
+  float mt = NEG_BIG;
+#pragma unroll
+  for (int k = 0; k < COMB_SLICES; ++k) mt = fmaxf(mt, sMl[k].x);
+  float lt = 0.0f;
+  float4 at = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+#pragma unroll
+  for (int k = 0; k < COMB_SLICES; ++k) {
+    const float wgt = fast_exp2(sMl[k].x - mt);
+    const float4 ov = sAcc[k][d4];
+    lt = fmaf(sMl[k].y, wgt, lt);
+    at.x = fmaf(ov.x, wgt, at.x);
+    at.y = fmaf(ov.y, wgt, at.y);
+    at.z = fmaf(ov.z, wgt, at.z);
+    at.w = fmaf(ov.w, wgt, at.w);
+  }
+  const float inv = lt > 0.0f ? 1.0f / lt : 0.0f;
+  *reinterpret_cast<float4*>(p.out + (size_t)row_lin * D + d4 * 4) = make_float4(at.x * inv, at.y * inv, at.z * inv, at.w * inv);
+  if (d4 == 0) p.out_lse[row_lin] = lt > 0.0f ? (mt + fast_log2(lt)) * 0.6931471805599453f : -__builtin_inff();
 }
 
 // ---- host side ----
@@ -270,7 +339,7 @@ void attend_plan(int m_rows, int64_t cache_len, int n_kv_heads, int n_cu, Attend
   plan->wprt_log = wprt_log;
   plan->n_splits = n_splits;
   plan->keys_per_split = (int)kps;
-  plan->n_parts = n_splits << wprt_log;
+  plan->n_parts = n_splits;
 }
 
 size_t attend_workspace_bytes(const AttendPlan& plan, int m_rows, int n_kv_heads, int head_dim) {
@@ -282,16 +351,16 @@ template <int DT, int D>
 static hipError_t launch_attend_t(const AttendParams& p, hipStream_t st) {
   constexpr int ES = DT == DT_BF16 ? 2 : 4;
   constexpr int KC = att_chunk_keys<DT>();
-  constexpr size_t lds = ((size_t)KC * (D * ES / 16 + 1) + (size_t)D * (KC / (16 / ES) + 1)) * 16;
+  constexpr size_t lds_chunk = ((size_t)KC * (D * ES / 16 + 1) + (size_t)D * (KC / (16 / ES) + 1)) * 16;
+  constexpr size_t lds_merge = (size_t)ATT_WAVES * 32 * ((D + 4) * 4 + 8);  // the waves' states when they share row tiles
+  constexpr size_t lds = lds_chunk > lds_merge ? lds_chunk : lds_merge;
   static_assert(lds <= 160 * 1024, "attention chunk does not fit the LDS");
   if (p.n_splits > 0) {
     hipLaunchKernelGGL((attend_kernel<DT, D>), dim3(p.n_splits, p.n_qgroups, p.n_kv_heads), dim3(ATT_THREADS), lds, st, p);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
   }
-  constexpr int rows_per_wg = 256 / (D / 4);
-  const int n_rows = p.n_kv_heads * p.m_rows;
-  hipLaunchKernelGGL((attend_combine_kernel<D>), dim3((n_rows + rows_per_wg - 1) / rows_per_wg), dim3(256), 0, st, p);
+  hipLaunchKernelGGL((attend_combine_kernel<D>), dim3(p.n_kv_heads * p.m_rows), dim3((D / 4) * COMB_SLICES), 0, st, p);
   return hipGetLastError();
 }
 

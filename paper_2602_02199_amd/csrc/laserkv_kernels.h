@@ -130,7 +130,7 @@ struct AttendParams {
   int keys_per_split;  // multiple of 32
   int n_splits;        // ceil(cache_len / keys_per_split); 0: empty cache
   int wprt_log;        // log2 of the waves that share a 32-row tile (over different key tiles)
-  int n_parts;         // n_splits << wprt_log partials per row
+  int n_parts;         // partials per row: one per key split
   int n_qgroups;       // ceil(M / 256)
   int n_kv_heads;
   float scale2;        // log2(e) / sqrt(d)

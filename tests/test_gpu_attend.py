@@ -19,7 +19,7 @@ from tests.parity_util import check_block
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
 TOL = {"f32": 1e-5, "bf16": 2e-2}
-OBSERVED = {"f32": 1e-5, "bf16": 6e-3}
+OBSERVED = {"f32": 1e-5, "bf16": 3e-3}   # regression bound on the output error actually seen (about 8e-4)
 
 
 def say(msg):
