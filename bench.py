@@ -35,6 +35,8 @@ def algorithmic_work(wl, B):
         # sweep 1 = the score contraction (priced once per sweep kernel) + the projection of the keys
         "sweep1": ("mfma", score + 2.0 * d * lk * hk * s),
         "sweep2": ("mfma", score),
+        # the one sweep of --lse complete: both contractions once
+        "single": ("mfma", score + 2.0 * d * lk * hk * s),
         "count": ("hbm", hk * s * (wl.lsh_tables * 2 + 4) + wl.n_q_heads * wl.window * wl.lsh_tables * 2),
         "select": ("hbm", hk * s * 8 + hk * B * 4),
         "append": ("hbm", hk * B * (4 * d * es + 4 + 8)),
@@ -193,7 +195,7 @@ def measure(wl, args, dev, cpu_seconds):
                                else "NOT met"))
     # whole-path roofline: serial sum of the contraction time at MFMA peak and the byte time at HBM peak
     es = 2 if wl.dtype == "bf16" else 4
-    flops_blk = work["sweep1"][1]
+    flops_blk = work["sweep1"][1]   # score + key projection once: the same figure with one sweep or two
     bytes_blk = wl.n_kv_heads * wl.s_block * wl.head_dim * es + wl.n_q_heads * wl.window * wl.head_dim * es \
         + work["append"][1]
     t_roof = (flops_blk / (peak_mfma * 1e12) + bytes_blk / (PEAK_HBM_GBS * 1e9)) * wl.n_blocks

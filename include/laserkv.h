@@ -204,8 +204,11 @@ int laserkv_set_row_lse(laserkv_ctx* ctx, const float* row_lse);
  * holds, per window query, the COMPLETE natural-log sum of exp(q.k / sqrt(d)) over every key the row
  * attends to (the block keys it sees, the look-back keys, the rest of the cache), exactly what a
  * flash-attention forward reports for those rows.  S_exact[h, i] = mean over the rows of
- * exp(q.k_i / sqrt(d) - row_lse) at the visible keys.  The library then computes no row statistics: the
- * first sweep only hashes, and k_ctx / t_ctx of the following calls are accepted but not read.
+ * exp(q.k_i / sqrt(d) - row_lse) at the visible keys.  The library then computes no row statistics, and
+ * k_ctx / t_ctx of the following calls are accepted but not read.  Where the shape allows it (G * w <= 512,
+ * rows of at most 256 bytes, query rows of a head contiguous, K such that L * 2^K 16-bit bins fit 512 KiB)
+ * a block then takes ONE sweep over its keys (hash, score and count from the same LDS rows) instead of two;
+ * otherwise the first of the two sweeps only hashes.
  *   row_lse  DEVICE [H_q, w] float, contiguous; NULL switches back to the library's own statistics.
  * Lifetime and scope as for laserkv_set_row_lse, which it replaces (and which replaces it).
  * Errors: LKV_EINVAL (null context, pointer not 4-byte aligned). */
@@ -290,7 +293,9 @@ typedef enum {
                           accumulation kernel of laserkv_score_block */
   LKV_KERN_APPEND = 4, /* gather-append as a kernel of its own */
   LKV_KERN_ATTEND = 5, /* attention over the compacted cache (both of its kernels) */
-  LKV_N_KERNELS = 6
+  LKV_KERN_SINGLE = 6, /* the one sweep of a block whose rows come with their complete log-sum-exp: SimHash codes,
+                          pooled probabilities and collision counts from one read of the keys */
+  LKV_N_KERNELS = 7
 } laserkv_kernel_id;
 #define LKV_PROFILE_MAX_LAUNCHES 8192
 

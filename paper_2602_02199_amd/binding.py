@@ -26,7 +26,7 @@ EXPORTS = (
     "laserkv_static_init", "laserkv_static_workspace_bytes", "laserkv_compress_block_static",
 )
 LKV_STATIC_SCRATCH_BYTES = 32 << 20
-KERNEL_NAMES = ("sweep1", "sweep2", "count", "select", "append", "attend")
+KERNEL_NAMES = ("sweep1", "sweep2", "count", "select", "append", "attend", "single")
 
 
 class LaserKVError(RuntimeError):

@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB_PATH = os.path.join(HERE, "liblaserkv.so")
-SOURCES = ["laserkv_api.hip", "laserkv_kernels.hip", "laserkv_attend.hip"]
+SOURCES = ["laserkv_api.hip", "laserkv_kernels.hip", "laserkv_attend.hip", "laserkv_single.hip"]
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -4,6 +4,7 @@
 
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
@@ -43,6 +44,7 @@ struct laserkv_ctx {
   int32_t* cnt;      // [n_qgroups_max, H_kv, max_block] count parts
   int32_t* cnt_sum;  // [H_kv, max_block] summed counts (stage output)
   uint32_t* qhist;   // [H_kv, L, 2^K / 2, n_qgroups] or null when the tables are too large
+  uint32_t* sync;    // single sweep: [0] epoch, [1] finished workgroups, [64 ..] per-table flags [H_kv, L]; null without qhist
   uint16_t* sig_k;   // [H_kv, max_block, L]
   uint16_t* sig_q;   // [H_q, max_window, L]
   int m_pad;
@@ -53,6 +55,8 @@ struct laserkv_ctx {
   // tuning switches, read from the environment once when the context is created
   int sweep_wg_per_cu;   // LASERKV_SWEEP_WG_PER_CU: sweep workgroups aimed at per compute unit (default 1)
   int append_split;      // LASERKV_APPEND_SPLIT: select+append workgroups per head (default: n_cu / heads)
+  int single_spin;       // LASERKV_SINGLE_SPIN: polls of a histogram flag before a workgroup computes the table itself
+                         // (default 64; negative: the single sweep is not used)
   char error[512];
   // per-kernel event timing (benchmarks only)
   bool profiling;
@@ -127,9 +131,9 @@ int check_config(const laserkv_config& c, const char* who) {
   return LKV_OK;
 }
 
-// The device workspace of a configuration: eight buffers, in the order of WsIndex.
-constexpr int kWsBuffers = 8;
-enum WsIndex { WS_PART, WS_S_PART, WS_S_EXACT, WS_CNT, WS_CNT_SUM, WS_SIG_K, WS_SIG_Q, WS_QHIST };
+// The device workspace of a configuration: nine buffers, in the order of WsIndex.
+constexpr int kWsBuffers = 9;
+enum WsIndex { WS_PART, WS_S_PART, WS_S_EXACT, WS_CNT, WS_CNT_SUM, WS_SIG_K, WS_SIG_Q, WS_QHIST, WS_SYNC };
 struct WsPlan {
   int m_pad, max_ranges;
   size_t bytes[kWsBuffers];  // 0: buffer not used by this configuration
@@ -162,6 +166,8 @@ void plan_workspace(const laserkv_config& c, bool allow_qhist, WsPlan& w) {
   w.bytes[WS_SIG_K] = hk * sb * c.lsh_tables * sizeof(uint16_t);
   w.bytes[WS_SIG_Q] = (size_t)c.n_q_heads * c.max_window * c.lsh_tables * sizeof(uint16_t);
   w.bytes[WS_QHIST] = use_qhist ? n_qg_max * hk * hist_bytes_head : 0;
+  // the single sweep's per-table flags and its two launch counters (zero before the first launch)
+  w.bytes[WS_SYNC] = use_qhist ? (hk * c.lsh_tables + 64) * sizeof(uint32_t) : 0;
 }
 
 void init_ctx_fields(laserkv_ctx* ctx, const laserkv_config& c) {
@@ -183,6 +189,7 @@ void bind_workspace(laserkv_ctx* ctx, const WsPlan& w, void* const ptr[kWsBuffer
   ctx->sig_k = (uint16_t*)ptr[WS_SIG_K];
   ctx->sig_q = (uint16_t*)ptr[WS_SIG_Q];
   ctx->qhist = (uint32_t*)ptr[WS_QHIST];
+  ctx->sync = (uint32_t*)ptr[WS_SYNC];
 }
 
 }  // namespace
@@ -239,6 +246,7 @@ int laserkv_create(const laserkv_config* cfg, laserkv_ctx** out) {
   }
   e = lkv::init_kernel_attributes();
   if (e == hipSuccess) e = lkv::init_attend_attributes();
+  if (e == hipSuccess) e = lkv::init_single_attributes();
   if (e != hipSuccess) {
     laserkv_destroy(ctx);
     return fail_hip(nullptr, e, "create: kernel attribute");
@@ -246,6 +254,7 @@ int laserkv_create(const laserkv_config* cfg, laserkv_ctx** out) {
   ctx->sweep_wg_per_cu = env_int("LASERKV_SWEEP_WG_PER_CU", 1);
   if (ctx->sweep_wg_per_cu < 1) ctx->sweep_wg_per_cu = 1;
   ctx->append_split = env_int("LASERKV_APPEND_SPLIT", 0);
+  ctx->single_spin = env_int("LASERKV_SINGLE_SPIN", 64);
   WsPlan ws;
   plan_workspace(c, env_int("LASERKV_NO_QHIST", 0) == 0, ws);
   void* ptr[kWsBuffers] = {};
@@ -272,13 +281,21 @@ int laserkv_create(const laserkv_config* cfg, laserkv_ctx** out) {
       return fail_hip(nullptr, e, "create: workspace fill");
     }
   }
+  if (ptr[WS_SYNC]) {
+    e = hipMemset(ptr[WS_SYNC], 0, ws.bytes[WS_SYNC]);
+    if (e == hipSuccess) e = hipDeviceSynchronize();
+    if (e != hipSuccess) {
+      laserkv_destroy(ctx);
+      return fail_hip(nullptr, e, "create: clearing the flags of the single sweep");
+    }
+  }
   *out = ctx;
   return LKV_OK;
 }
 
 void laserkv_destroy(laserkv_ctx* ctx) {
   if (!ctx) return;
-  void* ptrs[] = {ctx->part, ctx->s_part, ctx->s_exact, ctx->cnt, ctx->cnt_sum, ctx->qhist, ctx->sig_k, ctx->sig_q};
+  void* ptrs[] = {ctx->part, ctx->s_part, ctx->s_exact, ctx->cnt, ctx->cnt_sum, ctx->qhist, ctx->sig_k, ctx->sig_q, ctx->sync};
   if (ctx->owns_workspace)
     for (void* p : ptrs)
       if (p) (void)hipFree(p);
@@ -470,19 +487,76 @@ int select_impl(laserkv_ctx* ctx,
   lp.s_exact = dbg_s_exact ? ctx->s_exact : nullptr;
   lp.keep = keep_idx;
 
+  // With complete row statistics from the caller nothing depends on a first pass over all keys: one sweep
+  // hashes, scores and counts (keys read once), where the shape allows it (the GQA group's window rows in one
+  // workgroup, histograms of the window-row codes resident in global memory, rows of at most 256 bytes).
+  lkv::SingleParams sg = {};
+  bool single = lse_complete && ctx->qhist && ctx->sync && ctx->single_spin >= 0 && sp.q_linear &&
+                lkv::single_supports(c.dtype, d) && m_rows <= lkv::single_max_rows();
+  if (single) {
+    int snk = (int)(((int64_t)s_t * c.n_kv_heads + ctx->n_cu - 1) / ctx->n_cu + 31) / 32 * 32;
+    snk = std::max(32, std::min(snk, lkv::single_max_keys()));
+    for (;; snk -= 32) {
+      sg.keys_per_range = snk;
+      sg.n_ranges = (s_t + snk - 1) / snk;
+      sg.q_tab_per_wg = (c.lsh_tables + sg.n_ranges - 1) / sg.n_ranges;
+      sg.q_tiles = (sg.q_tab_per_wg + sp.q_tab_per_tile - 1) / sp.q_tab_per_tile;
+      const bool fits = sg.q_tiles <= lkv::single_max_qtiles() &&
+                        lkv::single_lds_bytes(c.dtype, d, snk, sg.q_tiles, sg.q_tab_per_wg, c.lsh_bits, c.lsh_tables) <= 160 * 1024;
+      if (fits || snk <= 32) {
+        single = fits;
+        break;
+      }
+    }
+  }
+  if (single) {
+    sg.q = sp.q;
+    sg.kb = sp.kb;
+    sg.planes = sp.planes;
+    sg.group = G;
+    sg.w = w;
+    sg.w_magic = sp.w_magic;
+    sg.m_rows = m_rows;
+    sg.s_t = s_t;
+    sg.n_kv_heads = c.n_kv_heads;
+    sg.causal = sp.causal;
+    sg.lim0 = sp.lim0;
+    sg.scale2 = sp.scale2;
+    sg.row_lse = ctx->row_lse;
+    sg.n_tables = c.lsh_tables;
+    sg.n_bits = c.lsh_bits;
+    sg.n_planes = sp.n_planes;
+    sg.q_tab_per_tile = sp.q_tab_per_tile;
+    sg.s_part = ctx->s_part;
+    sg.cnt = ctx->cnt;
+    sg.sig_k = dbg_sig_k ? ctx->sig_k : nullptr;
+    sg.sig_q = ctx->sig_q;
+    sg.qhist = ctx->qhist;
+    sg.sync = ctx->sync;
+    sg.flags = ctx->sync + 64;
+    sg.spin_limit = ctx->single_spin;
+    lp.n_qgroups = 1;
+    lp.n_cnt_parts = 1;
+  }
+
   hipError_t e;
   const int nh = c.n_kv_heads, dt = c.dtype;
-  if ((e = timed(ctx, LKV_KERN_SWEEP1, st, [&] { return lkv::launch_sweep1(dt, d, sp, st); })) != hipSuccess)
-    return fail_hip(ctx, e, "select_block: sweep 1 (row statistics + SimHash codes)");
-  if ((e = timed(ctx, LKV_KERN_SWEEP2, st, [&] { return lkv::launch_sweep2(dt, d, sp, st); })) != hipSuccess)
-    return fail_hip(ctx, e, "select_block: sweep 2 (pooled probabilities)");
-  if (!sp.qhist && (e = timed(ctx, LKV_KERN_COUNT, st, [&] { return lkv::launch_count(cp, nh, st); })) != hipSuccess)
-    return fail_hip(ctx, e, "select_block: count kernel");
+  if (single) {
+    if ((e = timed(ctx, LKV_KERN_SINGLE, st, [&] { return lkv::launch_single(dt, d, sg, st); })) != hipSuccess)
+      return fail_hip(ctx, e, "select_block: single sweep (SimHash codes + pooled probabilities + collision counts)");
+  } else {
+    if ((e = timed(ctx, LKV_KERN_SWEEP1, st, [&] { return lkv::launch_sweep1(dt, d, sp, st); })) != hipSuccess)
+      return fail_hip(ctx, e, "select_block: sweep 1 (row statistics + SimHash codes)");
+    if ((e = timed(ctx, LKV_KERN_SWEEP2, st, [&] { return lkv::launch_sweep2(dt, d, sp, st); })) != hipSuccess)
+      return fail_hip(ctx, e, "select_block: sweep 2 (pooled probabilities)");
+    if (!sp.qhist && (e = timed(ctx, LKV_KERN_COUNT, st, [&] { return lkv::launch_count(cp, nh, st); })) != hipSuccess)
+      return fail_hip(ctx, e, "select_block: count kernel");
+  }
   if (acc_score) {
     lkv::AccumParams acp;
     acp.s_part = ctx->s_part;
     acp.cnt = ctx->cnt;
-    acp.n_qgroups = n_qg;
+    acp.n_qgroups = lp.n_qgroups;
     acp.n_cnt_parts = lp.n_cnt_parts;
     acp.n_kv_heads = c.n_kv_heads;
     acp.s_t = s_t;

@@ -47,6 +47,19 @@ struct Mma<DT_F32> {
 
 __device__ __forceinline__ int acc_row(int r, int kg) { return 8 * (r >> 2) + 4 * kg + (r & 3); }
 
+__device__ __forceinline__ int div_w(int m, uint32_t magic) { return (int)__umulhi((uint32_t)m, magic); }
+
+// Plane (within a 32-plane tile) that a hashing wave feeds as row rho of its A operand.  Accumulator
+// register r of a lane in half kg is row 8*(r/4) + 4*kg + (r&3); with this order it is plane 16*kg + r,
+// so a lane's 16 registers are 16 consecutive sign bits.
+__device__ __forceinline__ int plane_row(int rho) { return 16 * ((rho >> 2) & 1) + 4 * (rho >> 3) + (rho & 3); }
+
+// Workgroups are handed to the eight XCDs (each with its own L2) round-robin by linear id.  This maps
+// id to an index whose consecutive values stay on one XCD: XCD x gets indices [x*n/8, (x+1)*n/8).
+__device__ __forceinline__ int xcd_major(int id, int n) {
+  return (n & 7) == 0 ? (id & 7) * (n >> 3) + (id >> 3) : id;
+}
+
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 __device__ __forceinline__ float fast_log2(float x) { return __builtin_amdgcn_logf(x); }
 

@@ -116,6 +116,42 @@ struct AppendParams {
   int64_t block_pos0;
 };
 
+// The single sweep of a block whose window rows come with their complete log-sum-exp.
+struct SingleParams {
+  RowSrc q;        // [H_q, W, d], rows of a KV head's query heads contiguous (row m of head h at h*G*W + m)
+  RowSrc kb;       // [H_kv, S, d]
+  const char* planes;  // [L*K, d] contiguous
+  int group, w;
+  uint32_t w_magic;
+  int m_rows;      // M = G * W <= single_max_rows()
+  int s_t;
+  int keys_per_range;  // multiple of 32, <= single_max_keys()
+  int n_ranges;        // ceil(S / keys_per_range)
+  int n_kv_heads;
+  int causal, lim0;    // block key i is visible to window row j iff i <= lim0 + j (when causal)
+  float scale2;
+  const float* row_lse;  // [H_kv, M] complete natural-log normaliser of every window row
+  int n_tables, n_bits, n_planes;
+  int q_tab_per_wg;    // tables whose window-row codes and histogram workgroup (range, head) owns: ceil(L / n_ranges)
+  int q_tab_per_tile;  // floor(32 / K)
+  int q_tiles;         // ceil(q_tab_per_wg / q_tab_per_tile) <= single_max_qtiles()
+  float* s_part;       // [H_kv, S] pooled probabilities (sum over the rows)
+  int32_t* cnt;        // [H_kv, S]
+  uint16_t* sig_k;     // [H_kv, S, L] or null: key codes only for the stage outputs
+  uint16_t* sig_q;     // [H_kv, M, L]
+  uint32_t* qhist;     // [H_kv, L, 2^K / 2] histograms of the window-row codes, two 16-bit bins per word
+  uint32_t* flags;     // [H_kv, L]: epoch + 1 of the launch that published the table's histogram
+  uint32_t* sync;      // [0] epoch, [1] workgroups of the running launch that have finished; both zero at first
+  int spin_limit;      // polls of a flag before the workgroup computes the table itself
+};
+size_t single_lds_bytes(int dtype, int head_dim, int keys_per_range, int q_tiles, int q_tab_per_wg, int n_bits, int n_tables);
+int single_max_rows();
+int single_max_keys();
+int single_max_qtiles();
+bool single_supports(int dtype, int head_dim);
+hipError_t launch_single(int dtype, int head_dim, const SingleParams& p, hipStream_t st);
+hipError_t init_single_attributes();
+
 // Attention of n_q queries per query head over the first cache_len rows of each KV head's compacted cache.
 struct AttendParams {
   RowSrc q;            // [H_q, n_q, d]

@@ -59,19 +59,6 @@ constexpr int BITS_PITCH = 17;        // words per vector row in the sign-bit sc
 template <int DT, int D>
 __host__ __device__ constexpr int row_pitch_chunks() { return D * (DT == DT_BF16 ? 2 : 4) / 16 + 1; }
 
-__device__ __forceinline__ int div_w(int m, uint32_t magic) { return (int)__umulhi((uint32_t)m, magic); }
-
-// Plane (within a 32-plane tile) that a hashing wave feeds as row rho of its A operand.  Accumulator
-// register r of a lane in half kg is row 8*(r/4) + 4*kg + (r&3); with this order it is plane 16*kg + r,
-// so a lane's 16 registers are 16 consecutive sign bits.
-__device__ __forceinline__ int plane_row(int rho) { return 16 * ((rho >> 2) & 1) + 4 * (rho >> 3) + (rho & 3); }
-
-// Workgroups are handed to the eight XCDs (each with its own L2) round-robin by linear id.  This maps
-// id to an index whose consecutive values stay on one XCD: XCD x gets indices [x*n/8, (x+1)*n/8).
-__device__ __forceinline__ int xcd_major(int id, int n) {
-  return (n & 7) == 0 ? (id & 7) * (n >> 3) + (id >> 3) : id;
-}
-
 template <int DT, int D, bool PASS2>
 __global__ __launch_bounds__(PASS_WAVES * 64) void pass_kernel(PassParams p) {
   constexpr int ES = DT == DT_BF16 ? 2 : 4;
