@@ -1,5 +1,6 @@
 // C-ABI of the LASER-KV block-selection library: argument checks, workspace, launch sequence.
 #include "../../include/laserkv.h"
+#include "../../include/laserkv_profile.h"
 #include "laserkv_kernels.h"
 
 #include <hip/hip_runtime.h>

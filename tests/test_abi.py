@@ -21,7 +21,8 @@ def lib():
 
 
 def test_every_declared_symbol_is_exported(lib):
-    header = open(os.path.join(ROOT, "include", "laserkv.h")).read()
+    inc = os.path.join(ROOT, "include")
+    header = "".join(open(os.path.join(inc, f)).read() for f in sorted(os.listdir(inc)) if f.endswith(".h"))
     declared = set(re.findall(r"\b(laserkv_[a-z_]+)\s*\(", header))
     assert declared == set(binding.EXPORTS)
     for name in declared:
