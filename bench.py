@@ -184,7 +184,7 @@ def measure(wl, args, dev, cpu_seconds):
                                 unit=unit, frac=round(achieved / peak, 4), launches_per_step=v["launches"])
     dom = max(per_kernel, key=lambda k: per_kernel[k]["avg_us"])
     traffic = None
-    tpath = os.path.join(ROOT, "profiles", f"traffic_{wl.name}.json")
+    tpath = os.path.join(ROOT, "profiles", f"traffic_{wl.name}{'-lse-complete' if args.lse == 'complete' else ''}.json")
     if os.path.exists(tpath):
         traffic = json.load(open(tpath)).get(dom)
     d = per_kernel[dom]
@@ -266,6 +266,8 @@ def main():
     ap.add_argument("--lse", choices=["own", "complete"], default="own",
                     help="complete: the window rows' complete log-sum-exp is handed to the library (as the model's "
                          "attention kernel would report it), so the first sweep only hashes; not the headline configuration")
+    ap.add_argument("--no-complete", dest="with_complete", action="store_false",
+                    help="skip the extra measurement of the workload with complete row statistics from the caller")
     ap.add_argument("--no-attend", dest="attend", action="store_false",
                     help="skip the timing of laserkv_attend_cache over the finished cache")
     ap.add_argument("--batch", type=int, default=1,
@@ -304,13 +306,26 @@ def main():
                          blocks=sec["config"]["blocks"], dominant_kernel=r["kernel"], bound=r["bound"], frac=r["frac"],
                          avg_us=r["avg_us"], traffic=r["traffic"], kernels=r["kernels"],
                          path_frac_of_roofline=r["path_frac_of_roofline"])
+    # the same workload with the window rows' complete log-sum-exp supplied by the caller (one sweep per block)
+    complete = None
+    if args.lse == "own" and args.with_complete and args.batch == 1 and not args.calibrate_copy:
+        c_args = argparse.Namespace(**vars(args))
+        c_args.attend = False
+        c_args.lse = "complete"
+        cm = measure(wl, c_args, dev, 0.0)
+        r = cm["roofline"]
+        complete = dict(row_statistics="complete, from the caller (stand-in for the model's attention kernel, outside the timed region)",
+                        value=cm["value"], unit="tokens/s/layer", ms_per_step=cm["ms_per_step"],
+                        ms_per_step_mean=cm["ms_per_step_mean"], dominant_kernel=r["kernel"], bound=r["bound"],
+                        frac=r["frac"], avg_us=r["avg_us"], traffic=r["traffic"], kernels=r["kernels"],
+                        path_frac_of_roofline=r["path_frac_of_roofline"])
     out = dict(metric="prefill-compression tokens/s/layer (score+LSH+top-k+gather) @128k; % roofline",
                value=res["value"], unit="tokens/s/layer", n_gpus=1, steps=args.steps, warmup=args.warmup,
                ms_per_step=res["ms_per_step"], higher_is_better=True, scaling="weak", vs_baseline=None,
                dtype=wl.dtype, data="synthetic", config=res["config"], roofline=res["roofline"],
                cpu_baseline=res["cpu_baseline"], ms_per_step_mean=res["ms_per_step_mean"],
                ms_per_step_min=res["ms_per_step_min"], ms_per_step_max=res["ms_per_step_max"], secondary=secondary,
-               attend_cache=res.get("attend_cache"))
+               attend_cache=res.get("attend_cache"), complete_statistics=complete)
     print(json.dumps(out), flush=True)
     return 0
 
