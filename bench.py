@@ -167,6 +167,8 @@ def measure(wl, args, dev, cpu_seconds):
     work = algorithmic_work(wl, comp.B)
     if not args.unfused:  # the last kernel selects and appends
         work["select"] = ("hbm", work["select"][1] + work["append"][1])
+    if args.attend:
+        res["attend_cache"] = measure_attend(wl, comp, ddev, dev, cases=args.attend_case.split(","))
     if not any(v["launches"] for v in kern.values()):
         return res
     peak_mfma = PEAK_MFMA_BF16_TFLOPS if wl.dtype == "bf16" else PEAK_MFMA_F32_TFLOPS
@@ -201,8 +203,6 @@ def measure(wl, args, dev, cpu_seconds):
     t_roof = (flops_blk / (peak_mfma * 1e12) + bytes_blk / (PEAK_HBM_GBS * 1e9)) * wl.n_blocks
     roofline["path_frac_of_roofline"] = round(t_roof / (ms_per_step * 1e-3), 4)
     res["roofline"] = roofline
-    if args.attend:
-        res["attend_cache"] = measure_attend(wl, comp, ddev, dev)
     if cpu_seconds > 0:
         res["cpu_baseline"] = cpu_baseline(wl, data, comp.B, cpu_seconds)
     del comp, ddev, data
@@ -210,7 +210,7 @@ def measure(wl, args, dev, cpu_seconds):
     return res
 
 
-def measure_attend(wl, comp, ddev, dev, reps=10):
+def measure_attend(wl, comp, ddev, dev, reps=10, cases=("decode", "window")):
     """laserkv_attend_cache over the layer's finished cache (the rows the timed steps kept): one decode query
     per head (bound by reading the cached K and V once) and the next block's window rows (bound by the two
     contractions QK^T and PV).  Event times on the launch stream, average of `reps` launches after two."""
@@ -220,6 +220,8 @@ def measure_attend(wl, comp, ddev, dev, reps=10):
     out = {}
     stream = torch.cuda.current_stream()
     for label, n_q in (("decode", 1), ("window", wl.window)):
+        if label not in cases:
+            continue
         q = ddev["q_win"][-1][:, :n_q].contiguous()
         o = torch.empty(wl.n_q_heads, n_q, wl.head_dim, dtype=torch.float32, device=dev)
         lse = torch.empty(wl.n_q_heads, n_q, dtype=torch.float32, device=dev)
@@ -268,6 +270,7 @@ def main():
                          "attention kernel would report it), so the first sweep only hashes; not the headline configuration")
     ap.add_argument("--no-complete", dest="with_complete", action="store_false",
                     help="skip the extra measurement of the workload with complete row statistics from the caller")
+    ap.add_argument("--attend-case", default="decode,window", help="which attention cases to time (profiling one at a time)")
     ap.add_argument("--no-attend", dest="attend", action="store_false",
                     help="skip the timing of laserkv_attend_cache over the finished cache")
     ap.add_argument("--batch", type=int, default=1,
