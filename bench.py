@@ -296,7 +296,8 @@ def main():
     res = measure(wl, args, dev, args.cpu_seconds)
     if res["roofline"] is None:
         print(json.dumps(dict(value=res["value"], unit="tokens/s/layer", ms_per_step=res["ms_per_step"],
-                              note="no per-kernel timing requested: roofline omitted")), flush=True)
+                              note="no per-kernel timing requested: roofline omitted",
+                              attend_cache=res.get("attend_cache"))), flush=True)
         return 0
     secondary = None
     if args.secondary not in ("none", args.workload) and args.batch == 1 and not args.calibrate_copy:
