@@ -185,14 +185,17 @@ __global__ __launch_bounds__(SG_THREADS) void single_sweep_kernel(SingleParams p
       }
   };
   // Publishing the finished LDS histograms of n_tt tables (first one t_tab0): the words go to global memory, and
-  // once every wave has seen its stores acknowledged (a later workgroup barrier) the tables' flags are raised.
+  // once every wave has seen its stores acknowledged (an explicit wait, then a workgroup barrier) the tables' flags
+  // are raised.
   auto publish_words = [&](const uint32_t* hist0, int t_tab0, int n_tt) {
     __syncthreads();
     uint32_t* dst = p.qhist + ((size_t)h * n_tables + t_tab0) * hist_w;
     for (int i = tid; i < n_tt * hist_w; i += NTHR) sg_store(dst + i, hist0[i]);
   };
   auto publish_flags = [&](int t_tab0, int n_tt) {
-    __syncthreads();  // each wave waits for its outstanding stores before the barrier
+    // every wave first waits until its own stores are acknowledged (the barrier alone waits for LDS traffic only)
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
     if (tid < n_tt) sg_store(p.flags + (size_t)h * n_tables + t_tab0 + tid, target);
   };
 
