@@ -219,11 +219,11 @@ def measure_attend(wl, comp, ddev, dev, reps=10, cases=("decode", "window")):
     es = 2 if wl.dtype == "bf16" else 4
     out = {}
     stream = torch.cuda.current_stream()
-    for label, n_q in (("decode", 1), ("window", wl.window)):
-        if label not in cases:
+    for label, n_q in (("decode", 1), ("window", wl.window), ("window_normaliser_only", wl.window)):
+        if label.split("_")[0] not in cases:
             continue
         q = ddev["q_win"][-1][:, :n_q].contiguous()
-        o = torch.empty(wl.n_q_heads, n_q, wl.head_dim, dtype=torch.float32, device=dev)
+        o = None if label.endswith("only") else torch.empty(wl.n_q_heads, n_q, wl.head_dim, dtype=torch.float32, device=dev)
         lse = torch.empty(wl.n_q_heads, n_q, dtype=torch.float32, device=dev)
         ws = torch.empty(comp.lib.laserkv_attend_workspace_bytes(n_q, n), dtype=torch.uint8, device=dev)
         run = lambda: comp.lib.laserkv_attend_cache(q, comp.k_cache, comp.v_cache, cache_len=n, out=o, out_lse=lse, workspace=ws)
@@ -235,8 +235,9 @@ def measure_attend(wl, comp, ddev, dev, reps=10, cases=("decode", "window")):
         e1.record(stream)
         e1.synchronize()
         us = 1e3 * e0.elapsed_time(e1) / reps
-        nbytes = 2 * wl.n_kv_heads * n * wl.head_dim * es
-        flops = 4 * wl.n_q_heads * n_q * n * wl.head_dim
+        both = 1 if o is None else 2   # contractions per (query, key) pair; tensors of the cache read
+        nbytes = both * wl.n_kv_heads * n * wl.head_dim * es
+        flops = 2 * both * wl.n_q_heads * n_q * n * wl.head_dim
         gbs, tfl = nbytes / us / 1e3, flops / us / 1e6
         peak_mfma = PEAK_MFMA_BF16_TFLOPS if wl.dtype == "bf16" else PEAK_MFMA_F32_TFLOPS
         out[label] = dict(n_q=n_q, cache_rows_per_head=n, avg_us=round(us, 2), hbm_gbs=round(gbs, 1),

@@ -226,7 +226,9 @@ int laserkv_set_row_lse_complete(laserkv_ctx* ctx, const float* row_lse);
  *              cache_stride_head in elements; cache_len rows per head are read, 0 <= cache_len,
  *              cache_len * d * elem size < 2^31
  *   n_q        1 .. max_window of the context's configuration
- *   out        DEVICE [H_q, n_q, d] float, contiguous, 16-byte aligned; zero when cache_len == 0
+ *   out        DEVICE [H_q, n_q, d] float, contiguous, 16-byte aligned; zero when cache_len == 0.  May be NULL:
+ *              then only out_lse is computed (the values are not read; v_cache may be NULL too), by kernels that
+ *              take a GQA group's whole window in one workgroup and read the keys once
  *   out_lse    DEVICE [H_q, n_q] float, contiguous; -inf when cache_len == 0
  *   workspace  DEVICE scratch of at least laserkv_attend_workspace_bytes(ctx, n_q, cache_len) bytes, 256-byte
  *              aligned, owned by the caller; partial results of the key splits, dead after the call's kernels

@@ -314,13 +314,14 @@ class LaserKV:
         return n
 
     def laserkv_attend_cache(self, q, k_cache, v_cache, *, cache_len, out, out_lse, workspace, stream=None):
-        """q [H_q, n_q, d]; k_cache / v_cache [H_kv, cap, d]; out float32 [H_q, n_q, d], out_lse float32 [H_q, n_q];
+        """q [H_q, n_q, d]; k_cache / v_cache [H_kv, cap, d]; out float32 [H_q, n_q, d] or None (normaliser only),
+        out_lse float32 [H_q, n_q];
         workspace: uint8 device tensor of at least laserkv_attend_workspace_bytes(n_q, cache_len) bytes."""
         d = self.cfg.head_dim
         qs = _strides3(q, d)
         assert k_cache.stride(2) == 1 and k_cache.stride(1) == d and v_cache.stride() == k_cache.stride()
         f32 = self._torch.float32
-        assert out.is_contiguous() and out.dtype == f32 and out.shape == q.shape
+        assert out is None or (out.is_contiguous() and out.dtype == f32 and out.shape == q.shape)
         assert out_lse.is_contiguous() and out_lse.dtype == f32 and out_lse.shape == q.shape[:2]
         assert workspace.is_contiguous() and workspace.element_size() == 1
         rc = self._lib.laserkv_attend_cache(

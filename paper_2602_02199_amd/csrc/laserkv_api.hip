@@ -718,9 +718,12 @@ int64_t laserkv_attend_workspace_bytes(const laserkv_ctx* ctx, int32_t n_q, int6
   if (!ctx || n_q < 1 || n_q > ctx->cfg.max_window || cache_len < 0 ||
       cache_len * ctx->cfg.head_dim * ctx->elem_size >= (int64_t(1) << 31))
     return -1;
-  lkv::AttendPlan plan;
+  lkv::AttendPlan plan, lplan;
   lkv::attend_plan(ctx->group * n_q, cache_len, ctx->cfg.n_kv_heads, ctx->n_cu, &plan);
-  return (int64_t)lkv::attend_workspace_bytes(plan, ctx->group * n_q, ctx->cfg.n_kv_heads, ctx->cfg.head_dim);
+  lkv::attend_lse_plan(ctx->group * n_q, cache_len, ctx->cfg.n_kv_heads, ctx->n_cu, &lplan);
+  const size_t full = lkv::attend_workspace_bytes(plan, ctx->group * n_q, ctx->cfg.n_kv_heads, ctx->cfg.head_dim);
+  const size_t lse_only = (size_t)ctx->cfg.n_kv_heads * lplan.n_parts * ctx->group * n_q * 8 + 256;
+  return (int64_t)std::max(full, lse_only);  // enough for the call with or without `out`
 }
 
 int laserkv_attend_cache(laserkv_ctx* ctx,
@@ -732,11 +735,12 @@ int laserkv_attend_cache(laserkv_ctx* ctx,
   if (!ctx) return fail(nullptr, LKV_EINVAL, "attend_cache: null context");
   const laserkv_config& c = ctx->cfg;
   const int es = ctx->elem_size, d = c.head_dim;
-  if (!q || !out || !out_lse || !workspace) return fail(ctx, LKV_EINVAL, "attend_cache: null tensor");
+  if (!q || !out_lse || !workspace) return fail(ctx, LKV_EINVAL, "attend_cache: null tensor");
+  const bool lse_only = out == nullptr;  // the normaliser alone: no values read, no output written
   if (n_q < 1 || n_q > c.max_window) return fail(ctx, LKV_EINVAL, "attend_cache: n_q must be 1..max_window (%d)", c.max_window);
   if (cache_len < 0 || cache_len * d * es >= (int64_t(1) << 31))
     return fail(ctx, LKV_EINVAL, "attend_cache: cache_len must be >= 0 with cache_len * d * elem size < 2^31");
-  if (cache_len > 0 && (!k_cache || !v_cache)) return fail(ctx, LKV_EINVAL, "attend_cache: null cache");
+  if (cache_len > 0 && (!k_cache || (!v_cache && !lse_only))) return fail(ctx, LKV_EINVAL, "attend_cache: null cache");
   if (q_stride_tok < d || q_stride_head < 0 || ((q_stride_tok * es) & 15) || ((q_stride_head * es) & 15))
     return fail(ctx, LKV_EINVAL, "attend_cache: query strides must cover a row and keep rows 16-byte aligned");
   if (cache_stride_head < cache_len * d || ((cache_stride_head * es) & 15))
@@ -746,8 +750,10 @@ int laserkv_attend_cache(laserkv_ctx* ctx,
     return fail(ctx, LKV_EINVAL, "attend_cache: tensors must be 16-byte aligned (out_lse 4, workspace 256)");
   const int m_rows = ctx->group * n_q;
   lkv::AttendPlan plan;
-  lkv::attend_plan(m_rows, cache_len, c.n_kv_heads, ctx->n_cu, &plan);
-  const size_t need = lkv::attend_workspace_bytes(plan, m_rows, c.n_kv_heads, d);
+  if (lse_only) lkv::attend_lse_plan(m_rows, cache_len, c.n_kv_heads, ctx->n_cu, &plan);
+  else lkv::attend_plan(m_rows, cache_len, c.n_kv_heads, ctx->n_cu, &plan);
+  const size_t need = lse_only ? (size_t)c.n_kv_heads * plan.n_parts * m_rows * 8 + 256
+                               : lkv::attend_workspace_bytes(plan, m_rows, c.n_kv_heads, d);
   if (workspace_bytes < (int64_t)need)
     return fail(ctx, LKV_EINVAL, "attend_cache: workspace of %lld bytes, %zu needed", (long long)workspace_bytes, need);
   lkv::AttendParams p = {};
@@ -769,12 +775,15 @@ int laserkv_attend_cache(laserkv_ctx* ctx,
   p.n_kv_heads = c.n_kv_heads;
   p.scale2 = (float)(1.4426950408889634 / sqrt((double)d));
   const size_t rows = (size_t)c.n_kv_heads * plan.n_parts * m_rows;
-  p.part_o = reinterpret_cast<float*>(workspace);
-  p.part_ml = reinterpret_cast<float2*>(reinterpret_cast<char*>(workspace) + ((rows * d * 4 + 255) & ~(size_t)255));
+  p.part_o = lse_only ? nullptr : reinterpret_cast<float*>(workspace);
+  p.part_ml = lse_only ? reinterpret_cast<float2*>(workspace)
+                       : reinterpret_cast<float2*>(reinterpret_cast<char*>(workspace) + ((rows * d * 4 + 255) & ~(size_t)255));
   p.out = out;
   p.out_lse = out_lse;
   hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
-  hipError_t e = timed(ctx, LKV_KERN_ATTEND, st, [&] { return lkv::launch_attend((int)c.dtype, d, p, st); });
+  hipError_t e = timed(ctx, LKV_KERN_ATTEND, st, [&] {
+    return lse_only ? lkv::launch_attend_lse((int)c.dtype, d, p, st) : lkv::launch_attend((int)c.dtype, d, p, st);
+  });
   if (e != hipSuccess) return fail_hip(ctx, e, "attend_cache: kernels");
   return LKV_OK;
 }

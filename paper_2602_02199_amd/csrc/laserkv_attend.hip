@@ -7,6 +7,7 @@
 //                          one partial per (split, wave share)                                       [MFMA]
 //   attend_combine_kernel  merges the partials of a row through their references and writes the output and
 //                          the natural-log normaliser, the number laserkv_set_row_lse takes
+//   attend_lse_kernel (+ attend_lse_combine_kernel)  the normaliser alone, for callers that want nothing else
 #include "laserkv_device.h"
 #include "laserkv_kernels.h"
 
@@ -324,6 +325,130 @@ __global__ __launch_bounds__((D / 4) * COMB_SLICES) void attend_combine_kernel(A
   if (d4 == 0) p.out_lse[row_lin] = lt > 0.0f ? (mt + fast_log2(lt)) * 0.6931471805599453f : -__builtin_inff();
 }
 
+// ---------------------------------------------------------------------------------------------
+// The normaliser alone (out == null): log sum_i exp(q.k_i / sqrt(d)) of every query over the cache, which is
+// all laserkv_set_row_lse needs.  No values are read, no output accumulators are kept, so 16 waves of 32
+// rows each share a workgroup (512 rows: a GQA group's whole window reads the keys once).  Workgroup = (key
+// split, group of 512 rows, KV head).  Keys pass through two LDS buffers in chunks (the next chunk's loads are
+// issued before the current one is worked on and stored after it: one barrier per chunk).  K Q^T with the
+// keys as the A operand puts a query row in a lane: each lane keeps (reference, sum of 2^(x - reference))
+// over its keys, the reference following the running maximum.
+// ---------------------------------------------------------------------------------------------
+constexpr int LSE_WAVES = 16;
+constexpr int LSE_THREADS = LSE_WAVES * 64;
+constexpr int LSE_ROWS = 32 * LSE_WAVES;
+
+template <int DT>
+__host__ __device__ constexpr int lse_chunk_keys() { return DT == DT_BF16 ? 256 : 128; }
+
+template <int DT, int D>
+__global__ __launch_bounds__(LSE_THREADS) void attend_lse_kernel(AttendParams p) {
+  constexpr int ES = DT == DT_BF16 ? 2 : 4;
+  constexpr int CH = D * ES / 16;
+  constexpr int NCH = CH / 2;
+  constexpr int CHP = CH + 1;
+  constexpr int KC = lse_chunk_keys<DT>();
+  constexpr int KL = KC * CH / LSE_THREADS;
+  constexpr int TPC = KC / 32;
+  constexpr int ROWS_PER_LOAD = LSE_THREADS / CH;
+  static_assert(KL >= 1 && KL * LSE_THREADS == KC * CH, "chunk not a whole number of loads per thread");
+
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, rl = lane & 31, kg = lane >> 5;
+  const int split = blockIdx.x, rg = blockIdx.y, h = blockIdx.z;
+  const int k_lo = split * p.keys_per_split;
+  const int k_hi = min(k_lo + p.keys_per_split, p.cache_len);
+  const int row = rg * LSE_ROWS + wave * 32 + rl;
+
+  extern __shared__ uint4 smem[];  // two key buffers [KC][CHP]
+
+  uint4 a[NCH];
+  {
+    const int m = min(row, p.m_rows - 1);
+    const int g = (int)__umulhi((uint32_t)m, p.nq_magic), j = m - g * p.n_q;
+    const char* ptr = p.q.base + (int64_t)(h * p.group + g) * p.q.stride_head + (int64_t)j * p.q.stride_row;
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) a[i] = ld16(ptr + (2 * i + kg) * 16);
+  }
+  const __amdgpu_buffer_rsrc_t ksrd =
+      make_srd(p.k_cache + (int64_t)h * p.cache_stride_head, (uint32_t)p.cache_len * (uint32_t)p.row_bytes);
+  const uint32_t k_row = tid / CH, k_col = tid % CH;
+  uint4 kpre[KL];
+  auto prefetch = [&](int kc0) {
+#pragma unroll
+    for (int u = 0; u < KL; ++u)
+      kpre[u] = buf_ld16(ksrd, (uint32_t)(kc0 + k_row + u * ROWS_PER_LOAD) * (uint32_t)p.row_bytes + k_col * 16);
+  };
+  auto store = [&](uint4* buf) {
+#pragma unroll
+    for (int u = 0; u < KL; ++u) buf[(k_row + u * ROWS_PER_LOAD) * CHP + k_col] = kpre[u];
+  };
+
+  float ref = NEG_BIG, sum = 0.0f;
+  prefetch(k_lo);
+  store(smem);
+  lds_barrier();
+  int cur = 0;
+  for (int kc0 = k_lo; kc0 < k_hi; kc0 += KC) {
+    const bool more = kc0 + KC < k_hi;
+    if (more) prefetch(kc0 + KC);
+    const uint4* sK = smem + (size_t)cur * KC * CHP;
+#pragma unroll 1
+    for (int nt = 0; nt < TPC; ++nt) {
+      const int kbase = kc0 + nt * 32;
+      if (kbase >= k_hi) break;  // workgroup-uniform
+      f32x16 acc;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
+      const uint4* krow = sK + (size_t)(nt * 32 + rl) * CHP + kg;
+#pragma unroll
+      for (int i = 0; i < NCH; ++i) Mma<DT>::run(acc, krow[2 * i], a[i]);
+      const int n_vis = k_hi - kbase;  // keys of this tile inside the split (>= 32: all)
+      if (n_vis >= 32) {
+        float mx = acc[0];
+#pragma unroll
+        for (int r = 1; r < 16; ++r) mx = fmaxf(mx, acc[r]);
+        const float nref = fmaxf(ref, mx * p.scale2);  // scale2 > 0
+        sum *= fast_exp2(ref - nref);
+        ref = nref;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) sum += fast_exp2(fmaf(acc[r], p.scale2, -ref));
+      } else if (acc_row(0, kg) < n_vis) {  // the split's last tile: a lane that sees none of its keys keeps its state
+        float mx = acc[0];
+#pragma unroll
+        for (int r = 1; r < 16; ++r) mx = acc_row(r, kg) < n_vis ? fmaxf(mx, acc[r]) : mx;
+        const float nref = fmaxf(ref, mx * p.scale2);
+        sum *= fast_exp2(ref - nref);
+        ref = nref;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) sum += acc_row(r, kg) < n_vis ? fast_exp2(fmaf(acc[r], p.scale2, -ref)) : 0.0f;
+      }
+    }
+    if (more) store(smem + (size_t)(cur ^ 1) * KC * CHP);
+    cur ^= 1;
+    lds_barrier();
+  }
+  lse_merge(ref, sum, __shfl_xor(ref, 32), __shfl_xor(sum, 32));  // the two halves hold the same rows over different keys
+  if (kg == 0 && row < p.m_rows) p.part_ml[((size_t)h * p.n_parts + split) * p.m_rows + row] = make_float2(ref, sum);
+}
+
+// lse = (M + log2 sum_p l_p 2^(m_p - M)) ln 2 per row; -inf without any partial (empty cache)
+__global__ __launch_bounds__(256) void attend_lse_combine_kernel(AttendParams p) {
+  const int row_lin = blockIdx.x * 256 + threadIdx.x;
+  if (row_lin >= p.n_kv_heads * p.m_rows) return;
+  const int h = row_lin / p.m_rows, m = row_lin - h * p.m_rows;
+  const float2* ml = p.part_ml + (size_t)h * p.n_parts * p.m_rows + m;
+  float mx = NEG_BIG;
+#pragma unroll 8
+  for (int q = 0; q < p.n_parts; ++q) mx = fmaxf(mx, ml[(size_t)q * p.m_rows].x);
+  float l = 0.0f;
+#pragma unroll 8
+  for (int q = 0; q < p.n_parts; ++q) {
+    const float2 v = ml[(size_t)q * p.m_rows];
+    l = fmaf(v.y, fast_exp2(v.x - mx), l);
+  }
+  p.out_lse[row_lin] = l > 0.0f ? (mx + fast_log2(l)) * 0.6931471805599453f : -__builtin_inff();
+}
+
 // ---- host side ----
 void attend_plan(int m_rows, int64_t cache_len, int n_kv_heads, int n_cu, AttendPlan* plan) {
   const int n_qg = (m_rows + ATT_ROWS - 1) / ATT_ROWS;
@@ -337,6 +462,20 @@ void attend_plan(int m_rows, int64_t cache_len, int n_kv_heads, int n_cu, Attend
   n_splits = cache_len > 0 ? (int)((cache_len + kps - 1) / kps) : 0;
   plan->n_qgroups = n_qg;
   plan->wprt_log = wprt_log;
+  plan->n_splits = n_splits;
+  plan->keys_per_split = (int)kps;
+  plan->n_parts = n_splits;
+}
+
+void attend_lse_plan(int m_rows, int64_t cache_len, int n_kv_heads, int n_cu, AttendPlan* plan) {
+  const int n_rg = (m_rows + LSE_ROWS - 1) / LSE_ROWS;
+  int n_splits = n_cu / (n_kv_heads * n_rg);
+  n_splits = max(1, min(n_splits, ATT_MAX_SPLITS));
+  int64_t kps = (cache_len + n_splits - 1) / n_splits;
+  kps = max((int64_t)32, (kps + 31) / 32 * 32);
+  n_splits = cache_len > 0 ? (int)((cache_len + kps - 1) / kps) : 0;
+  plan->n_qgroups = n_rg;
+  plan->wprt_log = 0;
   plan->n_splits = n_splits;
   plan->keys_per_split = (int)kps;
   plan->n_parts = n_splits;
@@ -364,6 +503,29 @@ static hipError_t launch_attend_t(const AttendParams& p, hipStream_t st) {
   return hipGetLastError();
 }
 
+template <int DT, int D>
+static hipError_t launch_attend_lse_t(const AttendParams& p, hipStream_t st) {
+  constexpr int ES = DT == DT_BF16 ? 2 : 4;
+  constexpr size_t lds = (size_t)2 * lse_chunk_keys<DT>() * (D * ES / 16 + 1) * 16;
+  static_assert(lds <= 160 * 1024, "two key chunks do not fit the LDS");
+  if (p.n_splits > 0) {
+    hipLaunchKernelGGL((attend_lse_kernel<DT, D>), dim3(p.n_splits, p.n_qgroups, p.n_kv_heads), dim3(LSE_THREADS), lds, st, p);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
+  const int n_rows = p.n_kv_heads * p.m_rows;
+  hipLaunchKernelGGL(attend_lse_combine_kernel, dim3((n_rows + 255) / 256), dim3(256), 0, st, p);
+  return hipGetLastError();
+}
+
+hipError_t launch_attend_lse(int dtype, int head_dim, const AttendParams& p, hipStream_t st) {
+  if (dtype == DT_BF16 && head_dim == 128) return launch_attend_lse_t<DT_BF16, 128>(p, st);
+  if (dtype == DT_BF16 && head_dim == 64) return launch_attend_lse_t<DT_BF16, 64>(p, st);
+  if (dtype == DT_F32 && head_dim == 128) return launch_attend_lse_t<DT_F32, 128>(p, st);
+  if (dtype == DT_F32 && head_dim == 64) return launch_attend_lse_t<DT_F32, 64>(p, st);
+  return hipErrorInvalidValue;
+}
+
 hipError_t launch_attend(int dtype, int head_dim, const AttendParams& p, hipStream_t st) {
   if (dtype == DT_BF16 && head_dim == 128) return launch_attend_t<DT_BF16, 128>(p, st);
   if (dtype == DT_BF16 && head_dim == 64) return launch_attend_t<DT_BF16, 64>(p, st);
@@ -374,7 +536,10 @@ hipError_t launch_attend(int dtype, int head_dim, const AttendParams& p, hipStre
 
 template <int DT, int D>
 static hipError_t attend_attr() {
-  return hipFuncSetAttribute(reinterpret_cast<const void*>(&attend_kernel<DT, D>), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attend_kernel<DT, D>), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+  if (e == hipSuccess)
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attend_lse_kernel<DT, D>), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+  return e;
 }
 
 hipError_t init_attend_attributes() {

@@ -181,6 +181,9 @@ struct AttendPlan {
 void attend_plan(int m_rows, int64_t cache_len, int n_kv_heads, int n_cu, AttendPlan* plan);
 size_t attend_workspace_bytes(const AttendPlan& plan, int m_rows, int n_kv_heads, int head_dim);  // part_o, then part_ml
 hipError_t launch_attend(int dtype, int head_dim, const AttendParams& p, hipStream_t st);
+// the normaliser alone (out unused): 512 rows per workgroup, keys only
+void attend_lse_plan(int m_rows, int64_t cache_len, int n_kv_heads, int n_cu, AttendPlan* plan);
+hipError_t launch_attend_lse(int dtype, int head_dim, const AttendParams& p, hipStream_t st);
 hipError_t init_attend_attributes();
 
 hipError_t launch_sweep1(int dtype, int head_dim, const PassParams& p, hipStream_t st);
