@@ -109,7 +109,7 @@ __global__ __launch_bounds__(ATT_THREADS) void attend_kernel(AttendParams p) {
   uint4 a[NCH];
   {
     const int m = min(row, p.m_rows - 1);
-    const int g = (int)__umulhi((uint32_t)m, p.nq_magic), j = m - g * p.n_q;
+    const int g = div_w(m, p.nq_magic), j = m - g * p.n_q;
     const char* ptr = p.q.base + (int64_t)(h * p.group + g) * p.q.stride_head + (int64_t)j * p.q.stride_row;
 #pragma unroll
     for (int i = 0; i < NCH; ++i) a[i] = ld16(ptr + (2 * i + kg) * 16);
@@ -364,7 +364,7 @@ __global__ __launch_bounds__(LSE_THREADS) void attend_lse_kernel(AttendParams p)
   uint4 a[NCH];
   {
     const int m = min(row, p.m_rows - 1);
-    const int g = (int)__umulhi((uint32_t)m, p.nq_magic), j = m - g * p.n_q;
+    const int g = div_w(m, p.nq_magic), j = m - g * p.n_q;
     const char* ptr = p.q.base + (int64_t)(h * p.group + g) * p.q.stride_head + (int64_t)j * p.q.stride_row;
 #pragma unroll
     for (int i = 0; i < NCH; ++i) a[i] = ld16(ptr + (2 * i + kg) * 16);

@@ -22,7 +22,7 @@ struct PassParams {
                    // sits at q.base + (h*G*W + m) * q.stride_row
   int group;       // G
   int w;           // W
-  uint32_t w_magic;  // ceil(2^32 / W): row / W == umulhi(row, w_magic) for row <= 1024
+  uint32_t w_magic;  // ceil(2^32 / W) (0 for W == 1): row / W for row <= 1024, see div_w
   int m_rows;      // M = G * W
   int s_t;         // S
   int t_ctx;       // T
@@ -156,7 +156,7 @@ hipError_t init_single_attributes();
 struct AttendParams {
   RowSrc q;            // [H_q, n_q, d]
   int group, n_q;
-  uint32_t nq_magic;   // ceil(2^32 / n_q): row / n_q == umulhi(row, nq_magic) for row <= 1024
+  uint32_t nq_magic;   // ceil(2^32 / n_q) (0 for n_q == 1): row / n_q for row <= 1024, see div_w
   int m_rows;          // M = G * n_q rows per KV head, row m = g * n_q + j
   const char* k_cache; // [H_kv, cap, d] rows contiguous
   const char* v_cache;

@@ -136,6 +136,20 @@ def test_attend_cache_strided_queries_and_repeat():
     lib.close()
 
 
+def test_attend_cache_single_query_with_padded_head_stride():
+    """Decode shape (one query per head) whose query heads are not contiguous: row index / n_q with n_q = 1."""
+    h_q, h_kv, d, cap, n = 12, 3, 64, 500, 431
+    q, k, v = make_inputs(h_q, h_kv, d, 1, cap, "f32", seed=91)
+    wide = torch.zeros(h_q, 3, d, dtype=torch.float32, device=DEV)
+    wide[:, 1:2] = q.to(DEV)
+    lib = binding.LaserKV(h_q, h_kv, d, "f32", 8, 8, max_block=256, max_window=32, max_ctx_keys=0)
+    out, lse = run_attend(lib, wide[:, 1:2], k.to(DEV), v.to(DEV), n)
+    compare(out, lse, q, k, v, n, "f32", "single-query-padded")
+    _, lse2 = run_attend(lib, wide[:, 1:2], k.to(DEV), v.to(DEV), n, lse_only=True)
+    compare_lse_only(lse2, q, k, v, n, "single-query-padded")
+    lib.close()
+
+
 def test_attend_cache_error_paths():
     lib = binding.LaserKV(8, 2, 128, "bf16", 8, 8, max_block=256, max_window=16, max_ctx_keys=0)
     q, k, v = (t.to(DEV) for t in make_inputs(8, 2, 128, 4, 64, "bf16", seed=3))

@@ -623,11 +623,12 @@ def test_layers_with_their_own_budgets_share_one_context():
         say(f"[per-layer budget] layer {layer} B={B} parts={parts}: {nb} blocks match the oracle")
 
 
-@pytest.mark.parametrize("dtype", ["bf16", "f32"])
-def test_padded_query_and_key_strides(dtype):
+@pytest.mark.parametrize("dtype,window", [("bf16", 40), ("f32", 40), ("bf16", 1)])
+def test_padded_query_and_key_strides(dtype, window):
     """Window queries whose head stride is not W rows (a slice of a longer tensor) and keys whose row stride
-    exceeds head_dim (a slice of a wider tensor): the general addressing paths of the sweeps' load phase."""
-    wl = synth.shrink(synth.WORKLOADS["llama8b-16k"], index=25, l_ctx=2048, s_block=1024, dtype=dtype, window=40)
+    exceeds head_dim (a slice of a wider tensor): the general addressing paths of the sweeps' load phase.
+    A window of one query exercises row / W with W = 1."""
+    wl = synth.shrink(synth.WORKLOADS["llama8b-16k"], index=25, l_ctx=2048, s_block=1024, dtype=dtype, window=window)
     B = O.budget(wl.s_block, wl.l_ctx, wl.r_num, wl.r_den)
     parts = O.partition(B, wl.n_div, wl.alpha, wl.s_block)
     data = synth.make_layer(wl, 0, parts[0], n_blocks=1)
