@@ -146,3 +146,49 @@ def test_single_sweep_graph_replays_on_changing_inputs():
             assert torch.equal(kc[:, :B].cpu(), eager[t][1]), f"replay round {rnd} block {t}: cache rows differ"
     lib.laserkv_set_row_lse_complete(None)
     lib.close()
+
+
+def test_single_sweep_counts_equal_the_two_sweep_route_over_many_launches(monkeypatch):
+    """The collision counts of the one-sweep route depend on histograms that other workgroups publish during the
+    same launch.  Sixteen blocks of four layers, each launched five times in a row through one context, must give
+    the counts, codes and kept sets of the two-sweep route (whose histograms cross a kernel boundary) every time."""
+    wl = synth.shrink(synth.WORKLOADS["llama8b-128k"], index=31, l_ctx=16384)
+    B = O.budget(wl.s_block, wl.l_ctx, wl.r_num, wl.r_den)
+    parts = O.partition(B, wl.n_div, wl.alpha, wl.s_block)
+    na, nl, ke, kl = parts
+    s, d, w = wl.s_block, wl.head_dim, wl.window
+    monkeypatch.setenv("LASERKV_SINGLE_SPIN", "-1")
+    two = binding.LaserKV(wl.n_q_heads, wl.n_kv_heads, d, wl.dtype, wl.lsh_tables, wl.lsh_bits, max_block=s, max_window=w,
+                          max_ctx_keys=0)
+    monkeypatch.delenv("LASERKV_SINGLE_SPIN")
+    one = binding.LaserKV(wl.n_q_heads, wl.n_kv_heads, d, wl.dtype, wl.lsh_tables, wl.lsh_bits, max_block=s, max_window=w,
+                          max_ctx_keys=0)
+    n_checked = 0
+    for layer in range(4):
+        data = synth.make_layer(wl, layer, na, n_blocks=4)
+        dev = to_dev(data)
+        for t in range(4):
+            lo = t * s
+            lse = complete_row_lse(data["q_win"][t], data["k"][:, lo:lo + s], None, s - w, d).to(DEV)
+            res = []
+            for lib, reps in ((two, 1), (one, 5)):
+                lib.laserkv_set_row_lse_complete(lse)
+                for _ in range(reps):
+                    dbg = dbg_buffers(wl, s)
+                    keep = torch.empty(wl.n_kv_heads, sum(parts), dtype=torch.int32, device=DEV)
+                    lib.laserkv_select_block(dev["q_win"][t], dev["k"][:, lo:lo + s], None, dev["planes"], block_pos0=lo,
+                                             n_anchor=na, n_local=nl, k_exact=ke, k_lsh=kl, keep_idx=keep,
+                                             dbg_s_exact=dbg["s_exact"], dbg_sig_k=dbg["sig_k"], dbg_sig_q=dbg["sig_q"],
+                                             dbg_count=dbg["cnt"])
+                    res.append(gpu_stage(dbg, keep))
+            torch.cuda.synchronize()
+            ref = res[0]
+            for i, r in enumerate(res[1:]):
+                for key in ("cnt", "sig_k", "sig_q"):
+                    assert np.array_equal(ref[key], r[key]), f"layer {layer} block {t} launch {i}: {key} differs"
+                assert np.array_equal(res[1]["keep"], r["keep"]) and np.array_equal(res[1]["s_exact"], r["s_exact"])
+                n_checked += 1
+    say(f"[single] {n_checked} launches checked against the two-sweep route")
+    for lib in (one, two):
+        lib.laserkv_set_row_lse_complete(None)
+        lib.close()
