@@ -292,6 +292,50 @@ def attend_cache(q, cache_k, cache_v, cache_len: int):
     return out, lse
 
 
+def attend_block(q, cache_k, cache_v, cache_len: int, k_blk, v_blk, block_pos0=0, q_pos0=None, causal=True):
+    """The block's own prefill attention: every query over the compacted cache followed by the block's keys.
+
+    q [H_q, n_q, d] are queries at absolute positions q_pos0 + j (default: the block's last n_q tokens);
+    cache_k / cache_v [H_kv, cap, d], the first cache_len rows of which are earlier blocks' kept tokens, all
+    visible (Sec. 3 first paragraph: only the kept tokens remain for later tokens to attend to); k_blk / v_blk
+    [H_kv, S_t, d] the current block at absolute positions block_pos0 + i, key i visible to query j iff
+    block_pos0 + i <= q_pos0 + j when causal.  One softmax per row over both segments:
+    out = sum_i p_i v_i, lse = log sum_i exp(l_i) over the visible keys (natural logarithm).  For the window
+    rows this lse is the complete normaliser of Alg. 1 step 3 (what exact_scores takes as row_lse_complete
+    when the look-back keys are inside the cache).  A row that sees no key gives zero and -inf.
+    Returns (out [H_q, n_q, d], lse [H_q, n_q]).
+    """
+    q = np.asarray(q, dtype=np.float64)
+    h_q, n_q, d = q.shape
+    k_blk = np.asarray(k_blk, dtype=np.float64)
+    v_blk = np.asarray(v_blk, dtype=np.float64)
+    h_kv, s_t, _ = k_blk.shape
+    assert h_q % h_kv == 0
+    g_sz = h_q // h_kv
+    if q_pos0 is None:
+        q_pos0 = block_pos0 + s_t - n_q
+    out = np.zeros((h_q, n_q, d), dtype=np.float64)
+    lse = np.full((h_q, n_q), -np.inf, dtype=np.float64)
+    key_pos = block_pos0 + np.arange(s_t)
+    for hq in range(h_q):
+        h = hq // g_sz
+        keys = np.concatenate([np.asarray(cache_k[h][:cache_len], dtype=np.float64).reshape(cache_len, d), k_blk[h]])
+        vals = np.concatenate([np.asarray(cache_v[h][:cache_len], dtype=np.float64).reshape(cache_len, d), v_blk[h]])
+        for j in range(n_q):
+            visible = np.ones(cache_len + s_t, dtype=bool)
+            if causal:
+                visible[cache_len:] = key_pos <= q_pos0 + j
+            if not visible.any():
+                continue
+            logits = (keys[visible] @ q[hq, j]) / np.sqrt(np.float64(d))
+            top = logits.max()
+            e = np.exp(logits - top)
+            denom = e.sum()
+            out[hq, j] = (e / denom) @ vals[visible]
+            lse[hq, j] = top + np.log(denom)
+    return out, lse
+
+
 # --------------------------------------------------------------------------
 # one block, one layer: the composition the C-ABI entry points implement
 # --------------------------------------------------------------------------
