@@ -206,7 +206,7 @@ int laserkv_set_row_lse(laserkv_ctx* ctx, const float* row_lse);
  * flash-attention forward reports for those rows.  S_exact[h, i] = mean over the rows of
  * exp(q.k_i / sqrt(d) - row_lse) at the visible keys.  The library then computes no row statistics, and
  * k_ctx / t_ctx of the following calls are accepted but not read.  Where the shape allows it (G * w <= 512,
- * rows of at most 256 bytes, query rows of a head contiguous, K such that L * 2^K 16-bit bins fit 512 KiB)
+ * rows of at most 256 bytes, the query heads of a KV head within 2 GiB, K such that L * 2^K 16-bit bins fit 512 KiB)
  * a block then takes ONE sweep over its keys (hash, score and count from the same LDS rows) instead of two;
  * otherwise the first of the two sweeps only hashes.
  *   row_lse  DEVICE [H_q, w] float, contiguous; NULL switches back to the library's own statistics.
@@ -239,6 +239,38 @@ int64_t laserkv_attend_workspace_bytes(const laserkv_ctx* ctx, int32_t n_q, int6
 int laserkv_attend_cache(laserkv_ctx* ctx,
                          const void* q, int64_t q_stride_head, int64_t q_stride_tok, int32_t n_q,
                          const void* k_cache, const void* v_cache, int64_t cache_stride_head, int64_t cache_len,
+                         float* out, float* out_lse,
+                         void* workspace, int64_t workspace_bytes,
+                         void* hip_stream);
+
+/* The block's own prefill attention (Sec. 3 first paragraph: block t attends to the kept tokens of the earlier
+ * blocks and, causally, to itself; Sec. 3.3 "Precision": the exact score is this attention's softmax).  Key
+ * order per KV head: the first cache_len cache rows, all visible, then the block's s_t keys, key i (absolute
+ * position block_pos0 + i) visible to query j (position q_pos0 + j) iff causal == 0 or block_pos0 + i <=
+ * q_pos0 + j.  One softmax per query over both segments: out = sum_i p_i v_i, out_lse = log sum_i exp(q.k_i /
+ * sqrt(d)) over the visible keys.  For the window rows out_lse is the COMPLETE statistic that
+ * laserkv_set_row_lse_complete takes (call this with the window rows alone, or copy the rows of a whole-block
+ * call into a contiguous [H_q, w] tensor): selection then takes one sweep over the block and reads no row
+ * statistics of its own.  A query that sees no key gets zero and -inf.
+ *   q          DEVICE [H_q, n_q, d], strides in elements, d contiguous, rows 16-byte aligned; 1 <= n_q <= max_block
+ *   k_cache, v_cache, cache_stride_head, cache_len   as for laserkv_attend_cache
+ *   k_blk, v_blk  DEVICE [H_kv, s_t, d], strides in elements, d contiguous, rows 16-byte aligned;
+ *              0 <= s_t <= max_block (0: attention over the cache alone), (s_t + 256) * token stride * elem size < 2^31
+ *   out        DEVICE [H_q, n_q, d] float, contiguous, 16-byte aligned (required)
+ *   out_lse    DEVICE [H_q, n_q] float, contiguous
+ *   workspace  DEVICE scratch of at least laserkv_attend_block_workspace_bytes(ctx, n_q, cache_len, s_t) bytes,
+ *              256-byte aligned (256 bytes when a workgroup sees all keys of its rows: the kernel then writes
+ *              the result itself; otherwise partial results of the key splits)
+ * The call allocates nothing and is asynchronous on hip_stream.  Errors: LKV_EINVAL (null / misaligned tensor,
+ * sizes out of range, workspace too small), LKV_EHIP.  laserkv_attend_block_workspace_bytes returns -1 for
+ * arguments the call would reject. */
+int64_t laserkv_attend_block_workspace_bytes(const laserkv_ctx* ctx, int32_t n_q, int64_t cache_len, int32_t s_t);
+int laserkv_attend_block(laserkv_ctx* ctx,
+                         const void* q, int64_t q_stride_head, int64_t q_stride_tok, int32_t n_q,
+                         const void* k_cache, const void* v_cache, int64_t cache_stride_head, int64_t cache_len,
+                         const void* k_blk, int64_t k_stride_head, int64_t k_stride_tok,
+                         const void* v_blk, int64_t v_stride_head, int64_t v_stride_tok,
+                         int32_t s_t, int64_t block_pos0, int64_t q_pos0, int32_t causal,
                          float* out, float* out_lse,
                          void* workspace, int64_t workspace_bytes,
                          void* hip_stream);

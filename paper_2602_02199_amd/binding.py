@@ -23,6 +23,7 @@ EXPORTS = (
     "laserkv_profile_begin", "laserkv_profile_end", "laserkv_profile_isolate",
     "laserkv_score_block", "laserkv_select_consensus", "laserkv_append_shared", "laserkv_set_row_lse",
     "laserkv_set_row_lse_complete", "laserkv_attend_workspace_bytes", "laserkv_attend_cache",
+    "laserkv_attend_block_workspace_bytes", "laserkv_attend_block",
     "laserkv_static_init", "laserkv_static_workspace_bytes", "laserkv_compress_block_static",
 )
 LKV_STATIC_SCRATCH_BYTES = 32 << 20
@@ -101,6 +102,11 @@ def load():
     lib.laserkv_attend_workspace_bytes.restype = i64
     lib.laserkv_attend_cache.argtypes = [vp, vp, i64, i64, i32, vp, vp, i64, i64, vp, vp, vp, i64, vp]
     lib.laserkv_attend_cache.restype = C.c_int
+    lib.laserkv_attend_block_workspace_bytes.argtypes = [vp, i32, i64, i32]
+    lib.laserkv_attend_block_workspace_bytes.restype = i64
+    lib.laserkv_attend_block.argtypes = [vp, vp, i64, i64, i32, vp, vp, i64, i64, vp, i64, i64, vp, i64, i64,
+                                         i32, i64, i64, i32, vp, vp, vp, i64, vp]
+    lib.laserkv_attend_block.restype = C.c_int
     lib.laserkv_profile_begin.argtypes = [vp]
     lib.laserkv_profile_begin.restype = C.c_int
     lib.laserkv_profile_end.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(i64)]
@@ -326,6 +332,37 @@ class LaserKV:
         assert workspace.is_contiguous() and workspace.element_size() == 1
         rc = self._lib.laserkv_attend_cache(
             self._ctx, _ptr(q), qs[0], qs[1], q.shape[1], _ptr(k_cache), _ptr(v_cache), k_cache.stride(0), cache_len,
+            _ptr(out), _ptr(out_lse), _ptr(workspace), workspace.numel(), self._stream(stream))
+        self._check(rc)
+
+    def laserkv_attend_block_workspace_bytes(self, n_q, cache_len, s_t):
+        n = int(self._lib.laserkv_attend_block_workspace_bytes(self._ctx, n_q, cache_len, s_t))
+        if n < 0:
+            raise LaserKVError(LKV_EINVAL, "attend_block_workspace_bytes: n_q, cache_len or s_t out of range")
+        return n
+
+    def laserkv_attend_block(self, q, k_cache, v_cache, k_blk, v_blk, *, cache_len, block_pos0, q_pos0=None, causal=True,
+                             out, out_lse, workspace, stream=None):
+        """q [H_q, n_q, d]; k_cache / v_cache [H_kv, cap, d] (may be None with cache_len 0); k_blk / v_blk
+        [H_kv, s_t, d] (views with strides allowed); out float32 [H_q, n_q, d], out_lse float32 [H_q, n_q];
+        q_pos0 defaults to the block's last n_q positions;
+        workspace: uint8 device tensor of at least laserkv_attend_block_workspace_bytes(n_q, cache_len, s_t) bytes."""
+        d = self.cfg.head_dim
+        qs, ks, vs = _strides3(q, d), _strides3(k_blk, d), _strides3(v_blk, d)
+        s_t = k_blk.shape[1]
+        assert v_blk.shape == k_blk.shape
+        if k_cache is not None:
+            assert k_cache.stride(2) == 1 and k_cache.stride(1) == d and v_cache.stride() == k_cache.stride()
+        f32 = self._torch.float32
+        assert out.is_contiguous() and out.dtype == f32 and out.shape == q.shape
+        assert out_lse.is_contiguous() and out_lse.dtype == f32 and out_lse.shape == q.shape[:2]
+        assert workspace.is_contiguous() and workspace.element_size() == 1
+        if q_pos0 is None:
+            q_pos0 = block_pos0 + s_t - q.shape[1]
+        rc = self._lib.laserkv_attend_block(
+            self._ctx, _ptr(q), qs[0], qs[1], q.shape[1], _ptr(k_cache), _ptr(v_cache),
+            k_cache.stride(0) if k_cache is not None else 0, cache_len,
+            _ptr(k_blk), ks[0], ks[1], _ptr(v_blk), vs[0], vs[1], s_t, block_pos0, q_pos0, 1 if causal else 0,
             _ptr(out), _ptr(out_lse), _ptr(workspace), workspace.numel(), self._stream(stream))
         self._check(rc)
 

@@ -365,7 +365,7 @@ int select_impl(laserkv_ctx* ctx,
   sp.kb = {(const char*)k_blk, k_stride_head * es, k_stride_tok * es};
   sp.kc = {(const char*)k_ctx, c_stride_head * es, c_stride_tok * es};
   sp.planes = (const char*)hyperplanes;
-  sp.q_linear = (q_stride_head == (int64_t)w * q_stride_tok && (int64_t)G * w * q_stride_tok * es < (int64_t(1) << 31)) ? 1 : 0;
+  sp.q_linear = (q_stride_head >= (int64_t)w * q_stride_tok && (int64_t)G * q_stride_head * es < (int64_t(1) << 31)) ? 1 : 0;
   sp.group = G;
   sp.w = w;
   sp.m_rows = m_rows;
@@ -714,61 +714,98 @@ int laserkv_set_row_lse_complete(laserkv_ctx* ctx, const float* row_lse) {
   return LKV_OK;
 }
 
-int64_t laserkv_attend_workspace_bytes(const laserkv_ctx* ctx, int32_t n_q, int64_t cache_len) {
-  if (!ctx || n_q < 1 || n_q > ctx->cfg.max_window || cache_len < 0 ||
-      cache_len * ctx->cfg.head_dim * ctx->elem_size >= (int64_t(1) << 31))
-    return -1;
-  lkv::AttendPlan plan, lplan;
-  lkv::attend_plan(ctx->group * n_q, cache_len, ctx->cfg.n_kv_heads, ctx->n_cu, &plan);
-  lkv::attend_lse_plan(ctx->group * n_q, cache_len, ctx->cfg.n_kv_heads, ctx->n_cu, &lplan);
-  const size_t full = lkv::attend_workspace_bytes(plan, ctx->group * n_q, ctx->cfg.n_kv_heads, ctx->cfg.head_dim);
-  const size_t lse_only = (size_t)ctx->cfg.n_kv_heads * lplan.n_parts * ctx->group * n_q * 8 + 256;
-  return (int64_t)std::max(full, lse_only);  // enough for the call with or without `out`
+// Shared by laserkv_attend_cache (no block keys) and laserkv_attend_block.
+static bool attend_sizes_ok(const laserkv_ctx* ctx, int64_t n_q, int64_t n_q_max, int64_t cache_len, int64_t s_t) {
+  return ctx && n_q >= 1 && n_q <= n_q_max && cache_len >= 0 && s_t >= 0 && s_t <= ctx->cfg.max_block &&
+         cache_len * ctx->cfg.head_dim * ctx->elem_size < (int64_t(1) << 31);
 }
 
-int laserkv_attend_cache(laserkv_ctx* ctx,
-                         const void* q, int64_t q_stride_head, int64_t q_stride_tok, int32_t n_q,
-                         const void* k_cache, const void* v_cache, int64_t cache_stride_head, int64_t cache_len,
-                         float* out, float* out_lse,
-                         void* workspace, int64_t workspace_bytes,
-                         void* hip_stream) {
-  if (!ctx) return fail(nullptr, LKV_EINVAL, "attend_cache: null context");
+static int64_t attend_workspace_need(const laserkv_ctx* ctx, int n_q, int64_t cache_len, int s_t, bool with_lse_only) {
+  const int m_rows = ctx->group * n_q;
+  lkv::AttendPlan plan;
+  lkv::attend_plan(m_rows, cache_len, s_t, ctx->cfg.n_kv_heads, ctx->n_cu, &plan);
+  size_t need = lkv::attend_workspace_bytes(plan, m_rows, ctx->cfg.n_kv_heads, ctx->cfg.head_dim);
+  if (with_lse_only) {
+    lkv::AttendPlan lplan;
+    lkv::attend_lse_plan(m_rows, cache_len, ctx->cfg.n_kv_heads, ctx->n_cu, &lplan);
+    need = std::max(need, (size_t)ctx->cfg.n_kv_heads * lplan.n_parts * m_rows * 8 + 256);
+  }
+  return (int64_t)need;
+}
+
+int64_t laserkv_attend_workspace_bytes(const laserkv_ctx* ctx, int32_t n_q, int64_t cache_len) {
+  if (!ctx || !attend_sizes_ok(ctx, n_q, ctx->cfg.max_window, cache_len, 0)) return -1;
+  return attend_workspace_need(ctx, n_q, cache_len, 0, true);  // enough for the call with or without `out`
+}
+
+int64_t laserkv_attend_block_workspace_bytes(const laserkv_ctx* ctx, int32_t n_q, int64_t cache_len, int32_t s_t) {
+  if (!ctx || !attend_sizes_ok(ctx, n_q, ctx->cfg.max_block, cache_len, s_t)) return -1;
+  return attend_workspace_need(ctx, n_q, cache_len, s_t, false);
+}
+
+static int attend_impl(laserkv_ctx* ctx, const char* fn, int64_t n_q_max,
+                       const void* q, int64_t q_stride_head, int64_t q_stride_tok, int32_t n_q,
+                       const void* k_cache, const void* v_cache, int64_t cache_stride_head, int64_t cache_len,
+                       const void* k_blk, int64_t k_stride_head, int64_t k_stride_tok,
+                       const void* v_blk, int64_t v_stride_head, int64_t v_stride_tok,
+                       int32_t s_t, int64_t diag64,
+                       float* out, float* out_lse, bool lse_only,
+                       void* workspace, int64_t workspace_bytes, void* hip_stream) {
   const laserkv_config& c = ctx->cfg;
   const int es = ctx->elem_size, d = c.head_dim;
-  if (!q || !out_lse || !workspace) return fail(ctx, LKV_EINVAL, "attend_cache: null tensor");
-  const bool lse_only = out == nullptr;  // the normaliser alone: no values read, no output written
-  if (n_q < 1 || n_q > c.max_window) return fail(ctx, LKV_EINVAL, "attend_cache: n_q must be 1..max_window (%d)", c.max_window);
-  if (cache_len < 0 || cache_len * d * es >= (int64_t(1) << 31))
-    return fail(ctx, LKV_EINVAL, "attend_cache: cache_len must be >= 0 with cache_len * d * elem size < 2^31");
-  if (cache_len > 0 && (!k_cache || (!v_cache && !lse_only))) return fail(ctx, LKV_EINVAL, "attend_cache: null cache");
+  if (!q || !out_lse || !workspace) return fail(ctx, LKV_EINVAL, "%s: null tensor", fn);
+  if (!attend_sizes_ok(ctx, n_q, n_q_max, cache_len, s_t))
+    return fail(ctx, LKV_EINVAL, "%s: n_q must be 1..%lld, s_t 0..max_block (%d), cache_len >= 0 with cache_len * d * elem size < 2^31",
+                fn, (long long)n_q_max, c.max_block);
+  if (cache_len > 0 && (!k_cache || (!v_cache && !lse_only))) return fail(ctx, LKV_EINVAL, "%s: null cache", fn);
   if (q_stride_tok < d || q_stride_head < 0 || ((q_stride_tok * es) & 15) || ((q_stride_head * es) & 15))
-    return fail(ctx, LKV_EINVAL, "attend_cache: query strides must cover a row and keep rows 16-byte aligned");
+    return fail(ctx, LKV_EINVAL, "%s: query strides must cover a row and keep rows 16-byte aligned", fn);
   if (cache_stride_head < cache_len * d || ((cache_stride_head * es) & 15))
-    return fail(ctx, LKV_EINVAL, "attend_cache: cache head stride too small or misaligned");
+    return fail(ctx, LKV_EINVAL, "%s: cache head stride too small or misaligned", fn);
+  if (s_t > 0) {
+    if (!k_blk || !v_blk) return fail(ctx, LKV_EINVAL, "%s: null block tensor", fn);
+    if (k_stride_tok < d || v_stride_tok < d || k_stride_head < 0 || v_stride_head < 0 || ((k_stride_tok * es) & 15) ||
+        ((v_stride_tok * es) & 15) || ((k_stride_head * es) & 15) || ((v_stride_head * es) & 15))
+      return fail(ctx, LKV_EINVAL, "%s: block strides must cover a row and keep rows 16-byte aligned", fn);
+    // the kernels address rows up to a chunk past the block with 32-bit byte offsets
+    if (((int64_t)s_t + 256) * std::max(k_stride_tok, v_stride_tok) * es >= (int64_t(1) << 31))
+      return fail(ctx, LKV_EINVAL, "%s: (s_t + 256) * token stride * elem size must stay below 2^31", fn);
+    if (!aligned16(k_blk) || !aligned16(v_blk)) return fail(ctx, LKV_EINVAL, "%s: block tensors must be 16-byte aligned", fn);
+  }
   if (!aligned16(q) || !aligned16(k_cache) || !aligned16(v_cache) || !aligned16(out) ||
       (reinterpret_cast<uintptr_t>(out_lse) & 3u) || (reinterpret_cast<uintptr_t>(workspace) & 255u))
-    return fail(ctx, LKV_EINVAL, "attend_cache: tensors must be 16-byte aligned (out_lse 4, workspace 256)");
+    return fail(ctx, LKV_EINVAL, "%s: tensors must be 16-byte aligned (out_lse 4, workspace 256)", fn);
   const int m_rows = ctx->group * n_q;
   lkv::AttendPlan plan;
   if (lse_only) lkv::attend_lse_plan(m_rows, cache_len, c.n_kv_heads, ctx->n_cu, &plan);
-  else lkv::attend_plan(m_rows, cache_len, c.n_kv_heads, ctx->n_cu, &plan);
+  else lkv::attend_plan(m_rows, cache_len, s_t, c.n_kv_heads, ctx->n_cu, &plan);
   const size_t need = lse_only ? (size_t)c.n_kv_heads * plan.n_parts * m_rows * 8 + 256
                                : lkv::attend_workspace_bytes(plan, m_rows, c.n_kv_heads, d);
   if (workspace_bytes < (int64_t)need)
-    return fail(ctx, LKV_EINVAL, "attend_cache: workspace of %lld bytes, %zu needed", (long long)workspace_bytes, need);
+    return fail(ctx, LKV_EINVAL, "%s: workspace of %lld bytes, %zu needed", fn, (long long)workspace_bytes, need);
   lkv::AttendParams p = {};
   p.q = {(const char*)q, q_stride_head * es, q_stride_tok * es};
   p.group = ctx->group;
   p.n_q = n_q;
-  p.nq_magic = (uint32_t)(((uint64_t(1) << 32) + n_q - 1) / n_q);
+  p.nq_magic = n_q > 1 ? (uint32_t)(((uint64_t(1) << 32) + n_q - 1) / n_q) : 0u;
   p.m_rows = m_rows;
   p.k_cache = (const char*)k_cache;
   p.v_cache = (const char*)v_cache;
   p.cache_stride_head = cache_stride_head * es;
   p.row_bytes = d * es;
   p.cache_len = (int)cache_len;
+  p.k_blk = (const char*)k_blk;
+  p.v_blk = (const char*)v_blk;
+  p.kb_stride_head = k_stride_head * es;
+  p.vb_stride_head = v_stride_head * es;
+  p.kb_stride_row = (int)(k_stride_tok * es);
+  p.vb_stride_row = (int)(v_stride_tok * es);
+  p.s_t = s_t;
+  p.diag = (int)std::max<int64_t>(-(int64_t(1) << 30), std::min<int64_t>(diag64, int64_t(1) << 30));
   p.keys_per_split = plan.keys_per_split;
+  p.blk_keys_per_split = plan.blk_keys_per_split;
   p.n_splits = plan.n_splits;
+  p.direct = plan.direct;
   p.wprt_log = plan.wprt_log;
   p.n_parts = plan.n_parts;
   p.n_qgroups = plan.n_qgroups;
@@ -784,8 +821,38 @@ int laserkv_attend_cache(laserkv_ctx* ctx,
   hipError_t e = timed(ctx, LKV_KERN_ATTEND, st, [&] {
     return lse_only ? lkv::launch_attend_lse((int)c.dtype, d, p, st) : lkv::launch_attend((int)c.dtype, d, p, st);
   });
-  if (e != hipSuccess) return fail_hip(ctx, e, "attend_cache: kernels");
+  if (e != hipSuccess) return fail(ctx, LKV_EHIP, "%s: kernels: %s", fn, hipGetErrorString(e));
   return LKV_OK;
+}
+
+int laserkv_attend_cache(laserkv_ctx* ctx,
+                         const void* q, int64_t q_stride_head, int64_t q_stride_tok, int32_t n_q,
+                         const void* k_cache, const void* v_cache, int64_t cache_stride_head, int64_t cache_len,
+                         float* out, float* out_lse,
+                         void* workspace, int64_t workspace_bytes,
+                         void* hip_stream) {
+  if (!ctx) return fail(nullptr, LKV_EINVAL, "attend_cache: null context");
+  return attend_impl(ctx, "attend_cache", ctx->cfg.max_window, q, q_stride_head, q_stride_tok, n_q, k_cache, v_cache,
+                     cache_stride_head, cache_len, nullptr, 0, 0, nullptr, 0, 0, 0, 0, out, out_lse, out == nullptr,
+                     workspace, workspace_bytes, hip_stream);
+}
+
+int laserkv_attend_block(laserkv_ctx* ctx,
+                         const void* q, int64_t q_stride_head, int64_t q_stride_tok, int32_t n_q,
+                         const void* k_cache, const void* v_cache, int64_t cache_stride_head, int64_t cache_len,
+                         const void* k_blk, int64_t k_stride_head, int64_t k_stride_tok,
+                         const void* v_blk, int64_t v_stride_head, int64_t v_stride_tok,
+                         int32_t s_t, int64_t block_pos0, int64_t q_pos0, int32_t causal,
+                         float* out, float* out_lse,
+                         void* workspace, int64_t workspace_bytes,
+                         void* hip_stream) {
+  if (!ctx) return fail(nullptr, LKV_EINVAL, "attend_block: null context");
+  if (!out) return fail(ctx, LKV_EINVAL, "attend_block: null output");
+  // key i (position block_pos0 + i) is visible to query j (position q_pos0 + j) iff i <= q_pos0 - block_pos0 + j
+  const int64_t diag = causal ? q_pos0 - block_pos0 : (int64_t(1) << 30);
+  return attend_impl(ctx, "attend_block", ctx->cfg.max_block, q, q_stride_head, q_stride_tok, n_q, k_cache, v_cache,
+                     cache_stride_head, cache_len, k_blk, k_stride_head, k_stride_tok, v_blk, v_stride_head, v_stride_tok,
+                     s_t, diag, out, out_lse, false, workspace, workspace_bytes, hip_stream);
 }
 
 int laserkv_score_block(laserkv_ctx* ctx,

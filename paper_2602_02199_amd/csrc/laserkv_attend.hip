@@ -72,11 +72,14 @@ __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
   return __builtin_bit_cast(uint32_t, t);
 }
 
-// One pass over the split's keys.  S^T = K Q^T puts a query row in a lane (column rl of the tile; the two
+// One pass over the split's keys: its share of the cache rows, then its share of the block's own keys (none
+// for attention over the cache alone).  S^T = K Q^T puts a query row in a lane (column rl of the tile; the two
 // halves kg of the wave hold the same rows over different keys), so the softmax state is lane-private, and
 // the 16 accumulator registers are already the B operand of O^T += V^T P^T: register r of half kg is key
 // acc_row(r, kg), so a group of 8 (bf16) or 4 (f32) registers is one 16-byte operand chunk whose keys the A
 // operand matches by reading V^T at the same key offsets.  V is transposed in registers on its way into LDS.
+// Block key i is visible to query j iff i <= diag + j: chunks past the last row of the workgroup are never
+// loaded, tiles past the last row of the wave are skipped, tiles that cross a row's limit take a masked path.
 template <int DT, int D>
 __global__ __launch_bounds__(ATT_THREADS) void attend_kernel(AttendParams p) {
   constexpr int ES = DT == DT_BF16 ? 2 : 4;
@@ -94,9 +97,10 @@ __global__ __launch_bounds__(ATT_THREADS) void attend_kernel(AttendParams p) {
   constexpr int V_GROUPS_PER_LOAD = ATT_THREADS / (EPC * CH);
 
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, rl = lane & 31, kg = lane >> 5;
-  const int split = blockIdx.x, qg = blockIdx.y, h = blockIdx.z;
-  const int k_lo = split * p.keys_per_split;
-  const int k_hi = min(k_lo + p.keys_per_split, p.cache_len);
+  // consecutive indices stay on one XCD: the row groups and splits of a head share that XCD's L2
+  const int n_wg = gridDim.x;
+  const int idx = xcd_major(blockIdx.x, n_wg);
+  const int split = idx % p.n_splits, qg = (idx / p.n_splits) % p.n_qgroups, h = idx / (p.n_splits * p.n_qgroups);
   const int wprt = 1 << p.wprt_log;           // waves that share a row tile, over different key tiles
   const int rt = wave >> p.wprt_log, ks = wave & (wprt - 1);
   const int row = qg * ATT_ROWS + rt * 32 + rl;
@@ -107,28 +111,48 @@ __global__ __launch_bounds__(ATT_THREADS) void attend_kernel(AttendParams p) {
 
   // the wave's 32 query rows, as the B operand of S^T
   uint4 a[NCH];
+  int blk_end_lane;  // block keys [0, blk_end_lane) are visible to this lane's row
   {
     const int m = min(row, p.m_rows - 1);
-    const int g = div_w(m, p.nq_magic), j = m - g * p.n_q;
+    const int g = m / p.n_q, j = m - g * p.n_q;
     const char* ptr = p.q.base + (int64_t)(h * p.group + g) * p.q.stride_head + (int64_t)j * p.q.stride_row;
 #pragma unroll
     for (int i = 0; i < NCH; ++i) a[i] = ld16(ptr + (2 * i + kg) * 16);
+    blk_end_lane = max(0, min(p.s_t, p.diag + j + 1));
+  }
+  // key ranges of this split in the two segments; the block range ends where the last row of the workgroup
+  // stops seeing keys
+  const int lo0 = min(split * p.keys_per_split, p.cache_len), hi0 = min(lo0 + p.keys_per_split, p.cache_len);
+  int lo1 = 0, hi1 = 0;
+  if (p.s_t > 0) {
+    const int m0 = qg * ATT_ROWS, m1 = min(m0 + ATT_ROWS, p.m_rows) - 1;
+    const int g0 = m0 / p.n_q, g1 = m1 / p.n_q;
+    const int j_max = g0 == g1 ? m1 - g1 * p.n_q : p.n_q - 1;
+    const int wg_end = max(0, min(p.s_t, p.diag + j_max + 1));
+    lo1 = min(split * p.blk_keys_per_split, wg_end);
+    hi1 = min(lo1 + p.blk_keys_per_split, wg_end);
   }
 
-  const uint32_t cache_bytes = (uint32_t)p.cache_len * (uint32_t)p.row_bytes;
-  const __amdgpu_buffer_rsrc_t ksrd = make_srd(p.k_cache + (int64_t)h * p.cache_stride_head, cache_bytes);
-  const __amdgpu_buffer_rsrc_t vsrd = make_srd(p.v_cache + (int64_t)h * p.cache_stride_head, cache_bytes);
+  const __amdgpu_buffer_rsrc_t ksrd0 = make_srd(p.k_cache + (int64_t)h * p.cache_stride_head, (uint32_t)p.cache_len * (uint32_t)p.row_bytes);
+  const __amdgpu_buffer_rsrc_t vsrd0 = make_srd(p.v_cache + (int64_t)h * p.cache_stride_head, (uint32_t)p.cache_len * (uint32_t)p.row_bytes);
+  const uint32_t kb_bytes = p.s_t > 0 ? (uint32_t)(p.s_t - 1) * (uint32_t)p.kb_stride_row + (uint32_t)p.row_bytes : 0u;
+  const uint32_t vb_bytes = p.s_t > 0 ? (uint32_t)(p.s_t - 1) * (uint32_t)p.vb_stride_row + (uint32_t)p.row_bytes : 0u;
+  const __amdgpu_buffer_rsrc_t ksrd1 = make_srd(p.k_blk + (int64_t)h * p.kb_stride_head, kb_bytes);
+  const __amdgpu_buffer_rsrc_t vsrd1 = make_srd(p.v_blk + (int64_t)h * p.vb_stride_head, vb_bytes);
   // K: chunk tid % CH of row tid / CH (+ K_ROWS_PER_LOAD per load).  V: lane groups of EPC consecutive lanes
   // hold EPC consecutive keys at the same chunk, the shape the register transpose wants.
   const uint32_t k_row = tid / CH, k_col = tid % CH;
   const uint32_t v_i = tid % EPC, v_c = (tid / EPC) % CH, v_grp = tid / (EPC * CH);
   uint4 kpre[KL], vpre[KL];
-  auto prefetch = [&](int kc0) {
+  auto prefetch = [&](int seg, int kc0) {
+    const __amdgpu_buffer_rsrc_t ksrd = seg ? ksrd1 : ksrd0, vsrd = seg ? vsrd1 : vsrd0;
+    const uint32_t kstride = seg ? (uint32_t)p.kb_stride_row : (uint32_t)p.row_bytes;
+    const uint32_t vstride = seg ? (uint32_t)p.vb_stride_row : (uint32_t)p.row_bytes;
 #pragma unroll
     for (int u = 0; u < KL; ++u) {
-      kpre[u] = buf_ld16(ksrd, (uint32_t)(kc0 + k_row + u * K_ROWS_PER_LOAD) * (uint32_t)p.row_bytes + k_col * 16);
+      kpre[u] = buf_ld16(ksrd, (uint32_t)(kc0 + k_row + u * K_ROWS_PER_LOAD) * kstride + k_col * 16);
       const uint32_t key = (u * V_GROUPS_PER_LOAD + v_grp) * EPC + v_i;
-      vpre[u] = buf_ld16(vsrd, (uint32_t)(kc0 + key) * (uint32_t)p.row_bytes + v_c * 16);
+      vpre[u] = buf_ld16(vsrd, (uint32_t)(kc0 + key) * vstride + v_c * 16);
     }
   };
 
@@ -139,8 +163,11 @@ __global__ __launch_bounds__(ATT_THREADS) void attend_kernel(AttendParams p) {
 #pragma unroll
     for (int r = 0; r < 16; ++r) o[dt][r] = 0.0f;
 
-  prefetch(k_lo);
-  for (int kc0 = k_lo; kc0 < k_hi; kc0 += KC) {
+  int seg = lo0 < hi0 ? 0 : 1;
+  int kc0 = seg ? lo1 : lo0;
+  bool have = seg ? lo1 < hi1 : true;
+  if (have) prefetch(seg, kc0);
+  while (have) {
     lds_barrier();  // every wave has finished with the previous chunk
 #pragma unroll
     for (int u = 0; u < KL; ++u) {
@@ -149,20 +176,33 @@ __global__ __launch_bounds__(ATT_THREADS) void attend_kernel(AttendParams p) {
       // the lane now holds head-dimension index v_c * EPC + v_i for the group's EPC keys
       sVT[(v_c * EPC + v_i) * VTP + (u * V_GROUPS_PER_LOAD + v_grp)] = t;
     }
-    if (kc0 + KC < k_hi) prefetch(kc0 + KC);  // in flight while this chunk is worked on
+    // the chunk after this one: the next of the segment, else the first of the block's keys
+    int nseg = seg, nkc = kc0 + KC;
+    bool nhave = nkc < (seg ? hi1 : hi0);
+    if (!nhave && seg == 0 && lo1 < hi1) {
+      nseg = 1;
+      nkc = lo1;
+      nhave = true;
+    }
+    if (nhave) prefetch(nseg, nkc);  // in flight while this chunk is worked on
     lds_barrier();
 
+    const int k_hi = seg ? hi1 : hi0;
+    const int lane_end = seg ? min(hi1, blk_end_lane) : hi0;  // end of the keys of this segment the lane's row sees
 #pragma unroll 1
     for (int nt = ks; nt < TPC; nt += wprt) {
       const int kbase = kc0 + nt * 32;
       if (kbase >= k_hi) break;  // wave-uniform
+      const int n_vis = lane_end - kbase;  // keys of this tile the lane's row sees (>= 32: all)
+      if (!__any(n_vis > 0)) continue;     // the tile lies past the limit of every row of the wave
       f32x16 acc;
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
       const uint4* krow = sK + (size_t)(nt * 32 + rl) * CHP + kg;
 #pragma unroll
       for (int i = 0; i < NCH; ++i) Mma<DT>::run(acc, krow[2 * i], a[i]);
-      const int n_vis = k_hi - kbase;  // keys of this tile inside the split (>= 32: all)
+      // hidden keys (past the end of the split or past the row's causal limit) weigh nothing, and a row that
+      // sees no key of the tile keeps its state
       float mx = NEG_BIG;
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
@@ -180,9 +220,10 @@ __global__ __launch_bounds__(ATT_THREADS) void attend_kernel(AttendParams p) {
           for (int r = 0; r < 16; ++r) o[dt][r] *= alpha;
         m_ref = m_new;
       }
+      const float m_sub = n_vis > 0 ? m_ref : 0.0f;  // a row without a visible key: 2^(NEG_BIG - 0) = 0, not 2^0
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        acc[r] = fast_exp2(acc[r] - m_ref);
+        acc[r] = fast_exp2(acc[r] - m_sub);
         l_sum += acc[r];
       }
 #pragma unroll
@@ -211,9 +252,30 @@ __global__ __launch_bounds__(ATT_THREADS) void attend_kernel(AttendParams p) {
         }
       }
     }
+    seg = nseg;
+    kc0 = nkc;
+    have = nhave;
   }
 
   l_sum += __shfl_xor(l_sum, 32);
+  if (p.direct) {
+    // one split and a wave per row tile: the state is final.  out = O / l, lse = (m + log2 l) ln 2; a row that
+    // saw no key gives zero and -inf
+    if (row < p.m_rows) {
+      const size_t at = (size_t)h * p.m_rows + row;
+      const float inv = l_sum > 0.0f ? 1.0f / l_sum : 0.0f;
+      if (kg == 0) p.out_lse[at] = l_sum > 0.0f ? (m_ref + fast_log2(l_sum)) * 0.6931471805599453f : -__builtin_inff();
+      float* dst = p.out + at * D;
+#pragma unroll
+      for (int dt = 0; dt < NDT; ++dt)
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4)
+          st16_stream(dst + dt * 32 + 8 * q4 + 4 * kg,
+                      make_uint4(__float_as_uint(o[dt][4 * q4] * inv), __float_as_uint(o[dt][4 * q4 + 1] * inv),
+                                 __float_as_uint(o[dt][4 * q4 + 2] * inv), __float_as_uint(o[dt][4 * q4 + 3] * inv)));
+    }
+    return;
+  }
   if (p.wprt_log == 0) {
     // a wave owns its row tile: its state is the split's partial (reference, sum, unnormalised output)
     if (row < p.m_rows) {
@@ -450,21 +512,27 @@ __global__ __launch_bounds__(256) void attend_lse_combine_kernel(AttendParams p)
 }
 
 // ---- host side ----
-void attend_plan(int m_rows, int64_t cache_len, int n_kv_heads, int n_cu, AttendPlan* plan) {
+void attend_plan(int m_rows, int64_t cache_len, int s_t, int n_kv_heads, int n_cu, AttendPlan* plan) {
   const int n_qg = (m_rows + ATT_ROWS - 1) / ATT_ROWS;
   const int n_rt = (min(m_rows, ATT_ROWS) + 31) / 32;
   int rt_pow2 = 1, wprt_log = 3;
   while (rt_pow2 < n_rt) { rt_pow2 <<= 1; --wprt_log; }
   int n_splits = n_cu / (n_kv_heads * n_qg);
   n_splits = max(1, min(n_splits, ATT_MAX_SPLITS));
+  // every split takes a share of the cache rows and a share of the block's keys
   int64_t kps = (cache_len + n_splits - 1) / n_splits;
   kps = max((int64_t)32, (kps + 31) / 32 * 32);
-  n_splits = cache_len > 0 ? (int)((cache_len + kps - 1) / kps) : 0;
+  int bps = (s_t + n_splits - 1) / n_splits;
+  bps = max(32, (bps + 31) / 32 * 32);
+  const int need_c = (int)((cache_len + kps - 1) / kps), need_b = (s_t + bps - 1) / bps;
+  n_splits = max(need_c, need_b);  // 0: no key at all
   plan->n_qgroups = n_qg;
   plan->wprt_log = wprt_log;
   plan->n_splits = n_splits;
   plan->keys_per_split = (int)kps;
+  plan->blk_keys_per_split = bps;
   plan->n_parts = n_splits;
+  plan->direct = n_splits == 1 && wprt_log == 0;
 }
 
 void attend_lse_plan(int m_rows, int64_t cache_len, int n_kv_heads, int n_cu, AttendPlan* plan) {
@@ -478,10 +546,13 @@ void attend_lse_plan(int m_rows, int64_t cache_len, int n_kv_heads, int n_cu, At
   plan->wprt_log = 0;
   plan->n_splits = n_splits;
   plan->keys_per_split = (int)kps;
+  plan->blk_keys_per_split = 32;
   plan->n_parts = n_splits;
+  plan->direct = 0;
 }
 
 size_t attend_workspace_bytes(const AttendPlan& plan, int m_rows, int n_kv_heads, int head_dim) {
+  if (plan.direct) return 256;  // the kernel writes the result itself
   const size_t rows = (size_t)n_kv_heads * plan.n_parts * m_rows;
   return ((rows * head_dim * 4 + 255) & ~(size_t)255) + rows * 8 + 256;
 }
@@ -495,9 +566,9 @@ static hipError_t launch_attend_t(const AttendParams& p, hipStream_t st) {
   constexpr size_t lds = lds_chunk > lds_merge ? lds_chunk : lds_merge;
   static_assert(lds <= 160 * 1024, "attention chunk does not fit the LDS");
   if (p.n_splits > 0) {
-    hipLaunchKernelGGL((attend_kernel<DT, D>), dim3(p.n_splits, p.n_qgroups, p.n_kv_heads), dim3(ATT_THREADS), lds, st, p);
+    hipLaunchKernelGGL((attend_kernel<DT, D>), dim3(p.n_splits * p.n_qgroups * p.n_kv_heads), dim3(ATT_THREADS), lds, st, p);
     hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
+    if (e != hipSuccess || p.direct) return e;
   }
   hipLaunchKernelGGL((attend_combine_kernel<D>), dim3(p.n_kv_heads * p.m_rows), dim3((D / 4) * COMB_SLICES), 0, st, p);
   return hipGetLastError();

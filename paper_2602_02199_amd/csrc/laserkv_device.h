@@ -47,8 +47,9 @@ struct Mma<DT_F32> {
 
 __device__ __forceinline__ int acc_row(int r, int kg) { return 8 * (r >> 2) + 4 * kg + (r & 3); }
 
-// m / n through the multiplier ceil(2^32 / n), exact for m <= 1024; n == 1 has no 32-bit multiplier (it is
-// passed as 0)
+// m / n through the multiplier ceil(2^32 / n), exact while m * n < 2^32 (the multiplier exceeds 2^32 / n by
+// less than 1, so the product exceeds m / n by less than m / 2^32 <= 1 / n); n == 1 has no 32-bit multiplier
+// (it is passed as 0)
 __device__ __forceinline__ int div_w(int m, uint32_t magic) { return magic ? (int)__umulhi((uint32_t)m, magic) : m; }
 
 // Plane (within a 32-plane tile) that a hashing wave feeds as row rho of its A operand.  Accumulator

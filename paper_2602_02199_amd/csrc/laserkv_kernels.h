@@ -18,11 +18,12 @@ struct PassParams {
   RowSrc kb;       // [H_kv, S, d]
   RowSrc kc;       // [H_kv, T, d] (base may be null when T == 0)
   const char* planes;   // [L*K, d] contiguous
-  int q_linear;    // q.stride_head == W * q.stride_row and the head's rows span < 2 GiB: window row m of KV head h
-                   // sits at q.base + (h*G*W + m) * q.stride_row
+  int q_linear;    // q.stride_head >= W * q.stride_row and a KV head's G query heads span < 2 GiB: window row
+                   // m = g*W + j of KV head h sits at 32-bit offset g * stride_head + j * stride_row from the
+                   // first row of query head h*G, and one buffer descriptor covers the group
   int group;       // G
   int w;           // W
-  uint32_t w_magic;  // ceil(2^32 / W) (0 for W == 1): row / W for row <= 1024, see div_w
+  uint32_t w_magic;  // ceil(2^32 / W) (0 for W == 1): row / W, see div_w
   int m_rows;      // M = G * W
   int s_t;         // S
   int t_ctx;       // T
@@ -118,7 +119,7 @@ struct AppendParams {
 
 // The single sweep of a block whose window rows come with their complete log-sum-exp.
 struct SingleParams {
-  RowSrc q;        // [H_q, W, d], rows of a KV head's query heads contiguous (row m of head h at h*G*W + m)
+  RowSrc q;        // [H_q, W, d]; stride_head >= W * stride_row, a KV head's G query heads within 2 GiB
   RowSrc kb;       // [H_kv, S, d]
   const char* planes;  // [L*K, d] contiguous
   int group, w;
@@ -156,15 +157,24 @@ hipError_t init_single_attributes();
 struct AttendParams {
   RowSrc q;            // [H_q, n_q, d]
   int group, n_q;
-  uint32_t nq_magic;   // ceil(2^32 / n_q) (0 for n_q == 1): row / n_q for row <= 1024, see div_w
+  uint32_t nq_magic;   // ceil(2^32 / n_q) (0 for n_q == 1): row / n_q, see div_w
   int m_rows;          // M = G * n_q rows per KV head, row m = g * n_q + j
   const char* k_cache; // [H_kv, cap, d] rows contiguous
   const char* v_cache;
   int64_t cache_stride_head;  // bytes
   int row_bytes;       // d * elem size
   int cache_len;       // rows
-  int keys_per_split;  // multiple of 32
-  int n_splits;        // ceil(cache_len / keys_per_split); 0: empty cache
+  // the block's own keys and values, behind the cache rows in key order (none: s_t == 0)
+  const char* k_blk;   // [H_kv, s_t, d]
+  const char* v_blk;
+  int64_t kb_stride_head, vb_stride_head;  // bytes
+  int kb_stride_row, vb_stride_row;        // bytes
+  int s_t;
+  int diag;            // block key i is visible to query j iff i <= diag + j (>= s_t: no mask); |diag| <= 2^30
+  int keys_per_split;  // cache rows per split, multiple of 32
+  int blk_keys_per_split;  // block keys per split, multiple of 32
+  int n_splits;        // every split takes its share of both segments; 0: no key at all
+  int direct;          // one split and a wave per row tile: attend_kernel writes out / out_lse itself
   int wprt_log;        // log2 of the waves that share a 32-row tile (over different key tiles)
   int n_parts;         // partials per row: one per key split
   int n_qgroups;       // ceil(M / 256)
@@ -176,9 +186,9 @@ struct AttendParams {
   float* out_lse;      // [H_kv * M] natural log
 };
 struct AttendPlan {
-  int n_qgroups, wprt_log, n_splits, keys_per_split, n_parts;
+  int n_qgroups, wprt_log, n_splits, keys_per_split, blk_keys_per_split, n_parts, direct;
 };
-void attend_plan(int m_rows, int64_t cache_len, int n_kv_heads, int n_cu, AttendPlan* plan);
+void attend_plan(int m_rows, int64_t cache_len, int s_t, int n_kv_heads, int n_cu, AttendPlan* plan);
 size_t attend_workspace_bytes(const AttendPlan& plan, int m_rows, int n_kv_heads, int head_dim);  // part_o, then part_ml
 hipError_t launch_attend(int dtype, int head_dim, const AttendParams& p, hipStream_t st);
 // the normaliser alone (out unused): 512 rows per workgroup, keys only

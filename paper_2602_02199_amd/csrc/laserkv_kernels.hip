@@ -191,12 +191,17 @@ __global__ __launch_bounds__(PASS_WAVES * 64) void pass_kernel(PassParams p) {
     constexpr int ROWS_PER_LOAD = NTHR / CH;
     const uint32_t trow = tid / CH, tcol = (tid % CH) * 16;
     if (p.q_linear) {
-      const uint32_t qstride = (uint32_t)p.q.stride_row;
-      const __amdgpu_buffer_rsrc_t qsrd =
-          make_srd(p.q.base + (int64_t)h * p.group * p.q.stride_head, (uint32_t)p.m_rows * qstride);
-      const uint32_t qoff = (qg * MQ + trow) * qstride + tcol;
+      // row m = g * W + j of the KV head's group at g * stride_head + j * stride_row from the group's first row;
+      // rows past M land at or past the descriptor's end (stride_head >= W * stride_row) and read as zero
+      const uint32_t qstride = (uint32_t)p.q.stride_row, hstride = (uint32_t)p.q.stride_head;
+      const __amdgpu_buffer_rsrc_t qsrd = make_srd(p.q.base + (int64_t)h * p.group * p.q.stride_head,
+                                                   (uint32_t)(p.group - 1) * hstride + (uint32_t)p.w * qstride);
 #pragma unroll
-      for (int u = 0; u < QL; ++u) qpre[u] = buf_ld16(qsrd, qoff + u * ROWS_PER_LOAD * qstride);
+      for (int u = 0; u < QL; ++u) {
+        const int m = qg * MQ + trow + u * ROWS_PER_LOAD;
+        const int g = div_w(m, p.w_magic);
+        qpre[u] = buf_ld16(qsrd, (uint32_t)g * hstride + (uint32_t)(m - g * p.w) * qstride + tcol);
+      }
     } else {
 #pragma unroll
       for (int u = 0; u < QL; ++u) {

@@ -93,12 +93,19 @@ __global__ __launch_bounds__(SG_THREADS) void single_sweep_kernel(SingleParams p
   const uint32_t trow = tid / CH, tcol = (tid % CH) * 16;
   uint4 qpre[QL], ppre[QL], kpre[KL], tpre[TL];
   {
-    const uint32_t qstride = (uint32_t)p.q.stride_row;
-    const __amdgpu_buffer_rsrc_t qsrd = make_srd(p.q.base + (int64_t)h * p.group * p.q.stride_head, (uint32_t)p.m_rows * qstride);
+    // window row m = g * W + j at g * stride_head + j * stride_row from the group's first row; rows past M land at
+    // or past the descriptor's end (stride_head >= W * stride_row) and read as zero
+    const uint32_t qstride = (uint32_t)p.q.stride_row, hstride = (uint32_t)p.q.stride_head;
+    const __amdgpu_buffer_rsrc_t qsrd = make_srd(p.q.base + (int64_t)h * p.group * p.q.stride_head,
+                                                 (uint32_t)(p.group - 1) * hstride + (uint32_t)p.w * qstride);
     const __amdgpu_buffer_rsrc_t psrd = make_srd(p.planes, (uint32_t)p.n_planes * (D * ES));
     const __amdgpu_buffer_rsrc_t ksrd = make_srd(p.kb.base + (int64_t)h * p.kb.stride_head, (uint32_t)p.s_t * (uint32_t)p.kb.stride_row);
 #pragma unroll
-    for (int u = 0; u < QL; ++u) qpre[u] = buf_ld16(qsrd, (trow + u * RPL) * qstride + tcol);  // rows past M read as zero
+    for (int u = 0; u < QL; ++u) {
+      const int m = trow + u * RPL;
+      const int g = div_w(m, p.w_magic);
+      qpre[u] = buf_ld16(qsrd, (uint32_t)g * hstride + (uint32_t)(m - g * p.w) * qstride + tcol);
+    }
 #pragma unroll
     for (int u = 0; u < QL; ++u) ppre[u] = buf_ld16(psrd, (trow + u * RPL) * (D * ES) + tcol); // planes past L*K read as zero
 #pragma unroll

@@ -654,6 +654,33 @@ def test_padded_query_and_key_strides(dtype, window):
     lib.close()
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_query_heads_that_alias_one_tensor(dtype):
+    """Every query head reads the same window rows (head stride 0, as an expanded tensor has): no single buffer
+    descriptor covers a group whose heads overlap, so the sweeps take their per-row addressing path."""
+    wl = synth.shrink(synth.WORKLOADS["llama8b-16k"], index=27, l_ctx=2048, s_block=1024, dtype=dtype)
+    B = O.budget(wl.s_block, wl.l_ctx, wl.r_num, wl.r_den)
+    parts = O.partition(B, wl.n_div, wl.alpha, wl.s_block)
+    data = synth.make_layer(wl, 0, parts[0], n_blocks=1)
+    s, d, w = wl.s_block, wl.head_dim, wl.window
+    q_one = data["q_win"][0][3:4].contiguous()
+    q_view = q_one.to(DEV).expand(wl.n_q_heads, w, d)
+    assert q_view.stride(0) == 0
+    lib = binding.LaserKV(wl.n_q_heads, wl.n_kv_heads, d, wl.dtype, wl.lsh_tables, wl.lsh_bits,
+                          max_block=s, max_window=w, max_ctx_keys=0)
+    dbg = dbg_buffers(wl, s)
+    keep = torch.empty(wl.n_kv_heads, sum(parts), dtype=torch.int32, device=DEV)
+    lib.laserkv_select_block(q_view, data["k"][:, :s].to(DEV), None, data["planes"].to(DEV), block_pos0=0,
+                             n_anchor=parts[0], n_local=parts[1], k_exact=parts[2], k_lsh=parts[3], keep_idx=keep,
+                             dbg_s_exact=dbg["s_exact"], dbg_sig_k=dbg["sig_k"], dbg_sig_q=dbg["sig_q"], dbg_count=dbg["cnt"])
+    torch.cuda.synchronize()
+    st = O.select_block(f64(q_one.expand(wl.n_q_heads, w, d)), f64(data["k"][:, :s]), None, f64(data["planes"]), wl.lsh_tables,
+                        wl.lsh_bits, *parts, block_pos0=0)
+    rep = check_block(st, gpu_stage(dbg, keep), parts, wl.dtype)
+    say(f"[aliased query heads {dtype}] max score err/(s+s_k) {rep['max_rel']:.2e}, tolerated {rep['tolerated']}")
+    lib.close()
+
+
 @pytest.mark.parametrize("s_t,t_ctx,dtype", [(96, 700, "bf16"), (40, 333, "f32"), (1024, 31, "bf16")])
 def test_look_back_keys_outnumbering_the_block(s_t, t_ctx, dtype):
     """Look-back keys are spread evenly over the block's key ranges; when there are far more of them than
