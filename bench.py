@@ -213,7 +213,8 @@ def measure(wl, args, dev, cpu_seconds):
 def measure_attend(wl, comp, ddev, dev, reps=10, cases=("decode", "window")):
     """laserkv_attend_cache over the layer's finished cache (the rows the timed steps kept): one decode query
     per head (bound by reading the cached K and V once) and the next block's window rows (bound by the two
-    contractions QK^T and PV).  Event times on the launch stream, average of `reps` launches after two."""
+    contractions QK^T and PV), with and without the output; and laserkv_attend_block for the last block (case
+    "prefill").  Event times on the launch stream, average of `reps` launches after two."""
     import torch
     n = wl.n_blocks * min(comp.B, wl.s_block)
     es = 2 if wl.dtype == "bf16" else 4
@@ -243,6 +244,35 @@ def measure_attend(wl, comp, ddev, dev, reps=10, cases=("decode", "window")):
         out[label] = dict(n_q=n_q, cache_rows_per_head=n, avg_us=round(us, 2), hbm_gbs=round(gbs, 1),
                           hbm_frac=round(gbs / PEAK_HBM_GBS, 4), tflops=round(tfl, 1), mfma_frac=round(tfl / peak_mfma, 4),
                           bound="hbm" if gbs / PEAK_HBM_GBS > tfl / peak_mfma else "mfma")
+    if "prefill" in cases:
+        # laserkv_attend_block: the last block's own attention, every row of the block over the cache of the
+        # earlier blocks and, causally, over the block itself (the model's attention call; its log-sum-exp of
+        # the window rows is what laserkv_set_row_lse_complete takes).  Queries: seeded N(0,1).
+        s, d = wl.s_block, wl.head_dim
+        n_c = (wl.n_blocks - 1) * min(comp.B, s)
+        lo = (wl.n_blocks - 1) * s
+        gen = torch.Generator(device=dev).manual_seed(1234)
+        q = torch.randn(wl.n_q_heads, s, d, generator=gen, device=dev).to(ddev["k"].dtype)
+        kb, vb = ddev["k"][:, lo:lo + s], ddev["v"][:, lo:lo + s]
+        o = torch.empty(wl.n_q_heads, s, d, dtype=torch.float32, device=dev)
+        lse = torch.empty(wl.n_q_heads, s, dtype=torch.float32, device=dev)
+        ws = torch.empty(comp.lib.laserkv_attend_block_workspace_bytes(s, n_c, s), dtype=torch.uint8, device=dev)
+        run = lambda: comp.lib.laserkv_attend_block(q, comp.k_cache, comp.v_cache, kb, vb, cache_len=n_c, block_pos0=lo,
+                                                    out=o, out_lse=lse, workspace=ws)
+        run()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for _ in range(3):
+            run()
+        e1.record(stream)
+        e1.synchronize()
+        us = 1e3 * e0.elapsed_time(e1) / 3
+        pairs = s * n_c + s * (s + 1) // 2   # (query, visible key) pairs per query head
+        flops = 4 * wl.n_q_heads * pairs * d
+        tfl = flops / us / 1e6
+        peak_mfma = PEAK_MFMA_BF16_TFLOPS if wl.dtype == "bf16" else PEAK_MFMA_F32_TFLOPS
+        out["prefill_block"] = dict(n_q=s, cache_rows_per_head=n_c, block_keys=s, avg_us=round(us, 1), tflops=round(tfl, 1),
+                                    mfma_frac=round(tfl / peak_mfma, 4), bound="mfma")
     return out
 
 
@@ -271,7 +301,7 @@ def main():
                          "attention kernel would report it), so the first sweep only hashes; not the headline configuration")
     ap.add_argument("--no-complete", dest="with_complete", action="store_false",
                     help="skip the extra measurement of the workload with complete row statistics from the caller")
-    ap.add_argument("--attend-case", default="decode,window", help="which attention cases to time (profiling one at a time)")
+    ap.add_argument("--attend-case", default="decode,window,prefill", help="which attention cases to time (profiling one at a time)")
     ap.add_argument("--no-attend", dest="attend", action="store_false",
                     help="skip the timing of laserkv_attend_cache over the finished cache")
     ap.add_argument("--batch", type=int, default=1,

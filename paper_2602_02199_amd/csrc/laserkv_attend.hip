@@ -18,8 +18,12 @@ constexpr int ATT_THREADS = ATT_WAVES * 64;
 constexpr int ATT_ROWS = 256;      // query rows per workgroup: up to 8 row tiles
 constexpr int ATT_MAX_SPLITS = 64;
 
+// Keys per LDS chunk.  When waves share a row tile (few query rows: decoding) the kernel is bound by the bytes it
+// keeps in flight, and the larger chunk is what the prefetch registers hold; with a row tile per wave the
+// smaller chunk leaves the compiler 30 registers more for the tile loop (4 % faster on the 128k prefill block).
 template <int DT>
 __host__ __device__ constexpr int att_chunk_keys() { return DT == DT_BF16 ? 256 : 128; }
+constexpr int ATT_ROWS_CHUNK = 128;
 
 // Transposes, inside groups of 8 consecutive lanes, the 8 x 8 matrix of 16-bit elements whose row i is lane
 // i's 16 bytes: afterwards lane i holds column i, element e of it being what lane e held at position i.
@@ -80,13 +84,12 @@ __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
 // operand matches by reading V^T at the same key offsets.  V is transposed in registers on its way into LDS.
 // Block key i is visible to query j iff i <= diag + j: chunks past the last row of the workgroup are never
 // loaded, tiles past the last row of the wave are skipped, tiles that cross a row's limit take a masked path.
-template <int DT, int D>
+template <int DT, int D, int KC>
 __global__ __launch_bounds__(ATT_THREADS) void attend_kernel(AttendParams p) {
   constexpr int ES = DT == DT_BF16 ? 2 : 4;
   constexpr int CH = D * ES / 16;             // 16-byte chunks per row
   constexpr int NCH = CH / 2;
   constexpr int CHP = CH + 1;                 // K row pitch in chunks (odd)
-  constexpr int KC = att_chunk_keys<DT>();    // keys per LDS chunk
   constexpr int EPC = 16 / ES;                // elements per 16-byte chunk
   constexpr int VTP = KC / EPC + 1;           // V^T row pitch in chunks (odd)
   constexpr int KL = KC * CH / ATT_THREADS;   // 16-byte loads per thread, tensor and chunk
@@ -203,13 +206,15 @@ __global__ __launch_bounds__(ATT_THREADS) void attend_kernel(AttendParams p) {
       for (int i = 0; i < NCH; ++i) Mma<DT>::run(acc, krow[2 * i], a[i]);
       // hidden keys (past the end of the split or past the row's causal limit) weigh nothing, and a row that
       // sees no key of the tile keeps its state
-      float mx = NEG_BIG;
+      if (!__all(n_vis >= 32)) {
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        acc[r] = acc_row(r, kg) < n_vis ? acc[r] * p.scale2 : NEG_BIG;
-        mx = fmaxf(mx, acc[r]);
+        for (int r = 0; r < 16; ++r) acc[r] = acc_row(r, kg) < n_vis ? acc[r] : NEG_BIG;
       }
+      float mx = acc[0];
+#pragma unroll
+      for (int r = 1; r < 16; ++r) mx = fmaxf(mx, acc[r]);
       mx = fmaxf(mx, __shfl_xor(mx, 32));  // both halves of the wave use one reference per row
+      mx = mx > NEG_BIG ? mx * p.scale2 : NEG_BIG;  // the reference lives in the scaled (log2) domain; scale2 > 0
       if (__any(mx > m_ref)) {
         const float m_new = fmaxf(m_ref, mx);
         const float alpha = fast_exp2(m_ref - m_new);
@@ -220,10 +225,11 @@ __global__ __launch_bounds__(ATT_THREADS) void attend_kernel(AttendParams p) {
           for (int r = 0; r < 16; ++r) o[dt][r] *= alpha;
         m_ref = m_new;
       }
-      const float m_sub = n_vis > 0 ? m_ref : 0.0f;  // a row without a visible key: 2^(NEG_BIG - 0) = 0, not 2^0
+      // a row without a visible key so far subtracts nothing: its hidden logits give 2^(NEG_BIG * scale2) = 0
+      const float m_sub = m_ref > NEG_BIG ? m_ref : 0.0f;
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        acc[r] = fast_exp2(acc[r] - m_sub);
+        acc[r] = fast_exp2(fmaf(acc[r], p.scale2, -m_sub));
         l_sum += acc[r];
       }
 #pragma unroll
@@ -557,17 +563,21 @@ size_t attend_workspace_bytes(const AttendPlan& plan, int m_rows, int n_kv_heads
   return ((rows * head_dim * 4 + 255) & ~(size_t)255) + rows * 8 + 256;
 }
 
-template <int DT, int D>
-static hipError_t launch_attend_t(const AttendParams& p, hipStream_t st) {
+template <int DT, int D, int KC>
+static hipError_t launch_attend_kc(const AttendParams& p, hipStream_t st) {
   constexpr int ES = DT == DT_BF16 ? 2 : 4;
-  constexpr int KC = att_chunk_keys<DT>();
   constexpr size_t lds_chunk = ((size_t)KC * (D * ES / 16 + 1) + (size_t)D * (KC / (16 / ES) + 1)) * 16;
   constexpr size_t lds_merge = (size_t)ATT_WAVES * 32 * ((D + 4) * 4 + 8);  // the waves' states when they share row tiles
   constexpr size_t lds = lds_chunk > lds_merge ? lds_chunk : lds_merge;
   static_assert(lds <= 160 * 1024, "attention chunk does not fit the LDS");
+  hipLaunchKernelGGL((attend_kernel<DT, D, KC>), dim3(p.n_splits * p.n_qgroups * p.n_kv_heads), dim3(ATT_THREADS), lds, st, p);
+  return hipGetLastError();
+}
+
+template <int DT, int D>
+static hipError_t launch_attend_t(const AttendParams& p, hipStream_t st) {
   if (p.n_splits > 0) {
-    hipLaunchKernelGGL((attend_kernel<DT, D>), dim3(p.n_splits * p.n_qgroups * p.n_kv_heads), dim3(ATT_THREADS), lds, st, p);
-    hipError_t e = hipGetLastError();
+    hipError_t e = p.wprt_log == 0 ? launch_attend_kc<DT, D, ATT_ROWS_CHUNK>(p, st) : launch_attend_kc<DT, D, att_chunk_keys<DT>()>(p, st);
     if (e != hipSuccess || p.direct) return e;
   }
   hipLaunchKernelGGL((attend_combine_kernel<D>), dim3(p.n_kv_heads * p.m_rows), dim3((D / 4) * COMB_SLICES), 0, st, p);
@@ -607,7 +617,9 @@ hipError_t launch_attend(int dtype, int head_dim, const AttendParams& p, hipStre
 
 template <int DT, int D>
 static hipError_t attend_attr() {
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attend_kernel<DT, D>), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attend_kernel<DT, D, att_chunk_keys<DT>()>), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+  if (e == hipSuccess)
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attend_kernel<DT, D, ATT_ROWS_CHUNK>), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
   if (e == hipSuccess)
     e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attend_lse_kernel<DT, D>), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
   return e;
