@@ -18,12 +18,9 @@ constexpr int ATT_THREADS = ATT_WAVES * 64;
 constexpr int ATT_ROWS = 256;      // query rows per workgroup: up to 8 row tiles
 constexpr int ATT_MAX_SPLITS = 64;
 
-// Keys per LDS chunk.  When waves share a row tile (few query rows: decoding) the kernel is bound by the bytes it
-// keeps in flight, and the larger chunk is what the prefetch registers hold; with a row tile per wave the
-// smaller chunk leaves the compiler 30 registers more for the tile loop (4 % faster on the 128k prefill block).
+// Keys per LDS chunk of attend_kernel (as many as its prefetch registers hold).
 template <int DT>
 __host__ __device__ constexpr int att_chunk_keys() { return DT == DT_BF16 ? 256 : 128; }
-constexpr int ATT_ROWS_CHUNK = 128;
 
 // Transposes, inside groups of 8 consecutive lanes, the 8 x 8 matrix of 16-bit elements whose row i is lane
 // i's 16 bytes: afterwards lane i holds column i, element e of it being what lane e held at position i.
@@ -64,6 +61,21 @@ __device__ __forceinline__ uint4 transpose_4x4_b32(const uint4& v, int lane) {
     if (i1) x[a] = recv; else x[a + 2] = recv;
   }
   return make_uint4(x[0], x[1], x[2], x[3]);
+}
+
+// Writes one transposed group (the group's EPC consecutive keys at one head-dimension index) into that index's
+// row of V^T.  fp32: keys in order.  bf16: the P operand of O^T += V^T P^T holds, per lane half kg and 16-key
+// block, keys 4kg + (0..3) and 8 + 4kg + (0..3) (the accumulator layout of S^T); the row stores every 16-key
+// block in that order, [0-3, 8-11 | 4-7, 12-15], so that a lane's eight keys are one 16-byte read.
+template <int DT>
+__device__ __forceinline__ void store_vt(uint4* row, int group, const uint4& t) {
+  if (DT == DT_BF16) {
+    uint2* r2 = reinterpret_cast<uint2*>(row) + 4 * (group >> 1) + (group & 1);
+    r2[0] = make_uint2(t.x, t.y);
+    r2[2] = make_uint2(t.z, t.w);
+  } else {
+    row[group] = t;
+  }
 }
 
 // Workgroup barrier for data exchanged through LDS only: waits for this wave's LDS traffic, not for its
@@ -177,7 +189,7 @@ __global__ __launch_bounds__(ATT_THREADS) void attend_kernel(AttendParams p) {
       sK[(k_row + u * K_ROWS_PER_LOAD) * CHP + k_col] = kpre[u];
       const uint4 t = DT == DT_BF16 ? transpose_8x8_b16(vpre[u], lane) : transpose_4x4_b32(vpre[u], lane);
       // the lane now holds head-dimension index v_c * EPC + v_i for the group's EPC keys
-      sVT[(v_c * EPC + v_i) * VTP + (u * V_GROUPS_PER_LOAD + v_grp)] = t;
+      store_vt<DT>(sVT + (v_c * EPC + v_i) * VTP, u * V_GROUPS_PER_LOAD + v_grp, t);
     }
     // the chunk after this one: the next of the segment, else the first of the block's keys
     int nseg = seg, nkc = kc0 + KC;
@@ -247,10 +259,7 @@ __global__ __launch_bounds__(ATT_THREADS) void attend_kernel(AttendParams p) {
           const uint4* vrow = sVT + (size_t)(dt * 32 + rl) * VTP;
           uint4 va;
           if (DT == DT_BF16) {
-            // registers 8s .. 8s+3 are keys 16s + 4kg + (0..3), registers 8s+4 .. 8s+7 the same + 8
-            const uint2* v2 = reinterpret_cast<const uint2*>(vrow) + nt * 8 + 4 * s + kg;
-            const uint2 lo = v2[0], hi = v2[2];
-            va = make_uint4(lo.x, lo.y, hi.x, hi.y);
+            va = vrow[nt * 4 + 2 * s + kg];  // registers 8s .. 8s+7 are keys 16s + 4kg + (0..3) and the same + 8: see store_vt
           } else {
             va = vrow[nt * 8 + 2 * s + kg];  // registers 4s .. 4s+3 are keys 8s + 4kg + (0..3)
           }
@@ -338,6 +347,235 @@ __global__ __launch_bounds__(ATT_THREADS) void attend_kernel(AttendParams p) {
     if (d4 == 0) p.part_ml[at] = make_float2(mx, l);
     *reinterpret_cast<float4*>(p.part_o + at * D + d4 * 4) = acc;
   }
+}
+
+// The same pass for launches in which every wave owns a row tile (8 or more query rows tiles per KV head: window
+// rows, whole blocks), arranged so that the matrix unit and the vector unit work at the same time.  The keys of
+// a chunk are complete tiles (hidden keys are masked, a tile nobody sees costs its arithmetic), so the tile loop
+// has no early exits and is unrolled: the logits of tile t+1 are issued before the softmax of tile t, whose
+// exponentials then run while the matrix unit multiplies.  Chunks alternate between two LDS stages: the next
+// chunk, prefetched into registers while the current one is worked on, is stored after the chunk's last tile,
+// so one barrier per chunk suffices (every wave has left the stage that is overwritten a barrier ago).
+template <int DT>
+__host__ __device__ constexpr int rows_chunk_keys() { return DT == DT_BF16 ? 128 : 64; }
+
+template <int DT, int D>
+__global__ __launch_bounds__(ATT_THREADS) void attend_rows_kernel(AttendParams p) {
+  constexpr int ES = DT == DT_BF16 ? 2 : 4;
+  constexpr int CH = D * ES / 16;             // 16-byte chunks per row
+  constexpr int NCH = CH / 2;
+  constexpr int CHP = CH + 1;                 // K row pitch in chunks (odd)
+  constexpr int KC = rows_chunk_keys<DT>();   // keys per LDS chunk
+  constexpr int EPC = 16 / ES;                // elements per 16-byte chunk
+  constexpr int VTP = KC / EPC + 1;           // V^T row pitch in chunks (odd)
+  constexpr int KL = KC * CH / ATT_THREADS;   // 16-byte loads per thread, tensor and chunk
+  constexpr int NDT = D / 32;                 // 32-wide tiles of the head dimension
+  constexpr int TPC = KC / 32;                // key tiles per chunk
+  constexpr int RUNS = 32 / (2 * EPC);        // operand chunks per lane and 32-key tile in P.V
+  constexpr int K_ROWS_PER_LOAD = ATT_THREADS / CH;
+  constexpr int V_GROUPS_PER_LOAD = ATT_THREADS / (EPC * CH);
+  constexpr int STAGE = KC * CHP + D * VTP;   // uint4 per LDS stage: K [KC][CHP], then V^T [D][VTP]
+  static_assert(KL >= 1 && KL * ATT_THREADS == KC * CH, "chunk not a whole number of loads per thread");
+
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, rl = lane & 31, kg = lane >> 5;
+  // consecutive indices stay on one XCD: the row groups and splits of a head share that XCD's L2
+  const int idx = xcd_major(blockIdx.x, gridDim.x);
+  const int split = idx % p.n_splits, qg = (idx / p.n_splits) % p.n_qgroups, h = idx / (p.n_splits * p.n_qgroups);
+  const int row = qg * ATT_ROWS + wave * 32 + rl;
+
+  extern __shared__ uint4 smem[];
+
+  // the wave's 32 query rows, as the B operand of S^T
+  uint4 a[NCH];
+  int blk_end_lane;  // block keys [0, blk_end_lane) are visible to this lane's row
+  {
+    const int m = min(row, p.m_rows - 1);
+    const int g = m / p.n_q, j = m - g * p.n_q;
+    const char* ptr = p.q.base + (int64_t)(h * p.group + g) * p.q.stride_head + (int64_t)j * p.q.stride_row;
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) a[i] = ld16(ptr + (2 * i + kg) * 16);
+    blk_end_lane = max(0, min(p.s_t, p.diag + j + 1));
+  }
+  const int lo0 = min(split * p.keys_per_split, p.cache_len), hi0 = min(lo0 + p.keys_per_split, p.cache_len);
+  int lo1 = 0, hi1 = 0;
+  if (p.s_t > 0) {
+    const int m0 = qg * ATT_ROWS, m1 = min(m0 + ATT_ROWS, p.m_rows) - 1;
+    const int g0 = m0 / p.n_q, g1 = m1 / p.n_q;
+    const int j_max = g0 == g1 ? m1 - g1 * p.n_q : p.n_q - 1;
+    const int wg_end = max(0, min(p.s_t, p.diag + j_max + 1));
+    lo1 = min(split * p.blk_keys_per_split, wg_end);
+    hi1 = min(lo1 + p.blk_keys_per_split, wg_end);
+  }
+
+  const __amdgpu_buffer_rsrc_t ksrd0 = make_srd(p.k_cache + (int64_t)h * p.cache_stride_head, (uint32_t)p.cache_len * (uint32_t)p.row_bytes);
+  const __amdgpu_buffer_rsrc_t vsrd0 = make_srd(p.v_cache + (int64_t)h * p.cache_stride_head, (uint32_t)p.cache_len * (uint32_t)p.row_bytes);
+  const uint32_t kb_bytes = p.s_t > 0 ? (uint32_t)(p.s_t - 1) * (uint32_t)p.kb_stride_row + (uint32_t)p.row_bytes : 0u;
+  const uint32_t vb_bytes = p.s_t > 0 ? (uint32_t)(p.s_t - 1) * (uint32_t)p.vb_stride_row + (uint32_t)p.row_bytes : 0u;
+  const __amdgpu_buffer_rsrc_t ksrd1 = make_srd(p.k_blk + (int64_t)h * p.kb_stride_head, kb_bytes);
+  const __amdgpu_buffer_rsrc_t vsrd1 = make_srd(p.v_blk + (int64_t)h * p.vb_stride_head, vb_bytes);
+  const uint32_t k_row = tid / CH, k_col = tid % CH;
+  const uint32_t v_i = tid % EPC, v_c = (tid / EPC) % CH, v_grp = tid / (EPC * CH);
+  uint4 kpre[KL], vpre[KL];
+  auto prefetch = [&](int seg, int kc0) {
+    const __amdgpu_buffer_rsrc_t ksrd = seg ? ksrd1 : ksrd0, vsrd = seg ? vsrd1 : vsrd0;
+    const uint32_t kstride = seg ? (uint32_t)p.kb_stride_row : (uint32_t)p.row_bytes;
+    const uint32_t vstride = seg ? (uint32_t)p.vb_stride_row : (uint32_t)p.row_bytes;
+#pragma unroll
+    for (int u = 0; u < KL; ++u) {
+      kpre[u] = buf_ld16(ksrd, (uint32_t)(kc0 + k_row + u * K_ROWS_PER_LOAD) * kstride + k_col * 16);
+      const uint32_t key = (u * V_GROUPS_PER_LOAD + v_grp) * EPC + v_i;
+      vpre[u] = buf_ld16(vsrd, (uint32_t)(kc0 + key) * vstride + v_c * 16);
+    }
+  };
+  auto store = [&](uint4* stage) {
+    uint4* sK = stage;
+    uint4* sVT = stage + KC * CHP;
+#pragma unroll
+    for (int u = 0; u < KL; ++u) {
+      sK[(k_row + u * K_ROWS_PER_LOAD) * CHP + k_col] = kpre[u];
+      const uint4 t = DT == DT_BF16 ? transpose_8x8_b16(vpre[u], lane) : transpose_4x4_b32(vpre[u], lane);
+      store_vt<DT>(sVT + (v_c * EPC + v_i) * VTP, u * V_GROUPS_PER_LOAD + v_grp, t);
+    }
+  };
+  // the chunk after (seg, kc0): the next of the segment, else the first of the block's keys
+  auto advance = [&](int& seg, int& kc0) -> bool {
+    kc0 += KC;
+    if (kc0 < (seg ? hi1 : hi0)) return true;
+    if (seg == 0 && lo1 < hi1) {
+      seg = 1;
+      kc0 = lo1;
+      return true;
+    }
+    return false;
+  };
+  auto logits = [&](const uint4* stage, int nt, f32x16& acc) {
+    const uint4* krow = stage + (size_t)(nt * 32 + rl) * CHP + kg;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) Mma<DT>::run(acc, krow[2 * i], a[i]);
+  };
+
+  float m_ref = NEG_BIG, l_sum = 0.0f;
+  f32x16 o[NDT];
+#pragma unroll
+  for (int dt = 0; dt < NDT; ++dt)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) o[dt][r] = 0.0f;
+
+  int seg = lo0 < hi0 ? 0 : 1;
+  int kc0 = seg ? lo1 : lo0;
+  bool have = seg ? lo1 < hi1 : true;
+  int nseg = seg, nkc = kc0;
+  bool nhave = false;
+  int cur = 0;
+  if (have) {
+    prefetch(seg, kc0);
+    store(smem);
+    nhave = advance(nseg, nkc);
+    if (nhave) prefetch(nseg, nkc);  // in flight while the first chunk is worked on
+    lds_barrier();
+  }
+  while (have) {
+    const uint4* stage = smem + (size_t)cur * STAGE;
+    const uint4* sVT = stage + KC * CHP;
+    const int lane_end = seg ? min(hi1, blk_end_lane) : hi0;  // end of the keys of this segment the lane's row sees
+    f32x16 acc, acc_next;
+    logits(stage, 0, acc);
+#pragma unroll
+    for (int nt = 0; nt < TPC; ++nt) {
+      if (nt + 1 < TPC) logits(stage, nt + 1, acc_next);  // the matrix unit works on these during the exponentials below
+      const int n_vis = lane_end - (kc0 + nt * 32);  // keys of this tile the lane's row sees (>= 32: all)
+      if (!__all(n_vis >= 32)) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[r] = acc_row(r, kg) < n_vis ? acc[r] : NEG_BIG;
+      }
+      float mx = acc[0];
+#pragma unroll
+      for (int r = 1; r < 16; ++r) mx = fmaxf(mx, acc[r]);
+      mx = fmaxf(mx, __shfl_xor(mx, 32));  // both halves of the wave use one reference per row
+      mx = mx > NEG_BIG ? mx * p.scale2 : NEG_BIG;  // the reference lives in the scaled (log2) domain; scale2 > 0
+      if (__any(mx > m_ref)) {
+        const float m_new = fmaxf(m_ref, mx);
+        const float alpha = fast_exp2(m_ref - m_new);
+        l_sum *= alpha;
+#pragma unroll
+        for (int dt = 0; dt < NDT; ++dt)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) o[dt][r] *= alpha;
+        m_ref = m_new;
+      }
+      // a row without a visible key so far subtracts nothing: its hidden logits give 2^(NEG_BIG * scale2) = 0
+      const float m_sub = m_ref > NEG_BIG ? m_ref : 0.0f;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        acc[r] = fast_exp2(fmaf(acc[r], p.scale2, -m_sub));
+        l_sum += acc[r];
+      }
+#pragma unroll
+      for (int s = 0; s < RUNS; ++s) {
+        uint4 pb;
+        if (DT == DT_BF16) {
+          pb = make_uint4(pack_bf16(acc[8 * s], acc[8 * s + 1]), pack_bf16(acc[8 * s + 2], acc[8 * s + 3]),
+                          pack_bf16(acc[8 * s + 4], acc[8 * s + 5]), pack_bf16(acc[8 * s + 6], acc[8 * s + 7]));
+        } else {
+          pb = make_uint4(__float_as_uint(acc[4 * s]), __float_as_uint(acc[4 * s + 1]),
+                          __float_as_uint(acc[4 * s + 2]), __float_as_uint(acc[4 * s + 3]));
+        }
+#pragma unroll
+        for (int dt = 0; dt < NDT; ++dt) {
+          const uint4* vrow = sVT + (size_t)(dt * 32 + rl) * VTP;
+          uint4 va;
+          if (DT == DT_BF16) {
+            va = vrow[nt * 4 + 2 * s + kg];  // registers 8s .. 8s+7 are keys 16s + 4kg + (0..3) and the same + 8: see store_vt
+          } else {
+            va = vrow[nt * 8 + 2 * s + kg];  // registers 4s .. 4s+3 are keys 8s + 4kg + (0..3)
+          }
+          Mma<DT>::run(o[dt], va, pb);
+        }
+      }
+      if (nt + 1 < TPC) acc = acc_next;
+    }
+    // the next chunk goes into the other stage, which every wave left before the previous barrier
+    have = nhave;
+    if (have) {
+      store(smem + (size_t)(cur ^ 1) * STAGE);
+      seg = nseg;
+      kc0 = nkc;
+      nhave = advance(nseg, nkc);
+      if (nhave) prefetch(nseg, nkc);
+      cur ^= 1;
+      lds_barrier();
+    }
+  }
+
+  l_sum += __shfl_xor(l_sum, 32);
+  if (row >= p.m_rows) return;
+  if (p.direct) {
+    // one split: the state is final.  out = O / l, lse = (m + log2 l) ln 2; a row that saw no key gives zero and -inf
+    const size_t at = (size_t)h * p.m_rows + row;
+    const float inv = l_sum > 0.0f ? 1.0f / l_sum : 0.0f;
+    if (kg == 0) p.out_lse[at] = l_sum > 0.0f ? (m_ref + fast_log2(l_sum)) * 0.6931471805599453f : -__builtin_inff();
+    float* dst = p.out + at * D;
+#pragma unroll
+    for (int dt = 0; dt < NDT; ++dt)
+#pragma unroll
+      for (int q4 = 0; q4 < 4; ++q4)
+        st16_stream(dst + dt * 32 + 8 * q4 + 4 * kg,
+                    make_uint4(__float_as_uint(o[dt][4 * q4] * inv), __float_as_uint(o[dt][4 * q4 + 1] * inv),
+                               __float_as_uint(o[dt][4 * q4 + 2] * inv), __float_as_uint(o[dt][4 * q4 + 3] * inv)));
+    return;
+  }
+  // the split's partial (reference, sum, unnormalised output)
+  const size_t at = ((size_t)h * p.n_parts + split) * p.m_rows + row;
+  if (kg == 0) p.part_ml[at] = make_float2(m_ref, l_sum);
+  float* dst = p.part_o + at * D;
+#pragma unroll
+  for (int dt = 0; dt < NDT; ++dt)
+#pragma unroll
+    for (int q4 = 0; q4 < 4; ++q4)
+      *reinterpret_cast<float4*>(dst + dt * 32 + 8 * q4 + 4 * kg) =
+          make_float4(o[dt][4 * q4], o[dt][4 * q4 + 1], o[dt][4 * q4 + 2], o[dt][4 * q4 + 3]);
 }
 
 // out = sum_p O_p 2^(m_p - M) / sum_p l_p 2^(m_p - M), lse = (M + log2 of that sum) ln 2.  One workgroup per row:
@@ -577,7 +815,17 @@ static hipError_t launch_attend_kc(const AttendParams& p, hipStream_t st) {
 template <int DT, int D>
 static hipError_t launch_attend_t(const AttendParams& p, hipStream_t st) {
   if (p.n_splits > 0) {
-    hipError_t e = p.wprt_log == 0 ? launch_attend_kc<DT, D, ATT_ROWS_CHUNK>(p, st) : launch_attend_kc<DT, D, att_chunk_keys<DT>()>(p, st);
+    hipError_t e;
+    if (p.wprt_log == 0) {
+      constexpr int ES = DT == DT_BF16 ? 2 : 4;
+      constexpr int KC = rows_chunk_keys<DT>();
+      constexpr size_t lds = (size_t)2 * ((size_t)KC * (D * ES / 16 + 1) + (size_t)D * (KC / (16 / ES) + 1)) * 16;
+      static_assert(lds <= 160 * 1024, "two attention chunks do not fit the LDS");
+      hipLaunchKernelGGL((attend_rows_kernel<DT, D>), dim3(p.n_splits * p.n_qgroups * p.n_kv_heads), dim3(ATT_THREADS), lds, st, p);
+      e = hipGetLastError();
+    } else {
+      e = launch_attend_kc<DT, D, att_chunk_keys<DT>()>(p, st);
+    }
     if (e != hipSuccess || p.direct) return e;
   }
   hipLaunchKernelGGL((attend_combine_kernel<D>), dim3(p.n_kv_heads * p.m_rows), dim3((D / 4) * COMB_SLICES), 0, st, p);
@@ -619,7 +867,7 @@ template <int DT, int D>
 static hipError_t attend_attr() {
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attend_kernel<DT, D, att_chunk_keys<DT>()>), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
   if (e == hipSuccess)
-    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attend_kernel<DT, D, ATT_ROWS_CHUNK>), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attend_rows_kernel<DT, D>), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
   if (e == hipSuccess)
     e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attend_lse_kernel<DT, D>), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
   return e;
