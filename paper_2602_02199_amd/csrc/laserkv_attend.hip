@@ -24,24 +24,27 @@ __host__ __device__ constexpr int att_chunk_keys() { return DT == DT_BF16 ? 256 
 
 // Transposes, inside groups of 8 consecutive lanes, the 8 x 8 matrix of 16-bit elements whose row i is lane
 // i's 16 bytes: afterwards lane i holds column i, element e of it being what lane e held at position i.
-// Three exchange steps, each swapping one bit of the lane index with one bit of the element index.
+// Three exchange steps, each swapping one bit of the lane index with one bit of the element index; lane
+// exchanges are DPP moves and every step is a select (no branches, no LDS traffic).
 __device__ __forceinline__ uint4 transpose_8x8_b16(const uint4& v, int lane) {
   uint32_t x[4] = {v.x, v.y, v.z, v.w};
   const bool i0 = lane & 1, i1 = lane & 2, i2 = lane & 4;
+  // lane bit 0 <-> half of the word: an even lane keeps its low half and takes the partner's low half as its
+  // high half; an odd lane takes the partner's high half as its low half and keeps its high half
+  const uint32_t sel = i0 ? 0x03020706u : 0x05040100u;  // byte picks from {partner (bytes 4-7), own (bytes 0-3)}
 #pragma unroll
-  for (int w = 0; w < 4; ++w) {  // lane bit 0 <-> half of the word
-    const uint32_t t = (uint32_t)__shfl_xor((int)x[w], 1);
-    x[w] = i0 ? ((t >> 16) | (x[w] & 0xffff0000u)) : ((x[w] & 0xffffu) | (t << 16));
-  }
+  for (int w = 0; w < 4; ++w) x[w] = __builtin_amdgcn_perm(lane_xor1(x[w]), x[w], sel);
 #pragma unroll
   for (int a = 0; a < 4; a += 2) {  // lane bit 1 <-> word bit 0
-    const uint32_t recv = (uint32_t)__shfl_xor((int)(i1 ? x[a] : x[a + 1]), 2);
-    if (i1) x[a] = recv; else x[a + 1] = recv;
+    const uint32_t recv = lane_xor2(i1 ? x[a] : x[a + 1]);
+    x[a] = i1 ? recv : x[a];
+    x[a + 1] = i1 ? x[a + 1] : recv;
   }
 #pragma unroll
   for (int a = 0; a < 2; ++a) {  // lane bit 2 <-> word bit 1
-    const uint32_t recv = (uint32_t)__shfl_xor((int)(i2 ? x[a] : x[a + 2]), 4);
-    if (i2) x[a] = recv; else x[a + 2] = recv;
+    const uint32_t recv = lane_xor4(i2 ? x[a] : x[a + 2], i2);
+    x[a] = i2 ? recv : x[a];
+    x[a + 2] = i2 ? x[a + 2] : recv;
   }
   return make_uint4(x[0], x[1], x[2], x[3]);
 }
@@ -52,13 +55,15 @@ __device__ __forceinline__ uint4 transpose_4x4_b32(const uint4& v, int lane) {
   const bool i0 = lane & 1, i1 = lane & 2;
 #pragma unroll
   for (int a = 0; a < 4; a += 2) {
-    const uint32_t recv = (uint32_t)__shfl_xor((int)(i0 ? x[a] : x[a + 1]), 1);
-    if (i0) x[a] = recv; else x[a + 1] = recv;
+    const uint32_t recv = lane_xor1(i0 ? x[a] : x[a + 1]);
+    x[a] = i0 ? recv : x[a];
+    x[a + 1] = i0 ? x[a + 1] : recv;
   }
 #pragma unroll
   for (int a = 0; a < 2; ++a) {
-    const uint32_t recv = (uint32_t)__shfl_xor((int)(i1 ? x[a] : x[a + 2]), 2);
-    if (i1) x[a] = recv; else x[a + 2] = recv;
+    const uint32_t recv = lane_xor2(i1 ? x[a] : x[a + 2]);
+    x[a] = i1 ? recv : x[a];
+    x[a + 2] = i1 ? x[a + 2] : recv;
   }
   return make_uint4(x[0], x[1], x[2], x[3]);
 }
@@ -225,7 +230,7 @@ __global__ __launch_bounds__(ATT_THREADS) void attend_kernel(AttendParams p) {
       float mx = acc[0];
 #pragma unroll
       for (int r = 1; r < 16; ++r) mx = fmaxf(mx, acc[r]);
-      mx = fmaxf(mx, __shfl_xor(mx, 32));  // both halves of the wave use one reference per row
+      mx = half_pair_max(mx);  // both halves of the wave use one reference per row
       mx = mx > NEG_BIG ? mx * p.scale2 : NEG_BIG;  // the reference lives in the scaled (log2) domain; scale2 > 0
       if (__any(mx > m_ref)) {
         const float m_new = fmaxf(m_ref, mx);
@@ -493,7 +498,7 @@ __global__ __launch_bounds__(ATT_THREADS) void attend_rows_kernel(AttendParams p
       float mx = acc[0];
 #pragma unroll
       for (int r = 1; r < 16; ++r) mx = fmaxf(mx, acc[r]);
-      mx = fmaxf(mx, __shfl_xor(mx, 32));  // both halves of the wave use one reference per row
+      mx = half_pair_max(mx);  // both halves of the wave use one reference per row
       mx = mx > NEG_BIG ? mx * p.scale2 : NEG_BIG;  // the reference lives in the scaled (log2) domain; scale2 > 0
       if (__any(mx > m_ref)) {
         const float m_new = fmaxf(m_ref, mx);

@@ -101,6 +101,24 @@ __device__ __forceinline__ int wave_incl_scan(int v) {
   return v;
 }
 
+// Value of lane (l ^ 1), (l ^ 2), (l ^ 4) through DPP moves (no LDS round trip as a bpermute takes).
+__device__ __forceinline__ uint32_t lane_xor1(uint32_t v) {
+  return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0xB1, 0xf, 0xf, true);  // quad_perm:[1,0,3,2]
+}
+__device__ __forceinline__ uint32_t lane_xor2(uint32_t v) {
+  return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x4E, 0xf, 0xf, true);  // quad_perm:[2,3,0,1]
+}
+__device__ __forceinline__ uint32_t lane_xor4(uint32_t v, bool bit2) {
+  const uint32_t up = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x104, 0xf, 0xf, true);    // row_shl:4: from lane l + 4
+  const uint32_t down = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x114, 0xf, 0xf, true);  // row_shr:4: from lane l - 4
+  return bit2 ? down : up;
+}
+// max of a value over the lane pair (l, l ^ 32): one swap of the wave's halves, no LDS round trip
+__device__ __forceinline__ float half_pair_max(float v) {
+  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));  // r[0]: the lower half's values in all lanes, r[1]: the upper half's
+}
+
 // (m, s) pairs describe sum_i 2^(x_i) as s * 2^m.
 __device__ __forceinline__ void lse_merge(float& m, float& s, float m2, float s2) {
   float mn = fmaxf(m, m2);
