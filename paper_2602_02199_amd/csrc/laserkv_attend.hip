@@ -277,7 +277,7 @@ __global__ __launch_bounds__(ATT_THREADS) void attend_kernel(AttendParams p) {
     have = nhave;
   }
 
-  l_sum += __shfl_xor(l_sum, 32);
+  l_sum = half_pair_sum(l_sum);
   if (p.direct) {
     // one split and a wave per row tile: the state is final.  out = O / l, lse = (m + log2 l) ln 2; a row that
     // saw no key gives zero and -inf
@@ -554,7 +554,7 @@ __global__ __launch_bounds__(ATT_THREADS) void attend_rows_kernel(AttendParams p
     }
   }
 
-  l_sum += __shfl_xor(l_sum, 32);
+  l_sum = half_pair_sum(l_sum);
   if (row >= p.m_rows) return;
   if (p.direct) {
     // one split: the state is final.  out = O / l, lse = (m + log2 l) ln 2; a row that saw no key gives zero and -inf
@@ -738,7 +738,7 @@ __global__ __launch_bounds__(LSE_THREADS) void attend_lse_kernel(AttendParams p)
     cur ^= 1;
     lds_barrier();
   }
-  lse_merge(ref, sum, __shfl_xor(ref, 32), __shfl_xor(sum, 32));  // the two halves hold the same rows over different keys
+  lse_merge(ref, sum, half_other(ref, kg), half_other(sum, kg));  // the two halves hold the same rows over different keys
   if (kg == 0 && row < p.m_rows) p.part_ml[((size_t)h * p.n_parts + split) * p.m_rows + row] = make_float2(ref, sum);
 }
 

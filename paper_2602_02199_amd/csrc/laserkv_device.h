@@ -113,7 +113,23 @@ __device__ __forceinline__ uint32_t lane_xor4(uint32_t v, bool bit2) {
   const uint32_t down = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x114, 0xf, 0xf, true);  // row_shr:4: from lane l - 4
   return bit2 ? down : up;
 }
-// max of a value over the lane pair (l, l ^ 32): one swap of the wave's halves, no LDS round trip
+__device__ __forceinline__ float lane_xor1(float v) { return __uint_as_float(lane_xor1(__float_as_uint(v))); }
+__device__ __forceinline__ float lane_xor2(float v) { return __uint_as_float(lane_xor2(__float_as_uint(v))); }
+__device__ __forceinline__ int lane_xor1(int v) { return (int)lane_xor1((uint32_t)v); }
+__device__ __forceinline__ int lane_xor2(int v) { return (int)lane_xor2((uint32_t)v); }
+__device__ __forceinline__ int lane_xor4(int v, bool bit2) { return (int)lane_xor4((uint32_t)v, bit2); }
+// Value of lane (l ^ 32): one swap of the wave's halves (upper: the lane is in the upper half), no LDS round trip.
+__device__ __forceinline__ uint32_t half_other(uint32_t v, bool upper) {
+  const auto r = __builtin_amdgcn_permlane32_swap(v, v, false, false);  // r[0]: the lower half's values in all lanes, r[1]: the upper half's
+  return upper ? r[0] : r[1];
+}
+__device__ __forceinline__ float half_other(float v, bool upper) { return __uint_as_float(half_other(__float_as_uint(v), upper)); }
+// sum of a value over the lane pair (l, l ^ 32), the same bits in both lanes
+__device__ __forceinline__ float half_pair_sum(float v) {
+  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+// max of a value over the lane pair (l, l ^ 32)
 __device__ __forceinline__ float half_pair_max(float v) {
   const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
   return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));  // r[0]: the lower half's values in all lanes, r[1]: the upper half's

@@ -328,11 +328,8 @@ __global__ __launch_bounds__(PASS_WAVES * 64) void pass_kernel(PassParams p) {
     // normaliser like one more partial (natural log -> exp2 domain)
     if (p.row_lse && (tid & 3) == 0 && qg * MQ + (tid >> 2) < p.m_rows)
       lse_merge(mm, ss, p.row_lse[(size_t)h * p.m_rows + qg * MQ + (tid >> 2)] * 1.4426950408889634f, 1.0f);
-#pragma unroll
-    for (int off = 1; off < 4; off <<= 1) {
-      const float m2 = __shfl_xor(mm, off), s2 = __shfl_xor(ss, off);
-      lse_merge(mm, ss, m2, s2);
-    }
+    lse_merge(mm, ss, lane_xor1(mm), lane_xor1(ss));
+    lse_merge(mm, ss, lane_xor2(mm), lane_xor2(ss));
     const int t = tid >> 2;
     if ((tid & 3) == 0) sLse[t] = (qg * MQ + t < p.m_rows) ? mm + fast_log2(ss) : 1.0e30f;  // padding rows: probability 0
   }
@@ -395,8 +392,8 @@ __global__ __launch_bounds__(PASS_WAVES * 64) void pass_kernel(PassParams p) {
           }
         }
       }
-      if (lpk > 1) sum += __shfl_xor(sum, 1);
-      if (lpk > 2) sum += __shfl_xor(sum, 2);
+      if (lpk > 1) sum += lane_xor1(sum);
+      if (lpk > 2) sum += lane_xor2(sum);
       if (sub == 0) p.cnt[((size_t)qg * p.n_kv_heads + h) * p.s_t + b0 + key] = sum;
     }
   }
@@ -464,7 +461,7 @@ __global__ __launch_bounds__(PASS_WAVES * 64) void pass_kernel(PassParams p) {
           }
         }
       }
-      col += __shfl_xor(col, 32);
+      col = half_pair_sum(col);
       if (kg == 0) sCol[rt * nkr + nt * 32 + rl] = col;
     }
     if (cnt_piped) {
@@ -494,8 +491,8 @@ __global__ __launch_bounds__(PASS_WAVES * 64) void pass_kernel(PassParams p) {
       for (int u = 0; u < 4; ++u)
         cnt_sum += (int)(((ra[u].x >> (rsh[u] & 31u)) & 0xffffu) + ((ra[u].y >> (rsh[u] & 31u)) & 0xffffu) +
                          ((rb[u].x >> (rsh[u] >> 8)) & 0xffffu) + ((rb[u].y >> (rsh[u] >> 8)) & 0xffffu));
-      if (lpk_log > 0) cnt_sum += __shfl_xor(cnt_sum, 1);
-      if (lpk_log > 1) cnt_sum += __shfl_xor(cnt_sum, 2);
+      if (lpk_log > 0) cnt_sum += lane_xor1(cnt_sum);
+      if (lpk_log > 1) cnt_sum += lane_xor2(cnt_sum);
       if (cnt_lane && (tid & ((1 << lpk_log) - 1)) == 0)
         p.cnt[((size_t)qg * p.n_kv_heads + h) * p.s_t + b0 + cnt_key] = cnt_sum;
     }
@@ -577,7 +574,7 @@ __global__ __launch_bounds__(PASS_WAVES * 64) void pass_kernel(PassParams p) {
       }
     }
     // the two halves of the wave hold the same rows over different keys
-    lse_merge(ref, sum, __shfl_xor(ref, 32), __shfl_xor(sum, 32));
+    lse_merge(ref, sum, half_other(ref, kg), half_other(sum, kg));
     if (kg == 0 && row < p.m_rows) p.part[((size_t)h * p.m_pad + row) * p.r_pad + kr] = make_float2(ref, sum);
     }
 
@@ -599,7 +596,7 @@ __global__ __launch_bounds__(PASS_WAVES * 64) void pass_kernel(PassParams p) {
 #pragma unroll
       for (int r = 15; r >= 0; --r) neg = __builtin_amdgcn_alignbit(neg, __float_as_uint(acc[r]), 31);
       const uint32_t pos = ~neg & 0xffffu;
-      const uint32_t other = (uint32_t)__shfl_xor((int)pos, 32);
+      const uint32_t other = half_other(pos, kg);
       const uint32_t word = kg ? (other | (pos << 16)) : (pos | (other << 16));
       // the tile's tables alternate between the two lanes that hold the row
       const int t_tab0 = qt0 + t * p.q_tab_per_tile;
@@ -637,7 +634,7 @@ __global__ __launch_bounds__(PASS_WAVES * 64) void pass_kernel(PassParams p) {
 #pragma unroll
         for (int r = 15; r >= 0; --r) neg = __builtin_amdgcn_alignbit(neg, __float_as_uint(acc[r]), 31);
         const uint32_t pos = ~neg & 0xffffu;  // bit = projection >= 0 (an accumulator is never -0)
-        const uint32_t mask = pos | ((uint32_t)__shfl_xor((int)pos, 32) << 16);
+        const uint32_t mask = pos | (half_other(pos, kg) << 16);
         if (kg == 0) sBits[(size_t)(base + rl) * BITS_PITCH + mt] = mask;
       }
     }

@@ -182,7 +182,7 @@ __global__ __launch_bounds__(SG_THREADS) void single_sweep_kernel(SingleParams p
 #pragma unroll
     for (int r = 15; r >= 0; --r) neg = __builtin_amdgcn_alignbit(neg, __float_as_uint(acc[r]), 31);
     const uint32_t pos = ~neg & 0xffffu;  // bit = projection >= 0
-    const uint32_t other = (uint32_t)__shfl_xor((int)pos, 32);
+    const uint32_t other = half_other(pos, kg);
     const uint32_t word = kg ? (other | (pos << 16)) : (pos | (other << 16));
     if (row < p.m_rows)
       for (int tt = kg; tt < n_tt; tt += 2) {  // the tile's tables alternate between the two lanes that hold the row
@@ -229,7 +229,7 @@ __global__ __launch_bounds__(SG_THREADS) void single_sweep_kernel(SingleParams p
 #pragma unroll
       for (int r = 15; r >= 0; --r) neg = __builtin_amdgcn_alignbit(neg, __float_as_uint(acc[r]), 31);
       const uint32_t pos = ~neg & 0xffffu;
-      const uint32_t mask = pos | ((uint32_t)__shfl_xor((int)pos, 32) << 16);
+      const uint32_t mask = pos | (half_other(pos, kg) << 16);
       if (kg == 0) sBits[(size_t)(vt * 32 + rl) * SG_BITS_PITCH + mt] = mask;
     }
   }
@@ -272,7 +272,7 @@ __global__ __launch_bounds__(SG_THREADS) void single_sweep_kernel(SingleParams p
           }
         }
       }
-      col += __shfl_xor(col, 32);
+      col = half_pair_sum(col);
       if (kg == 0) sCol[wave * nk + nt * 32 + rl] = col;
     }
   }
@@ -326,9 +326,9 @@ __global__ __launch_bounds__(SG_THREADS) void single_sweep_kernel(SingleParams p
 #pragma unroll
         for (int u = 0; u < 4; ++u) sum += (tb + u * SG_LPK < n_tables) ? (int)((hv[u] >> sh[u]) & 0xffffu) : 0;
       }
-      sum += __shfl_xor(sum, 1);
-      sum += __shfl_xor(sum, 2);
-      sum += __shfl_xor(sum, 4);
+      sum += lane_xor1(sum);
+      sum += lane_xor2(sum);
+      sum += lane_xor4(sum, (tid & 4) != 0);
       if (sub == 0) p.cnt[(size_t)h * p.s_t + b0 + key] = sum;
     }
   }
