@@ -169,6 +169,8 @@ def measure(wl, args, dev, cpu_seconds):
         work["select"] = ("hbm", work["select"][1] + work["append"][1])
     if args.attend:
         res["attend_cache"] = measure_attend(wl, comp, ddev, dev, cases=args.attend_case.split(","))
+    if args.pipeline and args.batch == 1 and args.lse == "own":
+        res["model_pipeline"] = measure_model_pipeline(wl, comp, ddev, dev)
     if not any(v["launches"] for v in kern.values()):
         return res
     peak_mfma = PEAK_MFMA_BF16_TFLOPS if wl.dtype == "bf16" else PEAK_MFMA_F32_TFLOPS
@@ -208,6 +210,57 @@ def measure(wl, args, dev, cpu_seconds):
     del comp, ddev, data
     torch.cuda.empty_cache()
     return res
+
+
+def measure_model_pipeline(wl, comp, ddev, dev, steps=3):
+    """One layer the way a model runs it: per block laserkv_attend_block over the compacted cache and the
+    block (all of the block's rows: queries are seeded N(0,1) except the window rows, which are the
+    workload's), the window rows' log-sum-exp handed to the selection (laserkv_set_row_lse_complete), then
+    select + append.  Step time from graph replays; the split between attention and selection from one eager
+    pass with an event pair around every kernel launch."""
+    import torch
+    s, d, w, nb = wl.s_block, wl.head_dim, wl.window, wl.n_blocks
+    gen = torch.Generator(device=dev).manual_seed(4321)
+    dt = ddev["k"].dtype
+    q_blocks = []
+    for t in range(nb):
+        q = torch.randn(wl.n_q_heads, s, d, generator=gen, device=dev).to(dt)
+        q[:, s - w:] = ddev["q_win"][t]
+        q_blocks.append(q)
+    out = torch.empty(wl.n_q_heads, s, d, dtype=torch.float32, device=dev)
+    lse = torch.empty(wl.n_q_heads, s, dtype=torch.float32, device=dev)
+    lse_win = torch.empty(wl.n_q_heads, w, dtype=torch.float32, device=dev)
+    n_last = (nb - 1) * min(comp.B, s)
+    ws = torch.empty(max(comp.lib.laserkv_attend_block_workspace_bytes(s, n, s) for n in (0, n_last)), dtype=torch.uint8, device=dev)
+    run = lambda: comp.run_layer_with_attention(ddev, q_blocks, out, lse, lse_win, ws)
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        run()
+        stream.synchronize()
+        comp.lib.laserkv_profile_begin()
+        run()
+        prof = comp.lib.laserkv_profile_end()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=stream):
+            run()
+        graph.replay()
+        stream.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for _ in range(steps):
+            graph.replay()
+        e1.record(stream)
+        e1.synchronize()
+    ms = e0.elapsed_time(e1) / steps
+    att = prof["attend"][0]
+    sel = sum(v[0] for k, v in prof.items() if k != "attend")
+    pairs = sum(s * t * min(comp.B, s) + s * (s + 1) // 2 for t in range(nb))
+    tfl = 4 * wl.n_q_heads * pairs * d / (att * 1e-3) / 1e12
+    peak = PEAK_MFMA_BF16_TFLOPS if wl.dtype == "bf16" else PEAK_MFMA_F32_TFLOPS
+    return dict(ms_per_layer=round(ms, 3), tokens_per_s_per_layer=round(wl.l_ctx / (ms * 1e-3), 1),
+                attention_ms=round(att, 3), attention_tflops=round(tfl, 1), attention_mfma_frac=round(tfl / peak, 4),
+                selection_ms=round(sel, 3), selection_share=round(sel / (att + sel), 4),
+                launches={k: v[1] for k, v in prof.items() if v[1]})
 
 
 def measure_attend(wl, comp, ddev, dev, reps=10, cases=("decode", "window")):
@@ -304,6 +357,8 @@ def main():
     ap.add_argument("--attend-case", default="decode,window,prefill", help="which attention cases to time (profiling one at a time)")
     ap.add_argument("--no-attend", dest="attend", action="store_false",
                     help="skip the timing of laserkv_attend_cache over the finished cache")
+    ap.add_argument("--no-pipeline", dest="pipeline", action="store_false",
+                    help="skip the layer run with the library's own block attention in front of every selection")
     ap.add_argument("--batch", type=int, default=1,
                     help="fold this many independent sequences into the head axis (heads x batch per call); the rate then "
                          "counts batch x context tokens. 1 is the headline configuration")
@@ -328,12 +383,13 @@ def main():
     if res["roofline"] is None:
         print(json.dumps(dict(value=res["value"], unit="tokens/s/layer", ms_per_step=res["ms_per_step"],
                               note="no per-kernel timing requested: roofline omitted",
-                              attend_cache=res.get("attend_cache"))), flush=True)
+                              attend_cache=res.get("attend_cache"), model_pipeline=res.get("model_pipeline"))), flush=True)
         return 0
     secondary = None
     if args.secondary not in ("none", args.workload) and args.batch == 1 and not args.calibrate_copy:
         sec_args = argparse.Namespace(**vars(args))
         sec_args.attend = False
+        sec_args.pipeline = False
         sec = measure(synth.WORKLOADS[args.secondary], sec_args, dev, 0.0)
         r = sec["roofline"]
         secondary = dict(workload=args.secondary, value=sec["value"], unit="tokens/s/layer", ms_per_step=sec["ms_per_step"],
@@ -346,6 +402,7 @@ def main():
     if args.lse == "own" and args.with_complete and args.batch == 1 and not args.calibrate_copy:
         c_args = argparse.Namespace(**vars(args))
         c_args.attend = False
+        c_args.pipeline = False
         c_args.lse = "complete"
         cm = measure(wl, c_args, dev, 0.0)
         r = cm["roofline"]
@@ -360,7 +417,8 @@ def main():
                dtype=wl.dtype, data="synthetic", config=res["config"], roofline=res["roofline"],
                cpu_baseline=res["cpu_baseline"], ms_per_step_mean=res["ms_per_step_mean"],
                ms_per_step_min=res["ms_per_step_min"], ms_per_step_max=res["ms_per_step_max"], secondary=secondary,
-               attend_cache=res.get("attend_cache"), complete_statistics=complete)
+               attend_cache=res.get("attend_cache"), complete_statistics=complete,
+               model_pipeline=res.get("model_pipeline"))
     print(json.dumps(out), flush=True)
     return 0
 

@@ -125,6 +125,43 @@ class LayerCompressor:
                                       lo, prev_local)
         return self.cache_len
 
+    def run_layer_with_attention(self, data, q_blocks, out, lse, lse_win, workspace, n_blocks=None):
+        """The block loop as a model runs it (Sec. 3 first paragraph; Sec. 3.3 "Precision"): block t's queries
+        attend to the compacted cache and, causally, to the block itself (laserkv_attend_block); the window
+        rows' log-sum-exp that kernel reports is handed to the selection as the complete row statistic
+        (laserkv_set_row_lse_complete: one sweep over the block, no statistics of its own); the kept rows join
+        the cache the next block attends to.  No host synchronisation.
+
+        q_blocks[t]: [H_q, S_t, d] queries of block t, whose last W rows are the observation window (passed to
+        the selection as a view).  out [H_q, S, d] and lse [H_q, S] float32 receive each block's attention,
+        lse_win [H_q, W] float32 the window rows' statistics, workspace the attention scratch (sized for the
+        last block); all are reused from block to block."""
+        wl = self.wl
+        self.reset()
+        nb = len(q_blocks) if n_blocks is None else n_blocks
+        l_tot = data["k"].shape[1]
+        w = wl.window
+        for t in range(nb):
+            lo, hi = t * wl.s_block, min((t + 1) * wl.s_block, l_tot)
+            s_t = hi - lo
+            q, k_blk, v_blk = q_blocks[t], data["k"][:, lo:hi], data["v"][:, lo:hi]
+            # contiguous [H_q, s_t, ...] tensors at the start of the buffers (a short last block uses less of them)
+            out_now = out.view(-1)[:q.shape[0] * s_t * wl.head_dim].view(q.shape[0], s_t, wl.head_dim)
+            lse_now = lse.view(-1)[:q.shape[0] * s_t].view(q.shape[0], s_t)
+            self.lib.laserkv_attend_block(q, self.k_cache, self.v_cache, k_blk, v_blk, cache_len=self.cache_len, block_pos0=lo,
+                                          out=out_now, out_lse=lse_now, workspace=workspace)
+            lse_win.copy_(lse_now[:, s_t - w:])
+            self.lib.laserkv_set_row_lse_complete(lse_win)
+            na, nl, ke, kl = self.block_budget(s_t)
+            b_t = na + nl + ke + kl
+            keep = self.keep if b_t == self.keep.shape[1] else torch.empty(wl.n_kv_heads, b_t, dtype=torch.int32, device=self.device)
+            self.lib.laserkv_compress_block(q[:, s_t - w:], k_blk, v_blk, None, data["planes"], block_pos0=lo, n_anchor=na,
+                                            n_local=nl, k_exact=ke, k_lsh=kl, keep_idx=keep, k_cache=self.k_cache,
+                                            v_cache=self.v_cache, cache_pos=self.cache_pos, cache_len=self.cache_len)
+            self.cache_len += b_t
+        self.lib.laserkv_set_row_lse_complete(None)
+        return self.cache_len
+
     # ---- pre-marshalled call lists: one ctypes call per library entry point, nothing else ----
     def plan_layer(self, data, n_blocks=None, fused=True, row_lse_complete=None):
         """Builds the layer's call list once: [(c_function, argument tuple without the stream)].

@@ -216,3 +216,41 @@ def test_complete_statistics_from_the_block_attention_kernel(name, kw, whole):
     assert np.array_equal(pc.cpu().numpy(), op)
     lib.laserkv_set_row_lse_complete(None)
     lib.close()
+
+
+def test_attend_block_at_the_benchmark_size_on_sampled_rows():
+    """The last block of the 128k workload in the launch shape bench.py times (4096 rows per query head over
+    61 535 cache rows and the block's 4096 keys, one workgroup per 256 rows seeing all keys, direct output):
+    sampled query positions (block start and end, row-tile and row-group edges, others) are recomputed one by
+    one by the oracle for every head."""
+    wl = synth.WORKLOADS["llama8b-128k"]
+    h_q, h_kv, d, s = wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.s_block
+    B = O.budget(s, wl.l_ctx, wl.r_num, wl.r_den)
+    n = (wl.n_blocks - 1) * B
+    q, kk, vv = make_inputs(h_q, h_kv, d, s, n + s, "bf16", seed=4242)
+    kc, vc, kb, vb = kk[:, :n].contiguous(), vv[:, :n].contiguous(), kk[:, n:].contiguous(), vv[:, n:].contiguous()
+    lib = binding.LaserKV(h_q, h_kv, d, "bf16", wl.lsh_tables, wl.lsh_bits, max_block=s, max_window=wl.window, max_ctx_keys=0)
+    assert lib.laserkv_attend_block_workspace_bytes(s, n, s) == 256   # the direct route
+    block_pos0 = (wl.n_blocks - 1) * s
+    out, lse = run_block(lib, q.to(DEV), kc.to(DEV), vc.to(DEV), n, kb.to(DEV), vb.to(DEV), block_pos0, block_pos0)
+    assert np.isfinite(out).all() and np.isfinite(lse).all()
+    # short runs of consecutive rows (one oracle call each) on three of the eight KV heads with their query heads
+    runs = [(0, 2), (31, 34), (255, 258), (2047, 2049), (3333, 3334), (3838, 3841), (4093, 4096)]
+    heads = [0, 3, 7]
+    g = h_q // h_kv
+    q_heads = [h * g + i for h in heads for i in range(g)]
+    kc64, vc64, kb64, vb64 = f64(kc[heads]), f64(vc[heads]), f64(kb[heads]), f64(vb[heads])
+    worst, worst_l, n_rows = 0.0, 0.0, 0
+    for j0, j1 in runs:
+        args = dict(block_pos0=block_pos0, q_pos0=block_pos0 + j0)
+        qq = f64(q[q_heads, j0:j1])
+        o_out, o_lse = O.attend_block(qq, kc64, vc64, n, kb64, vb64, **args)
+        scale, _ = O.attend_block(qq, kc64, np.abs(vc64), n, kb64, np.abs(vb64), **args)
+        err = np.abs(out[q_heads, j0:j1].astype(np.float64) - o_out)
+        assert np.all(err <= TOL["bf16"] * (np.abs(o_out) + scale)), f"rows {j0}..{j1 - 1}: output beyond tolerance"
+        worst = max(worst, float((err / (np.abs(o_out) + scale)).max()))
+        worst_l = max(worst_l, float(np.abs(lse[q_heads, j0:j1].astype(np.float64) - o_lse).max()))
+        n_rows += j1 - j0
+    assert worst <= OBSERVED["bf16"] and worst_l <= 1e-4
+    say(f"[attend_block 128k last block] {n_rows} sampled rows x {len(q_heads)} query heads: max err/(|o|+scale) {worst:.2e}, max |lse diff| {worst_l:.2e}")
+    lib.close()
