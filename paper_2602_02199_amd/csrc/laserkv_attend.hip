@@ -1,10 +1,16 @@
-// Attention over the compacted cache for gfx950 (Sec. 3 first paragraph: the kept tokens are what later
-// tokens attend to).  Every cached row is visible to every query: the cache holds earlier blocks only.
+// Attention kernels for gfx950: over the compacted cache (Sec. 3 first paragraph: the kept tokens are what
+// later tokens attend to; every cached row is visible, the cache holds earlier blocks only) and, behind the
+// cache rows, over the current block's own keys under the causal mask (the block's prefill attention, whose
+// log-sum-exp of the window rows is the complete statistic of Sec. 3.3 "Precision").
 //
-//   attend_kernel          workgroup = (key split, group of 256 query rows, KV head).  The split's keys and
-//                          values pass through LDS in chunks; each wave keeps 32 query rows in registers and
-//                          an online-softmax state (reference, sum, unnormalised output) per row, and leaves
-//                          one partial per (split, wave share)                                       [MFMA]
+//   attend_kernel          few query rows (decoding).  Workgroup = (key split, group of 256 query rows, KV
+//                          head); the waves share row tiles over different key tiles.  The split's keys and
+//                          values pass through LDS in chunks; each wave keeps 32 query rows in registers and an
+//                          online-softmax state (reference, sum, unnormalised output) per row; the waves'
+//                          states meet in LDS and leave one partial per split                          [MFMA]
+//   attend_rows_kernel     a row tile per wave (window rows, whole blocks): two LDS stages, the next tile's
+//                          logits issued before the current tile's softmax; writes the result itself when a
+//                          workgroup sees all keys of its rows                                         [MFMA]
 //   attend_combine_kernel  merges the partials of a row through their references and writes the output and
 //                          the natural-log normaliser, the number laserkv_set_row_lse takes
 //   attend_lse_kernel (+ attend_lse_combine_kernel)  the normaliser alone, for callers that want nothing else
@@ -93,7 +99,8 @@ __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
   return __builtin_bit_cast(uint32_t, t);
 }
 
-// One pass over the split's keys: its share of the cache rows, then its share of the block's own keys (none
+// One pass over the split's keys for launches with few query rows (the waves of a workgroup share row tiles
+// over different key tiles): its share of the cache rows, then its share of the block's own keys (none
 // for attention over the cache alone).  S^T = K Q^T puts a query row in a lane (column rl of the tile; the two
 // halves kg of the wave hold the same rows over different keys), so the softmax state is lane-private, and
 // the 16 accumulator registers are already the B operand of O^T += V^T P^T: register r of half kg is key
@@ -278,39 +285,6 @@ __global__ __launch_bounds__(ATT_THREADS) void attend_kernel(AttendParams p) {
   }
 
   l_sum = half_pair_sum(l_sum);
-  if (p.direct) {
-    // one split and a wave per row tile: the state is final.  out = O / l, lse = (m + log2 l) ln 2; a row that
-    // saw no key gives zero and -inf
-    if (row < p.m_rows) {
-      const size_t at = (size_t)h * p.m_rows + row;
-      const float inv = l_sum > 0.0f ? 1.0f / l_sum : 0.0f;
-      if (kg == 0) p.out_lse[at] = l_sum > 0.0f ? (m_ref + fast_log2(l_sum)) * 0.6931471805599453f : -__builtin_inff();
-      float* dst = p.out + at * D;
-#pragma unroll
-      for (int dt = 0; dt < NDT; ++dt)
-#pragma unroll
-        for (int q4 = 0; q4 < 4; ++q4)
-          st16_stream(dst + dt * 32 + 8 * q4 + 4 * kg,
-                      make_uint4(__float_as_uint(o[dt][4 * q4] * inv), __float_as_uint(o[dt][4 * q4 + 1] * inv),
-                                 __float_as_uint(o[dt][4 * q4 + 2] * inv), __float_as_uint(o[dt][4 * q4 + 3] * inv)));
-    }
-    return;
-  }
-  if (p.wprt_log == 0) {
-    // a wave owns its row tile: its state is the split's partial (reference, sum, unnormalised output)
-    if (row < p.m_rows) {
-      const size_t at = ((size_t)h * p.n_parts + split) * p.m_rows + row;
-      if (kg == 0) p.part_ml[at] = make_float2(m_ref, l_sum);
-      float* dst = p.part_o + at * D;
-#pragma unroll
-      for (int dt = 0; dt < NDT; ++dt)
-#pragma unroll
-        for (int q4 = 0; q4 < 4; ++q4)
-          *reinterpret_cast<float4*>(dst + dt * 32 + 8 * q4 + 4 * kg) =
-              make_float4(o[dt][4 * q4], o[dt][4 * q4 + 1], o[dt][4 * q4 + 2], o[dt][4 * q4 + 3]);
-    }
-    return;
-  }
   // several waves share a row tile over different key tiles: their states meet in LDS (rows padded by four
   // floats against bank conflicts) and leave as one partial per split
   constexpr int OP = D + 4;
