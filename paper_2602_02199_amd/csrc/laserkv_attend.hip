@@ -89,6 +89,13 @@ __device__ __forceinline__ void store_vt(uint4* row, int group, const uint4& t) 
   }
 }
 
+// ds_read_b64_tr_b16: four 16-bit values per lane, transposed within groups of 16 lanes (see its use)
+typedef short s16x4_lds __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint2 ds_read_tr16(const void* lds_ptr) {
+  const s16x4_lds v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4_lds*)lds_ptr);
+  return __builtin_bit_cast(uint2, v);
+}
+
 // Workgroup barrier for data exchanged through LDS only: waits for this wave's LDS traffic, not for its
 // global loads, so the next chunk's prefetch stays in flight across it (__syncthreads would wait for it).
 __device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
@@ -353,7 +360,11 @@ __global__ __launch_bounds__(ATT_THREADS) void attend_rows_kernel(AttendParams p
   constexpr int RUNS = 32 / (2 * EPC);        // operand chunks per lane and 32-key tile in P.V
   constexpr int K_ROWS_PER_LOAD = ATT_THREADS / CH;
   constexpr int V_GROUPS_PER_LOAD = ATT_THREADS / (EPC * CH);
-  constexpr int STAGE = KC * CHP + D * VTP;   // uint4 per LDS stage: K [KC][CHP], then V^T [D][VTP]
+  // bf16: V stays key-major in LDS (rows of CH chunks + 2: a 4-key x 32-byte transposing read touches every bank
+  // once) and ds_read_b64_tr_b16 delivers it transposed; fp32 has no such read: V^T is built in registers
+  constexpr bool TR = DT == DT_BF16;
+  constexpr int VP = CH + 2;                  // V row pitch in chunks (bf16)
+  constexpr int STAGE = KC * CHP + (TR ? KC * VP : D * VTP);   // uint4 per LDS stage: K [KC][CHP], then V [KC][VP] or V^T [D][VTP]
   static_assert(KL >= 1 && KL * ATT_THREADS == KC * CH, "chunk not a whole number of loads per thread");
 
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, rl = lane & 31, kg = lane >> 5;
@@ -402,20 +413,33 @@ __global__ __launch_bounds__(ATT_THREADS) void attend_rows_kernel(AttendParams p
 #pragma unroll
     for (int u = 0; u < KL; ++u) {
       kpre[u] = buf_ld16(ksrd, (uint32_t)(kc0 + k_row + u * K_ROWS_PER_LOAD) * kstride + k_col * 16);
-      const uint32_t key = (u * V_GROUPS_PER_LOAD + v_grp) * EPC + v_i;
-      vpre[u] = buf_ld16(vsrd, (uint32_t)(kc0 + key) * vstride + v_c * 16);
+      if (TR) {
+        vpre[u] = buf_ld16(vsrd, (uint32_t)(kc0 + k_row + u * K_ROWS_PER_LOAD) * vstride + k_col * 16);
+      } else {
+        const uint32_t key = (u * V_GROUPS_PER_LOAD + v_grp) * EPC + v_i;
+        vpre[u] = buf_ld16(vsrd, (uint32_t)(kc0 + key) * vstride + v_c * 16);
+      }
     }
   };
   auto store = [&](uint4* stage) {
     uint4* sK = stage;
-    uint4* sVT = stage + KC * CHP;
+    uint4* sV = stage + KC * CHP;
 #pragma unroll
     for (int u = 0; u < KL; ++u) {
       sK[(k_row + u * K_ROWS_PER_LOAD) * CHP + k_col] = kpre[u];
-      const uint4 t = DT == DT_BF16 ? transpose_8x8_b16(vpre[u], lane) : transpose_4x4_b32(vpre[u], lane);
-      store_vt<DT>(sVT + (v_c * EPC + v_i) * VTP, u * V_GROUPS_PER_LOAD + v_grp, t);
+      if (TR) {
+        sV[(k_row + u * K_ROWS_PER_LOAD) * VP + k_col] = vpre[u];
+      } else {
+        store_vt<DT>(sV + (v_c * EPC + v_i) * VTP, u * V_GROUPS_PER_LOAD + v_grp, transpose_4x4_b32(vpre[u], lane));
+      }
     }
   };
+  // Transposing read of V (bf16).  Within 16 lanes, lane i hands in the address of 4 consecutive 16-bit values and
+  // lane 4c + e receives value e of lanes c, c + 4, c + 8, c + 12.  Lane i points at key (i >> 2) of a run of four
+  // keys and head-dimension offset 4 (i & 3), so lane l of the sixteen receives the four keys at head-dimension
+  // offset l: the A operand of O^T += V^T P^T.  Byte offset of this lane's piece within a V stage, for key 0 of the
+  // tile's first 16-key block and head-dimension tile 0:
+  const uint32_t tr_off = (uint32_t)((4 * kg + ((lane & 15) >> 2)) * VP * 16 + ((lane >> 4) & 1) * 32 + (lane & 3) * 8);
   // the chunk after (seg, kc0): the next of the segment, else the first of the block's keys
   auto advance = [&](int& seg, int& kc0) -> bool {
     kc0 += KC;
@@ -458,6 +482,7 @@ __global__ __launch_bounds__(ATT_THREADS) void attend_rows_kernel(AttendParams p
   while (have) {
     const uint4* stage = smem + (size_t)cur * STAGE;
     const uint4* sVT = stage + KC * CHP;
+    const char* sVb = reinterpret_cast<const char*>(sVT) + tr_off;
     const int lane_end = seg ? min(hi1, blk_end_lane) : hi0;  // end of the keys of this segment the lane's row sees
     f32x16 acc, acc_next;
     logits(stage, 0, acc);
@@ -505,7 +530,12 @@ __global__ __launch_bounds__(ATT_THREADS) void attend_rows_kernel(AttendParams p
         for (int dt = 0; dt < NDT; ++dt) {
           const uint4* vrow = sVT + (size_t)(dt * 32 + rl) * VTP;
           uint4 va;
-          if (DT == DT_BF16) {
+          if (TR) {
+            // registers 8s .. 8s+3 are keys 16s + 4kg + (0..3), registers 8s+4 .. 8s+7 the same + 8
+            const char* at = sVb + (size_t)((nt * 32 + 16 * s) * VP) * 16 + dt * 64;
+            const uint2 lo = ds_read_tr16(at), hi = ds_read_tr16(at + 8 * VP * 16);
+            va = make_uint4(lo.x, lo.y, hi.x, hi.y);
+          } else if (DT == DT_BF16) {
             va = vrow[nt * 4 + 2 * s + kg];  // registers 8s .. 8s+7 are keys 16s + 4kg + (0..3) and the same + 8: see store_vt
           } else {
             va = vrow[nt * 8 + 2 * s + kg];  // registers 4s .. 4s+3 are keys 8s + 4kg + (0..3)
@@ -798,7 +828,8 @@ static hipError_t launch_attend_t(const AttendParams& p, hipStream_t st) {
     if (p.wprt_log == 0) {
       constexpr int ES = DT == DT_BF16 ? 2 : 4;
       constexpr int KC = rows_chunk_keys<DT>();
-      constexpr size_t lds = (size_t)2 * ((size_t)KC * (D * ES / 16 + 1) + (size_t)D * (KC / (16 / ES) + 1)) * 16;
+      constexpr size_t v_stage = DT == DT_BF16 ? (size_t)KC * (D * ES / 16 + 2) : (size_t)D * (KC / (16 / ES) + 1);
+      constexpr size_t lds = (size_t)2 * ((size_t)KC * (D * ES / 16 + 1) + v_stage) * 16;
       static_assert(lds <= 160 * 1024, "two attention chunks do not fit the LDS");
       hipLaunchKernelGGL((attend_rows_kernel<DT, D>), dim3(p.n_splits * p.n_qgroups * p.n_kv_heads), dim3(ATT_THREADS), lds, st, p);
       e = hipGetLastError();
