@@ -254,3 +254,57 @@ def test_attend_block_at_the_benchmark_size_on_sampled_rows():
     assert worst <= OBSERVED["bf16"] and worst_l <= 1e-4
     say(f"[attend_block 128k last block] {n_rows} sampled rows x {len(q_heads)} query heads: max err/(|o|+scale) {worst:.2e}, max |lse diff| {worst_l:.2e}")
     lib.close()
+
+
+def test_block_loop_with_attention_under_graph_replay():
+    """The whole block loop of a layer (attention, window statistics, one sweep, select + append per block)
+    captured once and replayed three times with eager launches and synchronisations of its own in between:
+    every replay must leave the cache, the positions, the last block's attention output and its log-sum-exp
+    exactly as the eager run left them."""
+    from paper_2602_02199_amd.driver import LayerCompressor
+    wl = synth.shrink(synth.WORKLOADS["llama8b-16k"], index=41, l_ctx=8192)
+    comp = LayerCompressor(wl, DEV)
+    data = synth.make_layer(wl, 1, comp.parts[0])
+    ddev = {k: v.to(DEV) for k, v in data.items() if k != "needles"}
+    s, d, w, nb = wl.s_block, wl.head_dim, wl.window, wl.n_blocks
+    gen = torch.Generator().manual_seed(9)
+    q_blocks = []
+    for t in range(nb):
+        q = torch.randn(wl.n_q_heads, s, d, generator=gen).to(wl.torch_dtype)
+        q[:, s - w:] = data["q_win"][t]
+        q_blocks.append(q.to(DEV))
+    out = torch.empty(wl.n_q_heads, s, d, dtype=torch.float32, device=DEV)
+    lse = torch.empty(wl.n_q_heads, s, dtype=torch.float32, device=DEV)
+    lse_win = torch.empty(wl.n_q_heads, w, dtype=torch.float32, device=DEV)
+    n_last = (nb - 1) * comp.B
+    ws = torch.empty(max(comp.lib.laserkv_attend_block_workspace_bytes(s, n, s) for n in (0, n_last)), dtype=torch.uint8, device=DEV)
+    run = lambda: comp.run_layer_with_attention(ddev, q_blocks, out, lse, lse_win, ws)
+
+    def state():
+        torch.cuda.synchronize()
+        return [t.cpu().clone() for t in (comp.k_cache, comp.v_cache, comp.cache_pos, out, lse, lse_win)]
+
+    def scrub():
+        for t in (comp.k_cache, comp.v_cache, out, lse, lse_win):
+            t.fill_(float("nan"))
+        comp.cache_pos.fill_(-7)
+
+    assert run() == nb * comp.B
+    want = state()
+    assert torch.isfinite(want[3]).all() and (want[2] >= 0).all()
+    stream = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(stream):
+        run()
+        stream.synchronize()
+        with torch.cuda.graph(graph, stream=stream):
+            run()
+    for rnd in range(3):
+        scrub()                      # eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        got = state()
+        for name, a, b in zip(("k_cache", "v_cache", "cache_pos", "out", "lse", "lse_win"), want, got):
+            assert torch.equal(a, b), f"replay {rnd}: {name} differs from the eager run"
+    say(f"[attend_block graph] {nb} blocks captured, 3 replays identical to the eager run")
+    comp.lib.close()
