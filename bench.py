@@ -359,6 +359,9 @@ def main():
                     help="skip the timing of laserkv_attend_cache over the finished cache")
     ap.add_argument("--no-pipeline", dest="pipeline", action="store_false",
                     help="skip the layer run with the library's own block attention in front of every selection")
+    ap.add_argument("--layer-sweep", type=int, default=0, metavar="N",
+                    help="time layers 0..N-1 of the workload one at a time (each generated with its own seed, one resident "
+                         "at a time) and print mean / min / max of the step time over the layers instead of the headline line")
     ap.add_argument("--batch", type=int, default=1,
                     help="fold this many independent sequences into the head axis (heads x batch per call); the rate then "
                          "counts batch x context tokens. 1 is the headline configuration")
@@ -379,6 +382,23 @@ def main():
     dev = "cuda:0"
     if args.policy == "consensus":
         return bench_consensus(args, wl, dev)
+    if args.layer_sweep > 0:
+        import statistics
+        import torch
+        l_args = argparse.Namespace(**vars(args))
+        l_args.attend = l_args.pipeline = False
+        l_args.profile_steps = 0
+        per_layer = []
+        for layer in range(args.layer_sweep):
+            l_args.layer = layer
+            per_layer.append(measure(wl, l_args, dev, 0.0)["ms_per_step"])
+            torch.cuda.empty_cache()
+        mean = statistics.mean(per_layer)
+        print(json.dumps(dict(metric="prefill-compression tokens/s/layer, every layer timed by itself", workload=wl.name,
+                              layers=args.layer_sweep, ms_per_layer_mean=round(mean, 4), ms_per_layer_min=min(per_layer),
+                              ms_per_layer_max=max(per_layer), value=round(wl.l_ctx / (mean * 1e-3), 1), unit="tokens/s/layer",
+                              steps=args.steps, warmup=args.warmup, data="synthetic", dtype=wl.dtype)), flush=True)
+        return 0
     res = measure(wl, args, dev, args.cpu_seconds)
     if res["roofline"] is None:
         print(json.dumps(dict(value=res["value"], unit="tokens/s/layer", ms_per_step=res["ms_per_step"],
