@@ -647,7 +647,8 @@ __global__ __launch_bounds__((D / 4) * COMB_SLICES) void attend_combine_kernel(A
 // split, group of 512 rows, KV head).  Keys pass through two LDS buffers in chunks (the next chunk's loads are
 // issued before the current one is worked on and stored after it: one barrier per chunk).  K Q^T with the
 // keys as the A operand puts a query row in a lane: each lane keeps (reference, sum of 2^(x - reference))
-// over its keys, the reference following the running maximum.
+// over its keys; the reference is the maximum over the split's first tile, and a pass whose sums overflow is
+// repeated with a reference that follows the running maximum.
 // ---------------------------------------------------------------------------------------------
 constexpr int LSE_WAVES = 16;
 constexpr int LSE_THREADS = LSE_WAVES * 64;
@@ -698,50 +699,68 @@ __global__ __launch_bounds__(LSE_THREADS) void attend_lse_kernel(AttendParams p)
     for (int u = 0; u < KL; ++u) buf[(k_row + u * ROWS_PER_LOAD) * CHP + k_col] = kpre[u];
   };
 
-  float ref = NEG_BIG, sum = 0.0f;
-  prefetch(k_lo);
-  store(smem);
-  lds_barrier();
-  int cur = 0;
-  for (int kc0 = k_lo; kc0 < k_hi; kc0 += KC) {
-    const bool more = kc0 + KC < k_hi;
-    if (more) prefetch(kc0 + KC);
-    const uint4* sK = smem + (size_t)cur * KC * CHP;
-#pragma unroll 1
-    for (int nt = 0; nt < TPC; ++nt) {
-      const int kbase = kc0 + nt * 32;
-      if (kbase >= k_hi) break;  // workgroup-uniform
-      f32x16 acc;
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
-      const uint4* krow = sK + (size_t)(nt * 32 + rl) * CHP + kg;
-#pragma unroll
-      for (int i = 0; i < NCH; ++i) Mma<DT>::run(acc, krow[2 * i], a[i]);
-      const int n_vis = k_hi - kbase;  // keys of this tile inside the split (>= 32: all)
-      if (n_vis >= 32) {
-        float mx = acc[0];
-#pragma unroll
-        for (int r = 1; r < 16; ++r) mx = fmaxf(mx, acc[r]);
-        const float nref = fmaxf(ref, mx * p.scale2);  // scale2 > 0
-        sum *= fast_exp2(ref - nref);
-        ref = nref;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) sum += fast_exp2(fmaf(acc[r], p.scale2, -ref));
-      } else if (acc_row(0, kg) < n_vis) {  // the split's last tile: a lane that sees none of its keys keeps its state
-        float mx = acc[0];
-#pragma unroll
-        for (int r = 1; r < 16; ++r) mx = acc_row(r, kg) < n_vis ? fmaxf(mx, acc[r]) : mx;
-        const float nref = fmaxf(ref, mx * p.scale2);
-        sum *= fast_exp2(ref - nref);
-        ref = nref;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) sum += acc_row(r, kg) < n_vis ? fast_exp2(fmaf(acc[r], p.scale2, -ref)) : 0.0f;
-      }
-    }
-    if (more) store(smem + (size_t)(cur ^ 1) * KC * CHP);
-    cur ^= 1;
+  // One pass over the split's keys.  fixed_ref: the reference is the lane's maximum over the split's first tile and
+  // is not raised by later complete tiles (one fma, one exponential, one add per logit and nothing else); a later
+  // logit 2^7 above it overflows the sum, which the caller detects.  Otherwise the reference follows the maximum.
+  float ref, sum;
+  auto pass = [&](bool fixed_ref) {
+    ref = NEG_BIG;
+    sum = 0.0f;
+    prefetch(k_lo);
+    store(smem);
     lds_barrier();
-  }
+    int cur = 0;
+    for (int kc0 = k_lo; kc0 < k_hi; kc0 += KC) {
+      const bool more = kc0 + KC < k_hi;
+      if (more) prefetch(kc0 + KC);
+      const uint4* sK = smem + (size_t)cur * KC * CHP;
+#pragma unroll 1
+      for (int nt = 0; nt < TPC; ++nt) {
+        const int kbase = kc0 + nt * 32;
+        if (kbase >= k_hi) break;  // workgroup-uniform
+        f32x16 acc;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
+        const uint4* krow = sK + (size_t)(nt * 32 + rl) * CHP + kg;
+#pragma unroll
+        for (int i = 0; i < NCH; ++i) Mma<DT>::run(acc, krow[2 * i], a[i]);
+        const int n_vis = k_hi - kbase;  // keys of this tile inside the split (>= 32: all)
+        if (n_vis >= 32 && fixed_ref && kbase > k_lo) {
+#pragma unroll
+          for (int r = 0; r < 16; ++r) sum += fast_exp2(fmaf(acc[r], p.scale2, -ref));
+        } else if (n_vis >= 32) {
+          float mx = acc[0];
+#pragma unroll
+          for (int r = 1; r < 16; ++r) mx = fmaxf(mx, acc[r]);
+          const float nref = fmaxf(ref, mx * p.scale2);  // scale2 > 0
+          sum *= fast_exp2(ref - nref);
+          ref = nref;
+#pragma unroll
+          for (int r = 0; r < 16; ++r) sum += fast_exp2(fmaf(acc[r], p.scale2, -ref));
+        } else if (acc_row(0, kg) < n_vis) {  // the split's last tile: a lane that sees none of its keys keeps its state
+          float mx = acc[0];
+#pragma unroll
+          for (int r = 1; r < 16; ++r) mx = acc_row(r, kg) < n_vis ? fmaxf(mx, acc[r]) : mx;
+          const float nref = fmaxf(ref, mx * p.scale2);
+          sum *= fast_exp2(ref - nref);
+          ref = nref;
+#pragma unroll
+          for (int r = 0; r < 16; ++r) sum += acc_row(r, kg) < n_vis ? fast_exp2(fmaf(acc[r], p.scale2, -ref)) : 0.0f;
+        }
+      }
+      if (more) store(smem + (size_t)(cur ^ 1) * KC * CHP);
+      cur ^= 1;
+      lds_barrier();
+    }
+  };
+  int* redo = reinterpret_cast<int*>(smem + (size_t)2 * KC * CHP);  // one word behind the two key buffers
+  if (tid == 0) *redo = 0;  // ordered before the writes below by the barriers of the pass
+  pass(true);
+  // an overflowed sum (inf, or NaN once it was rescaled) anywhere in the workgroup: once more with a running maximum
+  // (the decision is taken for the workgroup as a whole: the pass has barriers)
+  if (!(sum < 3.0e38f)) *redo = 1;
+  __syncthreads();
+  if (*redo) pass(false);
   lse_merge(ref, sum, half_other(ref, kg), half_other(sum, kg));  // the two halves hold the same rows over different keys
   if (kg == 0 && row < p.m_rows) p.part_ml[((size_t)h * p.n_parts + split) * p.m_rows + row] = make_float2(ref, sum);
 }
@@ -845,7 +864,7 @@ static hipError_t launch_attend_t(const AttendParams& p, hipStream_t st) {
 template <int DT, int D>
 static hipError_t launch_attend_lse_t(const AttendParams& p, hipStream_t st) {
   constexpr int ES = DT == DT_BF16 ? 2 : 4;
-  constexpr size_t lds = (size_t)2 * lse_chunk_keys<DT>() * (D * ES / 16 + 1) * 16;
+  constexpr size_t lds = (size_t)2 * lse_chunk_keys<DT>() * (D * ES / 16 + 1) * 16 + 16;  // two key buffers and the redo flag
   static_assert(lds <= 160 * 1024, "two key chunks do not fit the LDS");
   if (p.n_splits > 0) {
     hipLaunchKernelGGL((attend_lse_kernel<DT, D>), dim3(p.n_splits, p.n_qgroups, p.n_kv_heads), dim3(LSE_THREADS), lds, st, p);

@@ -235,3 +235,27 @@ def test_cache_normaliser_from_the_attention_kernel(name, kw):
     assert np.array_equal(pc.cpu().numpy(), op)
     lib.laserkv_set_row_lse(None)
     lib.close()
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_normaliser_only_route_when_a_late_key_dwarfs_the_first_tile(dtype):
+    """The normaliser-only kernel keeps each row's reference at the maximum over the split's first tile and adds
+    2^(logit - reference) afterwards; a later key whose logit lies more than 2^7 (in the log2 domain) above it
+    overflows that sum, which the kernel must notice and answer with a pass that follows the running maximum.
+    One key deep inside a split is aligned with the first query and huge (logit about 200 above the rest)."""
+    h_q, h_kv, d, n_q, n = 8, 2, 64, 40, 3000
+    q, k, v = make_inputs(h_q, h_kv, d, n_q, n, dtype, seed=123, needles=False)
+    q, k = q.float(), k.float()
+    u = q[0, 0] / q[0, 0].norm()
+    q[0, 0] = 40.0 * u                  # |q| = 40
+    k[0, 1777] = 40.0 * u               # q.k / sqrt(d) = 1600 / 8 = 200: about 289 in the log2 domain
+    td = torch.bfloat16 if dtype == "bf16" else torch.float32
+    q, k = q.to(td), k.to(td)
+    lib = binding.LaserKV(h_q, h_kv, d, dtype, 8, 8, max_block=256, max_window=64, max_ctx_keys=0)
+    _, lse = run_attend(lib, q.to(DEV), k.to(DEV), v.to(DEV), n, lse_only=True)
+    _, o_lse = O.attend_cache(f64(q), f64(k), f64(v), n)
+    assert o_lse[0, 0] > 150.0 and np.isfinite(lse).all()
+    compare_lse_only(lse, q, k, v, n, f"late dominant key {dtype}")
+    out, lse2 = run_attend(lib, q.to(DEV), k.to(DEV), v.to(DEV), n)
+    compare(out, lse2, q, k, v, n, dtype, f"late dominant key {dtype}")
+    lib.close()
