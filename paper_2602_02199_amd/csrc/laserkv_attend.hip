@@ -459,8 +459,20 @@ __global__ __launch_bounds__(ATT_THREADS) void attend_rows_kernel(AttendParams p
     for (int i = 0; i < NCH; ++i) Mma<DT>::run(acc, krow[2 * i], a[i]);
   };
 
-  float m_ref = NEG_BIG, l_sum = 0.0f;
+  // Two attempts at most.  In the first, a row's reference is its maximum over the first tile of the cache rows
+  // and complete tiles of cache rows after it skip the maximum, the comparison and the rescaling (an fma, an
+  // exponential and an add per logit are all that is left); sums that grow past 2^100 (a later logit far above
+  // the first tile's) make the workgroup repeat the pass with a reference that follows the running maximum
+  // everywhere, as the block's own keys (masked, and possibly a row's first visible keys) always do.
+  float m_ref, l_sum;
   f32x16 o[NDT];
+  int* redo = reinterpret_cast<int*>(smem + (size_t)2 * STAGE);  // one word behind the two stages
+  if (tid == 0) *redo = 0;  // ordered before the writes after the first attempt by the barriers in between
+#pragma unroll 1
+  for (int attempt = 0; attempt < 2; ++attempt) {
+  const bool fixed_ref = attempt == 0 && DT == DT_BF16;  // fp32 rows (512 bytes) leave no registers for a second tile body
+  m_ref = NEG_BIG;
+  l_sum = 0.0f;
 #pragma unroll
   for (int dt = 0; dt < NDT; ++dt)
 #pragma unroll
@@ -490,6 +502,14 @@ __global__ __launch_bounds__(ATT_THREADS) void attend_rows_kernel(AttendParams p
     for (int nt = 0; nt < TPC; ++nt) {
       if (nt + 1 < TPC) logits(stage, nt + 1, acc_next);  // the matrix unit works on these during the exponentials below
       const int n_vis = lane_end - (kc0 + nt * 32);  // keys of this tile the lane's row sees (>= 32: all)
+      // workgroup-uniform: a complete tile of cache rows that is not the pass's first
+      if (fixed_ref && seg == 0 && kc0 + nt * 32 > lo0 && kc0 + nt * 32 + 32 <= hi0) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          acc[r] = fast_exp2(fmaf(acc[r], p.scale2, -m_ref));
+          l_sum += acc[r];
+        }
+      } else {
       if (!__all(n_vis >= 32)) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[r] = acc_row(r, kg) < n_vis ? acc[r] : NEG_BIG;
@@ -515,6 +535,7 @@ __global__ __launch_bounds__(ATT_THREADS) void attend_rows_kernel(AttendParams p
       for (int r = 0; r < 16; ++r) {
         acc[r] = fast_exp2(fmaf(acc[r], p.scale2, -m_sub));
         l_sum += acc[r];
+      }
       }
 #pragma unroll
       for (int s = 0; s < RUNS; ++s) {
@@ -556,6 +577,12 @@ __global__ __launch_bounds__(ATT_THREADS) void attend_rows_kernel(AttendParams p
       cur ^= 1;
       lds_barrier();
     }
+  }
+  if (!fixed_ref) break;
+  // inf, NaN or large enough for O = sum p v to overflow next: repeat (decided for the workgroup: the pass has barriers)
+  if (!(l_sum < 1.0e30f)) *redo = 1;
+  __syncthreads();
+  if (!*redo) break;
   }
 
   l_sum = half_pair_sum(l_sum);
@@ -848,7 +875,7 @@ static hipError_t launch_attend_t(const AttendParams& p, hipStream_t st) {
       constexpr int ES = DT == DT_BF16 ? 2 : 4;
       constexpr int KC = rows_chunk_keys<DT>();
       constexpr size_t v_stage = DT == DT_BF16 ? (size_t)KC * (D * ES / 16 + 2) : (size_t)D * (KC / (16 / ES) + 1);
-      constexpr size_t lds = (size_t)2 * ((size_t)KC * (D * ES / 16 + 1) + v_stage) * 16;
+      constexpr size_t lds = (size_t)2 * ((size_t)KC * (D * ES / 16 + 1) + v_stage) * 16 + 16;  // two stages and the redo flag
       static_assert(lds <= 160 * 1024, "two attention chunks do not fit the LDS");
       hipLaunchKernelGGL((attend_rows_kernel<DT, D>), dim3(p.n_splits * p.n_qgroups * p.n_kv_heads), dim3(ATT_THREADS), lds, st, p);
       e = hipGetLastError();
