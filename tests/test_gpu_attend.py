@@ -259,3 +259,31 @@ def test_normaliser_only_route_when_a_late_key_dwarfs_the_first_tile(dtype):
     out, lse2 = run_attend(lib, q.to(DEV), k.to(DEV), v.to(DEV), n)
     compare(out, lse2, q, k, v, n, dtype, f"late dominant key {dtype}")
     lib.close()
+
+
+def test_attend_cache_at_the_benchmark_size():
+    """The three launch shapes bench.py times on the finished 128k cache (63 520 rows per head, 32/8 heads, d 128,
+    bf16): one decode query per head (every head compared), the next block's 128 window rows per head with and
+    without the output (sampled rows of three KV heads' query heads recomputed by the oracle)."""
+    wl = synth.WORKLOADS["llama8b-128k"]
+    h_q, h_kv, d, w = wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.window
+    n = wl.n_blocks * O.budget(wl.s_block, wl.l_ctx, wl.r_num, wl.r_den)
+    q, k, v = make_inputs(h_q, h_kv, d, w, n, "bf16", seed=777)
+    lib = binding.LaserKV(h_q, h_kv, d, "bf16", wl.lsh_tables, wl.lsh_bits, max_block=wl.s_block, max_window=w, max_ctx_keys=0)
+    kd, vd = k.to(DEV), v.to(DEV)
+    # decode: the first query of every head
+    q1 = q[:, :1].contiguous()
+    out, lse = run_attend(lib, q1.to(DEV), kd, vd, n)
+    compare(out, lse, q1, k, v, n, "bf16", "128k decode")
+    # window rows: all computed, a sample compared
+    out, lse = run_attend(lib, q.to(DEV), kd, vd, n)
+    _, lse_only = run_attend(lib, q.to(DEV), kd, vd, n, lse_only=True)
+    assert np.isfinite(out).all() and np.isfinite(lse).all() and np.isfinite(lse_only).all()
+    heads = [0, 4, 7]
+    g = h_q // h_kv
+    q_heads = [h * g + i for h in heads for i in range(g)]
+    rows = [0, 1, 31, 32, 63, 64, 100, 127]
+    qs = q[q_heads][:, rows].contiguous()
+    compare(out[q_heads][:, rows], lse[q_heads][:, rows], qs, k[heads], v[heads], n, "bf16", "128k window rows (sample)")
+    compare_lse_only(lse_only[q_heads][:, rows], qs, k[heads], v[heads], n, "128k window rows (sample)")
+    lib.close()
